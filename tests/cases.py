@@ -1,0 +1,71 @@
+"""Small message shapes shared by the CPU pins and the GPU parity tests.
+
+Pure descriptions (shape, element strides, element size) plus a seeded byte
+source; no arithmetic of the transfer lives here.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import List, Tuple
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class Case:
+    name: str
+    tensors: Tuple[Tuple[tuple, tuple, int], ...]   # (shape, strides in elements, esize)
+    k: int
+    B: int
+
+
+def contig(shape, esize):
+    st, acc = [], 1
+    for s in reversed(shape):
+        st.append(acc)
+        acc *= max(int(s), 1)
+    return (tuple(shape), tuple(reversed(st)), esize)
+
+
+def storage_bytes(shape, strides, esize):
+    if any(s == 0 for s in shape):
+        return 0
+    return (sum((s - 1) * st for s, st in zip(shape, strides)) + 1) * esize
+
+
+SMALL_CASES: List[Case] = [
+    Case("u8_1000_not_256_multiple", (contig((1000,), 1),), 2, 256),
+    Case("ragged_last_chunk_2p5", (contig((1280,), 2),), 3, 1024),          # 2560 B = 2.5 chunks
+    Case("fewer_chunks_than_lanes", (contig((300,), 4),), 8, 512),          # 1200 B -> 3 chunks, 8 lanes
+    Case("single_lane", (contig((17, 33), 2),), 1, 256),
+    Case("chunk_larger_than_message", (contig((100,), 2),), 4, 4096),
+    Case("three_tensors_with_gaps", (contig((10,), 1), contig((300,), 1), contig((4096,), 1)), 2, 1024),
+    Case("rows_not_16B_multiple", (((7, 100), (128, 1), 2),), 2, 512),       # 200-byte rows, padded pitch
+    Case("rows_interleaved_3d", (((6, 2, 64), (64, 6 * 64, 1), 2),), 3, 256),   # [seq,mb,h] view of [mb,seq,h]
+    Case("true_transpose_64x48", (((64, 48), (1, 64), 2),), 2, 512),
+    Case("transpose_f32_odd", (((33, 17), (1, 40), 4),), 2, 256),
+    Case("transpose_batched", (((3, 20, 24), (600, 1, 24), 2),), 2, 256),
+    Case("broadcast_stride0", (((5, 64), (0, 1), 4),), 2, 256),
+    Case("esize1_2d_strided", (((9, 31), (40, 1), 1),), 2, 256),
+    Case("esize8_strided", (((12, 10), (16, 1), 8),), 3, 256),
+    Case("esize8_transpose", (((10, 12), (1, 16), 8),), 2, 256),
+    Case("four_d_mixed", (((3, 4, 5, 6), (200, 6, 40, 1), 2),), 2, 256),     # middle dims permuted
+    Case("size_one_dims", (((1, 50, 1, 8), (7777, 8, 9999, 1), 2),), 2, 256),
+    Case("scalar_0d", (((), (), 4),), 1, 256),
+    Case("empty_tensor", (((0, 16), (16, 1), 2),), 2, 256),
+    Case("empty_between", (contig((100,), 2), ((0,), (1,), 2), contig((77,), 4)), 2, 256),
+    Case("inner_stride_2", (((40, 24), (48, 2), 2),), 2, 256),               # every other element
+    Case("mixed_dtypes_multi", (contig((33,), 1), ((8, 24), (32, 1), 2), ((16, 8), (1, 16), 4), contig((5,), 8)), 4, 512),
+]
+
+
+def case_by_name(name: str) -> Case:
+    for c in SMALL_CASES:
+        if c.name == name:
+            return c
+    raise KeyError(name)
+
+
+def make_storages(case: Case, seed: int) -> List[np.ndarray]:
+    rng = np.random.default_rng(seed)
+    return [rng.integers(0, 256, size=storage_bytes(*t), dtype=np.uint8) for t in case.tensors]
