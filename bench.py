@@ -1,0 +1,246 @@
+#!/usr/bin/env python3
+"""Benchmark of the pipeline-boundary transfer hot path on one MI355X.
+
+A step is one pass of the whole device-direct path over one batch of synthetic
+input: for every message of the workload (default: the LLaMA-8B-shaped boundary,
+a forward activation and a backward activation gradient, bf16 [4096,1,4096]),
+pack with send-side checksums, then unpack with receive-side checksums.  Inputs
+are resident in HBM before the timed region.  Buffer sets are rotated so that the
+working set is several times the 256 MB last-level cache: the figures are cold.
+
+Prints ONE JSON line.  `value` is the HBM traffic the pack and unpack kernels
+must move (read N + write N each) divided by wall time over the timed steps.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0     # MI355X HBM3E vendor peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--workload", default="llama8b_boundary")
+    ap.add_argument("--sets", type=int, default=8, help="rotating buffer sets (cold working set)")
+    ap.add_argument("--two-streams", action="store_true", help="issue the messages of a step on separate streams")
+    ap.add_argument("--no-checksum", action="store_true", help="diagnostic only: copies without checksums")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-staged", action="store_true")
+    return ap.parse_args()
+
+
+class MessageSet:
+    """Device buffers of one message: source tensors, packed buffer, destination tensors, checksum arrays."""
+
+    def __init__(self, torch, w, plan, seed):
+        dev = "cuda:0"
+        g = torch.Generator(device=dev)
+        g.manual_seed(seed)
+        self.src, self.dst = [], []
+        for t in w.tensors:
+            n = t.storage_elems
+            if w.dist == "bits16":
+                x = torch.randint(-32768, 32767, (n,), generator=g, device=dev, dtype=torch.int16).view(torch.bfloat16)
+            else:
+                x = (torch.randn(n, generator=g, device=dev, dtype=torch.float32) * w.std).to(torch.bfloat16)
+            self.src.append(x)
+            self.dst.append(torch.zeros_like(x))
+        self.packed = torch.empty(max(plan.packed_bytes, 256), dtype=torch.uint8, device=dev)
+        self.send_sums = torch.zeros(max(plan.num_chunks, 1), dtype=torch.int64, device=dev)
+        self.recv_sums = torch.zeros_like(self.send_sums)
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build measures one GPU only (the transfer is per-GPU work with no collective); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    from paper_2602_18007_amd import hxt
+    from paper_2602_18007_amd import workloads as wl
+
+    hxt.lib()                                   # fail loudly if the HIP library is not built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    w = wl.ALL[a.workload]()
+    plan = hxt.hxt_plan_multi([(t.shape, t.strides, t.esize) for t in w.tensors], w.n_lanes, w.chunk_bytes)
+    N = plan.message_bytes
+    nmsg = w.messages
+    sets = [[MessageSet(torch, w, plan, w.seed + 1000 * s + m * w.seed_step) for m in range(nmsg)]
+            for s in range(a.sets)]
+    main_stream = torch.cuda.current_stream()
+    streams = [torch.cuda.Stream() for _ in range(nmsg)] if a.two_streams else [main_stream] * nmsg
+    use_sums = not a.no_checksum
+
+    pack_events = []
+
+    def step(i, timed):
+        for m, ms in enumerate(sets[i % a.sets]):
+            st = streams[m]
+            if timed and m == 0:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(st)
+                hxt.hxt_pack(plan, ms.src, ms.packed, ms.send_sums if use_sums else None, st)
+                e1.record(st)
+                pack_events.append((e0, e1))
+            else:
+                hxt.hxt_pack(plan, ms.src, ms.packed, ms.send_sums if use_sums else None, st)
+            hxt.hxt_unpack(plan, ms.packed, ms.dst, ms.recv_sums if use_sums else None, st)
+
+    def fence():
+        if a.two_streams:
+            for st in streams:
+                main_stream.wait_stream(st)
+        torch.cuda.synchronize()
+
+    for i in range(a.warmup):
+        step(i, False)
+    fence()
+    t0 = time.perf_counter()
+    for i in range(a.steps):
+        step(a.warmup + i, True)
+    fence()
+    t1 = time.perf_counter()
+    sec = t1 - t0
+    step_bytes = 4 * N * nmsg                              # pack: read N + write N; unpack: the same
+    gbps = step_bytes * a.steps / sec / 1e9
+
+    # correctness of what was just timed: round trip identity and send == receive checksums
+    for ms in sets[(a.warmup + a.steps - 1) % a.sets]:
+        for s_, d_ in zip(ms.src, ms.dst):
+            assert torch.equal(s_.view(torch.int16), d_.view(torch.int16)), "round trip mismatch in the timed run"
+        if use_sums:
+            assert torch.equal(ms.send_sums, ms.recv_sums), "checksum mismatch in the timed run"
+
+    # dominant kernel: the pack copy (its twin, unpack, moves the same bytes).  Duration from HIP
+    # events recorded around the pack call of the first message of every timed step.
+    pack_ms = sorted(e0.elapsed_time(e1) for e0, e1 in pack_events)
+    pack_avg_ms = sum(pack_ms) / len(pack_ms)
+    pack_bytes = 2 * N
+    achieved = pack_bytes / (pack_avg_ms * 1e-3) / 1e9
+    out = {
+        "metric": "pack+unpack GB/s",
+        "value": round(gbps, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": a.steps,
+        "warmup": a.warmup,
+        "ms_per_step": round(sec / a.steps * 1e3, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "note": w.note, "message_bytes": N, "messages_per_step": nmsg,
+                   "n_lanes": w.n_lanes, "chunk_bytes": w.chunk_bytes, "path": "device_direct",
+                   "checksums": "fused send+receive" if use_sums else "off",
+                   "buffer_sets": a.sets, "cache_state": "cold (rotating sets)",
+                   "streams": nmsg if a.two_streams else 1},
+        "pct_hbm_peak": round(100 * gbps / HBM_PEAK_GBPS, 2),
+        "roofline": {"bound": "hbm", "kernel": "k_contig<pack, checksum> (plus its 1-block zero-fill of the sums)",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "bytes_per_launch": pack_bytes, "avg_launch_ms": round(pack_avg_ms, 6),
+                     "median_launch_ms": round(pack_ms[len(pack_ms) // 2], 6)},
+    }
+    if not a.no_staged:
+        out["staged"] = staged_round_trip(torch, hxt, w, plan, sets[0][0])
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+
+
+def staged_round_trip(torch, hxt, w, plan, ms):
+    """CPU-forwarding leg on the same message: D2H per lane on one stream, H2D per lane on another,
+    chained lane by lane with events; against a pinned hipMemcpy probe of the same size."""
+    nb, N, k = plan.packed_bytes, plan.message_bytes, w.n_lanes
+    host = torch.empty(nb, dtype=torch.uint8).pin_memory()
+    recv = torch.empty(nb, dtype=torch.uint8, device="cuda:0")
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def timed(fn, reps):
+        best = 1e9
+        for _ in range(reps):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            best = min(best, time.perf_counter() - t0)
+        return best
+
+    def d2h():
+        hxt.hxt_stage_d2h(plan, -1, ms.packed, host, s1)
+
+    def h2d():
+        hxt.hxt_stage_h2d(plan, -1, host, recv, s2)
+
+    def both():
+        hxt.hxt_stage_d2h(plan, -1, ms.packed, host, s1)
+        hxt.hxt_stage_h2d(plan, -1, host, recv, s2)
+
+    def round_trip():
+        for l in range(k):
+            hxt.hxt_stage_d2h(plan, l, ms.packed, host, s1)
+            ev = torch.cuda.Event()
+            ev.record(s1)
+            s2.wait_event(ev)
+            hxt.hxt_stage_h2d(plan, l, host, recv, s2)
+
+    for f in (d2h, h2d, both, round_trip):
+        f()
+    torch.cuda.synchronize()
+    t_d2h, t_h2d, t_both, t_rt = timed(d2h, 10), timed(h2d, 10), timed(both, 10), timed(round_trip, 10)
+    assert torch.equal(recv[:nb], ms.packed[:nb]) or plan.num_chunks == 0
+    link = min(N / t_d2h, N / t_h2d) / 1e9
+    return {"round_trip_gbps": round(N / t_rt / 1e9, 2), "pct_host_link": round(100 * (N / t_rt / 1e9) / link, 1),
+            "probe_d2h_gbps": round(N / t_d2h / 1e9, 2), "probe_h2d_gbps": round(N / t_h2d / 1e9, 2),
+            "probe_bidir_gbps": round(2 * N / t_both / 1e9, 2), "bytes": N, "lanes": k,
+            "note": "best of 10; round trip = first D2H start to last H2D end; link = min one-direction probe"}
+
+
+def cpu_baseline(w):
+    """The CPU oracle, as it stands, on the same message geometry: one full step."""
+    import numpy as np
+
+    from oracle import hxt_oracle as ho
+    from paper_2602_18007_amd import workloads as wl
+
+    cores = ho.max_threads()
+    m = ho.Message([ho.TensorSpec(t.shape, t.strides, t.esize) for t in w.tensors])
+    raws = wl.make_storages(w, 0)
+    B, k = w.chunk_bytes, w.n_lanes
+    dst = [np.zeros_like(r) for r in raws]
+    packed = np.zeros(ho.packed_bytes(m, B, k), np.uint8)
+    t0 = time.perf_counter()
+    reps = 0
+    while True:
+        ho.pack(m, raws, B, k, packed=packed, nthreads=cores)
+        s_send = ho.checksum(m, packed, B, k, nthreads=cores)
+        ho.unpack(m, packed, B, k, dst, nthreads=cores)
+        s_recv = ho.checksum(m, packed, B, k, nthreads=cores)
+        reps += 1
+        if time.perf_counter() - t0 > 10.0 or reps >= 50:
+            break
+    sec = time.perf_counter() - t0
+    assert np.array_equal(s_send, s_recv) and all(np.array_equal(a, b) for a, b in zip(raws, dst))
+    return {"value": round(4 * m.N * reps / sec / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": "%d message(s) of %d bytes: pack + checksum + unpack + checksum, %.1f s" % (reps, m.N, sec)}
+
+
+if __name__ == "__main__":
+    main()

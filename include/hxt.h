@@ -1,0 +1,164 @@
+/*
+ * hxt.h -- C ABI of the per-GPU side of pipeline-parallel stage-boundary
+ * transfers (activations forward, activation gradients backward) on MI355X.
+ *
+ * The operation follows the paper's Section 2.2 ("CPU-offloading P2P
+ * mechanism"): the sender copies the user tensor device-to-device into a chunk
+ * buffer, the chunk buffer is shipped, the receiver copies it symmetrically into
+ * its own tensor.  Section 2.1 adds multi-NIC parallel transfer (here: k lanes)
+ * and the CPU-forwarding variant with explicit GPU<->CPU buffer copies around
+ * the wire.  The wire itself is not part of this library: on one GPU the packed
+ * buffer written by hxt_pack (or refilled by hxt_stage_h2d) is the one
+ * hxt_unpack reads.
+ *
+ * Layout contract (the paper fixes no constants; these are this library's):
+ *   - Logical stream: tensors in order, each in row-major order of its shape
+ *     (last index fastest) whatever its strides; every tensor starts at a
+ *     multiple of 256 bytes and the stream length L is rounded up to 256; the
+ *     gaps are zero.  message_bytes N = sum of tensor bytes.
+ *   - Chunk c = stream bytes [c*chunk_bytes, min((c+1)*chunk_bytes, L)).
+ *   - lane(c) = c mod n_lanes, slot(c) = c div n_lanes (round-robin).
+ *   - Packed buffer, lane-major: lane l's region starts where lane l-1's ends
+ *     and holds its chunks in slot order, chunk_bytes per slot;
+ *     packed_bytes = num_chunks * chunk_bytes.  Slot bytes past a short last
+ *     chunk are never read or written.
+ *   - Checksum of chunk c = sum of its little-endian 32-bit words mod 2^64,
+ *     taken over the chunk's padded length (pad bytes are zero).
+ *
+ * Conventions
+ *   - Every function returns HXT_OK (0) or a negative hxt_status; nothing is
+ *     written to outputs on error.  No function throws or aborts.
+ *   - "device" pointers are HIP device addresses on the current device, "host"
+ *     pointers ordinary process memory, "pinned" host memory from hipHostMalloc.
+ *   - The caller owns every data buffer and every stream.  The library owns only
+ *     the plan (host tables plus one small device copy of its work tables,
+ *     allocated by hxt_plan*, released by hxt_plan_destroy).
+ *   - Data-plane calls only enqueue work on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and return; they never synchronise.
+ *     Ordering between streams is the caller's business (events).
+ *   - A plan is immutable after creation and may be used from several streams
+ *     at once.  Plans built from equal arguments on the sending and on the
+ *     receiving side are interchangeable (the receive is symmetric).
+ */
+#ifndef HXT_H
+#define HXT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HXT_MAX_DIMS 8
+#define HXT_ALIGN 256 /* tensor starts, stream end, chunk_bytes, packed/pinned base pointers */
+
+typedef enum {
+    HXT_OK = 0,
+    HXT_EINVAL = -1,       /* NULL where a pointer is required, bad count, bad lane, bad dtype ... */
+    HXT_EALIGN = -2,       /* packed/pinned pointer not 256-byte aligned, tensor base not element aligned */
+    HXT_EUNSUPPORTED = -3, /* valid request this build cannot serve (size limits) */
+    HXT_EOVERLAP = -4,     /* hxt_unpack into a view whose elements may alias each other */
+    HXT_EHIP = -5,         /* a HIP runtime call failed; hxt_last_hip_error() has the code */
+    HXT_ENOMEM = -6        /* host or device allocation for the plan failed */
+} hxt_status;
+
+/* Only the element size matters to the transfer: data is moved as raw bits. */
+typedef enum { HXT_U8 = 1, HXT_F16 = 2, HXT_BF16 = 3, HXT_F32 = 4, HXT_F64 = 5 } hxt_dtype_t;
+
+typedef struct hxt_plan hxt_plan_t; /* opaque */
+
+/* One tensor of a multi-tensor message.  strides in elements, NULL = contiguous. */
+typedef struct {
+    int ndim;               /* 0..HXT_MAX_DIMS */
+    const int64_t *shape;   /* [ndim], each >= 0 */
+    const int64_t *strides; /* [ndim], each >= 0, or NULL */
+    hxt_dtype_t dtype;
+} hxt_tensor_desc_t;
+
+typedef struct {
+    int32_t lane;        /* c mod n_lanes */
+    int32_t slot;        /* c div n_lanes */
+    uint64_t stream_off; /* c * chunk_bytes */
+    uint64_t padded;     /* bytes of the chunk in the stream (multiple of 256) */
+    uint64_t payload;    /* tensor bytes among them */
+    uint64_t packed_off; /* where the chunk starts in the packed buffer */
+} hxt_chunk_info_t;
+
+typedef struct {
+    uint64_t packed_off; /* start of the lane's region in the packed buffer */
+    uint64_t bytes;      /* used bytes: up to the padded end of the lane's last chunk */
+    int32_t n_chunks;
+} hxt_lane_info_t;
+
+/* ---- step 1: plan (host; Section 2.2: control work stays on the CPU) -------
+ * Validates the geometry, merges dimensions that are contiguous in memory, cuts
+ * the logical stream into chunks, deals the chunks over the lanes and builds the
+ * device work tables.  Needs a GPU only for the device copy of those tables; with
+ * no HIP device present the plan is still created and answers every query, and
+ * the data-plane calls return HXT_EHIP.
+ * Rejects with HXT_EINVAL: out == NULL, shape == NULL with ndim > 0, ndim < 0 or
+ * > HXT_MAX_DIMS, a negative extent or stride, unknown dtype, n_lanes < 1 or
+ * > 1024, chunk_bytes == 0 or not a multiple of 256, n_tensors < 0.
+ * HXT_EUNSUPPORTED: message larger than 2^40 bytes or more than 2^31 chunks. */
+int hxt_plan(const int64_t *shape, const int64_t *strides, int ndim, hxt_dtype_t dtype,
+             int n_lanes, size_t chunk_bytes, hxt_plan_t **out);
+int hxt_plan_multi(const hxt_tensor_desc_t *tensors, int n_tensors,
+                   int n_lanes, size_t chunk_bytes, hxt_plan_t **out);
+int hxt_plan_destroy(hxt_plan_t *plan); /* NULL is allowed */
+
+/* ---- queries (host only) ---------------------------------------------------- */
+size_t hxt_plan_message_bytes(const hxt_plan_t *plan); /* N */
+size_t hxt_plan_stream_bytes(const hxt_plan_t *plan);  /* L */
+size_t hxt_plan_packed_bytes(const hxt_plan_t *plan);  /* num_chunks * chunk_bytes */
+size_t hxt_plan_chunk_bytes(const hxt_plan_t *plan);
+int hxt_plan_num_chunks(const hxt_plan_t *plan);
+int hxt_plan_num_lanes(const hxt_plan_t *plan);
+int hxt_plan_num_tensors(const hxt_plan_t *plan);
+int hxt_plan_chunk_info(const hxt_plan_t *plan, int c, hxt_chunk_info_t *out);
+int hxt_plan_lane_info(const hxt_plan_t *plan, int lane, hxt_lane_info_t *out);
+/* 1 if hxt_unpack may write through tensor t's view (no two elements alias), else 0 */
+int hxt_plan_tensor_unpack_safe(const hxt_plan_t *plan, int t);
+/* which kernel family serves tensor t: 0 none (empty), 1 contiguous copy, 2 row gather,
+ * 3 LDS transpose, 4 per-element */
+int hxt_plan_tensor_kind(const hxt_plan_t *plan, int t);
+
+/* ---- step 2: pack (Section 2.2: user buffer -> chunk buffer, device to device)
+ * src: host array of n_tensors device base pointers (element aligned; a base that
+ *   is not 16-byte aligned is served by the slower per-element kernel).
+ * packed: device, >= packed_bytes, 256-byte aligned.  Every chunk's padded bytes
+ *   are written (pad = 0); nothing else.
+ * sums: NULL, or device array of num_chunks uint64 that receives the send-side
+ *   checksums of what was written (fused into the copy; no extra pass). */
+int hxt_pack(const hxt_plan_t *plan, const void *const *src, void *packed,
+             uint64_t *sums, void *stream);
+
+/* ---- step 3: CPU-forwarding staging (Section 2.1: explicit GPU<->CPU copies) -
+ * Copies the used bytes of one lane (lane >= 0) or of all lanes (lane == -1)
+ * between the device packed buffer and a pinned host buffer of the same layout
+ * (same offsets).  Both buffers >= packed_bytes and 256-byte aligned. */
+int hxt_stage_d2h(const hxt_plan_t *plan, int lane, const void *packed_dev,
+                  void *host_pinned, void *stream);
+int hxt_stage_h2d(const hxt_plan_t *plan, int lane, const void *host_pinned,
+                  void *packed_dev, void *stream);
+
+/* ---- step 4: unpack (Section 2.2: the receiver's symmetric copy) -------------
+ * dst: host array of n_tensors device base pointers.  Writes exactly the bytes
+ * the views address.  HXT_EOVERLAP if some tensor's view is not unpack-safe.
+ * sums: NULL, or device array receiving the receive-side checksums of the packed
+ * bytes as read (pad included). */
+int hxt_unpack(const hxt_plan_t *plan, const void *packed, void *const *dst,
+               uint64_t *sums, void *stream);
+
+/* ---- step 5: stand-alone per-chunk checksum of a packed buffer --------------- */
+int hxt_checksum(const hxt_plan_t *plan, const void *packed, uint64_t *sums, void *stream);
+
+/* ---- diagnostics -------------------------------------------------------------- */
+const char *hxt_strerror(int status);
+int hxt_last_hip_error(void);    /* hipError_t of the last failing HIP call on this thread */
+const char *hxt_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HXT_H */

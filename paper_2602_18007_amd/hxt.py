@@ -1,0 +1,254 @@
+"""Thin ctypes binding over libhxt.so (the C ABI declared in include/hxt.h).
+
+Same names as the C entry points; this layer only marshals arguments (tensor ->
+device pointer, stream -> hipStream_t, status -> exception).  Every step of the
+transfer runs in the library's HIP kernels; there is no Python or CPU fallback:
+if the library is missing, loading raises.
+
+PyTorch is used for device memory and streams only.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import torch  # imported before the library so both share one HIP runtime
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libhxt.so")
+
+HXT_OK, HXT_EINVAL, HXT_EALIGN, HXT_EUNSUPPORTED, HXT_EOVERLAP, HXT_EHIP, HXT_ENOMEM = 0, -1, -2, -3, -4, -5, -6
+HXT_U8, HXT_F16, HXT_BF16, HXT_F32, HXT_F64 = 1, 2, 3, 4, 5
+HXT_MAX_DIMS = 8
+KIND_NAMES = {0: "none", 1: "contig", 2: "rows", 3: "transpose", 4: "generic"}
+
+# every symbol include/hxt.h declares
+EXPORTS = (
+    "hxt_plan", "hxt_plan_multi", "hxt_plan_destroy", "hxt_plan_message_bytes", "hxt_plan_stream_bytes",
+    "hxt_plan_packed_bytes", "hxt_plan_chunk_bytes", "hxt_plan_num_chunks", "hxt_plan_num_lanes",
+    "hxt_plan_num_tensors", "hxt_plan_chunk_info", "hxt_plan_lane_info", "hxt_plan_tensor_unpack_safe",
+    "hxt_plan_tensor_kind", "hxt_pack", "hxt_stage_d2h", "hxt_stage_h2d", "hxt_unpack", "hxt_checksum",
+    "hxt_strerror", "hxt_last_hip_error", "hxt_version",
+)
+
+_DTYPE_BY_TORCH = {
+    torch.uint8: HXT_U8, torch.int8: HXT_U8, torch.bool: HXT_U8,
+    torch.float16: HXT_F16, torch.int16: HXT_F16, torch.bfloat16: HXT_BF16,
+    torch.float32: HXT_F32, torch.int32: HXT_F32, torch.float64: HXT_F64, torch.int64: HXT_F64,
+}
+_DTYPE_BY_SIZE = {1: HXT_U8, 2: HXT_BF16, 4: HXT_F32, 8: HXT_F64}
+
+
+class HxtError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().hxt_strerror(status).decode()
+        if status == HXT_EHIP:
+            msg += " [hipError %d]" % lib().hxt_last_hip_error()
+        super().__init__("%s: %s (%d)" % (where, msg, status))
+
+
+class _TensorDesc(C.Structure):
+    _fields_ = [("ndim", C.c_int), ("shape", C.POINTER(C.c_int64)), ("strides", C.POINTER(C.c_int64)),
+                ("dtype", C.c_int)]
+
+
+class ChunkInfo(C.Structure):
+    _fields_ = [("lane", C.c_int32), ("slot", C.c_int32), ("stream_off", C.c_uint64), ("padded", C.c_uint64),
+                ("payload", C.c_uint64), ("packed_off", C.c_uint64)]
+
+
+class LaneInfo(C.Structure):
+    _fields_ = [("packed_off", C.c_uint64), ("bytes", C.c_uint64), ("n_chunks", C.c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    """Load libhxt.so; raises if it has not been built (python -m paper_2602_18007_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libhxt.so is not built: run `python -m paper_2602_18007_amd.build` "
+                               "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        vp, i, sz, u64p = C.c_void_p, C.c_int, C.c_size_t, C.c_void_p
+        i64p = C.POINTER(C.c_int64)
+        sig = {
+            "hxt_plan": (i, [i64p, i64p, i, i, i, sz, C.POINTER(vp)]),
+            "hxt_plan_multi": (i, [C.POINTER(_TensorDesc), i, i, sz, C.POINTER(vp)]),
+            "hxt_plan_destroy": (i, [vp]),
+            "hxt_plan_message_bytes": (sz, [vp]),
+            "hxt_plan_stream_bytes": (sz, [vp]),
+            "hxt_plan_packed_bytes": (sz, [vp]),
+            "hxt_plan_chunk_bytes": (sz, [vp]),
+            "hxt_plan_num_chunks": (i, [vp]),
+            "hxt_plan_num_lanes": (i, [vp]),
+            "hxt_plan_num_tensors": (i, [vp]),
+            "hxt_plan_chunk_info": (i, [vp, i, C.POINTER(ChunkInfo)]),
+            "hxt_plan_lane_info": (i, [vp, i, C.POINTER(LaneInfo)]),
+            "hxt_plan_tensor_unpack_safe": (i, [vp, i]),
+            "hxt_plan_tensor_kind": (i, [vp, i]),
+            "hxt_pack": (i, [vp, C.POINTER(vp), vp, u64p, vp]),
+            "hxt_stage_d2h": (i, [vp, i, vp, vp, vp]),
+            "hxt_stage_h2d": (i, [vp, i, vp, vp, vp]),
+            "hxt_unpack": (i, [vp, vp, C.POINTER(vp), u64p, vp]),
+            "hxt_checksum": (i, [vp, vp, u64p, vp]),
+            "hxt_strerror": (C.c_char_p, [i]),
+            "hxt_last_hip_error": (i, []),
+            "hxt_version": (C.c_char_p, []),
+        }
+        for name, (res, args) in sig.items():
+            f = getattr(L, name)
+            f.restype, f.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def _check(status: int, where: str):
+    if status != HXT_OK:
+        raise HxtError(status, where)
+
+
+def _dtype_code(dt) -> int:
+    if isinstance(dt, torch.dtype):
+        return _DTYPE_BY_TORCH[dt]
+    if isinstance(dt, int) and dt in _DTYPE_BY_SIZE:       # element size in bytes
+        return _DTYPE_BY_SIZE[dt]
+    raise ValueError("unsupported dtype %r" % (dt,))
+
+
+def _ptr(x) -> Optional[int]:
+    if x is None:
+        return None
+    if isinstance(x, torch.Tensor):
+        return x.data_ptr()
+    return int(x)
+
+
+def _stream(s) -> Optional[int]:
+    if s is None:
+        return torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else None
+    if isinstance(s, torch.cuda.Stream):
+        return s.cuda_stream
+    return int(s)
+
+
+def _ptr_array(xs: Sequence):
+    arr = (C.c_void_p * max(len(xs), 1))()
+    for j, x in enumerate(xs):
+        arr[j] = _ptr(x)
+    return arr
+
+
+class Plan:
+    """Owner of one hxt_plan_t handle."""
+
+    def __init__(self, handle: int):
+        self.handle = C.c_void_p(handle)
+
+    def destroy(self):
+        if self.handle:
+            lib().hxt_plan_destroy(self.handle)
+            self.handle = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    # queries, named after the C functions without the prefix
+    message_bytes = property(lambda self: lib().hxt_plan_message_bytes(self.handle))
+    stream_bytes = property(lambda self: lib().hxt_plan_stream_bytes(self.handle))
+    packed_bytes = property(lambda self: lib().hxt_plan_packed_bytes(self.handle))
+    chunk_bytes = property(lambda self: lib().hxt_plan_chunk_bytes(self.handle))
+    num_chunks = property(lambda self: lib().hxt_plan_num_chunks(self.handle))
+    num_lanes = property(lambda self: lib().hxt_plan_num_lanes(self.handle))
+    num_tensors = property(lambda self: lib().hxt_plan_num_tensors(self.handle))
+
+    def chunk_info(self, c: int) -> dict:
+        out = ChunkInfo()
+        _check(lib().hxt_plan_chunk_info(self.handle, c, C.byref(out)), "hxt_plan_chunk_info")
+        return {k: getattr(out, k) for k, _ in ChunkInfo._fields_}
+
+    def lane_info(self, lane: int) -> dict:
+        out = LaneInfo()
+        _check(lib().hxt_plan_lane_info(self.handle, lane, C.byref(out)), "hxt_plan_lane_info")
+        return {k: getattr(out, k) for k, _ in LaneInfo._fields_}
+
+    def tensor_unpack_safe(self, t: int) -> bool:
+        r = lib().hxt_plan_tensor_unpack_safe(self.handle, t)
+        if r < 0:
+            raise HxtError(r, "hxt_plan_tensor_unpack_safe")
+        return bool(r)
+
+    def tensor_kind(self, t: int) -> str:
+        r = lib().hxt_plan_tensor_kind(self.handle, t)
+        if r < 0:
+            raise HxtError(r, "hxt_plan_tensor_kind")
+        return KIND_NAMES[r]
+
+
+def hxt_plan(shape, strides, dtype, n_lanes: int, chunk_bytes: int) -> Plan:
+    nd = len(shape)
+    shp = (C.c_int64 * max(nd, 1))(*shape)
+    st = (C.c_int64 * max(nd, 1))(*strides) if strides is not None else None
+    out = C.c_void_p()
+    _check(lib().hxt_plan(shp, st, nd, _dtype_code(dtype), n_lanes, chunk_bytes, C.byref(out)), "hxt_plan")
+    return Plan(out.value)
+
+
+def hxt_plan_multi(tensors: Sequence, n_lanes: int, chunk_bytes: int) -> Plan:
+    """tensors: sequence of (shape, strides_or_None, dtype) or torch tensors (their views are described)."""
+    n = len(tensors)
+    descs = (_TensorDesc * max(n, 1))()
+    keep = []
+    for j, t in enumerate(tensors):
+        if isinstance(t, torch.Tensor):
+            shape, strides, dt = tuple(t.shape), tuple(t.stride()), t.dtype
+        else:
+            shape, strides, dt = t
+        nd = len(shape)
+        shp = (C.c_int64 * max(nd, 1))(*shape)
+        st = (C.c_int64 * max(nd, 1))(*strides) if strides is not None else None
+        keep += [shp, st]
+        descs[j].ndim = nd
+        descs[j].shape = shp
+        descs[j].strides = st
+        descs[j].dtype = _dtype_code(dt)
+    out = C.c_void_p()
+    _check(lib().hxt_plan_multi(descs, n, n_lanes, chunk_bytes, C.byref(out)), "hxt_plan_multi")
+    return Plan(out.value)
+
+
+def hxt_plan_destroy(plan: Plan) -> None:
+    plan.destroy()
+
+
+def hxt_pack(plan: Plan, src: Sequence, packed, sums=None, stream=None) -> None:
+    _check(lib().hxt_pack(plan.handle, _ptr_array(src), _ptr(packed), _ptr(sums), _stream(stream)), "hxt_pack")
+
+
+def hxt_unpack(plan: Plan, packed, dst: Sequence, sums=None, stream=None) -> None:
+    _check(lib().hxt_unpack(plan.handle, _ptr(packed), _ptr_array(dst), _ptr(sums), _stream(stream)), "hxt_unpack")
+
+
+def hxt_checksum(plan: Plan, packed, sums, stream=None) -> None:
+    _check(lib().hxt_checksum(plan.handle, _ptr(packed), _ptr(sums), _stream(stream)), "hxt_checksum")
+
+
+def hxt_stage_d2h(plan: Plan, lane: int, packed_dev, host_pinned, stream=None) -> None:
+    _check(lib().hxt_stage_d2h(plan.handle, lane, _ptr(packed_dev), _ptr(host_pinned), _stream(stream)),
+           "hxt_stage_d2h")
+
+
+def hxt_stage_h2d(plan: Plan, lane: int, host_pinned, packed_dev, stream=None) -> None:
+    _check(lib().hxt_stage_h2d(plan.handle, lane, _ptr(host_pinned), _ptr(packed_dev), _stream(stream)),
+           "hxt_stage_h2d")
+
+
+def hxt_version() -> str:
+    return lib().hxt_version().decode()

@@ -1,0 +1,130 @@
+// Test helper (CPU): executes a plan's work tables one byte at a time, with every
+// access bounds-checked and every packed byte's write counted.  It exists to check the
+// host planner (tile offsets, clipping at chunk borders, launch groups) before anything
+// runs on a GPU; it is compiled together with the planner source only, never with the
+// kernels, and is not part of the product.
+#include <cstdint>
+#include <cstring>
+#include <vector>
+
+#include "hxt_internal.h"
+
+using namespace hxt;
+
+namespace {
+struct Ctx {
+    const Plan &p;
+    uint8_t *const *base;
+    const uint64_t *storage_bytes;
+    uint8_t *packed;
+    uint64_t packed_bytes;
+    uint8_t *written;   // per packed byte: times written
+    int error = 0;
+    bool user_ok(uint32_t t, uint64_t off, uint64_t n) { return off + n <= storage_bytes[t]; }
+    bool packed_ok(uint64_t off, uint64_t n) { return off + n <= packed_bytes; }
+};
+
+uint64_t logical_to_storage(const TensorDev &td, uint64_t byte)
+{
+    uint64_t e = byte / td.esize, b = byte % td.esize, off = 0;
+    for (int d = td.ndim - 1; d >= 0; --d) {
+        off += (e % uint64_t(td.shape[d])) * uint64_t(td.stride_b[d]);
+        e /= uint64_t(td.shape[d]);
+    }
+    return off + b;
+}
+}  // namespace
+
+// direction 0: pack (user -> packed), 1: unpack (packed -> user).  Returns 0, or a
+// negative code: -1 plan error, -2 user access out of bounds, -3 packed access out of
+// bounds, -4 tile crosses its chunk, -5 bad group bookkeeping.
+extern "C" int plan_interp(const hxt_tensor_desc_t *descs, int n_tensors, int n_lanes, uint64_t chunk_bytes,
+                           uint32_t tile_bytes, uint8_t *const *base, const uint64_t *storage_bytes,
+                           uint8_t *packed, uint64_t packed_bytes, uint8_t *written, int direction,
+                           int32_t *kinds_out)
+{
+    Plan p;
+    if (build_plan(descs, n_tensors, n_lanes, chunk_bytes, tile_bytes, p) != HXT_OK) return -1;
+    if (p.C * p.B != packed_bytes) return -1;
+    for (int t = 0; t < n_tensors; ++t) kinds_out[t] = p.tensors[t].kind;
+    Ctx c{p, base, storage_bytes, packed, packed_bytes, written};
+    uint64_t next = 0;
+    for (const Group &g : p.groups) {
+        if (g.first != next || g.n_tensors > uint32_t(kMaxGroupTensors)) return -5;
+        next = g.first + g.count;
+        for (uint32_t i = 0; i < g.count; ++i) {
+            const Tile &t = p.tiles[g.first + i];
+            const uint32_t ta = g.tensor_base + t.tensor;
+            if (t.tensor >= g.n_tensors || ta >= uint32_t(n_tensors)) return -5;
+            const TensorDev &td = p.tdev[ta];
+            const uint64_t c_lo = p.chunk_packed_off(t.chunk), c_hi = c_lo + p.chunk_padded(t.chunk);
+            auto put = [&](uint64_t poff, uint64_t uoff, bool zero) -> int {
+                if (!c.packed_ok(poff, 1)) return -3;
+                if (poff < c_lo || poff >= c_hi) return -4;
+                if (!zero && !c.user_ok(ta, uoff, 1)) return -2;
+                if (direction == 0) {
+                    packed[poff] = zero ? 0 : base[ta][uoff];
+                    if (written[poff] < 255) ++written[poff];
+                } else if (!zero) {
+                    base[ta][uoff] = packed[poff];
+                    if (written[poff] < 255) ++written[poff];
+                } else if (written[poff] < 255) {
+                    ++written[poff];
+                }
+                return 0;
+            };
+            int rc = 0;
+            switch (t.kind) {
+            case K_CONTIG:
+                if (g.kernel != K_CONTIG) return -5;
+                for (uint64_t b = 0; b < t.n0 && !rc; ++b) rc = put(t.packed_off + b, t.src_off + b, false);
+                break;
+            case K_ZERO:
+                if (g.kernel != K_CONTIG) return -5;
+                for (uint64_t b = 0; b < t.n0 && !rc; ++b) rc = put(t.packed_off + b, 0, true);
+                break;
+            case K_ROWS:
+            case K_GENERIC:
+                if (g.kernel != t.kind) return -5;
+                if (t.kind == K_ROWS && (t.n0 % 16 || td.row_bytes % 16)) return -5;
+                for (uint64_t b = 0; b < t.n0 && !rc; ++b)
+                    rc = put(t.packed_off + b, logical_to_storage(td, t.src_off + b), false);
+                break;
+            case K_TRANSPOSE:
+                if (g.kernel != K_TRANSPOSE || t.n0 > kTransposeTile || t.n1 > kTransposeTile) return -5;
+                for (uint64_t i2 = 0; i2 < t.n0 && !rc; ++i2)
+                    for (uint64_t j = 0; j < t.n1 && !rc; ++j)
+                        for (uint64_t b = 0; b < uint64_t(td.esize) && !rc; ++b)
+                            rc = put(t.packed_off + i2 * t.b + j * td.esize + b,
+                                     t.src_off + j * t.a + i2 * td.esize + b, false);
+                break;
+            default: return -5;
+            }
+            if (rc) return rc;
+        }
+    }
+    if (next != p.csum_first) return -5;
+    // the stand-alone checksum tiles must cover every chunk's padded bytes exactly once
+    std::vector<uint8_t> seen(packed_bytes, 0);
+    for (uint32_t i = 0; i < p.csum_count; ++i) {
+        const Tile &t = p.tiles[p.csum_first + i];
+        const uint64_t c_lo = p.chunk_packed_off(t.chunk), c_hi = c_lo + p.chunk_padded(t.chunk);
+        if (t.kind != K_CSUM || t.packed_off < c_lo || t.packed_off + t.n0 > c_hi || t.n0 % 16) return -5;
+        for (uint64_t b = 0; b < t.n0; ++b) ++seen[t.packed_off + b];
+    }
+    for (uint64_t ch = 0; ch < p.C; ++ch)
+        for (uint64_t b = 0; b < p.chunk_padded(ch); ++b)
+            if (seen[p.chunk_packed_off(ch) + b] != 1) return -5;
+    return 0;
+}
+
+// Exhaustive check of the multiply-shift division used by the row-gather kernel.
+extern "C" int fastdiv_check(uint32_t d, const uint32_t *ns, int count)
+{
+    FastDiv f = make_fastdiv(d);
+    for (int i = 0; i < count; ++i) {
+        uint32_t q = uint32_t((uint64_t(ns[i]) * f.mul) >> (31 + f.shift));
+        if (q != ns[i] / d) return -1;
+    }
+    return 0;
+}

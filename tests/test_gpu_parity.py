@@ -1,0 +1,388 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle,
+byte for byte, on the same seeded inputs.  Integer/byte work: the bar is bit-exact."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import hxt_oracle as ho
+from paper_2602_18007_amd import hxt
+from paper_2602_18007_amd import workloads as wl
+from tests.cases import SMALL_CASES, Case, case_by_name, contig, make_storages
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+NT = max(1, min(16, os.cpu_count() or 1))
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def oracle_msg(case):
+    return ho.Message([ho.TensorSpec(tuple(s), tuple(st), e) for (s, st, e) in case.tensors])
+
+
+def plan_of(case, tile_bytes=None):
+    old = os.environ.get("HXT_TILE_BYTES")
+    if tile_bytes:
+        os.environ["HXT_TILE_BYTES"] = str(tile_bytes)
+    try:
+        return hxt.hxt_plan_multi([(s, st, e) for (s, st, e) in case.tensors], case.k, case.B)
+    finally:
+        if tile_bytes:
+            if old is None:
+                del os.environ["HXT_TILE_BYTES"]
+            else:
+                os.environ["HXT_TILE_BYTES"] = old
+
+
+def to_dev(a: np.ndarray, offset: int = 0) -> torch.Tensor:
+    """Device copy of a byte array inside a 256-byte aligned allocation, shifted by ``offset`` bytes."""
+    buf = torch.empty(a.size + offset + 16, dtype=torch.uint8, device=DEV)
+    view = buf[offset:offset + a.size]
+    view.copy_(torch.from_numpy(a))
+    return view
+
+
+def specified_mask(m, B, k, nbytes):
+    spec = np.zeros(nbytes, bool)
+    for c in range(ho.num_chunks(m, B)):
+        i = ho.chunk_info(m, B, k, c)
+        spec[i["packed_off"]:i["packed_off"] + i["padded"]] = True
+    return spec
+
+
+def round_trip_check(case, raws, tile_bytes=None, base_offset=0, nthreads=1):
+    """pack / checksum / unpack on the GPU vs the oracle; returns the device packed buffer."""
+    m = oracle_msg(case)
+    p = plan_of(case, tile_bytes)
+    B, k = case.B, case.k
+    want = ho.pack(m, raws, B, k, fill=0xA5, nthreads=nthreads)
+    want_sums = ho.checksum(m, want, B, k, nthreads=nthreads)
+    assert p.packed_bytes == want.size and p.num_chunks == want_sums.size
+
+    src = [to_dev(r, base_offset) for r in raws]
+    packed = torch.full((max(want.size, 1),), 0xA5, dtype=torch.uint8, device=DEV)
+    sums = torch.full((max(want_sums.size, 1),), -1, dtype=torch.int64, device=DEV)   # garbage on purpose
+    hxt.hxt_pack(p, src, packed, sums)
+    got = packed.cpu().numpy()[:want.size]
+    assert np.array_equal(got, want), "packed bytes differ (unspecified bytes must keep their old value)"
+    got_sums = sums.cpu().numpy().view(np.uint64)[:want_sums.size]
+    assert np.array_equal(got_sums, want_sums), "send-side checksums differ"
+
+    # pack without checksums gives the same bytes; stand-alone checksum agrees with the fused one
+    packed2 = torch.full_like(packed, 0xA5)
+    hxt.hxt_pack(p, src, packed2, None)
+    assert torch.equal(packed, packed2)
+    sums2 = torch.full_like(sums, 7)
+    hxt.hxt_checksum(p, packed, sums2)
+    assert np.array_equal(sums2.cpu().numpy().view(np.uint64)[:want_sums.size], want_sums)
+
+    if all(p.tensor_unpack_safe(t) for t in range(len(case.tensors))):
+        dst_o = [np.full(r.size, 0x3C, np.uint8) for r in raws]
+        ho.unpack(m, want, B, k, dst_o, nthreads=nthreads)
+        dst = [to_dev(np.full(r.size, 0x3C, np.uint8), base_offset) for r in raws]
+        rsums = torch.full_like(sums, 5)
+        hxt.hxt_unpack(p, packed, dst, rsums)
+        for t, (a, b) in enumerate(zip(dst_o, dst)):
+            assert np.array_equal(b.cpu().numpy(), a), "tensor %d differs after unpack (or canary overwritten)" % t
+        assert np.array_equal(rsums.cpu().numpy().view(np.uint64)[:want_sums.size], want_sums)
+        dst2 = [to_dev(np.full(r.size, 0x3C, np.uint8), base_offset) for r in raws]
+        hxt.hxt_unpack(p, packed, dst2, None)
+        for a, b in zip(dst, dst2):
+            assert torch.equal(a, b)
+    else:
+        with pytest.raises(hxt.HxtError) as e:
+            hxt.hxt_unpack(p, packed, src, None)
+        assert e.value.status == hxt.HXT_EOVERLAP
+    torch.cuda.synchronize()
+    return p, packed, want, want_sums
+
+
+# ---------------------------------------------------------------------------
+# small shapes: every kernel family, ragged tails, empty lanes, gaps
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("tile_bytes", [256, 16384])
+@pytest.mark.parametrize("case", SMALL_CASES, ids=lambda c: c.name)
+def test_small_cases(case, tile_bytes):
+    say("case", case.name, "tile", tile_bytes)
+    round_trip_check(case, make_storages(case, 1234), tile_bytes)
+
+
+@pytest.mark.parametrize("name", ["u8_1000_not_256_multiple", "three_tensors_with_gaps", "rows_interleaved_3d",
+                                  "true_transpose_64x48", "mixed_dtypes_multi", "esize8_strided"])
+def test_base_pointers_that_are_only_element_aligned(name):
+    case = case_by_name(name)
+    off = max(e for (_, _, e) in case.tensors)            # element aligned, not 16-byte aligned
+    say("case", name, "base offset", off)
+    round_trip_check(case, make_storages(case, 99), None, base_offset=off)
+
+
+MID_CASES = [
+    Case("contig_1MB_ragged", (contig((1_000_001,), 1),), 3, 65536),
+    Case("contig_bf16_5MiB_tail", (contig((5 * 1024 * 1024 // 2 + 24,), 2),), 4, 1 << 20),
+    Case("rows_mid", (((300, 2, 112), (112, 300 * 112, 1), 2),), 3, 4096),
+    Case("rows_big_rows", (((96, 2, 3584), (3584, 96 * 3584, 1), 2),), 8, 65536),
+    Case("rows_padded_pitch", (((1000, 256), (320, 1), 4),), 5, 32768),
+    Case("rows_4d", (((5, 7, 3, 64), (64, 5 * 3 * 64, 5 * 64, 1), 2),), 2, 2048),
+    Case("transpose_mid", (((200, 150), (1, 200), 2),), 2, 4096),
+    Case("transpose_512", (((512, 384), (1, 512), 2),), 4, 65536),
+    Case("transpose_batch_f32", (((3, 70, 90), (70 * 100, 1, 70), 4),), 4, 1024),
+    Case("transpose_u8", (((130, 67), (1, 130), 1),), 2, 512),
+    Case("transpose_f64", (((100, 60), (1, 128), 8),), 3, 2048),
+    Case("generic_mid", (((50, 30, 20), (20, 1000, 1), 2),), 3, 4096),
+    Case("multi_mid", (contig((70001,), 1), ((64, 2, 128), (128, 64 * 128, 1), 2), ((96, 80), (1, 96), 4),
+                       contig((3, 1000), 8), ((33, 10), (20, 2), 2)), 4, 8192),
+]
+
+
+@pytest.mark.parametrize("case", MID_CASES, ids=lambda c: c.name)
+def test_mid_size_cases(case):
+    say("case", case.name)
+    round_trip_check(case, make_storages(case, 4321))
+
+
+def test_many_tensors_need_several_launch_groups():
+    rng = np.random.default_rng(8)
+    tensors = tuple(contig((int(rng.integers(1, 3000)),), int(rng.choice([1, 2, 4]))) for _ in range(150))
+    case = Case("many", tensors, 4, 4096)
+    say("case many tensors", len(tensors))
+    round_trip_check(case, make_storages(case, 55))
+
+
+# ---------------------------------------------------------------------------
+# staging (CPU-forwarding path) and fault detection
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name", ["ragged_last_chunk_2p5", "fewer_chunks_than_lanes", "three_tensors_with_gaps"])
+def test_staging_lane_by_lane_and_all_lanes(name):
+    case = case_by_name(name)
+    say("staging", name)
+    raws = make_storages(case, 17)
+    m = oracle_msg(case)
+    p, packed, want, _ = round_trip_check(case, raws)
+    n = want.size
+    for lanes in ([-1], list(range(case.k))):
+        host = torch.full((n,), 0x11, dtype=torch.uint8).pin_memory()
+        expect_host = np.full(n, 0x11, np.uint8)
+        for l in lanes:
+            hxt.hxt_stage_d2h(p, l, packed, host)
+        for l in (range(case.k) if lanes == [-1] else lanes):
+            ho.stage_lane(m, case.B, case.k, l, want, expect_host)
+        torch.cuda.synchronize()
+        assert np.array_equal(host.numpy(), expect_host), "D2H must move the used bytes of the lane(s) and nothing else"
+        recv = torch.full((n,), 0x22, dtype=torch.uint8, device=DEV)
+        expect_recv = np.full(n, 0x22, np.uint8)
+        for l in lanes:
+            hxt.hxt_stage_h2d(p, l, host, recv)
+        for l in (range(case.k) if lanes == [-1] else lanes):
+            ho.stage_lane(m, case.B, case.k, l, expect_host, expect_recv)
+        torch.cuda.synchronize()
+        assert np.array_equal(recv.cpu().numpy(), expect_recv)
+        # the receive side sees the same message
+        dst = [torch.zeros(r.size, dtype=torch.uint8, device=DEV) for r in raws]
+        rs = torch.zeros(p.num_chunks, dtype=torch.int64, device=DEV)
+        hxt.hxt_unpack(p, recv, dst, rs)
+        dst_o = [np.zeros(r.size, np.uint8) for r in raws]
+        ho.unpack(m, want, case.B, case.k, dst_o)
+        for a, b in zip(dst_o, dst):
+            assert np.array_equal(b.cpu().numpy(), a)
+
+
+def test_bit_flip_in_host_buffer_shows_in_exactly_one_checksum():
+    case = Case("flip", (contig((40000,), 2),), 3, 8192)
+    raws = make_storages(case, 23)
+    p, packed, want, want_sums = round_trip_check(case, raws)
+    host = torch.zeros(want.size, dtype=torch.uint8).pin_memory()
+    hxt.hxt_stage_d2h(p, -1, packed, host)
+    torch.cuda.synchronize()
+    info = p.chunk_info(4)
+    byte, bit = info["packed_off"] + 4 * 100 + 1, 3
+    was_set = bool(int(host[byte]) >> bit & 1)
+    host[byte] = int(host[byte]) ^ (1 << bit)                # the fault, planted on the host
+    recv = torch.zeros(want.size, dtype=torch.uint8, device=DEV)
+    hxt.hxt_stage_h2d(p, -1, host, recv)
+    dst = [torch.zeros(r.size, dtype=torch.uint8, device=DEV) for r in raws]
+    rs = torch.zeros(p.num_chunks, dtype=torch.int64, device=DEV)
+    hxt.hxt_unpack(p, recv, dst, rs)
+    got = rs.cpu().numpy().view(np.uint64)
+    delta = 1 << (8 + bit)
+    diff = [int(a) - int(b) for a, b in zip(got, want_sums)]
+    assert diff == [0, 0, 0, 0, (-delta if was_set else delta)] + [0] * (len(diff) - 5)
+
+
+def test_data_plane_argument_errors():
+    case = case_by_name("single_lane")
+    p = plan_of(case)
+    raws = make_storages(case, 1)
+    src = [to_dev(r) for r in raws]
+    packed = torch.zeros(p.packed_bytes + 256, dtype=torch.uint8, device=DEV)
+    L = hxt.lib()
+    with pytest.raises(hxt.HxtError) as e:
+        hxt.hxt_pack(p, src, packed[8:], None)
+    assert e.value.status == hxt.HXT_EALIGN
+    with pytest.raises(hxt.HxtError) as e:
+        hxt.hxt_pack(p, [src[0].data_ptr() + 1], packed, None)          # bf16 base on an odd byte
+    assert e.value.status == hxt.HXT_EALIGN
+    with pytest.raises(hxt.HxtError) as e:
+        hxt.hxt_pack(p, [None], packed, None)
+    assert e.value.status == hxt.HXT_EINVAL
+    with pytest.raises(hxt.HxtError) as e:
+        hxt.hxt_stage_d2h(p, 1, packed, packed)                          # lane out of range (k = 1)
+    assert e.value.status == hxt.HXT_EINVAL
+    assert L.hxt_checksum(p.handle, packed.data_ptr(), None, None) == hxt.HXT_EINVAL
+    torch.cuda.synchronize()
+
+
+# ---------------------------------------------------------------------------
+# the five benchmark messages at full size
+# ---------------------------------------------------------------------------
+
+def case_of(w):
+    return Case(w.name, tuple((t.shape, t.strides, t.esize) for t in w.tensors), w.n_lanes, w.chunk_bytes)
+
+
+def test_config_tiny():
+    w = wl.tiny()
+    round_trip_check(case_of(w), wl.make_storages(w))
+
+
+def test_config_llama8b_boundary_forward_and_backward():
+    w = wl.llama8b_boundary()
+    for msg in range(w.messages):                 # forward activation, backward gradient
+        say("llama message", msg)
+        round_trip_check(case_of(w), wl.make_storages(w, msg), nthreads=NT)
+
+
+def test_config_qwen2_both_paths_same_bytes():
+    w = wl.qwen2_7b_boundary()
+    case = case_of(w)
+    raws = wl.make_storages(w)
+    p, packed, want, want_sums = round_trip_check(case, raws, nthreads=NT)
+    # CPU-forwarding: D2H per lane on one stream, H2D per lane on another, chained by events
+    host = torch.zeros(want.size, dtype=torch.uint8).pin_memory()
+    recv = torch.zeros(want.size, dtype=torch.uint8, device=DEV)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    s1.wait_stream(torch.cuda.current_stream())
+    for l in range(w.n_lanes):
+        hxt.hxt_stage_d2h(p, l, packed, host, s1)
+        ev = torch.cuda.Event()
+        ev.record(s1)
+        s2.wait_event(ev)
+        hxt.hxt_stage_h2d(p, l, host, recv, s2)
+    torch.cuda.current_stream().wait_stream(s2)
+    dst = [torch.zeros(r.size, dtype=torch.uint8, device=DEV) for r in raws]
+    rs = torch.zeros(p.num_chunks, dtype=torch.int64, device=DEV)
+    hxt.hxt_unpack(p, recv, dst, rs)
+    torch.cuda.synchronize()
+    assert np.array_equal(host.numpy(), want)                       # identical packed bytes on the host
+    assert torch.equal(recv, packed[:want.size])                    # and on the receive side
+    assert np.array_equal(rs.cpu().numpy().view(np.uint64), want_sums)
+    assert np.array_equal(dst[0].cpu().numpy(), raws[0])
+
+
+@pytest.mark.parametrize("path", ["device_direct", "cpu_forward"])
+def test_config_stream_1f1b_three_streams_ping_pong(path):
+    w = wl.stream_1f1b(8 if path == "cpu_forward" else 32)
+    case = case_of(w)
+    m = oracle_msg(case)
+    p = plan_of(case)
+    assert p.tensor_kind(0) == "contig"
+    nmsg, C, nb = w.messages, p.num_chunks, p.packed_bytes
+    say("stream", path, "messages", nmsg)
+    raws = [wl.make_storages(w, i)[0] for i in range(nmsg)]
+    src = [to_dev(r) for r in raws]
+    dst = [torch.zeros(r.size, dtype=torch.uint8, device=DEV) for r in raws]
+    send_sums = torch.zeros((nmsg, C), dtype=torch.int64, device=DEV)
+    recv_sums = torch.zeros((nmsg, C), dtype=torch.int64, device=DEV)
+    # two buffer sets, poisoned so that a premature read would be seen
+    send_buf = [torch.full((nb,), 0xEE, dtype=torch.uint8, device=DEV) for _ in range(2)]
+    recv_buf = [torch.full((nb,), 0xDD, dtype=torch.uint8, device=DEV) for _ in range(2)] if path == "cpu_forward" else send_buf
+    host_buf = [torch.zeros(nb, dtype=torch.uint8).pin_memory() for _ in range(2)]
+    sp, ss, su = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    for s in (sp, ss, su):
+        s.wait_stream(torch.cuda.current_stream())
+    packed_ev = [None, None]      # buffer i%2 holds message i (pack done)
+    staged_ev = [None, None]      # receive buffer i%2 holds message i (H2D done)
+    freed_ev = [None, None]       # buffer i%2 may be overwritten (unpack of its previous message done)
+    sent_ev = [None, None]        # send buffer drained to the host
+    for i in range(nmsg):
+        b = i % 2
+        if freed_ev[b] is not None:
+            sp.wait_event(freed_ev[b] if path == "device_direct" else sent_ev[b])
+        hxt.hxt_pack(p, [src[i]], send_buf[b], send_sums[i], sp)
+        packed_ev[b] = torch.cuda.Event(); packed_ev[b].record(sp)
+        if path == "cpu_forward":
+            ss.wait_event(packed_ev[b])
+            if freed_ev[b] is not None:
+                ss.wait_event(freed_ev[b])
+            hxt.hxt_stage_d2h(p, -1, send_buf[b], host_buf[b], ss)
+            sent_ev[b] = torch.cuda.Event(); sent_ev[b].record(ss)
+            hxt.hxt_stage_h2d(p, -1, host_buf[b], recv_buf[b], ss)
+            staged_ev[b] = torch.cuda.Event(); staged_ev[b].record(ss)
+            su.wait_event(staged_ev[b])
+        else:
+            su.wait_event(packed_ev[b])
+        hxt.hxt_unpack(p, recv_buf[b], [dst[i]], recv_sums[i], su)
+        freed_ev[b] = torch.cuda.Event(); freed_ev[b].record(su)
+    torch.cuda.synchronize()
+    ss_h = send_sums.cpu().numpy().view(np.uint64)
+    rs_h = recv_sums.cpu().numpy().view(np.uint64)
+    assert np.array_equal(ss_h, rs_h)
+    for i in range(nmsg):
+        assert np.array_equal(dst[i].cpu().numpy(), raws[i]), "micro-batch %d" % i
+        if i % 8 == 0:                     # oracle checksums on a sample of the micro-batches
+            want = ho.pack(m, [raws[i]], w.chunk_bytes, w.n_lanes, nthreads=NT)
+            assert np.array_equal(ss_h[i], ho.checksum(m, want, w.chunk_bytes, w.n_lanes, nthreads=NT))
+
+
+def test_config_grad_buckets_full_size_both_paths():
+    w = wl.grad_buckets()
+    case = case_of(w)
+    m = oracle_msg(case)
+    p = plan_of(case)
+    say("grad buckets: drawing", w.message_bytes, "bytes")
+    raws = wl.make_storages(w)
+    src = [torch.from_numpy(r).to(DEV) for r in raws]
+    nb, C = p.packed_bytes, p.num_chunks
+    packed = torch.full((nb,), 0xA5, dtype=torch.uint8, device=DEV)
+    sums = torch.zeros(C, dtype=torch.int64, device=DEV)
+    hxt.hxt_pack(p, src, packed, sums)
+    say("grad buckets: oracle pack")
+    want = ho.pack(m, raws, w.chunk_bytes, w.n_lanes, fill=0xA5, nthreads=NT)
+    want_sums = ho.checksum(m, want, w.chunk_bytes, w.n_lanes, nthreads=NT)
+    got = packed.cpu().numpy()
+    assert np.array_equal(got, want)
+    assert np.array_equal(sums.cpu().numpy().view(np.uint64), want_sums)
+    del got
+    say("grad buckets: cpu-forward leg")
+    host = torch.zeros(nb, dtype=torch.uint8).pin_memory()
+    recv = torch.full((nb,), 0x5A, dtype=torch.uint8, device=DEV)
+    for l in range(w.n_lanes):
+        hxt.hxt_stage_d2h(p, l, packed, host)
+        hxt.hxt_stage_h2d(p, l, host, recv)
+    for path_buf in (packed, recv):
+        dst = [torch.zeros_like(s) for s in src]
+        rs = torch.zeros(C, dtype=torch.int64, device=DEV)
+        hxt.hxt_unpack(p, path_buf, dst, rs)
+        torch.cuda.synchronize()
+        assert np.array_equal(rs.cpu().numpy().view(np.uint64), want_sums)
+        for t, (a, b) in enumerate(zip(src, dst)):
+            assert torch.equal(a, b), "tensor %d" % t
+    # unspecified tail of the last slot: untouched by pack and by staging
+    last = p.chunk_info(C - 1)
+    tail0 = last["packed_off"] + last["padded"]
+    tail1 = last["packed_off"] + w.chunk_bytes
+    assert bool((packed[tail0:tail1] == 0xA5).all()) and bool((recv[tail0:tail1] == 0x5A).all())
+    assert bool((host[tail0:tail1] == 0).all())
+
+
+@pytest.mark.parametrize("name", ["qwen_rows_view", "transpose_view"])
+def test_supplementary_strided_messages_full_size(name):
+    w = wl.ALL[name]()
+    say("supplementary", name)
+    round_trip_check(case_of(w), wl.make_storages(w), nthreads=NT)

@@ -1,0 +1,249 @@
+"""Host logic of the library, on the CPU: the C ABI loads and exports what the header
+declares, plan queries agree with the oracle, argument errors come back as codes, and the
+planner's work tables (executed byte by byte by a bounds-checking interpreter) reproduce
+the oracle's packed buffer without touching a byte twice or out of range."""
+import ctypes as C
+import os
+import re
+import subprocess
+
+import numpy as np
+import pytest
+
+from oracle import hxt_oracle as ho
+from paper_2602_18007_amd import build as hxt_build
+from paper_2602_18007_amd import hxt
+from paper_2602_18007_amd import workloads as wl
+from tests.cases import SMALL_CASES, Case, contig, make_storages, storage_bytes
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="session", autouse=True)
+def built_library():
+    hxt_build.build(force=False)
+
+
+def oracle_msg(case):
+    return ho.Message([ho.TensorSpec(tuple(s), tuple(st), e) for (s, st, e) in case.tensors])
+
+
+def plan_of(case):
+    return hxt.hxt_plan_multi([(s, st, e) for (s, st, e) in case.tensors], case.k, case.B)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "hxt.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(hxt_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(hxt.EXPORTS)
+    raw = C.CDLL(hxt.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(raw, name), name
+    assert hxt.hxt_version().startswith("hxt")
+
+
+@pytest.mark.parametrize("case", SMALL_CASES, ids=lambda c: c.name)
+def test_plan_queries_match_oracle(case):
+    m, p = oracle_msg(case), plan_of(case)
+    assert (p.message_bytes, p.stream_bytes) == (m.N, m.L)
+    assert p.num_chunks == ho.num_chunks(m, case.B)
+    assert p.packed_bytes == ho.packed_bytes(m, case.B, case.k)
+    assert (p.num_lanes, p.chunk_bytes, p.num_tensors) == (case.k, case.B, len(case.tensors))
+    for c in range(p.num_chunks):
+        assert p.chunk_info(c) == ho.chunk_info(m, case.B, case.k, c)
+    for l in range(case.k):
+        assert p.lane_info(l) == ho.lane_info(m, case.B, case.k, l)
+
+
+@pytest.mark.parametrize("name", list(wl.ALL))
+def test_plan_queries_match_oracle_on_benchmark_messages(name):
+    w = wl.ALL[name]()
+    case = Case(name, tuple((t.shape, t.strides, t.esize) for t in w.tensors), w.n_lanes, w.chunk_bytes)
+    test_plan_queries_match_oracle(case)
+
+
+def test_receive_side_plan_is_interchangeable():
+    # same five arguments on both sides -> same table (the receive is symmetric, Section 2.2)
+    case = SMALL_CASES[5]
+    a, b = plan_of(case), plan_of(case)
+    assert [a.chunk_info(c) for c in range(a.num_chunks)] == [b.chunk_info(c) for c in range(b.num_chunks)]
+
+
+def test_transposed_view_with_unit_dim_is_planned_as_contiguous():
+    w = wl.stream_1f1b()
+    t = w.tensors[0]
+    view = hxt.hxt_plan(t.shape, t.strides, 2, w.n_lanes, w.chunk_bytes)
+    flat = hxt.hxt_plan((1, 4096, 4096), None, 2, w.n_lanes, w.chunk_bytes)
+    assert view.tensor_kind(0) == flat.tensor_kind(0) == "contig"
+    assert [view.chunk_info(c) for c in range(16)] == [flat.chunk_info(c) for c in range(16)]
+
+
+def test_kernel_family_per_view():
+    kinds = {c.name: [plan_of(c).tensor_kind(t) for t in range(len(c.tensors))] for c in SMALL_CASES}
+    assert kinds["rows_interleaved_3d"] == ["rows"]
+    assert kinds["true_transpose_64x48"] == ["transpose"]
+    assert kinds["transpose_batched"] == ["transpose"]
+    assert kinds["rows_not_16B_multiple"] == ["generic"]
+    assert kinds["inner_stride_2"] == ["generic"]
+    assert kinds["size_one_dims"] == ["contig"]
+    assert kinds["scalar_0d"] == ["contig"]
+    assert kinds["empty_tensor"] == ["none"]
+    assert kinds["mixed_dtypes_multi"] == ["contig", "rows", "transpose", "contig"]
+    assert plan_of(Case("q", (((4096, 2, 3584), (3584, 4096 * 3584, 1), 2),), 8, 4 << 20)).tensor_kind(0) == "rows"
+
+
+def test_unpack_safety_flag():
+    assert not plan_of(Case("b", (((5, 64), (0, 1), 4),), 2, 256)).tensor_unpack_safe(0)      # broadcast
+    assert not plan_of(Case("o", (((4, 8), (4, 1), 2),), 2, 256)).tensor_unpack_safe(0)       # rows overlap
+    assert plan_of(Case("t", (((64, 48), (1, 64), 2),), 2, 256)).tensor_unpack_safe(0)
+    assert plan_of(Case("p", (((3, 4, 5, 6), (200, 6, 40, 1), 2),), 2, 256)).tensor_unpack_safe(0)
+    assert plan_of(Case("e", (((0, 4), (0, 0), 2),), 2, 256)).tensor_unpack_safe(0)           # empty
+
+
+@pytest.mark.parametrize("kwargs,status", [
+    (dict(n_lanes=0), hxt.HXT_EINVAL), (dict(n_lanes=1025), hxt.HXT_EINVAL),
+    (dict(chunk_bytes=0), hxt.HXT_EINVAL), (dict(chunk_bytes=1000), hxt.HXT_EINVAL),
+    (dict(shape=(4, -1)), hxt.HXT_EINVAL), (dict(strides=(-2, 1)), hxt.HXT_EINVAL),
+    (dict(shape=(1,) * 9, strides=(1,) * 9), hxt.HXT_EINVAL),
+    (dict(shape=(1 << 30, 1 << 20), strides=None), hxt.HXT_EUNSUPPORTED),
+])
+def test_plan_rejects_bad_arguments(kwargs, status):
+    args = dict(shape=(4, 4), strides=(4, 1), dtype=2, n_lanes=2, chunk_bytes=256)
+    args.update(kwargs)
+    with pytest.raises(hxt.HxtError) as e:
+        hxt.hxt_plan(**args)
+    assert e.value.status == status
+
+
+def test_raw_abi_null_and_dtype_errors():
+    L = hxt.lib()
+    shp = (C.c_int64 * 2)(4, 4)
+    out = C.c_void_p()
+    assert L.hxt_plan(shp, None, 2, 3, 2, 256, None) == hxt.HXT_EINVAL              # out == NULL
+    assert L.hxt_plan(None, None, 2, 3, 2, 256, C.byref(out)) == hxt.HXT_EINVAL     # shape == NULL
+    assert L.hxt_plan(shp, None, 2, 99, 2, 256, C.byref(out)) == hxt.HXT_EINVAL     # dtype
+    assert L.hxt_plan(shp, None, -1, 3, 2, 256, C.byref(out)) == hxt.HXT_EINVAL
+    assert out.value is None
+    assert L.hxt_plan_destroy(None) == hxt.HXT_OK
+    assert L.hxt_pack(None, None, None, None, None) == hxt.HXT_EINVAL
+    assert L.hxt_stage_d2h(None, 0, None, None, None) == hxt.HXT_EINVAL
+    p = hxt.hxt_plan((4, 4), None, 2, 2, 256)
+    info = hxt.ChunkInfo()
+    assert L.hxt_plan_chunk_info(p.handle, 7, C.byref(info)) == hxt.HXT_EINVAL
+    assert L.hxt_plan_lane_info(p.handle, 2, None) == hxt.HXT_EINVAL
+    assert L.hxt_stage_d2h(p.handle, 5, 256, 256, None) == hxt.HXT_EINVAL           # bad lane
+    assert L.hxt_stage_d2h(p.handle, 0, 256 + 8, 256, None) == hxt.HXT_EALIGN
+    assert L.hxt_pack(p.handle, None, 256 + 16, None, None) == hxt.HXT_EALIGN       # packed misaligned
+    assert L.hxt_checksum(p.handle, None, None, None) == hxt.HXT_EINVAL
+    assert b"align" in L.hxt_strerror(hxt.HXT_EALIGN)
+
+
+def test_empty_message_calls_are_no_ops():
+    p = hxt.hxt_plan((0, 16), None, 2, 2, 256)
+    assert (p.message_bytes, p.num_chunks, p.packed_bytes) == (0, 0, 0)
+    L = hxt.lib()
+    assert L.hxt_pack(p.handle, None, None, None, None) == hxt.HXT_OK
+    assert L.hxt_unpack(p.handle, None, None, None, None) == hxt.HXT_OK
+    assert L.hxt_checksum(p.handle, None, None, None) == hxt.HXT_OK
+    assert L.hxt_stage_d2h(p.handle, -1, None, None, None) == hxt.HXT_OK
+
+
+# ---- the planner's work tables, executed on the CPU --------------------------------
+
+class _Desc(C.Structure):
+    _fields_ = [("ndim", C.c_int), ("shape", C.POINTER(C.c_int64)), ("strides", C.POINTER(C.c_int64)),
+                ("dtype", C.c_int)]
+
+
+@pytest.fixture(scope="session")
+def interp():
+    src = os.path.join(ROOT, "tests", "host", "plan_interp.cpp")
+    out = os.path.join(ROOT, "tests", "host", "libplan_interp.so")
+    csrc = os.path.join(ROOT, "paper_2602_18007_amd", "csrc")
+    deps = [src, os.path.join(csrc, "hxt_plan.cpp"), os.path.join(csrc, "hxt_internal.h")]
+    if not os.path.exists(out) or any(os.path.getmtime(d) > os.path.getmtime(out) for d in deps):
+        subprocess.run(["g++", "-std=c++17", "-O1", "-g", "-shared", "-fPIC", "-Wall", "-Wextra",
+                        "-I", os.path.join(ROOT, "include"), "-I", csrc, "-o", out, src,
+                        os.path.join(csrc, "hxt_plan.cpp")], check=True)
+    L = C.CDLL(out)
+    L.plan_interp.restype = C.c_int
+    L.fastdiv_check.restype = C.c_int
+    return L
+
+
+def run_interp(L, case, storages, packed, direction, tile_bytes):
+    n = len(case.tensors)
+    descs = (_Desc * max(n, 1))()
+    keep = []
+    size_code = {1: 1, 2: 3, 4: 4, 8: 5}
+    for j, (shape, strides, e) in enumerate(case.tensors):
+        shp = (C.c_int64 * max(len(shape), 1))(*shape)
+        st = (C.c_int64 * max(len(shape), 1))(*strides)
+        keep += [shp, st]
+        descs[j].ndim, descs[j].shape, descs[j].strides, descs[j].dtype = len(shape), shp, st, size_code[e]
+    bases = (C.c_void_p * max(n, 1))(*[s.ctypes.data for s in storages])
+    sizes = (C.c_uint64 * max(n, 1))(*[s.size for s in storages])
+    written = np.zeros(max(packed.size, 1), np.uint8)
+    kinds = (C.c_int32 * max(n, 1))()
+    rc = L.plan_interp(descs, n, case.k, C.c_uint64(case.B), C.c_uint32(tile_bytes), bases, sizes,
+                       C.c_void_p(packed.ctypes.data), C.c_uint64(packed.size), C.c_void_p(written.ctypes.data),
+                       direction, kinds)
+    return rc, written[:packed.size], list(kinds)[:n]
+
+
+@pytest.mark.parametrize("tile_bytes", [256, 1024, 16384])
+@pytest.mark.parametrize("case", SMALL_CASES, ids=lambda c: c.name)
+def test_work_tables_reproduce_oracle_pack_and_unpack(interp, case, tile_bytes):
+    m = oracle_msg(case)
+    raws = make_storages(case, 77)
+    want = ho.pack(m, raws, case.B, case.k, fill=0x99)
+    got = np.full(want.size, 0x99, np.uint8)
+    rc, written, _ = run_interp(interp, case, raws, got, 0, tile_bytes)
+    assert rc == 0
+    assert np.array_equal(got, want)
+    # every specified byte written exactly once, unspecified bytes never
+    spec = np.zeros(want.size, bool)
+    for c in range(ho.num_chunks(m, case.B)):
+        info = ho.chunk_info(m, case.B, case.k, c)
+        spec[info["packed_off"]:info["packed_off"] + info["padded"]] = True
+    assert np.all(written[spec] == 1) and np.all(written[~spec] == 0)
+    if case.name == "broadcast_stride0":
+        return
+    dst_o = [np.full(r.size, 0x42, np.uint8) for r in raws]
+    dst_t = [np.full(r.size, 0x42, np.uint8) for r in raws]
+    ho.unpack(m, want, case.B, case.k, dst_o)
+    rc, _, _ = run_interp(interp, case, dst_t, want.copy(), 1, tile_bytes)
+    assert rc == 0
+    for a, b in zip(dst_o, dst_t):
+        assert np.array_equal(a, b)
+
+
+def test_work_tables_for_mid_size_strided_messages(interp):
+    # chunk borders in the middle of rows, several transpose tiles per row, ragged edges
+    cases = [
+        Case("rows_mid", (((300, 2, 112), (112, 300 * 112, 1), 2),), 3, 4096),
+        Case("transpose_mid", (((200, 150), (1, 200), 2),), 2, 4096),
+        Case("transpose_batch_mid", (((3, 70, 90), (70 * 100, 1, 70), 4),), 4, 1024),
+        Case("transpose_u8", (((130, 67), (1, 130), 1),), 2, 512),
+    ]
+    for case in cases:
+        m = oracle_msg(case)
+        raws = make_storages(case, 5)
+        want = ho.pack(m, raws, case.B, case.k, fill=0x99)
+        got = np.full(want.size, 0x99, np.uint8)
+        rc, _, kinds = run_interp(interp, case, raws, got, 0, 2048)
+        assert rc == 0 and np.array_equal(got, want), case.name
+        assert kinds[0] == (2 if case.name == "rows_mid" else 3)
+
+
+def test_multiply_shift_division_is_exact(interp):
+    rng = np.random.default_rng(3)
+    edge = np.array([0, 1, 2, 3, (1 << 31) - 1, (1 << 31) - 2, 1 << 30, (1 << 30) - 1], np.uint32)
+    for d in [1, 2, 3, 5, 7, 16, 100, 7168, 3584, 4096, 4097, 65535, 65536, 65537, (1 << 30) - 1, 1 << 30,
+              (1 << 31) - 1] + [int(x) for x in rng.integers(1, 1 << 31, 40)]:
+        mult = (np.arange(0, 2000, dtype=np.uint64) * d)
+        near = np.concatenate([mult, mult + d - 1, mult + 1])
+        near = near[near < (1 << 31)].astype(np.uint32)
+        ns = np.ascontiguousarray(np.concatenate([edge, near, rng.integers(0, 1 << 31, 5000).astype(np.uint32)]))
+        assert interp.fastdiv_check(C.c_uint32(d), C.c_void_p(ns.ctypes.data), C.c_int(ns.size)) == 0, d
