@@ -20,7 +20,7 @@ def hipcc() -> str:
 
 def command() -> list:
     return [
-        hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+        hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-shared",
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
         "-Wall", "-Wextra", "-Wno-unused-parameter",
         "-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG, "csrc"),

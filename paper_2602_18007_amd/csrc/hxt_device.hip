@@ -19,58 +19,68 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "hxt_internal.h"
 
-using namespace hxt;
-
-namespace {
+namespace hxt {
 
 constexpr int kThreads = 256;
+constexpr int kUnroll = 4;
 
 struct BasePtrs {
     uint8_t *p[kMaxGroupTensors];
 };
 
+// Per-chunk accumulator of a checksum in flight.  One per chunk and per operation
+// (pack, unpack, stand-alone checksum), kAccStride bytes apart so that neighbouring
+// chunks' atomics land in different memory channels.  Always zero between kernels.
+struct Acc {
+    unsigned long long sum;
+    uint32_t cnt;
+    uint32_t pad;
+};
+
+struct SumCtx {
+    uint64_t *sums;      // caller's array, one entry per chunk
+    uint8_t *acc;        // plan-owned Acc slots
+    uint32_t stride;     // bytes between slots
+    uint32_t sum_bits;   // > 0: a chunk's total fits this many bits and the arrival count rides above it
+};
+
 // ---- small device helpers ----------------------------------------------------
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 template <bool NT>
-__device__ __forceinline__ uint4 load16(const uint4 *p)
+__device__ __forceinline__ u32x4 load16(const u32x4 *p)
 {
-    if constexpr (NT) {
-        return uint4{__builtin_nontemporal_load(&p->x), __builtin_nontemporal_load(&p->y),
-                     __builtin_nontemporal_load(&p->z), __builtin_nontemporal_load(&p->w)};
-    } else {
-        return *p;
-    }
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
 }
 
 template <bool NT>
-__device__ __forceinline__ void store16(uint4 *p, uint4 v)
+__device__ __forceinline__ void store16(u32x4 *p, u32x4 v)
 {
-    if constexpr (NT) {
-        __builtin_nontemporal_store(v.x, &p->x);
-        __builtin_nontemporal_store(v.y, &p->y);
-        __builtin_nontemporal_store(v.z, &p->z);
-        __builtin_nontemporal_store(v.w, &p->w);
-    } else {
-        *p = v;
-    }
+    if constexpr (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
 }
 
-__device__ __forceinline__ uint64_t words_sum(uint4 v)
+__device__ __forceinline__ uint64_t words_sum(u32x4 v)
 {
     return (uint64_t(v.x) + uint64_t(v.y)) + (uint64_t(v.z) + uint64_t(v.w));
 }
 
-__device__ __forceinline__ uint32_t fast_div(uint32_t n, FastDiv d)
-{
-    return uint32_t((uint64_t(n) * d.mul) >> (31 + d.shift));
-}
-
-// Sum over the workgroup, then one atomic into the chunk's total.
-__device__ __forceinline__ void block_add(uint64_t acc, uint64_t *dst)
+// Adds this workgroup's partial sum to its chunk.  The workgroup that arrives last owns the
+// total: it writes sums[chunk] and re-zeroes the slot.  Only relaxed device-scope atomics
+// touch the slot, so no cache write-back is needed.
+//   sum_bits > 0: the chunk's total is known to stay below 2^sum_bits (it has at most B/4
+//     words of 32 bits) and the number of contributors fits in the bits above, so one atomic
+//     adds the partial sum and takes the arrival ticket at once.
+//   sum_bits == 0 (huge chunks): the sum and the ticket are two words; the ticket is taken
+//     after the wave has seen its own addition return, which orders the two.
+__device__ __forceinline__ void chunk_commit(uint64_t acc, uint32_t chunk, uint32_t expected, const SumCtx &cx)
 {
     __shared__ uint64_t part[kThreads / 64];
     for (int o = 32; o > 0; o >>= 1) acc += __shfl_down(acc, o, 64);
@@ -78,85 +88,124 @@ __device__ __forceinline__ void block_add(uint64_t acc, uint64_t *dst)
     if (lane == 0) part[wave] = acc;
     __syncthreads();
     if (threadIdx.x == 0) {
-        uint64_t s = 0;
+        unsigned long long s = 0;
 #pragma unroll
         for (int w = 0; w < kThreads / 64; ++w) s += part[w];
-        atomicAdd(reinterpret_cast<unsigned long long *>(dst), static_cast<unsigned long long>(s));
+        Acc *a = reinterpret_cast<Acc *>(cx.acc + size_t(chunk) * cx.stride);
+        if (expected == 1) {                       // sole contributor: nothing to combine
+            cx.sums[chunk] = s;
+        } else if (cx.sum_bits) {
+            const unsigned long long one = 1ull << cx.sum_bits;
+            const unsigned long long before = __hip_atomic_fetch_add(&a->sum, one + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((before >> cx.sum_bits) == expected - 1) {
+                __hip_atomic_store(&a->sum, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                cx.sums[chunk] = (before + s) & (one - 1);
+            }
+        } else {
+            const unsigned long long before = __hip_atomic_fetch_add(&a->sum, s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            asm volatile("s_waitcnt vmcnt(0)" ::"v"(uint32_t(before)) : "memory");
+            const uint32_t ticket = __hip_atomic_fetch_add(&a->cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (ticket == expected - 1) {
+                const unsigned long long total = __hip_atomic_exchange(&a->sum, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(&a->cnt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                cx.sums[chunk] = total;
+            }
+        }
     }
 }
 
-// Pad bytes (fewer than 256): pack writes zeros, unpack only reads them for the sum.
-template <bool UNPACK, bool CSUM>
-__device__ __forceinline__ uint64_t zero_tile(const Tile &t, uint8_t *packed)
+// Copy `bytes` contiguous bytes between a user tensor and the packed buffer (pack: user ->
+// packed, unpack: packed -> user) in 16-byte vectors, UNROLL independent loads in flight per
+// thread before the first store; a last partial vector goes byte by byte.  NTU / NTP mark
+// the user-side / packed-side accesses non-temporal.
+template <bool UNPACK, bool CSUM, bool NTU, bool NTP>
+__device__ __forceinline__ uint64_t copy_span(uint8_t *user, uint8_t *pk, uint32_t bytes)
 {
+    constexpr bool NTL = UNPACK ? NTP : NTU, NTS = UNPACK ? NTU : NTP;
+    const u32x4 *s = reinterpret_cast<const u32x4 *>(UNPACK ? pk : user);
+    u32x4 *d = reinterpret_cast<u32x4 *>(UNPACK ? user : pk);
+    const uint32_t nvec = bytes >> 4;
+    constexpr uint32_t STEP = kThreads * kUnroll;
+    const uint32_t full = nvec / STEP * STEP;            // uniform: blocks that need no bounds checks
     uint64_t acc = 0;
-    uint8_t *pk = packed + t.packed_off;
-    for (uint32_t i = threadIdx.x; i < t.n0; i += kThreads) {
-        if constexpr (!UNPACK) pk[i] = 0;
-        if constexpr (UNPACK && CSUM) acc += uint64_t(pk[i]) << (8 * ((t.packed_off + i) & 3));
+    for (uint32_t v = threadIdx.x; v < full; v += STEP) {
+        u32x4 r[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) r[u] = load16<NTL>(s + v + u * kThreads);
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            store16<NTS>(d + v + u * kThreads, r[u]);
+            if constexpr (CSUM) acc += words_sum(r[u]);
+        }
+    }
+    for (uint32_t v = full + threadIdx.x; v < nvec; v += kThreads) {
+        const u32x4 r = load16<NTL>(s + v);
+        store16<NTS>(d + v, r);
+        if constexpr (CSUM) acc += words_sum(r);
+    }
+    const uint32_t tail = bytes & 15;                    // only at the very end of a tensor
+    if (threadIdx.x < tail) {
+        const uint32_t i = (nvec << 4) + threadIdx.x;
+        const uint8_t b = (UNPACK ? pk : user)[i];
+        (UNPACK ? user : pk)[i] = b;
+        if constexpr (CSUM) acc += uint64_t(b) << (8 * (i & 3));
     }
     return acc;
 }
 
-__global__ void k_fill_zero(uint64_t *p, uint32_t n)
+// Pad bytes (fewer than 256): pack writes zeros, unpack only reads them for the sum.
+// `phase` is the position of pk[0] within its 32-bit word.
+template <bool UNPACK, bool CSUM>
+__device__ __forceinline__ uint64_t pad_span(uint8_t *pk, uint32_t bytes, uint32_t phase)
 {
-    uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0;
+    uint64_t acc = 0;
+    for (uint32_t i = threadIdx.x; i < bytes; i += kThreads) {
+        if constexpr (!UNPACK) pk[i] = 0;
+        if constexpr (UNPACK && CSUM) acc += uint64_t(pk[i]) << (8 * ((phase + i) & 3));
+    }
+    return acc;
 }
 
-// ---- contiguous tensors: straight 128-bit copy --------------------------------
-// Each thread keeps UNROLL independent 16-byte loads in flight before its first store.
-template <bool UNPACK, bool CSUM, int UNROLL, bool NT>
-__global__ __launch_bounds__(kThreads) void k_contig(const Tile *__restrict__ tiles, BasePtrs bases,
-                                                     uint8_t *__restrict__ packed, uint64_t *__restrict__ sums)
+// ---- uniform copy: the message is one contiguous tensor ---------------------------
+// No table: tile -> (chunk, lane, slot, offsets) in closed form from the kernel arguments.
+template <bool UNPACK, bool CSUM, bool NTU, bool NTP>
+__global__ __launch_bounds__(kThreads) void k_uniform(ChunkGeom g, uint8_t *__restrict__ user,
+                                                      uint8_t *__restrict__ packed, SumCtx cx)
+{
+    const TileSpan t = locate_tile(g, blockIdx.x);
+    const uint64_t left = g.N > t.stream_off ? g.N - t.stream_off : 0;     // tensor bytes from here on
+    const uint32_t data = left < t.len ? uint32_t(left) : t.len;
+    uint8_t *pk = packed + t.packed_off;
+    uint64_t acc = copy_span<UNPACK, CSUM, NTU, NTP>(user + t.stream_off, pk, data);
+    if (data < t.len) acc += pad_span<UNPACK, CSUM>(pk + data, t.len - data, data);
+    if constexpr (CSUM) chunk_commit(acc, t.chunk, t.expected, cx);
+}
+
+// ---- contiguous tensors of a multi-tensor message: table driven ---------------------
+template <bool UNPACK, bool CSUM, bool NTU, bool NTP>
+__global__ __launch_bounds__(kThreads) void k_contig(const Tile *__restrict__ tiles,
+                                                     const uint32_t *__restrict__ chunk_tiles, BasePtrs bases,
+                                                     uint8_t *__restrict__ packed, SumCtx cx)
 {
     const Tile t = tiles[blockIdx.x];
-    uint64_t acc = 0;
-    if (t.kind == K_ZERO) {
-        acc = zero_tile<UNPACK, CSUM>(t, packed);
-    } else {
-        uint8_t *user = bases.p[t.tensor] + t.src_off;
-        uint8_t *pk = packed + t.packed_off;
-        const uint4 *s = reinterpret_cast<const uint4 *>(UNPACK ? pk : user);
-        uint4 *d = reinterpret_cast<uint4 *>(UNPACK ? user : pk);
-        const uint32_t nvec = t.n0 >> 4;
-        constexpr uint32_t STEP = kThreads * UNROLL;
-        const uint32_t full = nvec / STEP * STEP;            // uniform: blocks that need no bounds checks
-        for (uint32_t v = threadIdx.x; v < full; v += STEP) {
-            uint4 r[UNROLL];
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) r[u] = load16<NT>(s + v + u * kThreads);
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                store16<NT>(d + v + u * kThreads, r[u]);
-                if constexpr (CSUM) acc += words_sum(r[u]);
-            }
-        }
-        for (uint32_t v = full + threadIdx.x; v < nvec; v += kThreads) {
-            const uint4 r = load16<NT>(s + v);
-            store16<NT>(d + v, r);
-            if constexpr (CSUM) acc += words_sum(r);
-        }
-        const uint32_t tail = t.n0 & 15;                 // only the last tile of a tensor
-        if (threadIdx.x < tail) {
-            const uint32_t i = (nvec << 4) + threadIdx.x;
-            const uint8_t b = (UNPACK ? pk : user)[i];
-            (UNPACK ? user : pk)[i] = b;
-            if constexpr (CSUM) acc += uint64_t(b) << (8 * (i & 3));
-        }
-    }
-    if constexpr (CSUM) block_add(acc, sums + t.chunk);
+    uint64_t acc;
+    if (t.kind == K_ZERO)
+        acc = pad_span<UNPACK, CSUM>(packed + t.packed_off, t.n0, uint32_t(t.packed_off));
+    else
+        acc = copy_span<UNPACK, CSUM, NTU, NTP>(bases.p[t.tensor] + t.src_off, packed + t.packed_off, t.n0);
+    if constexpr (CSUM) chunk_commit(acc, t.chunk, chunk_tiles[t.chunk], cx);
 }
 
 // ---- rows: innermost dimension contiguous, outer dimensions strided -------------
 // A 16-byte vector never straddles a run (run length and strides are multiples of 16).
 // Logical byte -> (row, column) and row -> outer indices use multiply-shift division.
-template <bool UNPACK, bool CSUM, int UNROLL, bool NT>
+template <bool UNPACK, bool CSUM, bool NTU, bool NTP>
 __global__ __launch_bounds__(kThreads) void k_rows(const Tile *__restrict__ tiles,
+                                                   const uint32_t *__restrict__ chunk_tiles,
                                                    const TensorDev *__restrict__ tensors, uint32_t tensor_base,
-                                                   BasePtrs bases, uint8_t *__restrict__ packed,
-                                                   uint64_t *__restrict__ sums)
+                                                   BasePtrs bases, uint8_t *__restrict__ packed, SumCtx cx)
 {
+    constexpr bool NTL = UNPACK ? NTP : NTU, NTS = UNPACK ? NTU : NTP;
     const Tile t = tiles[blockIdx.x];
     const TensorDev &td = tensors[tensor_base + t.tensor];
     uint8_t *user = bases.p[t.tensor];
@@ -167,11 +216,11 @@ __global__ __launch_bounds__(kThreads) void k_rows(const Tile *__restrict__ tile
     const int outer = td.ndim - 1;
     const uint32_t nvec = t.n0 >> 4;
     uint64_t acc = 0;
-    for (uint32_t v0 = threadIdx.x; v0 < nvec; v0 += kThreads * UNROLL) {
-        uint4 r[UNROLL];
-        uint64_t off[UNROLL];
+    for (uint32_t v0 = threadIdx.x; v0 < nvec; v0 += kThreads * kUnroll) {
+        u32x4 r[kUnroll];
+        uint64_t off[kUnroll];
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
+        for (int u = 0; u < kUnroll; ++u) {
             const uint32_t v = v0 + u * kThreads;
             const uint32_t x = col0 + (v << 4);
             const uint32_t dr = fast_div(x, td.row_div);
@@ -184,18 +233,19 @@ __global__ __launch_bounds__(kThreads) void k_rows(const Tile *__restrict__ tile
             }
             o += uint64_t(row) * uint64_t(td.stride_b[0]);
             off[u] = o;
-            if (v < nvec) r[u] = load16<NT>(reinterpret_cast<const uint4 *>(UNPACK ? pk + (uint64_t(v) << 4) : user + o));
+            if (v < nvec)
+                r[u] = load16<NTL>(reinterpret_cast<const u32x4 *>(UNPACK ? pk + (uint64_t(v) << 4) : user + o));
         }
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
+        for (int u = 0; u < kUnroll; ++u) {
             const uint32_t v = v0 + u * kThreads;
             if (v < nvec) {
-                store16<NT>(reinterpret_cast<uint4 *>(UNPACK ? user + off[u] : pk + (uint64_t(v) << 4)), r[u]);
+                store16<NTS>(reinterpret_cast<u32x4 *>(UNPACK ? user + off[u] : pk + (uint64_t(v) << 4)), r[u]);
                 if constexpr (CSUM) acc += words_sum(r[u]);
             }
         }
     }
-    if constexpr (CSUM) block_add(acc, sums + t.chunk);
+    if constexpr (CSUM) chunk_commit(acc, t.chunk, chunk_tiles[t.chunk], cx);
 }
 
 // ---- transpose: logical inner dimension strided, the one before it contiguous ----
@@ -212,8 +262,9 @@ __device__ __forceinline__ uint64_t elem_weighted(E v, uint64_t packed_pos)
 }
 
 template <typename E, bool UNPACK, bool CSUM>
-__global__ __launch_bounds__(kThreads) void k_transpose(const Tile *__restrict__ tiles, BasePtrs bases,
-                                                        uint8_t *__restrict__ packed, uint64_t *__restrict__ sums)
+__global__ __launch_bounds__(kThreads) void k_transpose(const Tile *__restrict__ tiles,
+                                                        const uint32_t *__restrict__ chunk_tiles, BasePtrs bases,
+                                                        uint8_t *__restrict__ packed, SumCtx cx)
 {
     constexpr uint32_t T = kTransposeTile;
     __shared__ E lds[T][T + 1];
@@ -247,7 +298,7 @@ __global__ __launch_bounds__(kThreads) void k_transpose(const Tile *__restrict__
         if (tx < ni)
             for (uint32_t j = ty; j < nj; j += TY) *reinterpret_cast<E *>(user + j * t.a + tx * sizeof(E)) = lds[j][tx];
     }
-    if constexpr (CSUM) block_add(acc, sums + t.chunk);
+    if constexpr (CSUM) chunk_commit(acc, t.chunk, chunk_tiles[t.chunk], cx);
 }
 
 // ---- generic: any strides, one element at a time -------------------------------
@@ -255,14 +306,14 @@ __global__ __launch_bounds__(kThreads) void k_transpose(const Tile *__restrict__
 // logical index.  Slow, and only used for views the other kernels do not take.
 template <typename E, bool UNPACK, bool CSUM>
 __global__ __launch_bounds__(kThreads) void k_generic(const Tile *__restrict__ tiles,
+                                                      const uint32_t *__restrict__ chunk_tiles,
                                                       const TensorDev *__restrict__ tensors, uint32_t tensor_base,
-                                                      BasePtrs bases, uint8_t *__restrict__ packed,
-                                                      uint64_t *__restrict__ sums)
+                                                      BasePtrs bases, uint8_t *__restrict__ packed, SumCtx cx)
 {
     const Tile t = tiles[blockIdx.x];
     uint64_t acc = 0;
     if (t.kind == K_ZERO) {
-        acc = zero_tile<UNPACK, CSUM>(t, packed);
+        acc = pad_span<UNPACK, CSUM>(packed + t.packed_off, t.n0, uint32_t(t.packed_off));
     } else {
         const TensorDev &td = tensors[tensor_base + t.tensor];
         uint8_t *user = bases.p[t.tensor];
@@ -290,29 +341,55 @@ __global__ __launch_bounds__(kThreads) void k_generic(const Tile *__restrict__ t
             }
         }
     }
-    if constexpr (CSUM) block_add(acc, sums + t.chunk);
+    if constexpr (CSUM) chunk_commit(acc, t.chunk, chunk_tiles[t.chunk], cx);
 }
 
-// ---- stand-alone checksum of packed chunks ---------------------------------------
-template <int UNROLL, bool NT>
-__global__ __launch_bounds__(kThreads) void k_checksum(const Tile *__restrict__ tiles,
-                                                       const uint8_t *__restrict__ packed,
-                                                       uint64_t *__restrict__ sums)
+// ---- stand-alone checksum of packed chunks (closed-form geometry, no table) ----------
+template <bool NTP>
+__global__ __launch_bounds__(kThreads) void k_checksum(ChunkGeom g, const uint8_t *__restrict__ packed, SumCtx cx)
 {
-    const Tile t = tiles[blockIdx.x];
-    const uint4 *s = reinterpret_cast<const uint4 *>(packed + t.packed_off);
-    const uint32_t nvec = t.n0 >> 4;
+    const TileSpan t = locate_tile(g, blockIdx.x);
+    const u32x4 *s = reinterpret_cast<const u32x4 *>(packed + t.packed_off);
+    const uint32_t nvec = t.len >> 4;
     uint64_t acc = 0;
-    for (uint32_t v = threadIdx.x; v < nvec; v += kThreads * UNROLL) {
-        uint4 r[UNROLL];
+    for (uint32_t v = threadIdx.x; v < nvec; v += kThreads * kUnroll) {
+        u32x4 r[kUnroll];
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u)
-            r[u] = (v + u * kThreads < nvec) ? load16<NT>(s + v + u * kThreads) : uint4{0, 0, 0, 0};
+        for (int u = 0; u < kUnroll; ++u)
+            r[u] = (v + u * kThreads < nvec) ? load16<NTP>(s + v + u * kThreads) : u32x4{0, 0, 0, 0};
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) acc += words_sum(r[u]);
+        for (int u = 0; u < kUnroll; ++u) acc += words_sum(r[u]);
     }
-    block_add(acc, sums + t.chunk);
+    chunk_commit(acc, t.chunk, t.expected, cx);
 }
+
+}  // namespace hxt
+
+using namespace hxt;
+
+// The plan: host tables, their device copies, and the checksum accumulators.
+enum Op { OP_PACK = 0, OP_UNPACK = 1, OP_CHECKSUM = 2, OP_COUNT = 3 };
+
+struct OpState {              // accumulator slots of one operation and who used them last
+    uint8_t *acc = nullptr;
+    std::mutex mu;
+    bool used = false;
+    hipStream_t last = nullptr;
+    hipEvent_t ev = nullptr;
+};
+
+struct hxt_plan {
+    Plan p;
+    Tile *d_tiles = nullptr;
+    uint32_t *d_chunk_tiles = nullptr;
+    TensorDev *d_tensors = nullptr;
+    uint32_t acc_stride = 0;
+    uint32_t sum_bits_copy = 0, sum_bits_table = 0, sum_bits_csum = 0;   // see chunk_commit
+    int device = -1;
+    OpState ops[OP_COUNT];
+};
+
+namespace {
 
 // ---- host side --------------------------------------------------------------------
 
@@ -336,9 +413,11 @@ int env_int(const char *name, int dflt)
     return (s && *s) ? std::atoi(s) : dflt;
 }
 
+// Cache hints: tensors are streamed once (non-temporal); the packed buffer is written by
+// pack and read back soon after by the wire or by unpack, so it stays cacheable.
 struct Tuning {
-    bool nt;
-    Tuning() : nt(env_int("HXT_NONTEMPORAL", 1) != 0) {}
+    bool nt_user, nt_packed;
+    Tuning() : nt_user(env_int("HXT_NT_USER", 1) != 0), nt_packed(env_int("HXT_NT_PACKED", 0) != 0) {}
 };
 const Tuning &tuning()
 {
@@ -346,67 +425,129 @@ const Tuning &tuning()
     return t;
 }
 
-constexpr int kUnroll = 4;
-
-template <bool UNPACK, bool CSUM>
-void launch_contig(const Plan &p, const Group &g, const BasePtrs &b, uint8_t *packed, uint64_t *sums, hipStream_t st)
+// Calls f.template operator()<NTU, NTP>() for the configured cache hints.
+template <typename F>
+void with_hints(F &&f)
 {
-    const Tile *tiles = p.d_tiles + g.first;
-    if (tuning().nt)
-        k_contig<UNPACK, CSUM, kUnroll, true><<<g.count, kThreads, 0, st>>>(tiles, b, packed, sums);
-    else
-        k_contig<UNPACK, CSUM, kUnroll, false><<<g.count, kThreads, 0, st>>>(tiles, b, packed, sums);
-}
-
-template <bool UNPACK, bool CSUM>
-void launch_rows(const Plan &p, const Group &g, const BasePtrs &b, uint8_t *packed, uint64_t *sums, hipStream_t st)
-{
-    const Tile *tiles = p.d_tiles + g.first;
-    if (tuning().nt)
-        k_rows<UNPACK, CSUM, kUnroll, true><<<g.count, kThreads, 0, st>>>(tiles, p.d_tensors, g.tensor_base, b, packed, sums);
-    else
-        k_rows<UNPACK, CSUM, kUnroll, false><<<g.count, kThreads, 0, st>>>(tiles, p.d_tensors, g.tensor_base, b, packed, sums);
-}
-
-template <bool UNPACK, bool CSUM>
-void launch_transpose(const Plan &p, const Group &g, int esize, const BasePtrs &b, uint8_t *packed, uint64_t *sums,
-                      hipStream_t st)
-{
-    const Tile *tiles = p.d_tiles + g.first;
-    switch (esize) {
-    case 1: k_transpose<uint8_t, UNPACK, CSUM><<<g.count, kThreads, 0, st>>>(tiles, b, packed, sums); break;
-    case 2: k_transpose<uint16_t, UNPACK, CSUM><<<g.count, kThreads, 0, st>>>(tiles, b, packed, sums); break;
-    case 4: k_transpose<uint32_t, UNPACK, CSUM><<<g.count, kThreads, 0, st>>>(tiles, b, packed, sums); break;
-    default: k_transpose<uint64_t, UNPACK, CSUM><<<g.count, kThreads, 0, st>>>(tiles, b, packed, sums); break;
+    const Tuning &t = tuning();
+    if (t.nt_user) {
+        if (t.nt_packed) f.template operator()<true, true>();
+        else f.template operator()<true, false>();
+    } else {
+        if (t.nt_packed) f.template operator()<false, true>();
+        else f.template operator()<false, false>();
     }
 }
 
 template <bool UNPACK, bool CSUM>
-void launch_generic(const Plan &p, uint32_t first, uint32_t count, uint32_t tensor_base, int esize, const BasePtrs &b,
-                    uint8_t *packed, uint64_t *sums, hipStream_t st)
+void launch_uniform(const hxt_plan_t &pl, uint8_t *user, uint8_t *packed, const SumCtx &cx, hipStream_t st)
 {
-    const Tile *tiles = p.d_tiles + first;
+    with_hints([&]<bool NTU, bool NTP>() {
+        k_uniform<UNPACK, CSUM, NTU, NTP><<<pl.p.geom.ntiles, kThreads, 0, st>>>(pl.p.geom, user, packed, cx);
+    });
+}
+
+template <bool UNPACK, bool CSUM>
+void launch_contig(const hxt_plan_t &pl, const Group &g, const BasePtrs &b, uint8_t *packed, const SumCtx &cx,
+                   hipStream_t st)
+{
+    with_hints([&]<bool NTU, bool NTP>() {
+        k_contig<UNPACK, CSUM, NTU, NTP><<<g.count, kThreads, 0, st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, b, packed, cx);
+    });
+}
+
+template <bool UNPACK, bool CSUM>
+void launch_rows(const hxt_plan_t &pl, const Group &g, const BasePtrs &b, uint8_t *packed, const SumCtx &cx,
+                 hipStream_t st)
+{
+    with_hints([&]<bool NTU, bool NTP>() {
+        k_rows<UNPACK, CSUM, NTU, NTP><<<g.count, kThreads, 0, st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, pl.d_tensors,
+                                                                     g.tensor_base, b, packed, cx);
+    });
+}
+
+template <bool UNPACK, bool CSUM>
+void launch_transpose(const hxt_plan_t &pl, uint32_t first, uint32_t count, int esize, const BasePtrs &b,
+                      uint8_t *packed, const SumCtx &cx, hipStream_t st)
+{
+    const Tile *tiles = pl.d_tiles + first;
+    const uint32_t *ct = pl.d_chunk_tiles;
     switch (esize) {
-    case 1: k_generic<uint8_t, UNPACK, CSUM><<<count, kThreads, 0, st>>>(tiles, p.d_tensors, tensor_base, b, packed, sums); break;
-    case 2: k_generic<uint16_t, UNPACK, CSUM><<<count, kThreads, 0, st>>>(tiles, p.d_tensors, tensor_base, b, packed, sums); break;
-    case 4: k_generic<uint32_t, UNPACK, CSUM><<<count, kThreads, 0, st>>>(tiles, p.d_tensors, tensor_base, b, packed, sums); break;
-    default: k_generic<uint64_t, UNPACK, CSUM><<<count, kThreads, 0, st>>>(tiles, p.d_tensors, tensor_base, b, packed, sums); break;
+    case 1: k_transpose<uint8_t, UNPACK, CSUM><<<count, kThreads, 0, st>>>(tiles, ct, b, packed, cx); break;
+    case 2: k_transpose<uint16_t, UNPACK, CSUM><<<count, kThreads, 0, st>>>(tiles, ct, b, packed, cx); break;
+    case 4: k_transpose<uint32_t, UNPACK, CSUM><<<count, kThreads, 0, st>>>(tiles, ct, b, packed, cx); break;
+    default: k_transpose<uint64_t, UNPACK, CSUM><<<count, kThreads, 0, st>>>(tiles, ct, b, packed, cx); break;
     }
 }
 
-int zero_sums(const Plan &p, uint64_t *sums, hipStream_t st)
+template <bool UNPACK, bool CSUM>
+void launch_generic(const hxt_plan_t &pl, uint32_t first, uint32_t count, uint32_t tensor_base, int esize,
+                    const BasePtrs &b, uint8_t *packed, const SumCtx &cx, hipStream_t st)
 {
-    const uint32_t n = uint32_t(p.C);
-    k_fill_zero<<<(n + kThreads - 1) / kThreads, kThreads, 0, st>>>(sums, n);
-    HXT_HIP(hipGetLastError());
+    const Tile *tiles = pl.d_tiles + first;
+    const uint32_t *ct = pl.d_chunk_tiles;
+    const TensorDev *td = pl.d_tensors;
+    switch (esize) {
+    case 1: k_generic<uint8_t, UNPACK, CSUM><<<count, kThreads, 0, st>>>(tiles, ct, td, tensor_base, b, packed, cx); break;
+    case 2: k_generic<uint16_t, UNPACK, CSUM><<<count, kThreads, 0, st>>>(tiles, ct, td, tensor_base, b, packed, cx); break;
+    case 4: k_generic<uint32_t, UNPACK, CSUM><<<count, kThreads, 0, st>>>(tiles, ct, td, tensor_base, b, packed, cx); break;
+    default: k_generic<uint64_t, UNPACK, CSUM><<<count, kThreads, 0, st>>>(tiles, ct, td, tensor_base, b, packed, cx); break;
+    }
+}
+
+// The accumulator slots of an operation are shared by all calls of that operation on this
+// plan.  Calls on one stream are ordered by the stream; when the stream changes, the new
+// stream is made to wait for everything enqueued so far on the previous one.
+int claim_slots(hxt_plan_t &pl, Op op, hipStream_t st, SumCtx &cx, uint64_t *sums)
+{
+    OpState &o = pl.ops[op];
+    std::lock_guard<std::mutex> lock(o.mu);
+    if (o.used && o.last != st) {
+        if (!o.ev) HXT_HIP(hipEventCreateWithFlags(&o.ev, hipEventDisableTiming));
+        if (hipEventRecord(o.ev, o.last) == hipSuccess)
+            HXT_HIP(hipStreamWaitEvent(st, o.ev, 0));
+        else
+            (void)hipGetLastError();           // the previous stream no longer exists: nothing to wait for
+    }
+    o.used = true;
+    o.last = st;
+    cx.sums = sums;
+    cx.acc = o.acc;
+    cx.stride = pl.acc_stride;
+    cx.sum_bits = 0;
     return HXT_OK;
 }
 
-// The element size a launch of the per-element or transpose kernel is instantiated for is a
-// property of the tensor, so such launches are issued per run of tiles with one element size.
-template <bool UNPACK, bool CSUM>
-int run_groups(const Plan &p, void *const *ptrs, uint8_t *packed, uint64_t *sums, hipStream_t st)
+// Bits a chunk's checksum can occupy (at most B/4 words below 2^32), if the arrival count of
+// `contributors` workgroups still fits above them in a 64-bit word; else 0.
+uint32_t single_word_bits(uint64_t chunk_bytes, uint32_t contributors)
 {
+    uint32_t m = 0;
+    while ((uint64_t(1) << m) < chunk_bytes / 4) ++m;
+    uint32_t cb = 0;
+    while ((uint64_t(1) << cb) <= contributors) ++cb;
+    return 32 + m + cb <= 64 ? 32 + m : 0;
+}
+
+template <bool UNPACK, bool CSUM>
+int run_copy(hxt_plan_t &pl, void *const *ptrs, uint8_t *packed, uint64_t *sums, hipStream_t st)
+{
+    const Plan &p = pl.p;
+    SumCtx cx{nullptr, nullptr, 0, 0};
+    if constexpr (CSUM) {
+        int rc = claim_slots(pl, UNPACK ? OP_UNPACK : OP_PACK, st, cx, sums);
+        if (rc != HXT_OK) return rc;
+        cx.sum_bits = pl.sum_bits_table;
+    }
+    if (p.uniform) {
+        uint8_t *base = static_cast<uint8_t *>(ptrs[p.uniform_tensor]);
+        if (reinterpret_cast<uintptr_t>(base) % 16 == 0) {
+            cx.sum_bits = pl.sum_bits_copy;
+            launch_uniform<UNPACK, CSUM>(pl, base, packed, cx, st);
+            HXT_HIP(hipGetLastError());
+            return HXT_OK;
+        }
+    }
     for (const Group &g : p.groups) {
         BasePtrs b;
         std::memset(&b, 0, sizeof b);
@@ -415,31 +556,24 @@ int run_groups(const Plan &p, void *const *ptrs, uint8_t *packed, uint64_t *sums
             const TensorPlan &tp = p.tensors[g.tensor_base + i];
             uint8_t *base = static_cast<uint8_t *>(ptrs[g.tensor_base + i]);
             b.p[i] = base;
-            if (tp.bytes == 0) continue;
-            if (!base) return HXT_EINVAL;
-            if (reinterpret_cast<uintptr_t>(base) % tp.esize) return HXT_EALIGN;
-            if ((tp.kind == K_CONTIG || tp.kind == K_ROWS) && tp.kind == g.kernel &&
-                reinterpret_cast<uintptr_t>(base) % 16)
-                fast_ok = false;
+            if (tp.bytes && tp.kind == g.kernel && reinterpret_cast<uintptr_t>(base) % 16) fast_ok = false;
         }
         if (g.kernel == K_CONTIG && fast_ok) {
-            launch_contig<UNPACK, CSUM>(p, g, b, packed, sums, st);
+            launch_contig<UNPACK, CSUM>(pl, g, b, packed, cx, st);
         } else if (g.kernel == K_ROWS && fast_ok) {
-            launch_rows<UNPACK, CSUM>(p, g, b, packed, sums, st);
+            launch_rows<UNPACK, CSUM>(pl, g, b, packed, cx, st);
         } else {
-            // split the group's tiles into runs of equal element size (host table, same order as the device one)
+            // The transpose and per-element kernels are instantiated per element size: issue one
+            // launch per run of tiles whose tensors share it (host table, same order as on the device).
             uint32_t i = 0;
             while (i < g.count) {
                 const int es = p.tensors[g.tensor_base + p.tiles[g.first + i].tensor].esize;
                 uint32_t j = i + 1;
                 while (j < g.count && p.tensors[g.tensor_base + p.tiles[g.first + j].tensor].esize == es) ++j;
-                Group sub = g;
-                sub.first = g.first + i;
-                sub.count = j - i;
                 if (g.kernel == K_TRANSPOSE)
-                    launch_transpose<UNPACK, CSUM>(p, sub, es, b, packed, sums, st);
+                    launch_transpose<UNPACK, CSUM>(pl, g.first + i, j - i, es, b, packed, cx, st);
                 else
-                    launch_generic<UNPACK, CSUM>(p, sub.first, sub.count, g.tensor_base, es, b, packed, sums, st);
+                    launch_generic<UNPACK, CSUM>(pl, g.first + i, j - i, g.tensor_base, es, b, packed, cx, st);
                 i = j;
             }
         }
@@ -455,28 +589,60 @@ int check_common(const hxt_plan_t *plan, const void *packed)
     if (p.C == 0) return HXT_OK;
     if (!packed) return HXT_EINVAL;
     if (reinterpret_cast<uintptr_t>(packed) % HXT_ALIGN) return HXT_EALIGN;
-    if (!p.d_tiles) {
+    if (plan->device < 0 || !plan->ops[0].acc) {
         g_last_hip = int(hipErrorNoDevice);
         return HXT_EHIP;
     }
     return HXT_OK;
 }
 
-int upload(Plan &p)
+int check_tensor_pointers(const Plan &p, void *const *ptrs)
+{
+    if (!ptrs) return HXT_EINVAL;
+    for (size_t i = 0; i < p.tensors.size(); ++i) {
+        if (p.tensors[i].bytes == 0) continue;
+        if (!ptrs[i]) return HXT_EINVAL;
+        if (reinterpret_cast<uintptr_t>(ptrs[i]) % p.tensors[i].esize) return HXT_EALIGN;
+    }
+    return HXT_OK;
+}
+
+template <typename T>
+int to_device(T **dst, const std::vector<T> &src)
+{
+    if (src.empty()) return HXT_OK;
+    HXT_HIP(hipMalloc(reinterpret_cast<void **>(dst), src.size() * sizeof(T)));
+    HXT_HIP(hipMemcpy(*dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice));
+    return HXT_OK;
+}
+
+int upload(hxt_plan_t &pl)
 {
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess) {
         (void)hipGetLastError();
         return HXT_OK;                      // no GPU: queries still work, data-plane calls report HXT_EHIP
     }
-    p.device = dev;
-    if (p.tiles.empty()) return HXT_OK;
-    HXT_HIP(hipMalloc(reinterpret_cast<void **>(&p.d_tiles), p.tiles.size() * sizeof(Tile)));
-    HXT_HIP(hipMemcpy(p.d_tiles, p.tiles.data(), p.tiles.size() * sizeof(Tile), hipMemcpyHostToDevice));
-    if (!p.tdev.empty()) {
-        HXT_HIP(hipMalloc(reinterpret_cast<void **>(&p.d_tensors), p.tdev.size() * sizeof(TensorDev)));
-        HXT_HIP(hipMemcpy(p.d_tensors, p.tdev.data(), p.tdev.size() * sizeof(TensorDev), hipMemcpyHostToDevice));
+    pl.device = dev;
+    const Plan &p = pl.p;
+    if (p.C == 0) return HXT_OK;
+    int rc;
+    if ((rc = to_device(&pl.d_tiles, p.tiles)) != HXT_OK) return rc;
+    if ((rc = to_device(&pl.d_chunk_tiles, p.chunk_tiles)) != HXT_OK) return rc;
+    if ((rc = to_device(&pl.d_tensors, p.tdev)) != HXT_OK) return rc;
+    // accumulator slots: 256 bytes apart (separate memory channels) unless that would be large
+    pl.acc_stride = p.C <= 16384 ? 256 : uint32_t(sizeof(Acc));
+    uint32_t most = 0;
+    for (uint32_t n : p.chunk_tiles) most = std::max(most, n);
+    pl.sum_bits_table = env_int("HXT_TWO_WORD_COMMIT", 0) ? 0 : single_word_bits(p.B, most);
+    pl.sum_bits_copy = env_int("HXT_TWO_WORD_COMMIT", 0) ? 0 : single_word_bits(p.B, p.geom.tpc);
+    pl.sum_bits_csum = pl.sum_bits_copy;
+    const size_t bytes = size_t(p.C) * pl.acc_stride;
+    for (OpState &o : pl.ops) {
+        HXT_HIP(hipMalloc(reinterpret_cast<void **>(&o.acc), bytes));
+        HXT_HIP(hipMemset(o.acc, 0, bytes));
     }
+    HXT_HIP(hipDeviceSynchronize());
     return HXT_OK;
 }
 
@@ -541,7 +707,7 @@ int hxt_plan_multi(const hxt_tensor_desc_t *tensors, int n_tensors, int n_lanes,
     try {
         rc = build_plan(tensors, n_tensors, n_lanes, chunk_bytes,
                         uint32_t(env_int("HXT_TILE_BYTES", int(kDefaultTileBytes))), pl->p);
-        if (rc == HXT_OK) rc = upload(pl->p);
+        if (rc == HXT_OK) rc = upload(*pl);
     } catch (const std::bad_alloc &) {
         rc = HXT_ENOMEM;
     }
@@ -564,8 +730,16 @@ int hxt_plan_destroy(hxt_plan_t *plan)
 {
     if (!plan) return HXT_OK;
     int rc = HXT_OK;
-    if (plan->p.d_tiles && hipFree(plan->p.d_tiles) != hipSuccess) rc = HXT_EHIP;
-    if (plan->p.d_tensors && hipFree(plan->p.d_tensors) != hipSuccess) rc = HXT_EHIP;
+    auto release = [&](void *p) {
+        if (p && hipFree(p) != hipSuccess) rc = HXT_EHIP;
+    };
+    release(plan->d_tiles);
+    release(plan->d_chunk_tiles);
+    release(plan->d_tensors);
+    for (OpState &o : plan->ops) {
+        release(o.acc);
+        if (o.ev && hipEventDestroy(o.ev) != hipSuccess) rc = HXT_EHIP;
+    }
     delete plan;
     return rc;
 }
@@ -624,44 +798,24 @@ int hxt_pack(const hxt_plan_t *plan, const void *const *src, void *packed, uint6
 {
     int rc = check_common(plan, packed);
     if (rc != HXT_OK || plan->p.C == 0) return rc;
-    if (!src) return HXT_EINVAL;
-    const Plan &p = plan->p;
-    hipStream_t st = static_cast<hipStream_t>(stream);
     void *const *ptrs = const_cast<void *const *>(src);
-    // validate every pointer before anything is enqueued
-    for (size_t i = 0; i < p.tensors.size(); ++i) {
-        if (p.tensors[i].bytes == 0) continue;
-        if (!ptrs[i]) return HXT_EINVAL;
-        if (reinterpret_cast<uintptr_t>(ptrs[i]) % p.tensors[i].esize) return HXT_EALIGN;
-    }
-    if (sums) {
-        rc = zero_sums(p, sums, st);
-        if (rc != HXT_OK) return rc;
-        return run_groups<false, true>(p, ptrs, static_cast<uint8_t *>(packed), sums, st);
-    }
-    return run_groups<false, false>(p, ptrs, static_cast<uint8_t *>(packed), nullptr, st);
+    if ((rc = check_tensor_pointers(plan->p, ptrs)) != HXT_OK) return rc;
+    hxt_plan_t &pl = *const_cast<hxt_plan_t *>(plan);     // only the slot bookkeeping is mutable
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint8_t *pk = static_cast<uint8_t *>(packed);
+    return sums ? run_copy<false, true>(pl, ptrs, pk, sums, st) : run_copy<false, false>(pl, ptrs, pk, nullptr, st);
 }
 
 int hxt_unpack(const hxt_plan_t *plan, const void *packed, void *const *dst, uint64_t *sums, void *stream)
 {
     int rc = check_common(plan, packed);
     if (rc != HXT_OK || plan->p.C == 0) return rc;
-    if (!dst) return HXT_EINVAL;
-    const Plan &p = plan->p;
-    if (!p.all_unpack_safe) return HXT_EOVERLAP;
+    if ((rc = check_tensor_pointers(plan->p, dst)) != HXT_OK) return rc;
+    if (!plan->p.all_unpack_safe) return HXT_EOVERLAP;
+    hxt_plan_t &pl = *const_cast<hxt_plan_t *>(plan);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    for (size_t i = 0; i < p.tensors.size(); ++i) {
-        if (p.tensors[i].bytes == 0) continue;
-        if (!dst[i]) return HXT_EINVAL;
-        if (reinterpret_cast<uintptr_t>(dst[i]) % p.tensors[i].esize) return HXT_EALIGN;
-    }
     uint8_t *pk = const_cast<uint8_t *>(static_cast<const uint8_t *>(packed));
-    if (sums) {
-        rc = zero_sums(p, sums, st);
-        if (rc != HXT_OK) return rc;
-        return run_groups<true, true>(p, dst, pk, sums, st);
-    }
-    return run_groups<true, false>(p, dst, pk, nullptr, st);
+    return sums ? run_copy<true, true>(pl, dst, pk, sums, st) : run_copy<true, false>(pl, dst, pk, nullptr, st);
 }
 
 int hxt_checksum(const hxt_plan_t *plan, const void *packed, uint64_t *sums, void *stream)
@@ -669,15 +823,16 @@ int hxt_checksum(const hxt_plan_t *plan, const void *packed, uint64_t *sums, voi
     int rc = check_common(plan, packed);
     if (rc != HXT_OK || plan->p.C == 0) return rc;
     if (!sums) return HXT_EINVAL;
-    const Plan &p = plan->p;
+    hxt_plan_t &pl = *const_cast<hxt_plan_t *>(plan);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    rc = zero_sums(p, sums, st);
-    if (rc != HXT_OK) return rc;
-    const Tile *tiles = p.d_tiles + p.csum_first;
-    if (tuning().nt)
-        k_checksum<kUnroll, true><<<p.csum_count, kThreads, 0, st>>>(tiles, static_cast<const uint8_t *>(packed), sums);
+    SumCtx cx{nullptr, nullptr, 0, 0};
+    if ((rc = claim_slots(pl, OP_CHECKSUM, st, cx, sums)) != HXT_OK) return rc;
+    cx.sum_bits = pl.sum_bits_csum;
+    const uint8_t *pk = static_cast<const uint8_t *>(packed);
+    if (tuning().nt_packed)
+        k_checksum<true><<<pl.p.geom.ntiles, kThreads, 0, st>>>(pl.p.geom, pk, cx);
     else
-        k_checksum<kUnroll, false><<<p.csum_count, kThreads, 0, st>>>(tiles, static_cast<const uint8_t *>(packed), sums);
+        k_checksum<false><<<pl.p.geom.ntiles, kThreads, 0, st>>>(pl.p.geom, pk, cx);
     HXT_HIP(hipGetLastError());
     return HXT_OK;
 }
@@ -708,6 +863,6 @@ const char *hxt_strerror(int status)
 
 int hxt_last_hip_error(void) { return g_last_hip; }
 
-const char *hxt_version(void) { return "hxt 0.1 (gfx950)"; }
+const char *hxt_version(void) { return "hxt 0.2 (gfx950)"; }
 
 }  // extern "C"

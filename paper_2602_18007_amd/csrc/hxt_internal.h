@@ -8,6 +8,12 @@
 
 #include "hxt.h"
 
+#if defined(__HIPCC__)
+#define HXT_HD __host__ __device__ inline
+#else
+#define HXT_HD inline
+#endif
+
 namespace hxt {
 
 // Which kernel family moves a piece of the stream.
@@ -17,13 +23,12 @@ enum Kind : uint16_t {
     K_ROWS = 2,       // innermost dimension contiguous, 16-byte friendly rows: gather of runs
     K_TRANSPOSE = 3,  // innermost logical dim strided, second innermost contiguous: LDS tile transpose
     K_GENERIC = 4,    // anything else: one element at a time
-    K_ZERO = 5,       // pad bytes between tensors / after the last one (byte granular, < 256 bytes)
-    K_CSUM = 6        // stand-alone checksum pass over a packed chunk
+    K_ZERO = 5        // pad bytes between tensors / after the last one (byte granular, < 256 bytes)
 };
 
 // One unit of work for one workgroup.  64 bytes of 32/64-bit fields, read with scalar loads.
-//   linear kinds (CONTIG, ROWS, GENERIC, ZERO, CSUM):
-//     packed_off : first packed byte of the piece (CONTIG/ROWS/GENERIC/CSUM: multiple of 256)
+//   linear kinds (CONTIG, ROWS, GENERIC, ZERO):
+//     packed_off : first packed byte of the piece (CONTIG/ROWS/GENERIC: multiple of 256)
 //     src_off    : logical byte offset inside the tensor (equals the storage offset for CONTIG)
 //     n0         : bytes of the piece
 //   TRANSPOSE (a 2-D block of ni logical rows x nj logical columns inside one chunk):
@@ -50,6 +55,49 @@ struct FastDiv {
     uint32_t shift;
 };
 FastDiv make_fastdiv(uint32_t d);
+HXT_HD uint32_t fast_div(uint32_t n, FastDiv d) { return uint32_t((uint64_t(n) * d.mul) >> (31 + d.shift)); }
+
+// Chunk/lane geometry in closed form, for work that is uniform over the packed stream (a
+// message made of one contiguous tensor; the stand-alone checksum of any message).  The
+// stream is cut into chunks of B bytes and every chunk into tpc = ceil(B / tile) tiles;
+// tile number t belongs to chunk t / tpc.  Lane l holds q + (l < r) chunks, so its region
+// starts at (l*q + min(l, r)) * B.
+struct ChunkGeom {
+    uint64_t N;          // tensor bytes (uniform-copy path only)
+    uint64_t L;          // stream bytes (multiple of 256)
+    uint64_t B;          // chunk bytes
+    uint32_t k, C;       // lanes, chunks
+    uint32_t tile;       // bytes per tile (multiple of 256)
+    uint32_t tpc;        // tiles per full chunk
+    uint32_t q, r;       // C / k, C % k
+    uint32_t ntiles;     // (C - 1) * tpc + tiles of the last chunk
+    uint32_t last_tiles; // tiles of the last chunk
+    FastDiv div_tpc, div_k;
+};
+
+struct TileSpan {
+    uint32_t chunk;
+    uint32_t expected;   // tiles that make up this chunk
+    uint64_t stream_off; // first stream byte of the tile
+    uint64_t packed_off; // where it lives in the packed buffer
+    uint32_t len;        // stream bytes in the tile (multiple of 256)
+};
+
+HXT_HD TileSpan locate_tile(const ChunkGeom &g, uint32_t t)
+{
+    TileSpan s;
+    const uint32_t c = fast_div(t, g.div_tpc), j = t - c * g.tpc;
+    const uint32_t slot = fast_div(c, g.div_k), lane = c - slot * g.k;
+    const uint64_t in_chunk = uint64_t(j) * g.tile;
+    const uint64_t chunk_len = (c + 1 == g.C) ? g.L - uint64_t(c) * g.B : g.B;
+    const uint64_t left = chunk_len - in_chunk;
+    s.chunk = c;
+    s.expected = (c + 1 == g.C) ? g.last_tiles : g.tpc;
+    s.stream_off = uint64_t(c) * g.B + in_chunk;
+    s.packed_off = (uint64_t(lane) * g.q + (lane < g.r ? lane : g.r) + slot) * g.B + in_chunk;
+    s.len = left < g.tile ? uint32_t(left) : g.tile;
+    return s;
+}
 
 // Per-tensor view description for the ROWS and GENERIC kernels (merged dims, logical order).
 struct TensorDev {
@@ -89,16 +137,14 @@ struct Plan {
     std::vector<uint64_t> lane_off;      // k + 1 entries
     std::vector<uint64_t> lane_chunks;   // k
     uint32_t tile_bytes = 0;
-    std::vector<Tile> tiles;             // pack/unpack groups first, then the CSUM tiles
+    std::vector<Tile> tiles;             // grouped by kernel family, stream order inside a group
     std::vector<Group> groups;
-    uint32_t csum_first = 0, csum_count = 0;
+    std::vector<uint32_t> chunk_tiles;   // tiles of the table that belong to each chunk
     std::vector<TensorDev> tdev;
     bool all_unpack_safe = true;
-
-    // device copies (owned)
-    Tile *d_tiles = nullptr;
-    TensorDev *d_tensors = nullptr;
-    int device = -1;
+    ChunkGeom geom;                      // closed-form geometry of the packed stream
+    bool uniform = false;                // the message is one contiguous tensor: geom alone describes the copy
+    uint32_t uniform_tensor = 0;         // index of that tensor
 
     uint64_t chunk_padded(uint64_t c) const;
     uint64_t chunk_packed_off(uint64_t c) const { return lane_off[c % k] + (c / k) * B; }
@@ -112,9 +158,5 @@ constexpr uint32_t kDefaultTileBytes = 16384;  // bytes of the stream one workgr
 constexpr uint32_t kTransposeTile = 64;        // a TRANSPOSE tile is at most 64 x 64 elements
 
 }  // namespace hxt
-
-struct hxt_plan {
-    hxt::Plan p;
-};
 
 #endif

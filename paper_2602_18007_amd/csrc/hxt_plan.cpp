@@ -280,9 +280,9 @@ int build_plan(const hxt_tensor_desc_t *descs, int n_tensors, int n_lanes, size_
     }
     uint64_t total = 0;
     for (auto &v : b.by_kernel) total += v.size();
-    const uint64_t csum_tiles = (p.L + tile_bytes - 1) / tile_bytes + p.C;
-    if (total + csum_tiles >= (uint64_t(1) << 31)) return HXT_EUNSUPPORTED;
-    p.tiles.reserve(total + csum_tiles);
+    if (total >= (uint64_t(1) << 31)) return HXT_EUNSUPPORTED;
+    p.tiles.reserve(total);
+    p.chunk_tiles.assign(p.C, 0);
     for (Kind kern : {K_CONTIG, K_ROWS, K_TRANSPOSE, K_GENERIC}) {
         auto &v = b.by_kernel[kern];
         size_t i = 0;
@@ -293,21 +293,38 @@ int build_plan(const hxt_tensor_desc_t *descs, int n_tensors, int n_lanes, size_
                 t.tensor = v[i].tensor_abs - g.tensor_base;
                 g.n_tensors = std::max(g.n_tensors, t.tensor + 1);
                 p.tiles.push_back(t);
+                ++p.chunk_tiles[t.chunk];
                 ++g.count;
                 ++i;
             }
             p.groups.push_back(g);
         }
     }
-    // stand-alone checksum pass: every chunk's padded bytes, tile by tile
-    p.csum_first = uint32_t(p.tiles.size());
-    for (uint64_t c = 0; c < p.C; ++c) {
-        uint64_t len = p.chunk_padded(c), base = p.chunk_packed_off(c);
-        for (uint64_t o = 0; o < len; o += tile_bytes)
-            p.tiles.push_back(Tile{base + o, 0, 0, 0, uint32_t(c), 0, uint32_t(K_CSUM),
-                                   uint32_t(std::min<uint64_t>(tile_bytes, len - o)), 0, {0, 0, 0}});
-    }
-    p.csum_count = uint32_t(p.tiles.size()) - p.csum_first;
+    // closed-form geometry of the packed stream (stand-alone checksum; uniform copy)
+    ChunkGeom &g = p.geom;
+    std::memset(&g, 0, sizeof g);
+    g.L = p.L;
+    g.B = p.B;
+    g.k = uint32_t(p.k);
+    g.C = uint32_t(p.C);
+    g.tile = tile_bytes;
+    const uint64_t tpc = (p.B + tile_bytes - 1) / tile_bytes;
+    if (tpc * std::max<uint64_t>(p.C, 1) >= (uint64_t(1) << 31)) return HXT_EUNSUPPORTED;
+    g.tpc = uint32_t(tpc);
+    g.q = uint32_t(p.C / p.k);
+    g.r = uint32_t(p.C % p.k);
+    g.last_tiles = p.C ? uint32_t((p.chunk_padded(p.C - 1) + tile_bytes - 1) / tile_bytes) : 0;
+    g.ntiles = p.C ? uint32_t((p.C - 1) * tpc) + g.last_tiles : 0;
+    g.div_tpc = make_fastdiv(g.tpc);
+    g.div_k = make_fastdiv(g.k);
+    int live = 0;
+    for (int i = 0; i < n_tensors; ++i)
+        if (p.tensors[i].bytes) {
+            ++live;
+            p.uniform_tensor = uint32_t(i);
+        }
+    p.uniform = live == 1 && p.tensors[p.uniform_tensor].kind == K_CONTIG;
+    g.N = p.uniform ? p.tensors[p.uniform_tensor].bytes : 0;
     return HXT_OK;
 }
 

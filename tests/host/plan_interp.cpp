@@ -35,13 +35,14 @@ uint64_t logical_to_storage(const TensorDev &td, uint64_t byte)
 }
 }  // namespace
 
-// direction 0: pack (user -> packed), 1: unpack (packed -> user).  Returns 0, or a
+// direction 0: pack (user -> packed) from the tables, 1: unpack (packed -> user) from the tables,
+// 2: pack from the tables and then, if the message is uniform, again from the closed form.  Returns 0, or a
 // negative code: -1 plan error, -2 user access out of bounds, -3 packed access out of
-// bounds, -4 tile crosses its chunk, -5 bad group bookkeeping.
+// bounds, -4 tile crosses its chunk, -5 bad group bookkeeping, -6 bad closed-form geometry.
 extern "C" int plan_interp(const hxt_tensor_desc_t *descs, int n_tensors, int n_lanes, uint64_t chunk_bytes,
                            uint32_t tile_bytes, uint8_t *const *base, const uint64_t *storage_bytes,
                            uint8_t *packed, uint64_t packed_bytes, uint8_t *written, int direction,
-                           int32_t *kinds_out)
+                           int32_t *kinds_out, int32_t *uniform_out)
 {
     Plan p;
     if (build_plan(descs, n_tensors, n_lanes, chunk_bytes, tile_bytes, p) != HXT_OK) return -1;
@@ -62,7 +63,7 @@ extern "C" int plan_interp(const hxt_tensor_desc_t *descs, int n_tensors, int n_
                 if (!c.packed_ok(poff, 1)) return -3;
                 if (poff < c_lo || poff >= c_hi) return -4;
                 if (!zero && !c.user_ok(ta, uoff, 1)) return -2;
-                if (direction == 0) {
+                if (direction != 1) {
                     packed[poff] = zero ? 0 : base[ta][uoff];
                     if (written[poff] < 255) ++written[poff];
                 } else if (!zero) {
@@ -103,18 +104,48 @@ extern "C" int plan_interp(const hxt_tensor_desc_t *descs, int n_tensors, int n_
             if (rc) return rc;
         }
     }
-    if (next != p.csum_first) return -5;
-    // the stand-alone checksum tiles must cover every chunk's padded bytes exactly once
+    if (next != p.tiles.size()) return -5;
+    // per-chunk tile counts (the checksum's "last arrival" test depends on them)
+    std::vector<uint32_t> count(p.C, 0);
+    for (const Tile &t : p.tiles) ++count[t.chunk];
+    if (count != p.chunk_tiles) return -5;
+    // closed-form geometry: its tiles must cover every chunk's padded bytes exactly once, report
+    // the right chunk and the right number of tiles per chunk
     std::vector<uint8_t> seen(packed_bytes, 0);
-    for (uint32_t i = 0; i < p.csum_count; ++i) {
-        const Tile &t = p.tiles[p.csum_first + i];
+    std::vector<uint32_t> per_chunk(p.C, 0);
+    for (uint32_t i = 0; i < p.geom.ntiles; ++i) {
+        const TileSpan t = locate_tile(p.geom, i);
+        if (t.chunk >= p.C) return -6;
         const uint64_t c_lo = p.chunk_packed_off(t.chunk), c_hi = c_lo + p.chunk_padded(t.chunk);
-        if (t.kind != K_CSUM || t.packed_off < c_lo || t.packed_off + t.n0 > c_hi || t.n0 % 16) return -5;
-        for (uint64_t b = 0; b < t.n0; ++b) ++seen[t.packed_off + b];
+        if (t.packed_off < c_lo || t.packed_off + t.len > c_hi || t.len % 256 || t.len == 0) return -6;
+        if (t.packed_off - c_lo != t.stream_off - uint64_t(t.chunk) * p.B) return -6;
+        ++per_chunk[t.chunk];
+        for (uint64_t b = 0; b < t.len; ++b) ++seen[t.packed_off + b];
     }
-    for (uint64_t ch = 0; ch < p.C; ++ch)
+    for (uint64_t ch = 0; ch < p.C; ++ch) {
         for (uint64_t b = 0; b < p.chunk_padded(ch); ++b)
-            if (seen[p.chunk_packed_off(ch) + b] != 1) return -5;
+            if (seen[p.chunk_packed_off(ch) + b] != 1) return -6;
+        const TileSpan any = locate_tile(p.geom, uint32_t(ch) * p.geom.tpc);
+        if (any.expected != per_chunk[ch] || any.chunk != ch) return -6;
+    }
+    if ((p.C == 0) != (p.geom.ntiles == 0)) return -6;
+    *uniform_out = p.uniform ? 1 : 0;
+    if (p.uniform && direction == 2) {
+        // the uniform copy, byte by byte: tensor bytes then zero pad, from the closed form alone
+        const uint32_t ta = p.uniform_tensor;
+        for (uint32_t i = 0; i < p.geom.ntiles; ++i) {
+            const TileSpan t = locate_tile(p.geom, i);
+            for (uint64_t b = 0; b < t.len; ++b) {
+                const uint64_t s = t.stream_off + b;
+                if (s < p.geom.N) {
+                    if (!c.user_ok(ta, s, 1)) return -2;
+                    packed[t.packed_off + b] = base[ta][s];
+                } else {
+                    packed[t.packed_off + b] = 0;
+                }
+            }
+        }
+    }
     return 0;
 }
 

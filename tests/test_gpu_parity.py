@@ -25,18 +25,23 @@ def oracle_msg(case):
     return ho.Message([ho.TensorSpec(tuple(s), tuple(st), e) for (s, st, e) in case.tensors])
 
 
-def plan_of(case, tile_bytes=None):
-    old = os.environ.get("HXT_TILE_BYTES")
+def plan_of(case, tile_bytes=None, two_word=False):
+    """Plan for a case; tile size and the checksum commit variant are read from the environment at creation."""
+    env = {}
     if tile_bytes:
-        os.environ["HXT_TILE_BYTES"] = str(tile_bytes)
+        env["HXT_TILE_BYTES"] = str(tile_bytes)
+    if two_word:
+        env["HXT_TWO_WORD_COMMIT"] = "1"
+    old = {k: os.environ.get(k) for k in env}
+    os.environ.update(env)
     try:
         return hxt.hxt_plan_multi([(s, st, e) for (s, st, e) in case.tensors], case.k, case.B)
     finally:
-        if tile_bytes:
-            if old is None:
-                del os.environ["HXT_TILE_BYTES"]
+        for k, v in old.items():
+            if v is None:
+                del os.environ[k]
             else:
-                os.environ["HXT_TILE_BYTES"] = old
+                os.environ[k] = v
 
 
 def to_dev(a: np.ndarray, offset: int = 0) -> torch.Tensor:
@@ -55,10 +60,10 @@ def specified_mask(m, B, k, nbytes):
     return spec
 
 
-def round_trip_check(case, raws, tile_bytes=None, base_offset=0, nthreads=1):
+def round_trip_check(case, raws, tile_bytes=None, base_offset=0, nthreads=1, two_word=False):
     """pack / checksum / unpack on the GPU vs the oracle; returns the device packed buffer."""
     m = oracle_msg(case)
-    p = plan_of(case, tile_bytes)
+    p = plan_of(case, tile_bytes, two_word)
     B, k = case.B, case.k
     want = ho.pack(m, raws, B, k, fill=0xA5, nthreads=nthreads)
     want_sums = ho.checksum(m, want, B, k, nthreads=nthreads)
@@ -144,6 +149,33 @@ MID_CASES = [
 def test_mid_size_cases(case):
     say("case", case.name)
     round_trip_check(case, make_storages(case, 4321))
+
+
+@pytest.mark.parametrize("case", [c for c in MID_CASES if c.name in ("contig_1MB_ragged", "rows_mid", "transpose_512", "multi_mid")],
+                         ids=lambda c: c.name)
+def test_two_word_checksum_commit(case):
+    # the commit variant used when a chunk's sum and its arrival count do not fit one 64-bit word
+    say("two-word commit", case.name)
+    round_trip_check(case, make_storages(case, 777), two_word=True)
+    round_trip_check(case, make_storages(case, 778), tile_bytes=1024, two_word=True)
+
+
+def test_repeated_calls_leave_accumulators_clean():
+    case = [c for c in MID_CASES if c.name == "contig_bf16_5MiB_tail"][0]
+    raws = make_storages(case, 31)
+    m = oracle_msg(case)
+    p = plan_of(case)
+    want = ho.checksum(m, ho.pack(m, raws, case.B, case.k), case.B, case.k)
+    src = [to_dev(r) for r in raws]
+    packed = torch.zeros(p.packed_bytes, dtype=torch.uint8, device=DEV)
+    other = torch.cuda.Stream()
+    for it in range(6):
+        sums = torch.full((p.num_chunks,), it, dtype=torch.int64, device=DEV)
+        st = other if it % 2 else torch.cuda.current_stream()       # alternate streams: calls are ordered by the library
+        st.wait_stream(torch.cuda.current_stream())
+        hxt.hxt_pack(p, src, packed, sums, st)
+        st.synchronize()
+        assert np.array_equal(sums.cpu().numpy().view(np.uint64), want), "call %d" % it
 
 
 def test_many_tensors_need_several_launch_groups():

@@ -186,9 +186,11 @@ def run_interp(L, case, storages, packed, direction, tile_bytes):
     sizes = (C.c_uint64 * max(n, 1))(*[s.size for s in storages])
     written = np.zeros(max(packed.size, 1), np.uint8)
     kinds = (C.c_int32 * max(n, 1))()
+    uniform = C.c_int32(0)
     rc = L.plan_interp(descs, n, case.k, C.c_uint64(case.B), C.c_uint32(tile_bytes), bases, sizes,
                        C.c_void_p(packed.ctypes.data), C.c_uint64(packed.size), C.c_void_p(written.ctypes.data),
-                       direction, kinds)
+                       direction, kinds, C.byref(uniform))
+    run_interp.last_uniform = bool(uniform.value)
     return rc, written[:packed.size], list(kinds)[:n]
 
 
@@ -208,6 +210,12 @@ def test_work_tables_reproduce_oracle_pack_and_unpack(interp, case, tile_bytes):
         info = ho.chunk_info(m, case.B, case.k, c)
         spec[info["packed_off"]:info["packed_off"] + info["padded"]] = True
     assert np.all(written[spec] == 1) and np.all(written[~spec] == 0)
+    # closed-form path (messages made of one contiguous tensor)
+    got2 = np.full(want.size, 0x99, np.uint8)
+    rc, _, kinds = run_interp(interp, case, raws, got2, 2, tile_bytes)
+    assert rc == 0 and np.array_equal(got2, want)
+    live = [i for i, t in enumerate(case.tensors) if 0 not in t[0]]
+    assert run_interp.last_uniform == (len(live) == 1 and kinds[live[0]] == 1)
     if case.name == "broadcast_stride0":
         return
     dst_o = [np.full(r.size, 0x42, np.uint8) for r in raws]
