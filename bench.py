@@ -2,11 +2,12 @@
 """Benchmark of the pipeline-boundary transfer hot path on one MI355X.
 
 A step is one pass of the whole device-direct path over one batch of synthetic
-input: for every message of the workload (default: the LLaMA-8B-shaped boundary,
-a forward activation and a backward activation gradient, bf16 [4096,1,4096]),
-pack with send-side checksums, then unpack with receive-side checksums.  Inputs
-are resident in HBM before the timed region.  Buffer sets are rotated so that the
-working set is several times the 256 MB last-level cache: the figures are cold.
+input: the messages of the workload (default: the LLaMA-8B-shaped boundary, a
+forward activation and a backward activation gradient, bf16 [4096,1,4096], one
+plan each) are packed with send-side checksums by one batched call, then
+unpacked with receive-side checksums by another.  Inputs are resident in HBM
+before the timed region.  Buffer sets are rotated so that the working set is
+several times the 256 MB last-level cache: the figures are cold.
 
 Prints ONE JSON line.  `value` is the HBM traffic the pack and unpack kernels
 must move (read N + write N each) divided by wall time over the timed steps.
@@ -36,7 +37,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="llama8b_boundary")
     ap.add_argument("--sets", type=int, default=8, help="rotating buffer sets (cold working set)")
-    ap.add_argument("--two-streams", action="store_true", help="issue the messages of a step on separate streams")
+    ap.add_argument("--two-streams", action="store_true",
+                    help="issue the messages of a step one by one on separate streams instead of batched calls")
+    ap.add_argument("--unbatched", action="store_true", help="one call per message on one stream")
     ap.add_argument("--no-checksum", action="store_true", help="diagnostic only: copies without checksums")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-staged", action="store_true")
@@ -84,20 +87,32 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     w = wl.ALL[a.workload]()
-    plan = hxt.hxt_plan_multi([(t.shape, t.strides, t.esize) for t in w.tensors], w.n_lanes, w.chunk_bytes)
-    N = plan.message_bytes
     nmsg = w.messages
+    plans = [hxt.hxt_plan_multi([(t.shape, t.strides, t.esize) for t in w.tensors], w.n_lanes, w.chunk_bytes)
+             for _ in range(nmsg)]                  # independent messages: a plan each
+    plan = plans[0]
+    N = plan.message_bytes
     sets = [[MessageSet(torch, w, plan, w.seed + 1000 * s + m * w.seed_step) for m in range(nmsg)]
             for s in range(a.sets)]
     main_stream = torch.cuda.current_stream()
     streams = [torch.cuda.Stream() for _ in range(nmsg)] if a.two_streams else [main_stream] * nmsg
     use_sums = not a.no_checksum
 
+    batched = not (a.two_streams or a.unbatched)
+    pack_b = [hxt.Batch(plans, [ms.src for ms in S], [ms.packed for ms in S],
+                        [ms.send_sums for ms in S] if use_sums else None) for S in sets]
+    unpack_b = [hxt.Batch(plans, [ms.dst for ms in S], [ms.packed for ms in S],
+                          [ms.recv_sums for ms in S] if use_sums else None) for S in sets]
+
     def step(i):
+        if batched:
+            hxt.hxt_pack_batch(pack_b[i % a.sets], main_stream)
+            hxt.hxt_unpack_batch(unpack_b[i % a.sets], main_stream)
+            return
         for m, ms in enumerate(sets[i % a.sets]):
             st = streams[m]
-            hxt.hxt_pack(plan, ms.src, ms.packed, ms.send_sums if use_sums else None, st)
-            hxt.hxt_unpack(plan, ms.packed, ms.dst, ms.recv_sums if use_sums else None, st)
+            hxt.hxt_pack(plans[m], ms.src, ms.packed, ms.send_sums if use_sums else None, st)
+            hxt.hxt_unpack(plans[m], ms.packed, ms.dst, ms.recv_sums if use_sums else None, st)
 
     def fence():
         if a.two_streams:
@@ -134,12 +149,13 @@ def main():
         if use_sums:
             assert torch.equal(ms.send_sums, ms.recv_sums), "checksum mismatch in the timed run"
 
-    # dominant kernel: hxt::k_uniform, launched once per pack and once per unpack; every launch moves
-    # 2N algorithmic bytes (read N, write N).  Average launch duration = GPU time of the timed region
-    # (HIP events on the launch stream) / launches in it; the launches are back to back on the stream.
-    launches = 2 * nmsg * a.steps
+    # dominant kernel: hxt::k_uniform (pack and unpack instantiations); a launch moves 2N algorithmic bytes
+    # (read N, write N) for every message it serves.  Average launch duration = GPU time of the timed
+    # region (HIP events on the launch stream) / launches in it; the launches are back to back.
+    per_launch = min(nmsg, 4) if batched else 1       # messages served by one launch
+    launches = 2 * nmsg * a.steps // per_launch
     launch_ms = gpu_ms / (launches if not a.two_streams else launches / nmsg)
-    launch_bytes = 2 * N
+    launch_bytes = 2 * N * per_launch
     achieved = launch_bytes / (launch_ms * 1e-3) / 1e9
     out = {
         "metric": "pack+unpack GB/s",
@@ -158,7 +174,9 @@ def main():
                    "n_lanes": w.n_lanes, "chunk_bytes": w.chunk_bytes, "path": "device_direct",
                    "checksums": "fused send+receive" if use_sums else "off",
                    "buffer_sets": a.sets, "cache_state": "cold (rotating sets)",
-                   "streams": nmsg if a.two_streams else 1},
+                   "streams": nmsg if a.two_streams else 1,
+                   "issue": "batched calls (one launch packs all messages of the step, one unpacks them)" if batched
+                   else "one call per message"},
         "pct_hbm_peak": round(100 * gbps / HBM_PEAK_GBPS, 2),
         "roofline": {"bound": "hbm", "kernel": "hxt::k_uniform (pack and unpack instantiations, fused checksum)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",

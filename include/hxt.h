@@ -36,9 +36,14 @@
  *   - Data-plane calls only enqueue work on `stream` (a hipStream_t passed as
  *     void*, NULL = the default stream) and return; they never synchronise.
  *     Ordering between streams is the caller's business (events).
- *   - A plan is immutable after creation and may be used from several streams
- *     at once.  Plans built from equal arguments on the sending and on the
- *     receiving side are interchangeable (the receive is symmetric).
+ *   - A plan's tables are immutable after creation and it may be used from
+ *     several threads and streams.  Calls that ask for checksums use per-plan,
+ *     per-operation accumulators: such calls on one stream are ordered by the
+ *     stream, and when consecutive calls come on different streams the library
+ *     makes the later stream wait for the earlier one (an event), so they never
+ *     overlap.  Messages that should overlap with checksums need a plan each.
+ *     Plans built from equal arguments on the sending and on the receiving side
+ *     are interchangeable (the receive is symmetric).
  */
 #ifndef HXT_H
 #define HXT_H
@@ -149,6 +154,23 @@ int hxt_stage_h2d(const hxt_plan_t *plan, int lane, const void *host_pinned,
  * bytes as read (pad included). */
 int hxt_unpack(const hxt_plan_t *plan, const void *packed, void *const *dst,
                uint64_t *sums, void *stream);
+
+/* ---- steps 2 and 4 for several messages at once -------------------------------
+ * A stage boundary is crossed in both directions at the same point of the schedule
+ * (Section 3.1: two pipeline stages; the forward activation of one micro-batch and
+ * the backward gradient of another).  These calls take n independent messages, each
+ * with its own plan, tensors, packed buffer and (optional) checksum array, and give
+ * exactly the result of n hxt_pack / hxt_unpack calls on `stream` in order, but
+ * messages that consist of one contiguous 16-byte aligned tensor share kernel
+ * launches (up to 4 per launch), which removes per-launch ramp-up for small messages.
+ * plans[i], src[i] / dst[i] (array of that plan's tensor pointers) and packed[i] as
+ * in the single-message calls; sums may be NULL, and sums[i] may be NULL.
+ * HXT_EINVAL additionally if one plan appears twice with checksums requested (its
+ * accumulators serve one message at a time).  Nothing is enqueued on error. */
+int hxt_pack_batch(int n, const hxt_plan_t *const *plans, const void *const *const *src,
+                   void *const *packed, uint64_t *const *sums, void *stream);
+int hxt_unpack_batch(int n, const hxt_plan_t *const *plans, const void *const *packed,
+                     void *const *const *dst, uint64_t *const *sums, void *stream);
 
 /* ---- step 5: stand-alone per-chunk checksum of a packed buffer --------------- */
 int hxt_checksum(const hxt_plan_t *plan, const void *packed, uint64_t *sums, void *stream);

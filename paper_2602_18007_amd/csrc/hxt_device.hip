@@ -44,9 +44,11 @@ struct Acc {
 
 struct SumCtx {
     uint64_t *sums;      // caller's array, one entry per chunk
-    uint8_t *acc;        // plan-owned Acc slots
+    uint8_t *acc;        // plan-owned Acc slots: C * fan first-level slots, then C second-level slots
     uint32_t stride;     // bytes between slots
     uint32_t sum_bits;   // > 0: a chunk's total fits this many bits and the arrival count rides above it
+    uint32_t fan;        // first-level slots per chunk (power of two); 1 = second level only
+    uint32_t chunks;     // C
 };
 
 // ---- small device helpers ----------------------------------------------------
@@ -72,15 +74,39 @@ __device__ __forceinline__ uint64_t words_sum(u32x4 v)
     return (uint64_t(v.x) + uint64_t(v.y)) + (uint64_t(v.z) + uint64_t(v.w));
 }
 
-// Adds this workgroup's partial sum to its chunk.  The workgroup that arrives last owns the
-// total: it writes sums[chunk] and re-zeroes the slot.  Only relaxed device-scope atomics
-// touch the slot, so no cache write-back is needed.
-//   sum_bits > 0: the chunk's total is known to stay below 2^sum_bits (it has at most B/4
-//     words of 32 bits) and the number of contributors fits in the bits above, so one atomic
-//     adds the partial sum and takes the arrival ticket at once.
-//   sum_bits == 0 (huge chunks): the sum and the ticket are two words; the ticket is taken
-//     after the wave has seen its own addition return, which orders the two.
-__device__ __forceinline__ void chunk_commit(uint64_t acc, uint32_t chunk, uint32_t expected, const SumCtx &cx)
+// One arrival at an accumulator slot that expects `expected` of them: adds `value` and reports
+// whether this was the last arrival, in which case `value` becomes the slot's total and the
+// slot is zero again.  Only relaxed device-scope atomics touch a slot (no cache write-back).
+//   sum_bits > 0: totals stay below 2^sum_bits (a chunk has at most B/4 words of 32 bits) and
+//     the arrival count fits in the bits above, so one atomic adds and takes the ticket at once.
+//   sum_bits == 0: sum and ticket are two words; the ticket is taken after the wave has seen
+//     its own addition return, which orders the two.
+__device__ __forceinline__ bool slot_arrive(Acc *a, unsigned long long &value, uint32_t expected, uint32_t sum_bits)
+{
+    if (expected == 1) return true;
+    if (sum_bits) {
+        const unsigned long long one = 1ull << sum_bits;
+        const unsigned long long before = __hip_atomic_fetch_add(&a->sum, one + value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((before >> sum_bits) != expected - 1) return false;
+        __hip_atomic_store(&a->sum, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        value = (before + value) & (one - 1);
+        return true;
+    }
+    const unsigned long long before = __hip_atomic_fetch_add(&a->sum, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("s_waitcnt vmcnt(0)" ::"v"(uint32_t(before)) : "memory");
+    const uint32_t ticket = __hip_atomic_fetch_add(&a->cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (ticket != expected - 1) return false;
+    value = __hip_atomic_exchange(&a->sum, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(&a->cnt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return true;
+}
+
+// Adds this workgroup's partial sum to its chunk.  A chunk made of many tiles spreads its
+// arrivals over `fan` first-level slots (tile ordinal mod fan) so that they do not queue on
+// one address; the last arrival of a first-level slot carries that slot's total to the chunk's
+// second-level slot, and the last arrival there writes sums[chunk].
+__device__ __forceinline__ void chunk_commit(uint64_t acc, uint32_t chunk, uint32_t ordinal, uint32_t expected,
+                                             const SumCtx &cx)
 {
     __shared__ uint64_t part[kThreads / 64];
     for (int o = 32; o > 0; o >>= 1) acc += __shfl_down(acc, o, 64);
@@ -91,26 +117,17 @@ __device__ __forceinline__ void chunk_commit(uint64_t acc, uint32_t chunk, uint3
         unsigned long long s = 0;
 #pragma unroll
         for (int w = 0; w < kThreads / 64; ++w) s += part[w];
-        Acc *a = reinterpret_cast<Acc *>(cx.acc + size_t(chunk) * cx.stride);
-        if (expected == 1) {                       // sole contributor: nothing to combine
-            cx.sums[chunk] = s;
-        } else if (cx.sum_bits) {
-            const unsigned long long one = 1ull << cx.sum_bits;
-            const unsigned long long before = __hip_atomic_fetch_add(&a->sum, one + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if ((before >> cx.sum_bits) == expected - 1) {
-                __hip_atomic_store(&a->sum, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                cx.sums[chunk] = (before + s) & (one - 1);
-            }
+        Acc *top = reinterpret_cast<Acc *>(cx.acc + (size_t(cx.chunks) * cx.fan + chunk) * cx.stride);
+        bool last;
+        if (cx.fan == 1 || expected < 2 * cx.fan) {
+            last = slot_arrive(top, s, expected, cx.sum_bits);
         } else {
-            const unsigned long long before = __hip_atomic_fetch_add(&a->sum, s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            asm volatile("s_waitcnt vmcnt(0)" ::"v"(uint32_t(before)) : "memory");
-            const uint32_t ticket = __hip_atomic_fetch_add(&a->cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (ticket == expected - 1) {
-                const unsigned long long total = __hip_atomic_exchange(&a->sum, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(&a->cnt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                cx.sums[chunk] = total;
-            }
+            const uint32_t sub = ordinal & (cx.fan - 1);
+            const uint32_t share = expected / cx.fan + (sub < (expected & (cx.fan - 1)) ? 1u : 0u);
+            Acc *first = reinterpret_cast<Acc *>(cx.acc + (size_t(chunk) * cx.fan + sub) * cx.stride);
+            last = slot_arrive(first, s, share, cx.sum_bits) && slot_arrive(top, s, cx.fan, cx.sum_bits);
         }
+        if (last) cx.sums[chunk] = s;
     }
 }
 
@@ -166,19 +183,42 @@ __device__ __forceinline__ uint64_t pad_span(uint8_t *pk, uint32_t bytes, uint32
     return acc;
 }
 
-// ---- uniform copy: the message is one contiguous tensor ---------------------------
+// ---- uniform copy: messages that are one contiguous tensor each -------------------
 // No table: tile -> (chunk, lane, slot, offsets) in closed form from the kernel arguments.
+// One launch can serve several such messages (the forward activation and the backward
+// gradient that cross a stage boundary at the same point of the schedule): workgroups
+// [first_tile, first_tile + ntiles) belong to message i.
+constexpr int kMaxBatch = 4;
+
+struct UniformItem {
+    ChunkGeom g;
+    uint8_t *user;
+    uint8_t *packed;
+    SumCtx cx;
+    uint32_t first_tile;
+};
+
+struct UniformArgs {
+    UniformItem it[kMaxBatch];
+    uint32_t n;
+};
+
 template <bool UNPACK, bool CSUM, bool NTU, bool NTP>
-__global__ __launch_bounds__(kThreads) void k_uniform(ChunkGeom g, uint8_t *__restrict__ user,
-                                                      uint8_t *__restrict__ packed, SumCtx cx)
+__global__ __launch_bounds__(kThreads) void k_uniform(UniformArgs a)
 {
-    const TileSpan t = locate_tile(g, blockIdx.x);
+    uint32_t m = 0;
+#pragma unroll
+    for (uint32_t i = 1; i < kMaxBatch; ++i)
+        if (i < a.n && blockIdx.x >= a.it[i].first_tile) m = i;
+    const UniformItem &it = a.it[m];
+    const ChunkGeom &g = it.g;
+    const TileSpan t = locate_tile(g, blockIdx.x - it.first_tile);
     const uint64_t left = g.N > t.stream_off ? g.N - t.stream_off : 0;     // tensor bytes from here on
     const uint32_t data = left < t.len ? uint32_t(left) : t.len;
-    uint8_t *pk = packed + t.packed_off;
-    uint64_t acc = copy_span<UNPACK, CSUM, NTU, NTP>(user + t.stream_off, pk, data);
+    uint8_t *pk = it.packed + t.packed_off;
+    uint64_t acc = copy_span<UNPACK, CSUM, NTU, NTP>(it.user + t.stream_off, pk, data);
     if (data < t.len) acc += pad_span<UNPACK, CSUM>(pk + data, t.len - data, data);
-    if constexpr (CSUM) chunk_commit(acc, t.chunk, t.expected, cx);
+    if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, t.expected, it.cx);
 }
 
 // ---- contiguous tensors of a multi-tensor message: table driven ---------------------
@@ -193,7 +233,7 @@ __global__ __launch_bounds__(kThreads) void k_contig(const Tile *__restrict__ ti
         acc = pad_span<UNPACK, CSUM>(packed + t.packed_off, t.n0, uint32_t(t.packed_off));
     else
         acc = copy_span<UNPACK, CSUM, NTU, NTP>(bases.p[t.tensor] + t.src_off, packed + t.packed_off, t.n0);
-    if constexpr (CSUM) chunk_commit(acc, t.chunk, chunk_tiles[t.chunk], cx);
+    if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, chunk_tiles[t.chunk], cx);
 }
 
 // ---- rows: innermost dimension contiguous, outer dimensions strided -------------
@@ -245,7 +285,7 @@ __global__ __launch_bounds__(kThreads) void k_rows(const Tile *__restrict__ tile
             }
         }
     }
-    if constexpr (CSUM) chunk_commit(acc, t.chunk, chunk_tiles[t.chunk], cx);
+    if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, chunk_tiles[t.chunk], cx);
 }
 
 // ---- transpose: logical inner dimension strided, the one before it contiguous ----
@@ -298,7 +338,7 @@ __global__ __launch_bounds__(kThreads) void k_transpose(const Tile *__restrict__
         if (tx < ni)
             for (uint32_t j = ty; j < nj; j += TY) *reinterpret_cast<E *>(user + j * t.a + tx * sizeof(E)) = lds[j][tx];
     }
-    if constexpr (CSUM) chunk_commit(acc, t.chunk, chunk_tiles[t.chunk], cx);
+    if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, chunk_tiles[t.chunk], cx);
 }
 
 // ---- generic: any strides, one element at a time -------------------------------
@@ -341,7 +381,7 @@ __global__ __launch_bounds__(kThreads) void k_generic(const Tile *__restrict__ t
             }
         }
     }
-    if constexpr (CSUM) chunk_commit(acc, t.chunk, chunk_tiles[t.chunk], cx);
+    if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, chunk_tiles[t.chunk], cx);
 }
 
 // ---- stand-alone checksum of packed chunks (closed-form geometry, no table) ----------
@@ -360,7 +400,7 @@ __global__ __launch_bounds__(kThreads) void k_checksum(ChunkGeom g, const uint8_
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) acc += words_sum(r[u]);
     }
-    chunk_commit(acc, t.chunk, t.expected, cx);
+    chunk_commit(acc, t.chunk, t.ordinal, t.expected, cx);
 }
 
 }  // namespace hxt
@@ -384,7 +424,8 @@ struct hxt_plan {
     uint32_t *d_chunk_tiles = nullptr;
     TensorDev *d_tensors = nullptr;
     uint32_t acc_stride = 0;
-    uint32_t sum_bits_copy = 0, sum_bits_table = 0, sum_bits_csum = 0;   // see chunk_commit
+    uint32_t fan = 1;                           // first-level accumulator slots per chunk
+    uint32_t sum_bits_table = 0, sum_bits_geom = 0;   // see slot_arrive: table-driven copies / closed-form kernels
     int device = -1;
     OpState ops[OP_COUNT];
 };
@@ -440,11 +481,9 @@ void with_hints(F &&f)
 }
 
 template <bool UNPACK, bool CSUM>
-void launch_uniform(const hxt_plan_t &pl, uint8_t *user, uint8_t *packed, const SumCtx &cx, hipStream_t st)
+void launch_uniform(const UniformArgs &a, uint32_t tiles, hipStream_t st)
 {
-    with_hints([&]<bool NTU, bool NTP>() {
-        k_uniform<UNPACK, CSUM, NTU, NTP><<<pl.p.geom.ntiles, kThreads, 0, st>>>(pl.p.geom, user, packed, cx);
-    });
+    with_hints([&]<bool NTU, bool NTP>() { k_uniform<UNPACK, CSUM, NTU, NTP><<<tiles, kThreads, 0, st>>>(a); });
 }
 
 template <bool UNPACK, bool CSUM>
@@ -515,25 +554,33 @@ int claim_slots(hxt_plan_t &pl, Op op, hipStream_t st, SumCtx &cx, uint64_t *sum
     cx.acc = o.acc;
     cx.stride = pl.acc_stride;
     cx.sum_bits = 0;
+    cx.fan = pl.fan;
+    cx.chunks = uint32_t(pl.p.C);
     return HXT_OK;
 }
 
 // Bits a chunk's checksum can occupy (at most B/4 words below 2^32), if the arrival count of
-// `contributors` workgroups still fits above them in a 64-bit word; else 0.
-uint32_t single_word_bits(uint64_t chunk_bytes, uint32_t contributors)
+// up to `arrivals` per slot still fits above them in a 64-bit word; else 0.
+uint32_t single_word_bits(uint64_t chunk_bytes, uint32_t arrivals)
 {
     uint32_t m = 0;
     while ((uint64_t(1) << m) < chunk_bytes / 4) ++m;
     uint32_t cb = 0;
-    while ((uint64_t(1) << cb) <= contributors) ++cb;
+    while ((uint64_t(1) << cb) <= arrivals) ++cb;
     return 32 + m + cb <= 64 ? 32 + m : 0;
+}
+
+// Most arrivals any slot sees when chunks of up to `tiles` tiles fan out over `fan` slots.
+uint32_t max_arrivals(uint32_t tiles, uint32_t fan)
+{
+    return fan == 1 ? tiles : std::max((tiles + fan - 1) / fan, 2 * fan);
 }
 
 template <bool UNPACK, bool CSUM>
 int run_copy(hxt_plan_t &pl, void *const *ptrs, uint8_t *packed, uint64_t *sums, hipStream_t st)
 {
     const Plan &p = pl.p;
-    SumCtx cx{nullptr, nullptr, 0, 0};
+    SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};
     if constexpr (CSUM) {
         int rc = claim_slots(pl, UNPACK ? OP_UNPACK : OP_PACK, st, cx, sums);
         if (rc != HXT_OK) return rc;
@@ -542,8 +589,12 @@ int run_copy(hxt_plan_t &pl, void *const *ptrs, uint8_t *packed, uint64_t *sums,
     if (p.uniform) {
         uint8_t *base = static_cast<uint8_t *>(ptrs[p.uniform_tensor]);
         if (reinterpret_cast<uintptr_t>(base) % 16 == 0) {
-            cx.sum_bits = pl.sum_bits_copy;
-            launch_uniform<UNPACK, CSUM>(pl, base, packed, cx, st);
+            cx.sum_bits = pl.sum_bits_geom;
+            UniformArgs a;
+            std::memset(&a, 0, sizeof a);
+            a.n = 1;
+            a.it[0] = UniformItem{p.geom, base, packed, cx, 0};
+            launch_uniform<UNPACK, CSUM>(a, p.geom.ntiles, st);
             HXT_HIP(hipGetLastError());
             return HXT_OK;
         }
@@ -630,14 +681,24 @@ int upload(hxt_plan_t &pl)
     if ((rc = to_device(&pl.d_tiles, p.tiles)) != HXT_OK) return rc;
     if ((rc = to_device(&pl.d_chunk_tiles, p.chunk_tiles)) != HXT_OK) return rc;
     if ((rc = to_device(&pl.d_tensors, p.tdev)) != HXT_OK) return rc;
-    // accumulator slots: 256 bytes apart (separate memory channels) unless that would be large
-    pl.acc_stride = p.C <= 16384 ? 256 : uint32_t(sizeof(Acc));
-    uint32_t most = 0;
+    // Accumulator slots.  Chunks of 128 tiles or more fan out over up to 16 first-level slots so
+    // that a few dozen arrivals at most queue on one address (measured: a 25 MiB chunk of 1600
+    // tiles loses 20 % without it, a 1 MiB chunk of 64 tiles is faster with a single slot); slots
+    // are 256 bytes apart (separate memory channels) unless that would be large.
+    uint32_t most = p.geom.tpc;
     for (uint32_t n : p.chunk_tiles) most = std::max(most, n);
-    pl.sum_bits_table = env_int("HXT_TWO_WORD_COMMIT", 0) ? 0 : single_word_bits(p.B, most);
-    pl.sum_bits_copy = env_int("HXT_TWO_WORD_COMMIT", 0) ? 0 : single_word_bits(p.B, p.geom.tpc);
-    pl.sum_bits_csum = pl.sum_bits_copy;
-    const size_t bytes = size_t(p.C) * pl.acc_stride;
+    pl.fan = 1;
+    while (pl.fan < 16 && most >= 128 * pl.fan) pl.fan *= 2;
+    pl.fan = uint32_t(std::max(1, std::min<int>(int(pl.fan), env_int("HXT_FAN", 16))));
+    while (pl.fan & (pl.fan - 1)) pl.fan &= pl.fan - 1;                    // keep a power of two
+    const bool two_word = env_int("HXT_TWO_WORD_COMMIT", 0) != 0;
+    uint32_t most_table = 0;
+    for (uint32_t n : p.chunk_tiles) most_table = std::max(most_table, n);
+    pl.sum_bits_table = two_word ? 0 : single_word_bits(p.B, max_arrivals(most_table, pl.fan));
+    pl.sum_bits_geom = two_word ? 0 : single_word_bits(p.B, max_arrivals(p.geom.tpc, pl.fan));
+    const size_t slots = size_t(p.C) * (pl.fan + 1);
+    pl.acc_stride = slots <= 65536 ? 256 : uint32_t(sizeof(Acc));
+    const size_t bytes = slots * pl.acc_stride;
     for (OpState &o : pl.ops) {
         HXT_HIP(hipMalloc(reinterpret_cast<void **>(&o.acc), bytes));
         HXT_HIP(hipMemset(o.acc, 0, bytes));
@@ -688,6 +749,68 @@ int stage(const hxt_plan_t *plan, int lane, const void *from, void *to, hipMemcp
     for (int i = 0; i < n; ++i)
         HXT_HIP(hipMemcpyAsync(static_cast<uint8_t *>(to) + r[i][0], static_cast<const uint8_t *>(from) + r[i][0],
                                r[i][1], kind, static_cast<hipStream_t>(stream)));
+    return HXT_OK;
+}
+
+// Batch: the messages that the uniform kernel can take (one contiguous 16-byte aligned tensor,
+// same checksum choice) are fused, up to kMaxBatch per launch; the rest go one by one.
+template <bool UNPACK>
+int run_batch(int n, const hxt_plan_t *const *plans, void *const *const *tensors, void *const *packed,
+              uint64_t *const *sums, hipStream_t st)
+{
+    if (n < 0 || (n > 0 && (!plans || !tensors || !packed))) return HXT_EINVAL;
+    for (int i = 0; i < n; ++i) {                      // validate everything before enqueuing anything
+        int rc = check_common(plans[i], packed[i]);
+        if (rc != HXT_OK) return rc;
+        if (plans[i]->p.C == 0) continue;
+        if ((rc = check_tensor_pointers(plans[i]->p, tensors[i])) != HXT_OK) return rc;
+        if (UNPACK && !plans[i]->p.all_unpack_safe) return HXT_EOVERLAP;
+        for (int j = 0; j < i; ++j)
+            if (plans[j] == plans[i] && sums && sums[i] && sums[j]) return HXT_EINVAL;   // one accumulator set per plan
+    }
+    int i = 0;
+    while (i < n) {
+        hxt_plan_t &pl = *const_cast<hxt_plan_t *>(plans[i]);
+        const Plan &p = pl.p;
+        uint64_t *sm = sums ? sums[i] : nullptr;
+        auto fusable = [&](int j) {
+            const Plan &q = plans[j]->p;
+            return q.C != 0 && q.uniform && reinterpret_cast<uintptr_t>(tensors[j][q.uniform_tensor]) % 16 == 0 &&
+                   ((sums ? sums[j] : nullptr) != nullptr) == (sm != nullptr);
+        };
+        if (p.C == 0) {
+            ++i;
+            continue;
+        }
+        if (!fusable(i)) {
+            uint8_t *pk = static_cast<uint8_t *>(packed[i]);
+            int rc = sm ? run_copy<UNPACK, true>(pl, tensors[i], pk, sm, st) : run_copy<UNPACK, false>(pl, tensors[i], pk, nullptr, st);
+            if (rc != HXT_OK) return rc;
+            ++i;
+            continue;
+        }
+        UniformArgs a;
+        std::memset(&a, 0, sizeof a);
+        uint64_t tiles = 0;
+        int j = i;
+        while (j < n && a.n < uint32_t(kMaxBatch) && fusable(j) && tiles + plans[j]->p.geom.ntiles < (uint64_t(1) << 31)) {
+            hxt_plan_t &pj = *const_cast<hxt_plan_t *>(plans[j]);
+            SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};
+            if (sm) {
+                int rc = claim_slots(pj, UNPACK ? OP_UNPACK : OP_PACK, st, cx, sums[j]);
+                if (rc != HXT_OK) return rc;
+                cx.sum_bits = pj.sum_bits_geom;
+            }
+            a.it[a.n++] = UniformItem{pj.p.geom, static_cast<uint8_t *>(tensors[j][pj.p.uniform_tensor]),
+                                      static_cast<uint8_t *>(packed[j]), cx, uint32_t(tiles)};
+            tiles += pj.p.geom.ntiles;
+            ++j;
+        }
+        if (sm) launch_uniform<UNPACK, true>(a, uint32_t(tiles), st);
+        else launch_uniform<UNPACK, false>(a, uint32_t(tiles), st);
+        HXT_HIP(hipGetLastError());
+        i = j;
+    }
     return HXT_OK;
 }
 
@@ -818,6 +941,19 @@ int hxt_unpack(const hxt_plan_t *plan, const void *packed, void *const *dst, uin
     return sums ? run_copy<true, true>(pl, dst, pk, sums, st) : run_copy<true, false>(pl, dst, pk, nullptr, st);
 }
 
+int hxt_pack_batch(int n, const hxt_plan_t *const *plans, const void *const *const *src, void *const *packed,
+                   uint64_t *const *sums, void *stream)
+{
+    return run_batch<false>(n, plans, const_cast<void *const *const *>(src), packed, sums,
+                            static_cast<hipStream_t>(stream));
+}
+
+int hxt_unpack_batch(int n, const hxt_plan_t *const *plans, const void *const *packed, void *const *const *dst,
+                     uint64_t *const *sums, void *stream)
+{
+    return run_batch<true>(n, plans, dst, const_cast<void *const *>(packed), sums, static_cast<hipStream_t>(stream));
+}
+
 int hxt_checksum(const hxt_plan_t *plan, const void *packed, uint64_t *sums, void *stream)
 {
     int rc = check_common(plan, packed);
@@ -825,9 +961,9 @@ int hxt_checksum(const hxt_plan_t *plan, const void *packed, uint64_t *sums, voi
     if (!sums) return HXT_EINVAL;
     hxt_plan_t &pl = *const_cast<hxt_plan_t *>(plan);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    SumCtx cx{nullptr, nullptr, 0, 0};
+    SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};
     if ((rc = claim_slots(pl, OP_CHECKSUM, st, cx, sums)) != HXT_OK) return rc;
-    cx.sum_bits = pl.sum_bits_csum;
+    cx.sum_bits = pl.sum_bits_geom;
     const uint8_t *pk = static_cast<const uint8_t *>(packed);
     if (tuning().nt_packed)
         k_checksum<true><<<pl.p.geom.ntiles, kThreads, 0, st>>>(pl.p.geom, pk, cx);

@@ -45,7 +45,8 @@ struct Tile {
     uint32_t kind;
     uint32_t n0;
     uint32_t n1;
-    uint32_t reserved[3];
+    uint32_t ordinal;  // position of this tile among the tiles of its chunk (0 .. chunk_tiles[chunk] - 1)
+    uint32_t reserved[2];
 };
 static_assert(sizeof(Tile) == 64, "Tile must stay 64 bytes");
 
@@ -77,6 +78,7 @@ struct ChunkGeom {
 
 struct TileSpan {
     uint32_t chunk;
+    uint32_t ordinal;    // position of the tile inside its chunk
     uint32_t expected;   // tiles that make up this chunk
     uint64_t stream_off; // first stream byte of the tile
     uint64_t packed_off; // where it lives in the packed buffer
@@ -92,6 +94,7 @@ HXT_HD TileSpan locate_tile(const ChunkGeom &g, uint32_t t)
     const uint64_t chunk_len = (c + 1 == g.C) ? g.L - uint64_t(c) * g.B : g.B;
     const uint64_t left = chunk_len - in_chunk;
     s.chunk = c;
+    s.ordinal = j;
     s.expected = (c + 1 == g.C) ? g.last_tiles : g.tpc;
     s.stream_off = uint64_t(c) * g.B + in_chunk;
     s.packed_off = (uint64_t(lane) * g.q + (lane < g.r ? lane : g.r) + slot) * g.B + in_chunk;

@@ -139,7 +139,7 @@ struct Builder {
              uint64_t b, uint32_t chunk, uint32_t n0, uint32_t n1)
     {
         RawTile r;
-        r.t = Tile{packed_off, src_off, a, b, chunk, 0, uint32_t(kind), n0, n1, {0, 0, 0}};
+        r.t = Tile{packed_off, src_off, a, b, chunk, 0, uint32_t(kind), n0, n1, 0, {0, 0}};
         r.tensor_abs = tensor;
         by_kernel[kernel].push_back(r);
     }
@@ -292,8 +292,8 @@ int build_plan(const hxt_tensor_desc_t *descs, int n_tensors, int n_lanes, size_
                 Tile t = v[i].t;
                 t.tensor = v[i].tensor_abs - g.tensor_base;
                 g.n_tensors = std::max(g.n_tensors, t.tensor + 1);
+                t.ordinal = p.chunk_tiles[t.chunk]++;
                 p.tiles.push_back(t);
-                ++p.chunk_tiles[t.chunk];
                 ++g.count;
                 ++i;
             }

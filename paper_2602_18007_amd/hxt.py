@@ -29,6 +29,7 @@ EXPORTS = (
     "hxt_plan_packed_bytes", "hxt_plan_chunk_bytes", "hxt_plan_num_chunks", "hxt_plan_num_lanes",
     "hxt_plan_num_tensors", "hxt_plan_chunk_info", "hxt_plan_lane_info", "hxt_plan_tensor_unpack_safe",
     "hxt_plan_tensor_kind", "hxt_pack", "hxt_stage_d2h", "hxt_stage_h2d", "hxt_unpack", "hxt_checksum",
+    "hxt_pack_batch", "hxt_unpack_batch",
     "hxt_strerror", "hxt_last_hip_error", "hxt_version",
 )
 
@@ -96,6 +97,8 @@ def lib():
             "hxt_stage_h2d": (i, [vp, i, vp, vp, vp]),
             "hxt_unpack": (i, [vp, vp, C.POINTER(vp), u64p, vp]),
             "hxt_checksum": (i, [vp, vp, u64p, vp]),
+            "hxt_pack_batch": (i, [i, C.POINTER(vp), C.POINTER(C.POINTER(vp)), C.POINTER(vp), C.POINTER(vp), vp]),
+            "hxt_unpack_batch": (i, [i, C.POINTER(vp), C.POINTER(vp), C.POINTER(C.POINTER(vp)), C.POINTER(vp), vp]),
             "hxt_strerror": (C.c_char_p, [i]),
             "hxt_last_hip_error": (i, []),
             "hxt_version": (C.c_char_p, []),
@@ -234,6 +237,31 @@ def hxt_pack(plan: Plan, src: Sequence, packed, sums=None, stream=None) -> None:
 
 def hxt_unpack(plan: Plan, packed, dst: Sequence, sums=None, stream=None) -> None:
     _check(lib().hxt_unpack(plan.handle, _ptr(packed), _ptr_array(dst), _ptr(sums), _stream(stream)), "hxt_unpack")
+
+
+class Batch:
+    """Pre-marshalled arguments of hxt_pack_batch / hxt_unpack_batch for a fixed set of messages."""
+
+    def __init__(self, plans: Sequence[Plan], tensors: Sequence[Sequence], packed: Sequence, sums: Optional[Sequence]):
+        n = len(plans)
+        assert len(tensors) == n and len(packed) == n and (sums is None or len(sums) == n)
+        self.n = n
+        self.plans = (C.c_void_p * max(n, 1))(*[p.handle.value for p in plans])
+        self._rows = [_ptr_array(t) for t in tensors]
+        self.tensors = (C.POINTER(C.c_void_p) * max(n, 1))(*[C.cast(r, C.POINTER(C.c_void_p)) for r in self._rows])
+        self.packed = _ptr_array(packed)
+        self.sums = _ptr_array(sums) if sums is not None else None
+        self._keep = (plans, tensors, packed, sums)
+
+
+def hxt_pack_batch(batch: Batch, stream=None) -> None:
+    _check(lib().hxt_pack_batch(batch.n, batch.plans, batch.tensors, batch.packed, batch.sums, _stream(stream)),
+           "hxt_pack_batch")
+
+
+def hxt_unpack_batch(batch: Batch, stream=None) -> None:
+    _check(lib().hxt_unpack_batch(batch.n, batch.plans, batch.packed, batch.tensors, batch.sums, _stream(stream)),
+           "hxt_unpack_batch")
 
 
 def hxt_checksum(plan: Plan, packed, sums, stream=None) -> None:

@@ -107,7 +107,12 @@ extern "C" int plan_interp(const hxt_tensor_desc_t *descs, int n_tensors, int n_
     if (next != p.tiles.size()) return -5;
     // per-chunk tile counts (the checksum's "last arrival" test depends on them)
     std::vector<uint32_t> count(p.C, 0);
-    for (const Tile &t : p.tiles) ++count[t.chunk];
+    std::vector<std::vector<uint8_t>> ord(p.C);
+    for (uint64_t ch = 0; ch < p.C; ++ch) ord[ch].assign(p.chunk_tiles[ch], 0);
+    for (const Tile &t : p.tiles) {
+        ++count[t.chunk];
+        if (t.ordinal >= p.chunk_tiles[t.chunk] || ord[t.chunk][t.ordinal]++) return -5;   // ordinals are a permutation
+    }
     if (count != p.chunk_tiles) return -5;
     // closed-form geometry: its tiles must cover every chunk's padded bytes exactly once, report
     // the right chunk and the right number of tiles per chunk
@@ -119,6 +124,7 @@ extern "C" int plan_interp(const hxt_tensor_desc_t *descs, int n_tensors, int n_
         const uint64_t c_lo = p.chunk_packed_off(t.chunk), c_hi = c_lo + p.chunk_padded(t.chunk);
         if (t.packed_off < c_lo || t.packed_off + t.len > c_hi || t.len % 256 || t.len == 0) return -6;
         if (t.packed_off - c_lo != t.stream_off - uint64_t(t.chunk) * p.B) return -6;
+        if (t.ordinal != per_chunk[t.chunk]) return -6;
         ++per_chunk[t.chunk];
         for (uint64_t b = 0; b < t.len; ++b) ++seen[t.packed_off + b];
     }

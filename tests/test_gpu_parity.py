@@ -178,6 +178,42 @@ def test_repeated_calls_leave_accumulators_clean():
         assert np.array_equal(sums.cpu().numpy().view(np.uint64), want), "call %d" % it
 
 
+def test_batch_calls_equal_single_calls():
+    # mixed batch: three uniform messages (one without checksums, so it cannot share a launch with its
+    # neighbours), a strided one, an empty one and a multi-tensor one
+    names = ["contig_1MB_ragged", "contig_bf16_5MiB_tail", "rows_mid", "contig_1MB_ragged", "multi_mid"]
+    cases = [c for n in names for c in MID_CASES if c.name == n] + [case_by_name("empty_tensor"), case_by_name("single_lane")]
+    want_sums = [True, True, True, False, True, True, True]
+    plans = [plan_of(c) for c in cases]
+    raws = [make_storages(c, 900 + i) for i, c in enumerate(cases)]
+    src = [[to_dev(r) for r in rs] for rs in raws]
+    packed = [torch.full((max(p.packed_bytes, 1),), 0xA5, dtype=torch.uint8, device=DEV) for p in plans]
+    sums = [torch.full((max(p.num_chunks, 1),), -3, dtype=torch.int64, device=DEV) if w else None
+            for p, w in zip(plans, want_sums)]
+    say("batch of", len(cases))
+    hxt.hxt_pack_batch(hxt.Batch(plans, src, packed, sums))
+    dst = [[to_dev(np.full(r.size, 0x3C, np.uint8)) for r in rs] for rs in raws]
+    rsums = [torch.full_like(s_, 9) if s_ is not None else None for s_ in sums]
+    hxt.hxt_unpack_batch(hxt.Batch(plans, dst, packed, rsums))
+    torch.cuda.synchronize()
+    for i, c in enumerate(cases):
+        m = oracle_msg(c)
+        want = ho.pack(m, raws[i], c.B, c.k, fill=0xA5)
+        assert np.array_equal(packed[i].cpu().numpy()[:want.size], want), c.name
+        if want_sums[i]:
+            ws = ho.checksum(m, want, c.B, c.k)
+            assert np.array_equal(sums[i].cpu().numpy().view(np.uint64)[:ws.size], ws), c.name
+            assert np.array_equal(rsums[i].cpu().numpy().view(np.uint64)[:ws.size], ws), c.name
+        dst_o = [np.full(r.size, 0x3C, np.uint8) for r in raws[i]]
+        ho.unpack(m, want, c.B, c.k, dst_o)
+        for a, b in zip(dst_o, dst[i]):
+            assert np.array_equal(b.cpu().numpy(), a), c.name
+    # the same plan twice with checksums is refused
+    with pytest.raises(hxt.HxtError) as e:
+        hxt.hxt_pack_batch(hxt.Batch([plans[0], plans[0]], [src[0], src[0]], [packed[0], packed[0]], [sums[0], sums[0]]))
+    assert e.value.status == hxt.HXT_EINVAL
+
+
 def test_many_tensors_need_several_launch_groups():
     rng = np.random.default_rng(8)
     tensors = tuple(contig((int(rng.integers(1, 3000)),), int(rng.choice([1, 2, 4]))) for _ in range(150))
