@@ -289,7 +289,7 @@ __global__ __launch_bounds__(kThreads) void k_rows(const Tile *__restrict__ tile
 }
 
 // ---- transpose: logical inner dimension strided, the one before it contiguous ----
-// A tile is ni x nj elements (<= 64 x 64).  Storage is read/written along i, the packed
+// A tile is ni x nj elements (at most 128 x 128 for 1- and 2-byte elements, 64 x 64 otherwise).  Storage is read/written along i, the packed
 // stream along j, both coalesced; the swap of roles goes through a padded LDS tile.
 template <typename E>
 __device__ __forceinline__ uint64_t elem_weighted(E v, uint64_t packed_pos)
@@ -301,42 +301,90 @@ __device__ __forceinline__ uint64_t elem_weighted(E v, uint64_t packed_pos)
     }
 }
 
+// Vector path of the transpose: src has R rows of Cc contiguous elements, dst gets Cc rows of R
+// contiguous elements, dst[c][r] = src[r][c]; R and Cc are multiples of V = 16 / sizeof(E) and
+// every row start is 16-byte aligned.  16-byte global loads along src rows land in LDS rows of
+// T elements whose 16-byte slots are XOR-swizzled with the row group, so that the V element
+// reads that assemble one dst vector (same column, V consecutive rows) and the other lanes'
+// reads of the same instruction fall into distinct banks; then 16-byte global stores along dst
+// rows.  The sum is taken on whichever side is the packed buffer.
+template <typename E, bool SRC_IS_PACKED, bool CSUM>
+__device__ __forceinline__ uint64_t transpose_vec(const uint8_t *src, uint64_t src_pitch, uint32_t R, uint32_t Cc,
+                                                  uint8_t *dst, uint64_t dst_pitch, uint8_t *lds)
+{
+    constexpr uint32_t T = transpose_tile(sizeof(E)), V = 16 / sizeof(E), ROWB = T * sizeof(E), NV = T / V;
+    uint64_t acc = 0;
+    const uint32_t nvs = Cc / V;                           // vectors per src row
+    for (uint32_t v = threadIdx.x; v < R * nvs; v += kThreads) {
+        const uint32_t r = v / nvs, cv = v - r * nvs;
+        const u32x4 x = *reinterpret_cast<const u32x4 *>(src + r * src_pitch + cv * 16);
+        if constexpr (CSUM && SRC_IS_PACKED) acc += words_sum(x);
+        *reinterpret_cast<u32x4 *>(lds + r * ROWB + ((cv ^ ((r / V) % NV)) * 16)) = x;
+    }
+    __syncthreads();
+    const uint32_t nvd = R / V;                            // vectors per dst row
+    for (uint32_t v = threadIdx.x; v < Cc * nvd; v += kThreads) {
+        const uint32_t c = v / nvd, dv = v - c * nvd;
+        union {
+            E e[V];
+            u32x4 x;
+        } o;
+#pragma unroll
+        for (uint32_t q = 0; q < V; ++q) {
+            const uint32_t r = dv * V + q;
+            o.e[q] = *reinterpret_cast<const E *>(lds + r * ROWB + (((c / V) ^ ((r / V) % NV)) * 16) + (c % V) * sizeof(E));
+        }
+        if constexpr (CSUM && !SRC_IS_PACKED) acc += words_sum(o.x);
+        *reinterpret_cast<u32x4 *>(dst + c * dst_pitch + dv * 16) = o.x;
+    }
+    return acc;
+}
+
 template <typename E, bool UNPACK, bool CSUM>
 __global__ __launch_bounds__(kThreads) void k_transpose(const Tile *__restrict__ tiles,
                                                         const uint32_t *__restrict__ chunk_tiles, BasePtrs bases,
                                                         uint8_t *__restrict__ packed, SumCtx cx)
 {
-    constexpr uint32_t T = kTransposeTile;
-    __shared__ E lds[T][T + 1];
+    constexpr uint32_t T = transpose_tile(sizeof(E)), V = 16 / sizeof(E);
+    __shared__ __attribute__((aligned(16))) uint8_t lds_raw[T * (T + 1) * sizeof(E)];
     const Tile t = tiles[blockIdx.x];
     uint8_t *user = bases.p[t.tensor] + t.src_off;
     uint8_t *pk = packed + t.packed_off;
     const uint32_t ni = t.n0, nj = t.n1;
-    const uint32_t tx = threadIdx.x & (T - 1), ty = threadIdx.x / T;
-    constexpr uint32_t TY = kThreads / T;
     uint64_t acc = 0;
-    if constexpr (!UNPACK) {
-        if (tx < ni)
-            for (uint32_t j = ty; j < nj; j += TY) lds[j][tx] = *reinterpret_cast<const E *>(user + j * t.a + tx * sizeof(E));
-        __syncthreads();
-        if (tx < nj)
-            for (uint32_t i = ty; i < ni; i += TY) {
-                const E v = lds[tx][i];
-                const uint64_t pos = i * t.b + tx * sizeof(E);
-                *reinterpret_cast<E *>(pk + pos) = v;
-                if constexpr (CSUM) acc += elem_weighted(v, t.packed_off + pos);
-            }
+    const bool vec_ok = ((ni | nj) % V) == 0 &&
+                        ((reinterpret_cast<uintptr_t>(user) | reinterpret_cast<uintptr_t>(pk) | t.a | t.b) % 16) == 0;
+    if (vec_ok) {
+        // storage: nj rows (pitch a) of ni contiguous elements; packed: ni rows (pitch b) of nj elements
+        if constexpr (!UNPACK) acc = transpose_vec<E, false, CSUM>(user, t.a, nj, ni, pk, t.b, lds_raw);
+        else acc = transpose_vec<E, true, CSUM>(pk, t.b, ni, nj, user, t.a, lds_raw);
     } else {
-        if (tx < nj)
-            for (uint32_t i = ty; i < ni; i += TY) {
-                const uint64_t pos = i * t.b + tx * sizeof(E);
-                const E v = *reinterpret_cast<const E *>(pk + pos);
-                lds[tx][i] = v;
-                if constexpr (CSUM) acc += elem_weighted(v, t.packed_off + pos);
-            }
-        __syncthreads();
-        if (tx < ni)
-            for (uint32_t j = ty; j < nj; j += TY) *reinterpret_cast<E *>(user + j * t.a + tx * sizeof(E)) = lds[j][tx];
+        E(*lds)[T + 1] = reinterpret_cast<E(*)[T + 1]>(lds_raw);
+        const uint32_t tx = threadIdx.x & (T - 1), ty = threadIdx.x / T;
+        constexpr uint32_t TY = kThreads / T;
+        if constexpr (!UNPACK) {
+            if (tx < ni)
+                for (uint32_t j = ty; j < nj; j += TY) lds[j][tx] = *reinterpret_cast<const E *>(user + j * t.a + tx * sizeof(E));
+            __syncthreads();
+            if (tx < nj)
+                for (uint32_t i = ty; i < ni; i += TY) {
+                    const E v = lds[tx][i];
+                    const uint64_t pos = i * t.b + tx * sizeof(E);
+                    *reinterpret_cast<E *>(pk + pos) = v;
+                    if constexpr (CSUM) acc += elem_weighted(v, t.packed_off + pos);
+                }
+        } else {
+            if (tx < nj)
+                for (uint32_t i = ty; i < ni; i += TY) {
+                    const uint64_t pos = i * t.b + tx * sizeof(E);
+                    const E v = *reinterpret_cast<const E *>(pk + pos);
+                    lds[tx][i] = v;
+                    if constexpr (CSUM) acc += elem_weighted(v, t.packed_off + pos);
+                }
+            __syncthreads();
+            if (tx < ni)
+                for (uint32_t j = ty; j < nj; j += TY) *reinterpret_cast<E *>(user + j * t.a + tx * sizeof(E)) = lds[j][tx];
+        }
     }
     if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, chunk_tiles[t.chunk], cx);
 }

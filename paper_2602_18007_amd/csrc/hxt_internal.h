@@ -158,7 +158,8 @@ int build_plan(const hxt_tensor_desc_t *tensors, int n_tensors, int n_lanes, siz
                uint32_t tile_bytes, Plan &out);
 
 constexpr uint32_t kDefaultTileBytes = 16384;  // bytes of the stream one workgroup moves (linear kinds)
-constexpr uint32_t kTransposeTile = 64;        // a TRANSPOSE tile is at most 64 x 64 elements
+// A TRANSPOSE tile is at most T x T elements, T chosen so that a tile row is 128-512 bytes.
+HXT_HD constexpr uint32_t transpose_tile(uint32_t esize) { return esize <= 2 ? 128u : 64u; }
 
 }  // namespace hxt
 

@@ -163,7 +163,7 @@ struct Builder {
         const TensorPlan &t = p.tensors[ti];
         const int n = t.ndim;
         const uint64_t e = t.esize, I = t.shape[n - 2], J = t.shape[n - 1], sJ = t.stride[n - 1];
-        const uint64_t T = kTransposeTile;
+        const uint64_t T = transpose_tile(uint32_t(e));
         auto batch_off = [&](uint64_t batch) {           // storage offset (elements) of a batch index
             uint64_t off = 0;
             for (int d = n - 3; d >= 0; --d) {

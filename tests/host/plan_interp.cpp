@@ -92,7 +92,7 @@ extern "C" int plan_interp(const hxt_tensor_desc_t *descs, int n_tensors, int n_
                     rc = put(t.packed_off + b, logical_to_storage(td, t.src_off + b), false);
                 break;
             case K_TRANSPOSE:
-                if (g.kernel != K_TRANSPOSE || t.n0 > kTransposeTile || t.n1 > kTransposeTile) return -5;
+                if (g.kernel != K_TRANSPOSE || t.n0 > transpose_tile(td.esize) || t.n1 > transpose_tile(td.esize)) return -5;
                 for (uint64_t i2 = 0; i2 < t.n0 && !rc; ++i2)
                     for (uint64_t j = 0; j < t.n1 && !rc; ++j)
                         for (uint64_t b = 0; b < uint64_t(td.esize) && !rc; ++b)

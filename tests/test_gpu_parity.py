@@ -139,6 +139,9 @@ MID_CASES = [
     Case("transpose_batch_f32", (((3, 70, 90), (70 * 100, 1, 70), 4),), 4, 1024),
     Case("transpose_u8", (((130, 67), (1, 130), 1),), 2, 512),
     Case("transpose_f64", (((100, 60), (1, 128), 8),), 3, 2048),
+    Case("transpose_u8_vec", (((128, 96), (1, 128), 1),), 2, 4096),
+    Case("transpose_bf16_vec_partial", (((72, 40), (1, 80), 2),), 2, 8192),
+    Case("transpose_f32_vec_batched", (((5, 128, 68), (128, 1, 5 * 128), 4),), 4, 32768),
     Case("generic_mid", (((50, 30, 20), (20, 1000, 1), 2),), 3, 4096),
     Case("multi_mid", (contig((70001,), 1), ((64, 2, 128), (128, 64 * 128, 1), 2), ((96, 80), (1, 96), 4),
                        contig((3, 1000), 8), ((33, 10), (20, 2), 2)), 4, 8192),
