@@ -40,6 +40,8 @@ def parse():
     ap.add_argument("--two-streams", action="store_true",
                     help="issue the messages of a step one by one on separate streams instead of batched calls")
     ap.add_argument("--unbatched", action="store_true", help="one call per message on one stream")
+    ap.add_argument("--path", default="device_direct", choices=["device_direct", "cpu_forward"],
+                    help="for --workload stream_1f1b: how the packed buffer travels")
     ap.add_argument("--no-checksum", action="store_true", help="diagnostic only: copies without checksums")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-staged", action="store_true")
@@ -87,6 +89,9 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     w = wl.ALL[a.workload]()
+    if w.name == "stream_1f1b":
+        print(json.dumps(stream_bench(torch, hxt, w, a)))
+        return
     nmsg = w.messages
     plans = [hxt.hxt_plan_multi([(t.shape, t.strides, t.esize) for t in w.tensors], w.n_lanes, w.chunk_bytes)
              for _ in range(nmsg)]                  # independent messages: a plan each
@@ -185,21 +190,79 @@ def main():
                      "launches": launches, "gpu_ms_timed_region": round(gpu_ms, 4)},
     }
     if not a.no_staged:
-        out["staged"] = staged_round_trip(torch, hxt, w, plan, sets[0][0])
+        out["staged"] = staged_round_trip(torch, hxt, w, plans, sets[0])
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))
 
 
-def staged_round_trip(torch, hxt, w, plan, ms):
-    """CPU-forwarding leg on the same message: D2H per lane on one stream, H2D per lane on another,
-    chained lane by lane with events; against a pinned hipMemcpy probe of the same size."""
-    nb, N, k = plan.packed_bytes, plan.message_bytes, w.n_lanes
-    host = torch.empty(nb, dtype=torch.uint8).pin_memory()
-    recv = torch.empty(nb, dtype=torch.uint8, device="cuda:0")
+def stream_bench(torch, hxt, w, a):
+    """The micro-batch stream: one step = all micro-batches through hxt_exchange_stream (two buffer sets,
+    three streams), so that pack of one micro-batch overlaps staging/unpack of the previous ones."""
+    dev = "cuda:0"
+    t = w.tensors[0]
+    plan = hxt.hxt_plan(t.shape, t.strides, t.esize, w.n_lanes, w.chunk_bytes)
+    N, C, nb, nmsg = plan.message_bytes, plan.num_chunks, plan.packed_bytes, w.messages
+    g = torch.Generator(device=dev)
+    g.manual_seed(w.seed)
+    src = [[(torch.randn(t.storage_elems, generator=g, device=dev) * w.std).to(torch.bfloat16)] for _ in range(nmsg)]
+    dst = [[torch.zeros_like(s_[0])] for s_ in src]
+    fwd = a.path == "cpu_forward"
+    send = [torch.empty(nb, dtype=torch.uint8, device=dev) for _ in range(2)]
+    recv = [torch.empty(nb, dtype=torch.uint8, device=dev) for _ in range(2)] if fwd else None
+    host = [torch.empty(nb, dtype=torch.uint8).pin_memory() for _ in range(2)] if fwd else None
+    s_send = torch.zeros((nmsg, C), dtype=torch.int64, device=dev)
+    s_recv = torch.zeros_like(s_send)
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    x = hxt.Exchange(src, dst, send, hxt.HXT_CPU_FORWARD if fwd else hxt.HXT_DEVICE_DIRECT, recv, host,
+                     None if a.no_checksum else s_send, None if a.no_checksum else s_recv, *streams)
+    steps = a.steps if not fwd else max(1, min(a.steps, 20))
+    warm = a.warmup if not fwd else max(1, min(a.warmup, 2))
+
+    def one_pass():
+        hxt.hxt_exchange_stream(plan, x)
+        for st in streams[:2]:                        # the next pass reuses the buffers: join on the last stream
+            streams[2].wait_stream(st)
+        for st in streams[:2]:
+            st.wait_stream(streams[2])
+
+    for _ in range(warm):
+        one_pass()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        one_pass()
+    torch.cuda.synchronize()
+    sec = time.perf_counter() - t0
+    for s_, d_ in zip(src, dst):
+        assert torch.equal(s_[0].view(torch.int16), d_[0].view(torch.int16)), "round trip mismatch"
+    if not a.no_checksum:
+        assert torch.equal(s_send, s_recv)
+    gbps = 4 * N * nmsg * steps / sec / 1e9
+    out = {"metric": "pack+unpack GB/s", "value": round(gbps, 1), "unit": "GB/s", "n_gpus": 1, "steps": steps,
+           "warmup": warm, "ms_per_step": round(sec / steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "u32", "data": "synthetic",
+           "config": {"workload": w.name, "note": w.note, "message_bytes": N, "messages_per_step": nmsg,
+                      "n_lanes": w.n_lanes, "chunk_bytes": w.chunk_bytes, "path": a.path, "buffer_sets": 2,
+                      "streams": 3, "checksums": "off" if a.no_checksum else "fused send+receive",
+                      "cache_state": "cold (%d MiB of sources per pass)" % (N * nmsg >> 20)},
+           "pct_hbm_peak": round(100 * gbps / HBM_PEAK_GBPS, 2),
+           "us_per_micro_batch": round(sec / steps / nmsg * 1e6, 2)}
+    if fwd:
+        out["staged_gbps_per_direction"] = round(N * nmsg * steps / sec / 1e9, 2)
+    return out
+
+
+def staged_round_trip(torch, hxt, w, plans, msgs):
+    """CPU-forwarding leg: D2H lane by lane on one stream, H2D of each lane on another as soon as its D2H is
+    done (events), through one pinned buffer per message; against a pinned hipMemcpy probe (256 MiB, each
+    direction alone and both at once on separate buffers) taken in the same run."""
+    dev = "cuda:0"
+    k, N = w.n_lanes, plans[0].message_bytes
     s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
 
-    def timed(fn, reps):
+    def best_of(fn, reps=10):
+        fn()
         best = 1e9
         for _ in range(reps):
             torch.cuda.synchronize()
@@ -209,34 +272,53 @@ def staged_round_trip(torch, hxt, w, plan, ms):
             best = min(best, time.perf_counter() - t0)
         return best
 
-    def d2h():
-        hxt.hxt_stage_d2h(plan, -1, ms.packed, host, s1)
+    # link probe
+    P = 256 << 20
+    d_a, d_b = (torch.empty(P, dtype=torch.uint8, device=dev) for _ in range(2))
+    h_a, h_b = (torch.empty(P, dtype=torch.uint8).pin_memory() for _ in range(2))
 
-    def h2d():
-        hxt.hxt_stage_h2d(plan, -1, host, recv, s2)
+    def p_d2h():
+        with torch.cuda.stream(s1):
+            h_a.copy_(d_a, non_blocking=True)
 
-    def both():
-        hxt.hxt_stage_d2h(plan, -1, ms.packed, host, s1)
-        hxt.hxt_stage_h2d(plan, -1, host, recv, s2)
+    def p_h2d():
+        with torch.cuda.stream(s2):
+            d_b.copy_(h_b, non_blocking=True)
 
-    def round_trip():
-        for l in range(k):
-            hxt.hxt_stage_d2h(plan, l, ms.packed, host, s1)
-            ev = torch.cuda.Event()
-            ev.record(s1)
-            s2.wait_event(ev)
-            hxt.hxt_stage_h2d(plan, l, host, recv, s2)
+    def p_both():
+        p_d2h()
+        p_h2d()
 
-    for f in (d2h, h2d, both, round_trip):
-        f()
-    torch.cuda.synchronize()
-    t_d2h, t_h2d, t_both, t_rt = timed(d2h, 10), timed(h2d, 10), timed(both, 10), timed(round_trip, 10)
-    assert torch.equal(recv[:nb], ms.packed[:nb]) or plan.num_chunks == 0
-    link = min(N / t_d2h, N / t_h2d) / 1e9
-    return {"round_trip_gbps": round(N / t_rt / 1e9, 2), "pct_host_link": round(100 * (N / t_rt / 1e9) / link, 1),
-            "probe_d2h_gbps": round(N / t_d2h / 1e9, 2), "probe_h2d_gbps": round(N / t_h2d / 1e9, 2),
-            "probe_bidir_gbps": round(2 * N / t_both / 1e9, 2), "bytes": N, "lanes": k,
-            "note": "best of 10; round trip = first D2H start to last H2D end; link = min one-direction probe"}
+    t_d2h, t_h2d, t_both = best_of(p_d2h), best_of(p_h2d), best_of(p_both)
+    link = min(P / t_d2h, P / t_h2d) / 1e9
+    del d_a, d_b, h_a, h_b
+
+    host = [torch.empty(p.packed_bytes, dtype=torch.uint8).pin_memory() for p in plans]
+    recv = [torch.empty(p.packed_bytes, dtype=torch.uint8, device=dev) for p in plans]
+
+    def round_trip(which):
+        for m in which:
+            for l in range(k):
+                hxt.hxt_stage_d2h(plans[m], l, msgs[m].packed, host[m], s1)
+                ev = torch.cuda.Event()
+                ev.record(s1)
+                s2.wait_event(ev)
+                hxt.hxt_stage_h2d(plans[m], l, host[m], recv[m], s2)
+
+    t_one = best_of(lambda: round_trip([0]))
+    t_all = best_of(lambda: round_trip(range(len(plans))))
+    for m in range(len(plans)):
+        assert torch.equal(recv[m], msgs[m].packed[:plans[m].packed_bytes]), "staged bytes differ"
+    one, all_ = N / t_one / 1e9, N * len(plans) / t_all / 1e9
+    return {"round_trip_gbps": round(one, 2), "pct_host_link": round(100 * one / link, 1),
+            "step_round_trip_gbps": round(all_, 2), "step_pct_host_link": round(100 * all_ / link, 1),
+            "messages_in_step": len(plans), "lanes": k, "message_bytes": N,
+            "probe_bytes": P, "probe_d2h_gbps": round(P / t_d2h / 1e9, 2), "probe_h2d_gbps": round(P / t_h2d / 1e9, 2),
+            "probe_bidir_gbps": round(2 * P / t_both / 1e9, 2),
+            "bidir_pct": round(100 * (2 * N * len(plans) / t_all / 1e9) / (2 * P / t_both / 1e9), 1),
+            "note": "best of 10, wall clock around a synchronised region; round trip = first D2H start to last "
+                    "H2D end of one message; step = all messages of the step pipelined lane by lane; "
+                    "link = min one-direction probe; bidir_pct = 2 x step rate / both-directions probe"}
 
 
 def cpu_baseline(w):
@@ -264,8 +346,15 @@ def cpu_baseline(w):
             break
     sec = time.perf_counter() - t0
     assert np.array_equal(s_send, s_recv) and all(np.array_equal(a, b) for a, b in zip(raws, dst))
+    t1 = time.perf_counter()                              # the same pass on one core
+    ho.pack(m, raws, B, k, packed=packed, nthreads=1)
+    ho.checksum(m, packed, B, k, nthreads=1)
+    ho.unpack(m, packed, B, k, dst, nthreads=1)
+    ho.checksum(m, packed, B, k, nthreads=1)
+    sec1 = time.perf_counter() - t1
     return {"value": round(4 * m.N * reps / sec / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
-            "sample": "%d message(s) of %d bytes: pack + checksum + unpack + checksum, %.1f s" % (reps, m.N, sec)}
+            "sample": "%d message(s) of %d bytes: pack + checksum + unpack + checksum, %.1f s" % (reps, m.N, sec),
+            "one_core_value": round(4 * m.N / sec1 / 1e9, 3)}
 
 
 if __name__ == "__main__":

@@ -172,6 +172,42 @@ int hxt_pack_batch(int n, const hxt_plan_t *const *plans, const void *const *con
 int hxt_unpack_batch(int n, const hxt_plan_t *const *plans, const void *const *packed,
                      void *const *const *dst, uint64_t *const *sums, void *stream);
 
+/* ---- step 6: a stream of micro-batches through ping-pong buffers ----------------
+ * Enqueues pack -> (staging) -> unpack for n_messages messages of one geometry so that
+ * the steps of consecutive messages overlap: message i uses buffer set i mod n_buffers;
+ * pack runs on stream_pack, the device-to-host copies on stream_stage, the
+ * host-to-device copies and unpack on stream_unpack; events created by the call order
+ * them (pack of message i waits until buffer set i mod n_buffers has been drained by
+ * message i - n_buffers, and so on).  This is the host-side "event handling" half of
+ * Section 2.2's control plane for a 1F1B schedule, where a stage sends one micro-batch
+ * while the previous one is still in flight.
+ *   path HXT_DEVICE_DIRECT: unpack reads packed_send[b] (packed_recv, host_pinned unused).
+ *   path HXT_CPU_FORWARD  : packed_send[b] -> host_pinned[b] -> packed_recv[b] -> unpack.
+ * src/dst: n_messages * n_tensors device pointers, message-major.  send_sums/recv_sums:
+ * NULL or device arrays of n_messages * num_chunks uint64, message-major.
+ * The call only enqueues; when the three streams have drained, every message has
+ * arrived.  HXT_EINVAL: n_messages < 0, n_buffers < 1, a NULL array that the path needs,
+ * a NULL stream handle shared by two roles is allowed (the steps then serialise). */
+typedef enum { HXT_DEVICE_DIRECT = 0, HXT_CPU_FORWARD = 1 } hxt_path_t;
+
+typedef struct {
+    int n_messages;
+    int n_buffers;
+    hxt_path_t path;
+    const void *const *src;    /* [n_messages * n_tensors] */
+    void *const *dst;          /* [n_messages * n_tensors] */
+    void *const *packed_send;  /* [n_buffers] device, >= packed_bytes, 256-byte aligned */
+    void *const *packed_recv;  /* [n_buffers] device (CPU forwarding) */
+    void *const *host_pinned;  /* [n_buffers] pinned host (CPU forwarding) */
+    uint64_t *send_sums;       /* device, n_messages * num_chunks, or NULL */
+    uint64_t *recv_sums;       /* device, n_messages * num_chunks, or NULL */
+    void *stream_pack;
+    void *stream_stage;
+    void *stream_unpack;
+} hxt_exchange_t;
+
+int hxt_exchange_stream(const hxt_plan_t *plan, const hxt_exchange_t *x);
+
 /* ---- step 5: stand-alone per-chunk checksum of a packed buffer --------------- */
 int hxt_checksum(const hxt_plan_t *plan, const void *packed, uint64_t *sums, void *stream);
 

@@ -21,6 +21,7 @@
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <vector>
 
 #include "hxt_internal.h"
 
@@ -1012,6 +1013,80 @@ int hxt_unpack_batch(int n, const hxt_plan_t *const *plans, const void *const *p
                      uint64_t *const *sums, void *stream)
 {
     return run_batch<true>(n, plans, dst, const_cast<void *const *>(packed), sums, static_cast<hipStream_t>(stream));
+}
+
+int hxt_exchange_stream(const hxt_plan_t *plan, const hxt_exchange_t *x)
+{
+    if (!plan || !x || x->n_messages < 0 || x->n_buffers < 1) return HXT_EINVAL;
+    if (x->path != HXT_DEVICE_DIRECT && x->path != HXT_CPU_FORWARD) return HXT_EINVAL;
+    const Plan &p = plan->p;
+    if (x->n_messages == 0 || p.C == 0) return HXT_OK;
+    const bool fwd = x->path == HXT_CPU_FORWARD;
+    if (!x->src || !x->dst || !x->packed_send || (fwd && (!x->packed_recv || !x->host_pinned))) return HXT_EINVAL;
+    const size_t T = p.tensors.size();
+    int rc;
+    for (int b = 0; b < x->n_buffers; ++b) {                  // validate before anything is enqueued
+        if ((rc = check_common(plan, x->packed_send[b])) != HXT_OK) return rc;
+        if (fwd) {
+            if ((rc = check_common(plan, x->packed_recv[b])) != HXT_OK) return rc;
+            if (!x->host_pinned[b]) return HXT_EINVAL;
+            if (reinterpret_cast<uintptr_t>(x->host_pinned[b]) % HXT_ALIGN) return HXT_EALIGN;
+        }
+    }
+    if (!p.all_unpack_safe) return HXT_EOVERLAP;
+    for (int i = 0; i < x->n_messages; ++i) {
+        if ((rc = check_tensor_pointers(p, const_cast<void *const *>(x->src + i * T))) != HXT_OK) return rc;
+        if ((rc = check_tensor_pointers(p, x->dst + i * T)) != HXT_OK) return rc;
+    }
+    hipStream_t sp = static_cast<hipStream_t>(x->stream_pack), ss = static_cast<hipStream_t>(x->stream_stage),
+                su = static_cast<hipStream_t>(x->stream_unpack);
+    // per buffer set: packed (pack done), drained (send buffer may be rewritten), staged (host copy
+    // complete), landed (host buffer may be rewritten)
+    enum { PACKED, DRAINED, STAGED, LANDED, KINDS };
+    const int nb = x->n_buffers;
+    std::vector<hipEvent_t> ev(size_t(nb) * KINDS, nullptr);
+    auto at = [&](int kind, int b) -> hipEvent_t & { return ev[size_t(b) * KINDS + kind]; };
+    auto cleanup = [&]() {
+        for (hipEvent_t e : ev)
+            if (e) (void)hipEventDestroy(e);                  // pending events are released when they complete
+    };
+    rc = HXT_OK;
+    for (hipEvent_t &e : ev)
+        if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
+            g_last_hip = int(hipGetLastError());
+            cleanup();
+            return HXT_EHIP;
+        }
+    auto hip = [&](hipError_t e) {
+        if (e != hipSuccess && rc == HXT_OK) rc = hip_fail(e);
+        return e == hipSuccess;
+    };
+    for (int i = 0; i < x->n_messages && rc == HXT_OK; ++i) {
+        const int b = i % nb;
+        uint64_t *s_send = x->send_sums ? x->send_sums + size_t(i) * p.C : nullptr;
+        uint64_t *s_recv = x->recv_sums ? x->recv_sums + size_t(i) * p.C : nullptr;
+        if (i >= nb && !hip(hipStreamWaitEvent(sp, at(DRAINED, b), 0))) break;
+        if ((rc = hxt_pack(plan, x->src + i * T, x->packed_send[b], s_send, sp)) != HXT_OK) break;
+        if (!hip(hipEventRecord(at(PACKED, b), sp))) break;
+        const void *arrived = x->packed_send[b];
+        if (fwd) {
+            if (!hip(hipStreamWaitEvent(ss, at(PACKED, b), 0))) break;
+            if (i >= nb && !hip(hipStreamWaitEvent(ss, at(LANDED, b), 0))) break;
+            if ((rc = hxt_stage_d2h(plan, -1, x->packed_send[b], x->host_pinned[b], ss)) != HXT_OK) break;
+            if (!hip(hipEventRecord(at(STAGED, b), ss))) break;
+            if (!hip(hipEventRecord(at(DRAINED, b), ss))) break;
+            if (!hip(hipStreamWaitEvent(su, at(STAGED, b), 0))) break;
+            if ((rc = hxt_stage_h2d(plan, -1, x->host_pinned[b], x->packed_recv[b], su)) != HXT_OK) break;
+            if (!hip(hipEventRecord(at(LANDED, b), su))) break;
+            arrived = x->packed_recv[b];
+        } else {
+            if (!hip(hipStreamWaitEvent(su, at(PACKED, b), 0))) break;
+        }
+        if ((rc = hxt_unpack(plan, arrived, x->dst + i * T, s_recv, su)) != HXT_OK) break;
+        if (!fwd && !hip(hipEventRecord(at(DRAINED, b), su))) break;
+    }
+    cleanup();
+    return rc;
 }
 
 int hxt_checksum(const hxt_plan_t *plan, const void *packed, uint64_t *sums, void *stream)

@@ -29,7 +29,7 @@ EXPORTS = (
     "hxt_plan_packed_bytes", "hxt_plan_chunk_bytes", "hxt_plan_num_chunks", "hxt_plan_num_lanes",
     "hxt_plan_num_tensors", "hxt_plan_chunk_info", "hxt_plan_lane_info", "hxt_plan_tensor_unpack_safe",
     "hxt_plan_tensor_kind", "hxt_pack", "hxt_stage_d2h", "hxt_stage_h2d", "hxt_unpack", "hxt_checksum",
-    "hxt_pack_batch", "hxt_unpack_batch",
+    "hxt_pack_batch", "hxt_unpack_batch", "hxt_exchange_stream",
     "hxt_strerror", "hxt_last_hip_error", "hxt_version",
 )
 
@@ -58,6 +58,17 @@ class _TensorDesc(C.Structure):
 class ChunkInfo(C.Structure):
     _fields_ = [("lane", C.c_int32), ("slot", C.c_int32), ("stream_off", C.c_uint64), ("padded", C.c_uint64),
                 ("payload", C.c_uint64), ("packed_off", C.c_uint64)]
+
+
+class _Exchange(C.Structure):
+    _fields_ = [("n_messages", C.c_int), ("n_buffers", C.c_int), ("path", C.c_int),
+                ("src", C.POINTER(C.c_void_p)), ("dst", C.POINTER(C.c_void_p)),
+                ("packed_send", C.POINTER(C.c_void_p)), ("packed_recv", C.POINTER(C.c_void_p)),
+                ("host_pinned", C.POINTER(C.c_void_p)), ("send_sums", C.c_void_p), ("recv_sums", C.c_void_p),
+                ("stream_pack", C.c_void_p), ("stream_stage", C.c_void_p), ("stream_unpack", C.c_void_p)]
+
+
+HXT_DEVICE_DIRECT, HXT_CPU_FORWARD = 0, 1
 
 
 class LaneInfo(C.Structure):
@@ -99,6 +110,7 @@ def lib():
             "hxt_checksum": (i, [vp, vp, u64p, vp]),
             "hxt_pack_batch": (i, [i, C.POINTER(vp), C.POINTER(C.POINTER(vp)), C.POINTER(vp), C.POINTER(vp), vp]),
             "hxt_unpack_batch": (i, [i, C.POINTER(vp), C.POINTER(vp), C.POINTER(C.POINTER(vp)), C.POINTER(vp), vp]),
+            "hxt_exchange_stream": (i, [vp, C.POINTER(_Exchange)]),
             "hxt_strerror": (C.c_char_p, [i]),
             "hxt_last_hip_error": (i, []),
             "hxt_version": (C.c_char_p, []),
@@ -262,6 +274,24 @@ def hxt_pack_batch(batch: Batch, stream=None) -> None:
 def hxt_unpack_batch(batch: Batch, stream=None) -> None:
     _check(lib().hxt_unpack_batch(batch.n, batch.plans, batch.packed, batch.tensors, batch.sums, _stream(stream)),
            "hxt_unpack_batch")
+
+
+class Exchange:
+    """Pre-marshalled hxt_exchange_t: src/dst are lists (one entry per message) of lists of tensors."""
+
+    def __init__(self, src, dst, packed_send, path=HXT_DEVICE_DIRECT, packed_recv=None, host_pinned=None,
+                 send_sums=None, recv_sums=None, stream_pack=None, stream_stage=None, stream_unpack=None):
+        flat = lambda rows: [t for row in rows for t in row]
+        self._keep = (src, dst, packed_send, packed_recv, host_pinned, send_sums, recv_sums)
+        self._arrays = [_ptr_array(flat(src)), _ptr_array(flat(dst)), _ptr_array(packed_send),
+                        _ptr_array(packed_recv) if packed_recv is not None else None,
+                        _ptr_array(host_pinned) if host_pinned is not None else None]
+        self.c = _Exchange(len(src), len(packed_send), path, *self._arrays, _ptr(send_sums), _ptr(recv_sums),
+                           _stream(stream_pack), _stream(stream_stage), _stream(stream_unpack))
+
+
+def hxt_exchange_stream(plan: Plan, x: Exchange) -> None:
+    _check(lib().hxt_exchange_stream(plan.handle, C.byref(x.c)), "hxt_exchange_stream")
 
 
 def hxt_checksum(plan: Plan, packed, sums, stream=None) -> None:

@@ -411,6 +411,77 @@ def test_config_stream_1f1b_three_streams_ping_pong(path):
             assert np.array_equal(ss_h[i], ho.checksum(m, want, w.chunk_bytes, w.n_lanes, nthreads=NT))
 
 
+def run_exchange(case, raws_per_msg, path, n_buffers, streams):
+    """hxt_exchange_stream on a list of messages; checks every destination and every checksum."""
+    m = oracle_msg(case)
+    p = plan_of(case)
+    nmsg, C, nb = len(raws_per_msg), p.num_chunks, max(p.packed_bytes, 256)
+    src = [[to_dev(r) for r in raws] for raws in raws_per_msg]
+    dst = [[to_dev(np.full(r.size, 0x3C, np.uint8)) for r in raws] for raws in raws_per_msg]
+    send_sums = torch.full((nmsg, max(C, 1)), -1, dtype=torch.int64, device=DEV)
+    recv_sums = torch.full((nmsg, max(C, 1)), -2, dtype=torch.int64, device=DEV)
+    send_buf = [torch.full((nb,), 0xEE, dtype=torch.uint8, device=DEV) for _ in range(n_buffers)]      # poisoned
+    fwd = path == "cpu_forward"
+    recv_buf = [torch.full((nb,), 0xDD, dtype=torch.uint8, device=DEV) for _ in range(n_buffers)] if fwd else None
+    host_buf = [torch.zeros(nb, dtype=torch.uint8).pin_memory() for _ in range(n_buffers)] if fwd else None
+    for s_ in streams:
+        s_.wait_stream(torch.cuda.current_stream())
+    x = hxt.Exchange(src, dst, send_buf, hxt.HXT_CPU_FORWARD if fwd else hxt.HXT_DEVICE_DIRECT, recv_buf, host_buf,
+                     send_sums, recv_sums, *streams)
+    hxt.hxt_exchange_stream(p, x)
+    torch.cuda.synchronize()
+    ss_h = send_sums.cpu().numpy().view(np.uint64)[:, :C]
+    rs_h = recv_sums.cpu().numpy().view(np.uint64)[:, :C]
+    assert np.array_equal(ss_h, rs_h)
+    for i, raws in enumerate(raws_per_msg):
+        want = ho.pack(m, raws, case.B, case.k, nthreads=NT)
+        assert np.array_equal(ss_h[i], ho.checksum(m, want, case.B, case.k, nthreads=NT)), "message %d" % i
+        dst_o = [np.full(r.size, 0x3C, np.uint8) for r in raws]
+        ho.unpack(m, want, case.B, case.k, dst_o, nthreads=NT)
+        for a, b in zip(dst_o, dst[i]):
+            assert np.array_equal(b.cpu().numpy(), a), "message %d" % i
+
+
+@pytest.mark.parametrize("path", ["device_direct", "cpu_forward"])
+@pytest.mark.parametrize("n_buffers", [1, 2, 3])
+def test_exchange_stream_small_messages(path, n_buffers):
+    say("exchange", path, "buffers", n_buffers)
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    for name, nmsg in (("contig_1MB_ragged", 7), ("multi_mid", 5), ("rows_mid", 4)):
+        case = [c for c in MID_CASES if c.name == name][0]
+        run_exchange(case, [make_storages(case, 3000 + i) for i in range(nmsg)], path, n_buffers, streams)
+    # all three roles on one stream: the steps simply serialise
+    case = [c for c in MID_CASES if c.name == "contig_1MB_ragged"][0]
+    one = torch.cuda.Stream()
+    run_exchange(case, [make_storages(case, 3100 + i) for i in range(3)], path, n_buffers, [one, one, one])
+
+
+@pytest.mark.parametrize("path", ["device_direct", "cpu_forward"])
+def test_config_stream_1f1b_native_exchange(path):
+    w = wl.stream_1f1b(8 if path == "cpu_forward" else 32)
+    say("native stream", path, "messages", w.messages)
+    run_exchange(case_of(w), [wl.make_storages(w, i) for i in range(w.messages)], path, 2,
+                 [torch.cuda.Stream() for _ in range(3)])
+
+
+def test_exchange_stream_argument_errors():
+    case = case_by_name("single_lane")
+    p = plan_of(case)
+    raws = make_storages(case, 1)
+    src, dst = [[to_dev(r) for r in raws]], [[to_dev(r) for r in raws]]
+    buf = [torch.zeros(p.packed_bytes, dtype=torch.uint8, device=DEV)]
+    with pytest.raises(hxt.HxtError) as e:
+        hxt.hxt_exchange_stream(p, hxt.Exchange(src, dst, buf, hxt.HXT_CPU_FORWARD))       # no host buffers
+    assert e.value.status == hxt.HXT_EINVAL
+    with pytest.raises(hxt.HxtError) as e:
+        hxt.hxt_exchange_stream(p, hxt.Exchange(src, dst, [buf[0][8:]]))                   # misaligned packed
+    assert e.value.status == hxt.HXT_EALIGN
+    with pytest.raises(hxt.HxtError) as e:
+        hxt.hxt_exchange_stream(p, hxt.Exchange(src, dst, buf, 7))
+    assert e.value.status == hxt.HXT_EINVAL
+    torch.cuda.synchronize()
+
+
 def test_config_grad_buckets_full_size_both_paths():
     w = wl.grad_buckets()
     case = case_of(w)
