@@ -197,7 +197,10 @@ struct UniformItem {
     uint8_t *packed;
     SumCtx cx;
     uint32_t first_tile;
+    uint32_t unpack;       // direction of this item; only read by the mixed-direction instantiation
 };
+
+enum Direction { DIR_PACK = 0, DIR_UNPACK = 1, DIR_MIXED = 2 };
 
 struct UniformArgs {
     UniformItem it[kMaxBatch];
@@ -205,6 +208,21 @@ struct UniformArgs {
 };
 
 template <bool UNPACK, bool CSUM, bool NTU, bool NTP>
+__device__ __forceinline__ void uniform_tile(const UniformItem &it, uint32_t tile)
+{
+    const ChunkGeom &g = it.g;
+    const TileSpan t = locate_tile(g, tile);
+    const uint64_t left = g.N > t.stream_off ? g.N - t.stream_off : 0;     // tensor bytes from here on
+    const uint32_t data = left < t.len ? uint32_t(left) : t.len;
+    uint8_t *pk = it.packed + t.packed_off;
+    uint64_t acc = copy_span<UNPACK, CSUM, NTU, NTP>(it.user + t.stream_off, pk, data);
+    if (data < t.len) acc += pad_span<UNPACK, CSUM>(pk + data, t.len - data, data);
+    if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, t.expected, it.cx);
+}
+
+// DIR: all items pack, all unpack, or each item says which (a micro-batch stream overlaps the
+// unpack of one message with the pack of the next inside one launch).
+template <int DIR, bool CSUM, bool NTU, bool NTP>
 __global__ __launch_bounds__(kThreads) void k_uniform(UniformArgs a)
 {
     uint32_t m = 0;
@@ -212,14 +230,13 @@ __global__ __launch_bounds__(kThreads) void k_uniform(UniformArgs a)
     for (uint32_t i = 1; i < kMaxBatch; ++i)
         if (i < a.n && blockIdx.x >= a.it[i].first_tile) m = i;
     const UniformItem &it = a.it[m];
-    const ChunkGeom &g = it.g;
-    const TileSpan t = locate_tile(g, blockIdx.x - it.first_tile);
-    const uint64_t left = g.N > t.stream_off ? g.N - t.stream_off : 0;     // tensor bytes from here on
-    const uint32_t data = left < t.len ? uint32_t(left) : t.len;
-    uint8_t *pk = it.packed + t.packed_off;
-    uint64_t acc = copy_span<UNPACK, CSUM, NTU, NTP>(it.user + t.stream_off, pk, data);
-    if (data < t.len) acc += pad_span<UNPACK, CSUM>(pk + data, t.len - data, data);
-    if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, t.expected, it.cx);
+    const uint32_t tile = blockIdx.x - it.first_tile;
+    if constexpr (DIR == DIR_MIXED) {
+        if (it.unpack) uniform_tile<true, CSUM, NTU, NTP>(it, tile);
+        else uniform_tile<false, CSUM, NTU, NTP>(it, tile);
+    } else {
+        uniform_tile<DIR == DIR_UNPACK, CSUM, NTU, NTP>(it, tile);
+    }
 }
 
 // ---- contiguous tensors of a multi-tensor message: table driven ---------------------
@@ -540,10 +557,10 @@ void with_hints(bool nt_packed, F &&f)
     }
 }
 
-template <bool UNPACK, bool CSUM>
+template <int DIR, bool CSUM>
 void launch_uniform(const UniformArgs &a, uint32_t tiles, bool nt_packed, hipStream_t st)
 {
-    with_hints(nt_packed, [&]<bool NTU, bool NTP>() { k_uniform<UNPACK, CSUM, NTU, NTP><<<tiles, kThreads, 0, st>>>(a); });
+    with_hints(nt_packed, [&]<bool NTU, bool NTP>() { k_uniform<DIR, CSUM, NTU, NTP><<<tiles, kThreads, 0, st>>>(a); });
 }
 
 template <bool UNPACK, bool CSUM>
@@ -653,8 +670,8 @@ int run_copy(hxt_plan_t &pl, void *const *ptrs, uint8_t *packed, uint64_t *sums,
             UniformArgs a;
             std::memset(&a, 0, sizeof a);
             a.n = 1;
-            a.it[0] = UniformItem{p.geom, base, packed, cx, 0};
-            launch_uniform<UNPACK, CSUM>(a, p.geom.ntiles, packed_nontemporal(p.C * p.B), st);
+            a.it[0] = UniformItem{p.geom, base, packed, cx, 0, UNPACK};
+            launch_uniform<UNPACK ? DIR_UNPACK : DIR_PACK, CSUM>(a, p.geom.ntiles, packed_nontemporal(p.C * p.B), st);
             HXT_HIP(hipGetLastError());
             return HXT_OK;
         }
@@ -862,15 +879,64 @@ int run_batch(int n, const hxt_plan_t *const *plans, void *const *const *tensors
                 cx.sum_bits = pj.sum_bits_geom;
             }
             a.it[a.n++] = UniformItem{pj.p.geom, static_cast<uint8_t *>(tensors[j][pj.p.uniform_tensor]),
-                                      static_cast<uint8_t *>(packed[j]), cx, uint32_t(tiles)};
+                                      static_cast<uint8_t *>(packed[j]), cx, uint32_t(tiles), UNPACK};
             tiles += pj.p.geom.ntiles;
             bytes += pj.p.C * pj.p.B;
             ++j;
         }
-        if (sm) launch_uniform<UNPACK, true>(a, uint32_t(tiles), packed_nontemporal(bytes), st);
-        else launch_uniform<UNPACK, false>(a, uint32_t(tiles), packed_nontemporal(bytes), st);
+        constexpr int DIR = UNPACK ? DIR_UNPACK : DIR_PACK;
+        if (sm) launch_uniform<DIR, true>(a, uint32_t(tiles), packed_nontemporal(bytes), st);
+        else launch_uniform<DIR, false>(a, uint32_t(tiles), packed_nontemporal(bytes), st);
         HXT_HIP(hipGetLastError());
         i = j;
+    }
+    return HXT_OK;
+}
+
+// Device-direct micro-batch stream for single-tensor messages, without cross-stream handshakes:
+// launch k unpacks message k-1 and packs message k (different buffer sets, independent work, so
+// the two overlap inside the launch and fill each other's ramp-up and tail); consecutive launches
+// on one stream carry the pack -> unpack dependency.  The other two streams are made to wait for
+// the last launch, so that draining any of the three means every message has arrived.
+int fused_direct_stream(hxt_plan_t &pl, const hxt_exchange_t &x, hipStream_t sp, hipStream_t ss, hipStream_t su)
+{
+    const Plan &p = pl.p;
+    const size_t T = p.tensors.size();
+    const bool nt_packed = packed_nontemporal(p.C * p.B);
+    for (int k = 0; k <= x.n_messages; ++k) {
+        UniformArgs a;
+        std::memset(&a, 0, sizeof a);
+        uint32_t tiles = 0;
+        auto add = [&](int msg, bool unpack) -> int {
+            SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};
+            uint64_t *sm = unpack ? x.recv_sums : x.send_sums;
+            if (sm) {
+                int rc = claim_slots(pl, unpack ? OP_UNPACK : OP_PACK, sp, cx, sm + size_t(msg) * p.C);
+                if (rc != HXT_OK) return rc;
+                cx.sum_bits = pl.sum_bits_geom;
+            }
+            void *user = unpack ? x.dst[msg * T + p.uniform_tensor] : const_cast<void *>(x.src[msg * T + p.uniform_tensor]);
+            a.it[a.n++] = UniformItem{p.geom, static_cast<uint8_t *>(user),
+                                      static_cast<uint8_t *>(x.packed_send[msg % x.n_buffers]), cx, tiles, unpack ? 1u : 0u};
+            tiles += p.geom.ntiles;
+            return HXT_OK;
+        };
+        int rc = HXT_OK;
+        if (k > 0) rc = add(k - 1, true);
+        if (rc == HXT_OK && k < x.n_messages) rc = add(k, false);
+        if (rc != HXT_OK) return rc;
+        if (x.send_sums) launch_uniform<DIR_MIXED, true>(a, tiles, nt_packed, sp);
+        else launch_uniform<DIR_MIXED, false>(a, tiles, nt_packed, sp);
+        HXT_HIP(hipGetLastError());
+    }
+    if (su != sp || ss != sp) {
+        hipEvent_t done;
+        HXT_HIP(hipEventCreateWithFlags(&done, hipEventDisableTiming));
+        hipError_t e = hipEventRecord(done, sp);
+        if (e == hipSuccess && su != sp) e = hipStreamWaitEvent(su, done, 0);
+        if (e == hipSuccess && ss != sp) e = hipStreamWaitEvent(ss, done, 0);
+        (void)hipEventDestroy(done);
+        if (e != hipSuccess) return hip_fail(e);
     }
     return HXT_OK;
 }
@@ -1040,6 +1106,13 @@ int hxt_exchange_stream(const hxt_plan_t *plan, const hxt_exchange_t *x)
     }
     hipStream_t sp = static_cast<hipStream_t>(x->stream_pack), ss = static_cast<hipStream_t>(x->stream_stage),
                 su = static_cast<hipStream_t>(x->stream_unpack);
+    if (!fwd && x->n_buffers >= 2 && p.uniform && !x->send_sums == !x->recv_sums && env_int("HXT_FUSED_STREAM", 1)) {
+        bool aligned = true;
+        for (int i = 0; i < x->n_messages; ++i)
+            aligned = aligned && reinterpret_cast<uintptr_t>(x->src[i * T + p.uniform_tensor]) % 16 == 0 &&
+                      reinterpret_cast<uintptr_t>(x->dst[i * T + p.uniform_tensor]) % 16 == 0;
+        if (aligned) return fused_direct_stream(*const_cast<hxt_plan_t *>(plan), *x, sp, ss, su);
+    }
     // per buffer set: packed (pack done), drained (send buffer may be rewritten), staged (host copy
     // complete), landed (host buffer may be rewritten)
     enum { PACKED, DRAINED, STAGED, LANDED, KINDS };
@@ -1051,6 +1124,7 @@ int hxt_exchange_stream(const hxt_plan_t *plan, const hxt_exchange_t *x)
             if (e) (void)hipEventDestroy(e);                  // pending events are released when they complete
     };
     rc = HXT_OK;
+    const bool by_lane = env_int("HXT_STAGE_BY_LANE", 0) != 0;
     for (hipEvent_t &e : ev)
         if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
             g_last_hip = int(hipGetLastError());
@@ -1072,11 +1146,17 @@ int hxt_exchange_stream(const hxt_plan_t *plan, const hxt_exchange_t *x)
         if (fwd) {
             if (!hip(hipStreamWaitEvent(ss, at(PACKED, b), 0))) break;
             if (i >= nb && !hip(hipStreamWaitEvent(ss, at(LANDED, b), 0))) break;
-            if ((rc = hxt_stage_d2h(plan, -1, x->packed_send[b], x->host_pinned[b], ss)) != HXT_OK) break;
+            if (by_lane) {
+                for (int l = 0; l < p.k && rc == HXT_OK; ++l) rc = hxt_stage_d2h(plan, l, x->packed_send[b], x->host_pinned[b], ss);
+                if (rc != HXT_OK) break;
+            } else if ((rc = hxt_stage_d2h(plan, -1, x->packed_send[b], x->host_pinned[b], ss)) != HXT_OK) break;
             if (!hip(hipEventRecord(at(STAGED, b), ss))) break;
             if (!hip(hipEventRecord(at(DRAINED, b), ss))) break;
             if (!hip(hipStreamWaitEvent(su, at(STAGED, b), 0))) break;
-            if ((rc = hxt_stage_h2d(plan, -1, x->host_pinned[b], x->packed_recv[b], su)) != HXT_OK) break;
+            if (by_lane) {
+                for (int l = 0; l < p.k && rc == HXT_OK; ++l) rc = hxt_stage_h2d(plan, l, x->host_pinned[b], x->packed_recv[b], su);
+                if (rc != HXT_OK) break;
+            } else if ((rc = hxt_stage_h2d(plan, -1, x->host_pinned[b], x->packed_recv[b], su)) != HXT_OK) break;
             if (!hip(hipEventRecord(at(LANDED, b), su))) break;
             arrived = x->packed_recv[b];
         } else {

@@ -464,6 +464,42 @@ def test_config_stream_1f1b_native_exchange(path):
                  [torch.cuda.Stream() for _ in range(3)])
 
 
+def test_exchange_stream_event_path_for_single_tensor_messages(monkeypatch):
+    # single-tensor device-direct streams normally take the fused-launch path; the event-chained
+    # path must give the same result
+    monkeypatch.setenv("HXT_FUSED_STREAM", "0")
+    case = [c for c in MID_CASES if c.name == "contig_bf16_5MiB_tail"][0]
+    run_exchange(case, [make_storages(case, 3200 + i) for i in range(6)], "device_direct", 2,
+                 [torch.cuda.Stream() for _ in range(3)])
+
+
+def test_packed_buffer_in_pinned_host_memory():
+    # the packed buffer may live in pinned host memory (the kernels then move the bytes over the
+    # host link themselves, with no device-side staging buffer)
+    case = [c for c in MID_CASES if c.name == "multi_mid"][0]
+    m = oracle_msg(case)
+    p = plan_of(case)
+    raws = make_storages(case, 64)
+    want = ho.pack(m, raws, case.B, case.k, fill=0x77)
+    want_sums = ho.checksum(m, want, case.B, case.k)
+    host = torch.full((p.packed_bytes,), 0x77, dtype=torch.uint8).pin_memory()
+    src = [to_dev(r) for r in raws]
+    ssum = torch.zeros(p.num_chunks, dtype=torch.int64, device=DEV)
+    hxt.hxt_pack(p, src, host, ssum)
+    torch.cuda.synchronize()
+    assert np.array_equal(host.numpy(), want)
+    dst = [to_dev(np.full(r.size, 0x3C, np.uint8)) for r in raws]
+    rsum = torch.zeros_like(ssum)
+    hxt.hxt_unpack(p, host, dst, rsum)
+    torch.cuda.synchronize()
+    dst_o = [np.full(r.size, 0x3C, np.uint8) for r in raws]
+    ho.unpack(m, want, case.B, case.k, dst_o)
+    for a, b in zip(dst_o, dst):
+        assert np.array_equal(b.cpu().numpy(), a)
+    assert np.array_equal(ssum.cpu().numpy().view(np.uint64), want_sums)
+    assert np.array_equal(rsum.cpu().numpy().view(np.uint64), want_sums)
+
+
 def test_exchange_stream_argument_errors():
     case = case_by_name("single_lane")
     p = plan_of(case)
