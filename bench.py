@@ -214,8 +214,6 @@ def stream_bench(torch, hxt, w, a):
     s_send = torch.zeros((nmsg, C), dtype=torch.int64, device=dev)
     s_recv = torch.zeros_like(s_send)
     streams = [torch.cuda.Stream() for _ in range(3)]
-    if fwd:
-        prime_copy_streams(torch, streams[1], streams[2])
     x = hxt.Exchange(src, dst, send, hxt.HXT_CPU_FORWARD if fwd else hxt.HXT_DEVICE_DIRECT, recv, host,
                      None if a.no_checksum else s_send, None if a.no_checksum else s_recv, *streams)
     steps = a.steps if not fwd else max(1, min(a.steps, 20))
@@ -252,23 +250,6 @@ def stream_bench(torch, hxt, w, a):
     return out
 
 
-def prime_copy_streams(torch, s_d2h, s_h2d):
-    """First use of the two copy streams: one device-to-host and one host-to-device copy in flight at the
-    same time.  The HIP runtime bundled with this PyTorch (ROCm 7.0) binds a DMA engine to a stream at its
-    first copy and picks an idle one; two streams first used one after the other end up on the same engine and
-    their copies never overlap afterwards (measured: 57 GB/s for both directions together instead of 97)."""
-    n = 64 << 20
-    d0, d1 = (torch.empty(n, dtype=torch.uint8, device="cuda:0") for _ in range(2))
-    h0, h1 = (torch.empty(n, dtype=torch.uint8).pin_memory() for _ in range(2))
-    torch.cuda.synchronize()
-    for _ in range(2):
-        with torch.cuda.stream(s_d2h):
-            h0.copy_(d0, non_blocking=True)
-        with torch.cuda.stream(s_h2d):
-            d1.copy_(h1, non_blocking=True)
-    torch.cuda.synchronize()
-
-
 def staged_round_trip(torch, hxt, w, plans, msgs):
     """CPU-forwarding leg: D2H lane by lane on one stream, H2D of each lane on another as soon as its D2H is
     done (events), through one pinned buffer per message; against a pinned hipMemcpy probe (256 MiB, each
@@ -276,7 +257,6 @@ def staged_round_trip(torch, hxt, w, plans, msgs):
     dev = "cuda:0"
     k, N = w.n_lanes, plans[0].message_bytes
     s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
-    prime_copy_streams(torch, s1, s2)
 
     def best_of(fn, reps=10):
         fn()

@@ -1124,7 +1124,6 @@ int hxt_exchange_stream(const hxt_plan_t *plan, const hxt_exchange_t *x)
             if (e) (void)hipEventDestroy(e);                  // pending events are released when they complete
     };
     rc = HXT_OK;
-    const bool by_lane = env_int("HXT_STAGE_BY_LANE", 0) != 0;
     for (hipEvent_t &e : ev)
         if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
             g_last_hip = int(hipGetLastError());
@@ -1146,17 +1145,11 @@ int hxt_exchange_stream(const hxt_plan_t *plan, const hxt_exchange_t *x)
         if (fwd) {
             if (!hip(hipStreamWaitEvent(ss, at(PACKED, b), 0))) break;
             if (i >= nb && !hip(hipStreamWaitEvent(ss, at(LANDED, b), 0))) break;
-            if (by_lane) {
-                for (int l = 0; l < p.k && rc == HXT_OK; ++l) rc = hxt_stage_d2h(plan, l, x->packed_send[b], x->host_pinned[b], ss);
-                if (rc != HXT_OK) break;
-            } else if ((rc = hxt_stage_d2h(plan, -1, x->packed_send[b], x->host_pinned[b], ss)) != HXT_OK) break;
+            if ((rc = hxt_stage_d2h(plan, -1, x->packed_send[b], x->host_pinned[b], ss)) != HXT_OK) break;
             if (!hip(hipEventRecord(at(STAGED, b), ss))) break;
             if (!hip(hipEventRecord(at(DRAINED, b), ss))) break;
             if (!hip(hipStreamWaitEvent(su, at(STAGED, b), 0))) break;
-            if (by_lane) {
-                for (int l = 0; l < p.k && rc == HXT_OK; ++l) rc = hxt_stage_h2d(plan, l, x->host_pinned[b], x->packed_recv[b], su);
-                if (rc != HXT_OK) break;
-            } else if ((rc = hxt_stage_h2d(plan, -1, x->host_pinned[b], x->packed_recv[b], su)) != HXT_OK) break;
+            if ((rc = hxt_stage_h2d(plan, -1, x->host_pinned[b], x->packed_recv[b], su)) != HXT_OK) break;
             if (!hip(hipEventRecord(at(LANDED, b), su))) break;
             arrived = x->packed_recv[b];
         } else {

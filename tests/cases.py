@@ -69,3 +69,26 @@ def case_by_name(name: str) -> Case:
 def make_storages(case: Case, seed: int) -> List[np.ndarray]:
     rng = np.random.default_rng(seed)
     return [rng.integers(0, 256, size=storage_bytes(*t), dtype=np.uint8) for t in case.tensors]
+
+
+def random_view(rng):
+    """(shape, strides, esize) of a random non-negative-stride view with a small storage footprint."""
+    esize = int(rng.choice([1, 2, 4, 8]))
+    nd = int(rng.integers(0, 5))
+    shape = [int(rng.choice([1, 2, 3, 5, 8, 16, 17, 40, 64, 72, 130])) for _ in range(nd)]
+    if rng.random() < 0.08 and nd:
+        shape[int(rng.integers(0, nd))] = 0
+    order = list(rng.permutation(nd))                      # order[0] is the fastest-varying dim in memory
+    strides, run = [0] * nd, 1
+    for d in order:
+        pad = int(rng.choice([0, 0, 0, 1, 3, 8]))
+        strides[d] = run
+        run *= max(shape[d], 1) + pad
+        if run > 60000:                                    # keep storage small: flatten the rest with stride reuse
+            run = 60000
+    if rng.random() < 0.1 and nd:
+        strides[int(rng.integers(0, nd))] = 0              # broadcast
+    if rng.random() < 0.1 and nd:
+        d = int(rng.integers(0, nd))
+        strides[d] *= 2                                    # holes
+    return tuple(shape), tuple(int(x) for x in strides), esize

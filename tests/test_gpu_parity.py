@@ -9,7 +9,7 @@ import torch
 from oracle import hxt_oracle as ho
 from paper_2602_18007_amd import hxt
 from paper_2602_18007_amd import workloads as wl
-from tests.cases import SMALL_CASES, Case, case_by_name, contig, make_storages
+from tests.cases import SMALL_CASES, Case, case_by_name, contig, make_storages, random_view, storage_bytes
 
 pytestmark = pytest.mark.gpu
 
@@ -215,6 +215,20 @@ def test_batch_calls_equal_single_calls():
     with pytest.raises(hxt.HxtError) as e:
         hxt.hxt_pack_batch(hxt.Batch([plans[0], plans[0]], [src[0], src[0]], [packed[0], packed[0]], [sums[0], sums[0]]))
     assert e.value.status == hxt.HXT_EINVAL
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_views(seed):
+    rng = np.random.default_rng(7000 + seed)
+    done = 0
+    while done < 10:
+        tensors = tuple(random_view(rng) for _ in range(int(rng.integers(1, 5))))
+        if sum(storage_bytes(*t) for t in tensors) > 4_000_000:
+            continue
+        case = Case("rand%d_%d" % (seed, done), tensors, int(rng.integers(1, 6)), int(rng.choice([256, 1024, 4096, 16384])))
+        say("random case", case.tensors, case.k, case.B)
+        round_trip_check(case, make_storages(case, seed), tile_bytes=int(rng.choice([256, 1024, 16384])))
+        done += 1
 
 
 def test_many_tensors_need_several_launch_groups():

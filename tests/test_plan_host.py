@@ -14,7 +14,7 @@ from oracle import hxt_oracle as ho
 from paper_2602_18007_amd import build as hxt_build
 from paper_2602_18007_amd import hxt
 from paper_2602_18007_amd import workloads as wl
-from tests.cases import SMALL_CASES, Case, contig, make_storages, storage_bytes
+from tests.cases import SMALL_CASES, Case, contig, make_storages, random_view, storage_bytes
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -164,6 +164,7 @@ def interp():
     deps = [src, os.path.join(csrc, "hxt_plan.cpp"), os.path.join(csrc, "hxt_internal.h")]
     if not os.path.exists(out) or any(os.path.getmtime(d) > os.path.getmtime(out) for d in deps):
         subprocess.run(["g++", "-std=c++17", "-O1", "-g", "-shared", "-fPIC", "-Wall", "-Wextra",
+                        "-fsanitize=undefined", "-fno-sanitize-recover=all",
                         "-I", os.path.join(ROOT, "include"), "-I", csrc, "-o", out, src,
                         os.path.join(csrc, "hxt_plan.cpp")], check=True)
     L = C.CDLL(out)
@@ -255,3 +256,51 @@ def test_multiply_shift_division_is_exact(interp):
         near = near[near < (1 << 31)].astype(np.uint32)
         ns = np.ascontiguousarray(np.concatenate([edge, near, rng.integers(0, 1 << 31, 5000).astype(np.uint32)]))
         assert interp.fastdiv_check(C.c_uint32(d), C.c_void_p(ns.ctypes.data), C.c_int(ns.size)) == 0, d
+
+
+# ---- randomised views: planner tables vs oracle ------------------------------------
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_views_tables_reproduce_oracle(interp, seed):
+    rng = np.random.default_rng(1000 + seed)
+    for _ in range(25):
+        tensors = tuple(random_view(rng) for _ in range(int(rng.integers(1, 5))))
+        case = Case("rand", tensors, int(rng.integers(1, 6)), int(rng.choice([256, 512, 1024, 4096, 16384])))
+        if sum(storage_bytes(*t) for t in tensors) > 4_000_000:
+            continue
+        m = oracle_msg(case)
+        raws = make_storages(case, seed)
+        want = ho.pack(m, raws, case.B, case.k, fill=0x99)
+        tile = int(rng.choice([256, 1024, 16384]))
+        got = np.full(want.size, 0x99, np.uint8)
+        rc, written, _ = run_interp(interp, case, raws, got, 2, tile)
+        assert rc == 0 and np.array_equal(got, want), (tensors, case.k, case.B, tile)
+        p = plan_of(case)
+        assert p.packed_bytes == want.size
+        if all(p.tensor_unpack_safe(t) for t in range(len(tensors))):
+            dst_o = [np.full(r.size, 0x42, np.uint8) for r in raws]
+            dst_t = [np.full(r.size, 0x42, np.uint8) for r in raws]
+            ho.unpack(m, want, case.B, case.k, dst_o)
+            rc, _, _ = run_interp(interp, case, dst_t, want.copy(), 1, tile)
+            assert rc == 0
+            for a, b in zip(dst_o, dst_t):
+                assert np.array_equal(a, b), (tensors, case.k, case.B, tile)
+
+
+def test_unpack_safety_flag_never_accepts_an_aliasing_view():
+    # brute force on small random views: whenever the planner calls a view safe, all its element
+    # addresses are distinct (the converse need not hold: the test is only sufficient)
+    rng = np.random.default_rng(5)
+    accepted = 0
+    for _ in range(400):
+        shape, strides, e = random_view(rng)
+        if 0 in shape or int(np.prod(shape)) > 20000:
+            continue
+        p = hxt.hxt_plan(shape, strides, e, 2, 256)
+        if p.tensor_unpack_safe(0):
+            accepted += 1
+            idx = np.zeros((), np.int64)
+            for s_, st in zip(shape, strides):
+                idx = idx[..., None] + np.arange(s_, dtype=np.int64) * st
+            assert np.unique(idx).size == idx.size, (shape, strides)
+    assert accepted > 50
