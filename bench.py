@@ -97,6 +97,7 @@ def main():
              for _ in range(nmsg)]                  # independent messages: a plan each
     plan = plans[0]
     N = plan.message_bytes
+    a.sets = max(1, min(a.sets, int(12e9 // (3 * N * nmsg))))      # keep the resident working set near 12 GB
     sets = [[MessageSet(torch, w, plan, w.seed + 1000 * s + m * w.seed_step) for m in range(nmsg)]
             for s in range(a.sets)]
     main_stream = torch.cuda.current_stream()
@@ -157,7 +158,11 @@ def main():
     # dominant kernel: hxt::k_uniform (pack and unpack instantiations); a launch moves 2N algorithmic bytes
     # (read N, write N) for every message it serves.  Average launch duration = GPU time of the timed
     # region (HIP events on the launch stream) / launches in it; the launches are back to back.
-    per_launch = min(nmsg, 4) if batched else 1       # messages served by one launch
+    uniform = plan.num_tensors == 1 and plan.tensor_kind(0) == "contig"
+    per_launch = min(nmsg, 4) if batched and uniform else 1       # messages served by one launch
+    kinds = sorted({plan.tensor_kind(t) for t in range(plan.num_tensors)} - {"none"})
+    kernel = "hxt::k_uniform" if uniform else " + ".join("hxt::k_" + k for k in kinds)
+    default_run = w.name == "llama8b_boundary" and batched and use_sums
     launches = 2 * nmsg * a.steps // per_launch
     launch_ms = gpu_ms / (launches if not a.two_streams else launches / nmsg)
     launch_bytes = 2 * N * per_launch
@@ -178,14 +183,15 @@ def main():
         "config": {"workload": w.name, "note": w.note, "message_bytes": N, "messages_per_step": nmsg,
                    "n_lanes": w.n_lanes, "chunk_bytes": w.chunk_bytes, "path": "device_direct",
                    "checksums": "fused send+receive" if use_sums else "off",
-                   "buffer_sets": a.sets, "cache_state": "cold (rotating sets)",
+                   "buffer_sets": a.sets, "cache_state": "cold (rotating sets)" if a.sets * 3 * N * nmsg > 1e9 else
+                   "working set %d MiB" % (a.sets * 3 * N * nmsg >> 20),
                    "streams": nmsg if a.two_streams else 1,
                    "issue": "batched calls (one launch packs all messages of the step, one unpacks them)" if batched
                    else "one call per message"},
         "pct_hbm_peak": round(100 * gbps / HBM_PEAK_GBPS, 2),
-        "roofline": {"bound": "hbm", "kernel": "hxt::k_uniform (pack and unpack instantiations, fused checksum)",
+        "roofline": {"bound": "hbm", "kernel": kernel + " (pack and unpack instantiations%s)" % (", fused checksum" if use_sums else ""),
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": TRAFFIC_BYTES_PER_LAUNCH,
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": TRAFFIC_BYTES_PER_LAUNCH if default_run else None,
                      "bytes_per_launch": launch_bytes, "avg_launch_ms": round(launch_ms, 6),
                      "launches": launches, "gpu_ms_timed_region": round(gpu_ms, 4)},
     }
