@@ -335,7 +335,8 @@ __device__ __forceinline__ uint64_t transpose_vec(const uint8_t *src, uint64_t s
     const uint32_t nvs = Cc / V;                           // vectors per src row
     for (uint32_t v = threadIdx.x; v < R * nvs; v += kThreads) {
         const uint32_t r = v / nvs, cv = v - r * nvs;
-        const u32x4 x = *reinterpret_cast<const u32x4 *>(src + r * src_pitch + cv * 16);
+        // the user tensor is streamed once (non-temporal); the packed side stays cacheable
+        const u32x4 x = load16<!SRC_IS_PACKED>(reinterpret_cast<const u32x4 *>(src + r * src_pitch + cv * 16));
         if constexpr (CSUM && SRC_IS_PACKED) acc += words_sum(x);
         *reinterpret_cast<u32x4 *>(lds + r * ROWB + ((cv ^ ((r / V) % NV)) * 16)) = x;
     }
@@ -353,7 +354,7 @@ __device__ __forceinline__ uint64_t transpose_vec(const uint8_t *src, uint64_t s
             o.e[q] = *reinterpret_cast<const E *>(lds + r * ROWB + (((c / V) ^ ((r / V) % NV)) * 16) + (c % V) * sizeof(E));
         }
         if constexpr (CSUM && !SRC_IS_PACKED) acc += words_sum(o.x);
-        *reinterpret_cast<u32x4 *>(dst + c * dst_pitch + dv * 16) = o.x;
+        store16<SRC_IS_PACKED>(reinterpret_cast<u32x4 *>(dst + c * dst_pitch + dv * 16), o.x);
     }
     return acc;
 }
