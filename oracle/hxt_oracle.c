@@ -239,6 +239,83 @@ int hxo_unpack(const hxo_msg *m, const uint8_t *packed, int64_t B, int k,
     return 0;
 }
 
+/* ---- widening: unpack that adds the arriving tensor to the one already there ----
+ * The paper's Section 2.2 sends the intermediate results of a vendor-local reduction across
+ * the boundary by the same P2P mechanism; the receiver combines them with its own.  Contract
+ * chosen here (the paper gives none): per element, new = round(old + arriving), where
+ *   kind 1 (bf16): both operands are widened exactly to binary32, added in binary32
+ *                  (round to nearest even), and the binary32 sum is rounded to the nearest
+ *                  bf16 value, ties to the value with an even last mantissa bit;
+ *   kind 2 (f32) : IEEE binary32 addition, round to nearest even.
+ * Any NaN result is stored as the canonical quiet NaN (bf16 0x7FC0, f32 0x7FC00000), so that
+ * the outcome does not depend on how a machine propagates NaN payloads.
+ * The bf16 rounding is written as the definition: scale the binary32 sum by a power of two so
+ * that one bf16 unit in the last place becomes 1.0, round to an integer with ties to even,
+ * scale back; double holds every intermediate exactly. */
+#include <math.h>
+
+static float bits_to_float(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }
+static uint32_t float_to_bits(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
+
+uint16_t hxo_round_to_bf16(float x)
+{
+    if (isnan(x)) return 0x7FC0;
+    if (isinf(x)) return x > 0 ? 0x7F80 : 0xFF80;
+    double a = fabs((double)x);
+    uint16_t sign = signbit(x) ? 0x8000 : 0;
+    if (a == 0.0) return sign;
+    int e;
+    frexp(a, &e);                      /* a = m * 2^e, 0.5 <= m < 1: the leading bit has weight 2^(e-1) */
+    int lead = e - 1;
+    if (lead < -126) lead = -126;      /* subnormal range: fixed spacing */
+    int ulp_exp = lead - 7;            /* bf16 keeps 7 fraction bits below the leading one */
+    double q = nearbyint(ldexp(a, -ulp_exp));      /* default rounding mode: to nearest, ties to even */
+    double r = ldexp(q, ulp_exp);                  /* the chosen bf16 value, exactly */
+    if (r >= ldexp(1.0, 128)) return sign | 0x7F80;          /* rounded past the largest finite value */
+    /* r is representable in binary32 with at most 8 significant bits: its top 16 bits are the answer */
+    return sign | (uint16_t)(float_to_bits((float)r) >> 16);
+}
+
+uint32_t hxo_add_f32_bits(uint32_t a, uint32_t b)
+{
+    volatile float s = bits_to_float(a) + bits_to_float(b);
+    if (isnan(s)) return 0x7FC00000u;
+    return float_to_bits(s);
+}
+
+uint16_t hxo_add_bf16_bits(uint16_t a, uint16_t b)
+{
+    volatile float s = bits_to_float((uint32_t)a << 16) + bits_to_float((uint32_t)b << 16);
+    return hxo_round_to_bf16(s);
+}
+
+/* kind[t]: 1 = bf16, 2 = f32 (element size must agree).  Returns -1 for anything else. */
+int hxo_unpack_accumulate(const hxo_msg *m, const int32_t *kind, const uint8_t *packed, int64_t B, int k,
+                          uint8_t *const *base, int nthreads)
+{
+    hxo_geom g;
+    if (geom_init(&g, m, B, k)) return -1;
+    for (int t = 0; t < m->T; ++t)
+        if (!((kind[t] == 1 && m->esize[t] == 2) || (kind[t] == 2 && m->esize[t] == 4))) return -1;
+    (void)nthreads;
+    for (int t = 0; t < m->T; ++t) {
+        int64_t off = hxo_tensor_offset(m, t), n = hxo_tensor_elems(m, t);
+        int es = m->esize[t];
+#pragma omp parallel for num_threads(nthreads) schedule(static)
+        for (int64_t e = 0; e < n; ++e) {
+            uint8_t *dst = base[t] + hxo_element_storage_offset(m, t, e);
+            uint32_t in = 0, old = 0;
+            for (int b = 0; b < es; ++b) {             /* little-endian element, byte by byte */
+                in |= (uint32_t)packed[geom_map(&g, off + e * es + b)] << (8 * b);
+                old |= (uint32_t)dst[b] << (8 * b);
+            }
+            uint32_t out = kind[t] == 1 ? hxo_add_bf16_bits((uint16_t)old, (uint16_t)in) : hxo_add_f32_bits(old, in);
+            for (int b = 0; b < es; ++b) dst[b] = (uint8_t)(out >> (8 * b));
+        }
+    }
+    return 0;
+}
+
 /* ---- step 3: staging one lane (device->host or host->device): identity ----- */
 
 int hxo_stage_lane(int64_t L, int64_t B, int k, int l, const uint8_t *from, uint8_t *to)

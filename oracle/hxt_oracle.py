@@ -28,7 +28,7 @@ def build(force: bool = False) -> str:
     """Compile the oracle with gcc (about a second)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.run(
-            ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra", "-o", _LIB, _SRC],
+            ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"],
             check=True,
         )
     return _LIB
@@ -98,6 +98,10 @@ def lib():
             "hxo_checksum": (i32, [i64, i64, i32, p, p, i32]),
             "hxo_packed_origin": (i32, [M, i64, i32, i64, C.POINTER(C.c_int32), C.POINTER(C.c_int64)]),
             "hxo_max_threads": (i32, []),
+            "hxo_round_to_bf16": (C.c_uint16, [C.c_float]),
+            "hxo_add_f32_bits": (C.c_uint32, [C.c_uint32, C.c_uint32]),
+            "hxo_add_bf16_bits": (C.c_uint16, [C.c_uint16, C.c_uint16]),
+            "hxo_unpack_accumulate": (i32, [M, C.POINTER(C.c_int32), p, i64, i32, p, i32]),
         }
         for name, (res, args) in sigs.items():
             f = getattr(L, name)
@@ -215,6 +219,19 @@ def unpack(msg: Message, packed: np.ndarray, B: int, k: int, storages: Sequence[
     rc = lib().hxo_unpack(msg.ref, packed.ctypes.data, B, k, _ptr_array(storages), nthreads)
     if rc:
         raise ValueError("hxo_unpack rejected the arguments")
+
+
+KIND_BF16, KIND_F32 = 1, 2
+
+
+def unpack_accumulate(msg: Message, kinds: Sequence[int], packed: np.ndarray, B: int, k: int,
+                      storages: Sequence[np.ndarray], nthreads: int = 1) -> None:
+    """storages[t] += arriving tensor t, element-wise, in the arithmetic stated in hxt_oracle.c."""
+    _check_storage(msg, storages)
+    kk = (C.c_int32 * max(len(kinds), 1))(*kinds)
+    rc = lib().hxo_unpack_accumulate(msg.ref, kk, packed.ctypes.data, B, k, _ptr_array(storages), nthreads)
+    if rc:
+        raise ValueError("hxo_unpack_accumulate rejected the arguments")
 
 
 def stage_lane(msg: Message, B: int, k: int, lane: int, src: np.ndarray, dst: np.ndarray) -> None:
