@@ -42,6 +42,8 @@ def parse():
     ap.add_argument("--unbatched", action="store_true", help="one call per message on one stream")
     ap.add_argument("--path", default="device_direct", choices=["device_direct", "cpu_forward"],
                     help="for --workload stream_1f1b: how the packed buffer travels")
+    ap.add_argument("--accumulate", action="store_true",
+                    help="receive with hxt_unpack_accumulate (old + arriving) instead of hxt_unpack; one call per message")
     ap.add_argument("--no-checksum", action="store_true", help="diagnostic only: copies without checksums")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-staged", action="store_true")
@@ -104,7 +106,7 @@ def main():
     streams = [torch.cuda.Stream() for _ in range(nmsg)] if a.two_streams else [main_stream] * nmsg
     use_sums = not a.no_checksum
 
-    batched = not (a.two_streams or a.unbatched)
+    batched = not (a.two_streams or a.unbatched or a.accumulate)
     pack_b = [hxt.Batch(plans, [ms.src for ms in S], [ms.packed for ms in S],
                         [ms.send_sums for ms in S] if use_sums else None) for S in sets]
     unpack_b = [hxt.Batch(plans, [ms.dst for ms in S], [ms.packed for ms in S],
@@ -118,7 +120,8 @@ def main():
         for m, ms in enumerate(sets[i % a.sets]):
             st = streams[m]
             hxt.hxt_pack(plans[m], ms.src, ms.packed, ms.send_sums if use_sums else None, st)
-            hxt.hxt_unpack(plans[m], ms.packed, ms.dst, ms.recv_sums if use_sums else None, st)
+            recv = hxt.hxt_unpack_accumulate if a.accumulate else hxt.hxt_unpack
+            recv(plans[m], ms.packed, ms.dst, ms.recv_sums if use_sums else None, st)
 
     def fence():
         if a.two_streams:
@@ -145,13 +148,15 @@ def main():
     t1 = time.perf_counter()
     sec = t1 - t0
     gpu_ms = max(e0.elapsed_time(e1) for e0, e1 in ev)
-    step_bytes = 4 * N * nmsg                              # pack: read N + write N; unpack: the same
+    # pack: read N + write N; unpack: the same; accumulate: read N arriving + read N old + write N
+    step_bytes = (5 if a.accumulate else 4) * N * nmsg
     gbps = step_bytes * a.steps / sec / 1e9
 
     # correctness of what was just timed: round trip identity and send == receive checksums
     for ms in sets[(a.warmup + a.steps - 1) % a.sets]:
         for s_, d_ in zip(ms.src, ms.dst):
-            assert torch.equal(s_.view(torch.int16), d_.view(torch.int16)), "round trip mismatch in the timed run"
+            if not a.accumulate:
+                assert torch.equal(s_.view(torch.int16), d_.view(torch.int16)), "round trip mismatch in the timed run"
         if use_sums:
             assert torch.equal(ms.send_sums, ms.recv_sums), "checksum mismatch in the timed run"
 
@@ -165,10 +170,10 @@ def main():
     default_run = w.name == "llama8b_boundary" and batched and use_sums
     launches = 2 * nmsg * a.steps // per_launch
     launch_ms = gpu_ms / (launches if not a.two_streams else launches / nmsg)
-    launch_bytes = 2 * N * per_launch
+    launch_bytes = (2.5 if a.accumulate else 2) * N * per_launch      # accumulate: mean of a 2N pack and a 3N receive
     achieved = launch_bytes / (launch_ms * 1e-3) / 1e9
     out = {
-        "metric": "pack+unpack GB/s",
+        "metric": "pack+unpack GB/s" if not a.accumulate else "pack+accumulate GB/s",
         "value": round(gbps, 1),
         "unit": "GB/s",
         "n_gpus": 1,

@@ -155,6 +155,20 @@ int hxt_stage_h2d(const hxt_plan_t *plan, int lane, const void *host_pinned,
 int hxt_unpack(const hxt_plan_t *plan, const void *packed, void *const *dst,
                uint64_t *sums, void *stream);
 
+/* ---- widening of step 4: receive and accumulate --------------------------------
+ * Section 2.2: the intermediate results of each vendor's local reduction cross the
+ * boundary by the same P2P mechanism and are combined on arrival.  Like hxt_unpack,
+ * but every destination element becomes old + arriving instead of being overwritten:
+ *   HXT_BF16: both operands widened exactly to binary32, added in binary32 (round to
+ *             nearest even), the sum rounded to bf16 to nearest, ties to even;
+ *   HXT_F32 : IEEE binary32 addition.
+ * A NaN result is stored as the canonical quiet NaN (0x7FC0 / 0x7FC00000).
+ * Supported for plans whose non-empty tensors are all contiguous and of those two
+ * dtypes (HXT_EUNSUPPORTED otherwise), with 16-byte aligned destinations (HXT_EALIGN).
+ * sums: as in hxt_unpack (checksums of the packed bytes as read). */
+int hxt_unpack_accumulate(const hxt_plan_t *plan, const void *packed, void *const *dst,
+                          uint64_t *sums, void *stream);
+
 /* ---- steps 2 and 4 for several messages at once -------------------------------
  * A stage boundary is crossed in both directions at the same point of the schedule
  * (Section 3.1: two pipeline stages; the forward activation of one micro-batch and

@@ -34,6 +34,10 @@ struct BasePtrs {
     uint8_t *p[kMaxGroupTensors];
 };
 
+struct ElemKinds {                     // per tensor of a launch group: 1 = 32-bit float, 0 = bf16
+    uint8_t f32[kMaxGroupTensors];
+};
+
 // Per-chunk accumulator of a checksum in flight.  One per chunk and per operation
 // (pack, unpack, stand-alone checksum), kAccStride bytes apart so that neighbouring
 // chunks' atomics land in different memory channels.  Always zero between kernels.
@@ -171,6 +175,88 @@ __device__ __forceinline__ uint64_t copy_span(uint8_t *user, uint8_t *pk, uint32
     return acc;
 }
 
+// ---- receive and accumulate -----------------------------------------------------
+// new = round(old + arriving) per element.  bf16: both operands widened exactly to binary32,
+// added in binary32, the sum rounded to bf16 to nearest with ties to even.  f32: binary32
+// addition.  Every NaN result becomes the canonical quiet NaN, so that the outcome does not
+// depend on NaN payload propagation.
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f)
+{
+    const uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0u;
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+__device__ __forceinline__ uint32_t add_bf16x2(uint32_t old, uint32_t in)
+{
+    const float lo = __uint_as_float(old << 16) + __uint_as_float(in << 16);
+    const float hi = __uint_as_float(old & 0xFFFF0000u) + __uint_as_float(in & 0xFFFF0000u);
+    return f32_to_bf16_rne(lo) | (f32_to_bf16_rne(hi) << 16);
+}
+
+__device__ __forceinline__ uint32_t add_f32(uint32_t old, uint32_t in)
+{
+    const uint32_t u = __float_as_uint(__uint_as_float(old) + __uint_as_float(in));
+    return (u & 0x7FFFFFFFu) > 0x7F800000u ? 0x7FC00000u : u;
+}
+
+template <bool F32>
+__device__ __forceinline__ u32x4 add_vec(u32x4 old, u32x4 in)
+{
+    if constexpr (F32) return u32x4{add_f32(old.x, in.x), add_f32(old.y, in.y), add_f32(old.z, in.z), add_f32(old.w, in.w)};
+    else return u32x4{add_bf16x2(old.x, in.x), add_bf16x2(old.y, in.y), add_bf16x2(old.z, in.z), add_bf16x2(old.w, in.w)};
+}
+
+// Adds `bytes` arriving contiguous bytes at pk to the tensor bytes at user (both 16-byte aligned
+// except for a last partial vector, which goes element by element).  Returns the checksum
+// contribution of the packed bytes read.
+template <bool F32, bool CSUM, bool NTU, bool NTP>
+__device__ __forceinline__ uint64_t accumulate_span(uint8_t *user, const uint8_t *pk, uint32_t bytes)
+{
+    const u32x4 *in = reinterpret_cast<const u32x4 *>(pk);
+    u32x4 *io = reinterpret_cast<u32x4 *>(user);
+    const uint32_t nvec = bytes >> 4;
+    constexpr int U = 2;                                   // two vectors of each operand in flight per thread
+    constexpr uint32_t STEP = kThreads * U;
+    const uint32_t full = nvec / STEP * STEP;
+    uint64_t acc = 0;
+    for (uint32_t v = threadIdx.x; v < full; v += STEP) {
+        u32x4 a[U], b[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            a[u] = load16<NTP>(in + v + u * kThreads);
+            b[u] = load16<NTU>(io + v + u * kThreads);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            store16<NTU>(io + v + u * kThreads, add_vec<F32>(b[u], a[u]));
+            if constexpr (CSUM) acc += words_sum(a[u]);
+        }
+    }
+    for (uint32_t v = full + threadIdx.x; v < nvec; v += kThreads) {
+        const u32x4 a = load16<NTP>(in + v);
+        store16<NTU>(io + v, add_vec<F32>(load16<NTU>(io + v), a));
+        if constexpr (CSUM) acc += words_sum(a);
+    }
+    constexpr uint32_t ES = F32 ? 4 : 2;
+    const uint32_t tail = (bytes & 15) / ES;               // whole elements in the last partial vector
+    if (threadIdx.x < tail) {
+        const uint32_t off = (nvec << 4) + threadIdx.x * ES;
+        if constexpr (F32) {
+            const uint32_t a = *reinterpret_cast<const uint32_t *>(pk + off);
+            uint32_t *d = reinterpret_cast<uint32_t *>(user + off);
+            *d = add_f32(*d, a);
+            if constexpr (CSUM) acc += a;
+        } else {
+            const uint32_t a = *reinterpret_cast<const uint16_t *>(pk + off);
+            uint16_t *d = reinterpret_cast<uint16_t *>(user + off);
+            *d = uint16_t(add_bf16x2(*d, a));
+            if constexpr (CSUM) acc += uint64_t(a) << (8 * (off & 3));
+        }
+    }
+    return acc;
+}
+
 // Pad bytes (fewer than 256): pack writes zeros, unpack only reads them for the sum.
 // `phase` is the position of pk[0] within its 32-bit word.
 template <bool UNPACK, bool CSUM>
@@ -251,6 +337,39 @@ __global__ __launch_bounds__(kThreads) void k_contig(const Tile *__restrict__ ti
         acc = pad_span<UNPACK, CSUM>(packed + t.packed_off, t.n0, uint32_t(t.packed_off));
     else
         acc = copy_span<UNPACK, CSUM, NTU, NTP>(bases.p[t.tensor] + t.src_off, packed + t.packed_off, t.n0);
+    if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, chunk_tiles[t.chunk], cx);
+}
+
+// ---- receive and accumulate: the uniform and the table-driven contiguous kernels -----
+template <bool CSUM, bool NTU, bool NTP>
+__global__ __launch_bounds__(kThreads) void k_uniform_accumulate(UniformArgs a)
+{
+    const UniformItem &it = a.it[0];
+    const ChunkGeom &g = it.g;
+    const TileSpan t = locate_tile(g, blockIdx.x);
+    const uint64_t left = g.N > t.stream_off ? g.N - t.stream_off : 0;
+    const uint32_t data = left < t.len ? uint32_t(left) : t.len;
+    uint8_t *pk = it.packed + t.packed_off;
+    uint64_t acc = it.unpack ? accumulate_span<true, CSUM, NTU, NTP>(it.user + t.stream_off, pk, data)
+                             : accumulate_span<false, CSUM, NTU, NTP>(it.user + t.stream_off, pk, data);
+    if (data < t.len) acc += pad_span<true, CSUM>(pk + data, t.len - data, data);
+    if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, t.expected, it.cx);
+}
+
+template <bool CSUM, bool NTU, bool NTP>
+__global__ __launch_bounds__(kThreads) void k_contig_accumulate(const Tile *__restrict__ tiles,
+                                                                const uint32_t *__restrict__ chunk_tiles,
+                                                                BasePtrs bases, ElemKinds kinds,
+                                                                uint8_t *__restrict__ packed, SumCtx cx)
+{
+    const Tile t = tiles[blockIdx.x];
+    uint64_t acc;
+    if (t.kind == K_ZERO)
+        acc = pad_span<true, CSUM>(packed + t.packed_off, t.n0, uint32_t(t.packed_off));
+    else if (kinds.f32[t.tensor])
+        acc = accumulate_span<true, CSUM, NTU, NTP>(bases.p[t.tensor] + t.src_off, packed + t.packed_off, t.n0);
+    else
+        acc = accumulate_span<false, CSUM, NTU, NTP>(bases.p[t.tensor] + t.src_off, packed + t.packed_off, t.n0);
     if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, chunk_tiles[t.chunk], cx);
 }
 
@@ -711,6 +830,51 @@ int run_copy(hxt_plan_t &pl, void *const *ptrs, uint8_t *packed, uint64_t *sums,
     return HXT_OK;
 }
 
+// Receive and accumulate: contiguous bf16 / f32 tensors with 16-byte aligned bases only.
+template <bool CSUM>
+int run_accumulate(hxt_plan_t &pl, void *const *ptrs, uint8_t *packed, uint64_t *sums, hipStream_t st)
+{
+    const Plan &p = pl.p;
+    SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};
+    if constexpr (CSUM) {
+        int rc = claim_slots(pl, OP_UNPACK, st, cx, sums);
+        if (rc != HXT_OK) return rc;
+        cx.sum_bits = pl.sum_bits_table;
+    }
+    const bool ntp = packed_nontemporal(p.C * p.B);
+    if (p.uniform) {
+        const TensorPlan &tp = p.tensors[p.uniform_tensor];
+        UniformArgs a;
+        std::memset(&a, 0, sizeof a);
+        a.n = 1;
+        cx.sum_bits = CSUM ? pl.sum_bits_geom : 0;
+        // `unpack` carries the element kind here: 1 = f32, 0 = bf16
+        a.it[0] = UniformItem{p.geom, static_cast<uint8_t *>(ptrs[p.uniform_tensor]), packed, cx, 0,
+                              tp.dtype == HXT_F32 ? 1u : 0u};
+        with_hints(ntp, [&]<bool NTU, bool NTP>() {
+            k_uniform_accumulate<CSUM, NTU, NTP><<<p.geom.ntiles, kThreads, 0, st>>>(a);
+        });
+        HXT_HIP(hipGetLastError());
+        return HXT_OK;
+    }
+    for (const Group &g : p.groups) {                      // only K_CONTIG groups exist in such a plan
+        BasePtrs b;
+        ElemKinds kinds;
+        std::memset(&b, 0, sizeof b);
+        std::memset(&kinds, 0, sizeof kinds);
+        for (uint32_t i = 0; i < g.n_tensors; ++i) {
+            b.p[i] = static_cast<uint8_t *>(ptrs[g.tensor_base + i]);
+            kinds.f32[i] = p.tensors[g.tensor_base + i].dtype == HXT_F32;
+        }
+        with_hints(ntp, [&]<bool NTU, bool NTP>() {
+            k_contig_accumulate<CSUM, NTU, NTP><<<g.count, kThreads, 0, st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, b,
+                                                                              kinds, packed, cx);
+        });
+        HXT_HIP(hipGetLastError());
+    }
+    return HXT_OK;
+}
+
 int check_common(const hxt_plan_t *plan, const void *packed)
 {
     if (!plan) return HXT_EINVAL;
@@ -1080,6 +1244,22 @@ int hxt_unpack_batch(int n, const hxt_plan_t *const *plans, const void *const *p
                      uint64_t *const *sums, void *stream)
 {
     return run_batch<true>(n, plans, dst, const_cast<void *const *>(packed), sums, static_cast<hipStream_t>(stream));
+}
+
+int hxt_unpack_accumulate(const hxt_plan_t *plan, const void *packed, void *const *dst, uint64_t *sums,
+                          void *stream)
+{
+    int rc = check_common(plan, packed);
+    if (rc != HXT_OK || plan->p.C == 0) return rc;
+    if ((rc = check_tensor_pointers(plan->p, dst)) != HXT_OK) return rc;
+    const Plan &p = plan->p;
+    if (!p.can_accumulate) return HXT_EUNSUPPORTED;
+    for (size_t i = 0; i < p.tensors.size(); ++i)
+        if (p.tensors[i].bytes && reinterpret_cast<uintptr_t>(dst[i]) % 16) return HXT_EALIGN;
+    hxt_plan_t &pl = *const_cast<hxt_plan_t *>(plan);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint8_t *pk = const_cast<uint8_t *>(static_cast<const uint8_t *>(packed));
+    return sums ? run_accumulate<true>(pl, dst, pk, sums, st) : run_accumulate<false>(pl, dst, pk, nullptr, st);
 }
 
 int hxt_exchange_stream(const hxt_plan_t *plan, const hxt_exchange_t *x)

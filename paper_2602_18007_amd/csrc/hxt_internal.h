@@ -120,6 +120,7 @@ struct TensorPlan {
     int64_t shape[HXT_MAX_DIMS] = {0};
     int64_t stride[HXT_MAX_DIMS] = {0};  // elements
     int esize = 1;
+    hxt_dtype_t dtype = HXT_U8;
     uint64_t elems = 0, bytes = 0, stream_off = 0;
     Kind kind = K_NONE;
     bool unpack_safe = true;
@@ -145,6 +146,7 @@ struct Plan {
     std::vector<uint32_t> chunk_tiles;   // tiles of the table that belong to each chunk
     std::vector<TensorDev> tdev;
     bool all_unpack_safe = true;
+    bool can_accumulate = true;          // every non-empty tensor is contiguous bf16 or f32
     ChunkGeom geom;                      // closed-form geometry of the packed stream
     bool uniform = false;                // the message is one contiguous tensor: geom alone describes the copy
     uint32_t uniform_tensor = 0;         // index of that tensor

@@ -228,6 +228,7 @@ int build_plan(const hxt_tensor_desc_t *descs, int n_tensors, int n_lanes, size_
         if (d.ndim < 0 || d.ndim > HXT_MAX_DIMS || (d.ndim > 0 && !d.shape)) return HXT_EINVAL;
         t.esize = dtype_size(d.dtype);
         if (t.esize == 0) return HXT_EINVAL;
+        t.dtype = d.dtype;
         uint64_t elems = 1;
         for (int k = 0; k < d.ndim; ++k) {
             if (d.shape[k] < 0 || (d.strides && d.strides[k] < 0)) return HXT_EINVAL;
@@ -245,6 +246,7 @@ int build_plan(const hxt_tensor_desc_t *descs, int n_tensors, int n_lanes, size_
         t.kind = classify(t);
         t.unpack_safe = elems == 0 || view_is_injective(t);
         p.all_unpack_safe = p.all_unpack_safe && t.unpack_safe;
+        if (elems > 0 && !(t.kind == K_CONTIG && (t.dtype == HXT_BF16 || t.dtype == HXT_F32))) p.can_accumulate = false;
         p.N += t.bytes;
         off = roundup(off + t.bytes, HXT_ALIGN);
         if (off > kMaxBytes) return HXT_EUNSUPPORTED;

@@ -29,7 +29,7 @@ EXPORTS = (
     "hxt_plan_packed_bytes", "hxt_plan_chunk_bytes", "hxt_plan_num_chunks", "hxt_plan_num_lanes",
     "hxt_plan_num_tensors", "hxt_plan_chunk_info", "hxt_plan_lane_info", "hxt_plan_tensor_unpack_safe",
     "hxt_plan_tensor_kind", "hxt_pack", "hxt_stage_d2h", "hxt_stage_h2d", "hxt_unpack", "hxt_checksum",
-    "hxt_pack_batch", "hxt_unpack_batch", "hxt_exchange_stream",
+    "hxt_pack_batch", "hxt_unpack_batch", "hxt_exchange_stream", "hxt_unpack_accumulate",
     "hxt_strerror", "hxt_last_hip_error", "hxt_version",
 )
 
@@ -108,6 +108,7 @@ def lib():
             "hxt_stage_h2d": (i, [vp, i, vp, vp, vp]),
             "hxt_unpack": (i, [vp, vp, C.POINTER(vp), u64p, vp]),
             "hxt_checksum": (i, [vp, vp, u64p, vp]),
+            "hxt_unpack_accumulate": (i, [vp, vp, C.POINTER(vp), u64p, vp]),
             "hxt_pack_batch": (i, [i, C.POINTER(vp), C.POINTER(C.POINTER(vp)), C.POINTER(vp), C.POINTER(vp), vp]),
             "hxt_unpack_batch": (i, [i, C.POINTER(vp), C.POINTER(vp), C.POINTER(C.POINTER(vp)), C.POINTER(vp), vp]),
             "hxt_exchange_stream": (i, [vp, C.POINTER(_Exchange)]),
@@ -249,6 +250,11 @@ def hxt_pack(plan: Plan, src: Sequence, packed, sums=None, stream=None) -> None:
 
 def hxt_unpack(plan: Plan, packed, dst: Sequence, sums=None, stream=None) -> None:
     _check(lib().hxt_unpack(plan.handle, _ptr(packed), _ptr_array(dst), _ptr(sums), _stream(stream)), "hxt_unpack")
+
+
+def hxt_unpack_accumulate(plan: Plan, packed, dst: Sequence, sums=None, stream=None) -> None:
+    _check(lib().hxt_unpack_accumulate(plan.handle, _ptr(packed), _ptr_array(dst), _ptr(sums), _stream(stream)),
+           "hxt_unpack_accumulate")
 
 
 class Batch:
