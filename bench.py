@@ -207,6 +207,12 @@ def main():
     print(json.dumps(out))
 
 
+def _wall(fn):
+    t0 = time.perf_counter()
+    fn()
+    return time.perf_counter() - t0
+
+
 def stream_bench(torch, hxt, w, a):
     """The micro-batch stream: one step = all micro-batches through hxt_exchange_stream (two buffer sets,
     three streams), so that pack of one micro-batch overlaps staging/unpack of the previous ones."""
@@ -236,6 +242,7 @@ def stream_bench(torch, hxt, w, a):
         hxt.hxt_exchange_stream(plan, x)
         torch.cuda.synchronize()
 
+    torch.cuda.synchronize()                          # inputs were drawn on the default stream
     for _ in range(warm):
         one_pass()
     t0 = time.perf_counter()
@@ -297,9 +304,9 @@ def staged_round_trip(torch, hxt, w, plans, msgs):
         p_d2h()
         p_h2d()
 
-    t_d2h, t_h2d, t_both = best_of(p_d2h), best_of(p_h2d), best_of(p_both)
-    link = min(P / t_d2h, P / t_h2d) / 1e9
-    del d_a, d_b, h_a, h_b
+    # Both directions together first: the HIP runtime in this process keeps using one DMA engine for
+    # two streams whose first copies ran one after the other (57 GB/s for both directions instead of 97).
+    t_both = best_of(p_both)
 
     host = [torch.empty(p.packed_bytes, dtype=torch.uint8).pin_memory() for p in plans]
     recv = [torch.empty(p.packed_bytes, dtype=torch.uint8, device=dev) for p in plans]
@@ -317,10 +324,19 @@ def staged_round_trip(torch, hxt, w, plans, msgs):
     t_all = best_of(lambda: round_trip(range(len(plans))))
     for m in range(len(plans)):
         assert torch.equal(recv[m], msgs[m].packed[:plans[m].packed_bytes]), "staged bytes differ"
+    # the host-to-host hop of the chain (pinned to pinned), one thread per lane and one thread
+    hop_dst = torch.empty(plans[0].packed_bytes, dtype=torch.uint8).pin_memory()
+    t_hop = min(_wall(lambda: hxt.hxt_host_forward(plans[0], -1, host[0], hop_dst, 0)) for _ in range(5))
+    t_hop1 = min(_wall(lambda: hxt.hxt_host_forward(plans[0], -1, host[0], hop_dst, 1)) for _ in range(5))
+    assert torch.equal(hop_dst, host[0])
+    t_d2h, t_h2d = best_of(p_d2h), best_of(p_h2d)
+    link = min(P / t_d2h, P / t_h2d) / 1e9
+    del d_a, d_b, h_a, h_b
     one, all_ = N / t_one / 1e9, N * len(plans) / t_all / 1e9
     return {"round_trip_gbps": round(one, 2), "pct_host_link": round(100 * one / link, 1),
             "step_round_trip_gbps": round(all_, 2), "step_pct_host_link": round(100 * all_ / link, 1),
             "messages_in_step": len(plans), "lanes": k, "message_bytes": N,
+            "host_hop_gbps": round(N / t_hop / 1e9, 2), "host_hop_one_thread_gbps": round(N / t_hop1 / 1e9, 2),
             "probe_bytes": P, "probe_d2h_gbps": round(P / t_d2h / 1e9, 2), "probe_h2d_gbps": round(P / t_h2d / 1e9, 2),
             "probe_bidir_gbps": round(2 * P / t_both / 1e9, 2),
             "bidir_pct": round(100 * (2 * N * len(plans) / t_all / 1e9) / (2 * P / t_both / 1e9), 1),

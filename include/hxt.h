@@ -147,6 +147,22 @@ int hxt_stage_d2h(const hxt_plan_t *plan, int lane, const void *packed_dev,
 int hxt_stage_h2d(const hxt_plan_t *plan, int lane, const void *host_pinned,
                   void *packed_dev, void *stream);
 
+/* ---- widening of step 3: the host-side hop of the CPU-forwarding path ------------
+ * Section 2.1: in the compatibility path the data travels between the two hosts through
+ * a CPU-side transport, one NIC per lane.  On one machine that hop is a host-to-host
+ * copy from the pinned buffer device-to-host staging filled into the pinned buffer
+ * host-to-device staging reads, lane by lane on parallel threads.
+ *   hxt_host_forward: synchronous, pure host (no GPU needed).  Copies the used bytes of
+ *     lane `lane` (or of every lane, lane == -1) from `from` to `to` at the same offsets,
+ *     with up to n_threads threads (one lane per thread at a time; n_threads < 1 = one per
+ *     lane).  Both buffers >= packed_bytes; they must not overlap.
+ *   hxt_stage_hop: the same copy enqueued on `stream` (it runs on a host thread once the
+ *     work enqueued before it has finished, and later work on the stream waits for it).
+ * HXT_EINVAL for NULL buffers or a bad lane. */
+int hxt_host_forward(const hxt_plan_t *plan, int lane, const void *from, void *to, int n_threads);
+int hxt_stage_hop(const hxt_plan_t *plan, int lane, const void *from_pinned, void *to_pinned,
+                  int n_threads, void *stream);
+
 /* ---- step 4: unpack (Section 2.2: the receiver's symmetric copy) -------------
  * dst: host array of n_tensors device base pointers.  Writes exactly the bytes
  * the views address.  HXT_EOVERLAP if some tensor's view is not unpack-safe.

@@ -21,6 +21,7 @@
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <thread>
 #include <vector>
 
 #include "hxt_internal.h"
@@ -1244,6 +1245,70 @@ int hxt_unpack_batch(int n, const hxt_plan_t *const *plans, const void *const *p
                      uint64_t *const *sums, void *stream)
 {
     return run_batch<true>(n, plans, dst, const_cast<void *const *>(packed), sums, static_cast<hipStream_t>(stream));
+}
+
+int hxt_host_forward(const hxt_plan_t *plan, int lane, const void *from, void *to, int n_threads)
+{
+    if (!plan) return HXT_EINVAL;
+    const Plan &p = plan->p;
+    if (lane < -1 || lane >= p.k) return HXT_EINVAL;
+    if (p.C == 0) return HXT_OK;
+    if (!from || !to) return HXT_EINVAL;
+    std::vector<int> lanes;
+    for (int l = (lane < 0 ? 0 : lane); l < (lane < 0 ? p.k : lane + 1); ++l) lanes.push_back(l);
+    auto copy_lane = [&](int l) {
+        uint64_t r[2][2];
+        if (stage_ranges(p, l, r))
+            std::memcpy(static_cast<uint8_t *>(to) + r[0][0], static_cast<const uint8_t *>(from) + r[0][0], r[0][1]);
+    };
+    const size_t workers = std::min<size_t>(lanes.size(), n_threads < 1 ? lanes.size() : size_t(n_threads));
+    if (workers <= 1) {
+        for (int l : lanes) copy_lane(l);
+        return HXT_OK;
+    }
+    try {
+        std::vector<std::thread> pool;
+        for (size_t w = 0; w < workers; ++w)
+            pool.emplace_back([&, w] {
+                for (size_t i = w; i < lanes.size(); i += workers) copy_lane(lanes[i]);
+            });
+        for (std::thread &t : pool) t.join();
+    } catch (const std::exception &) {
+        return HXT_ENOMEM;                         // thread creation failed
+    }
+    return HXT_OK;
+}
+
+namespace {
+struct HopJob {
+    const hxt_plan_t *plan;
+    int lane;
+    const void *from;
+    void *to;
+    int n_threads;
+};
+void run_hop(void *arg)
+{
+    HopJob *j = static_cast<HopJob *>(arg);
+    (void)hxt_host_forward(j->plan, j->lane, j->from, j->to, j->n_threads);
+    delete j;
+}
+}  // namespace
+
+int hxt_stage_hop(const hxt_plan_t *plan, int lane, const void *from_pinned, void *to_pinned, int n_threads,
+                  void *stream)
+{
+    if (!plan || lane < -1 || lane >= plan->p.k) return HXT_EINVAL;
+    if (plan->p.C == 0) return HXT_OK;
+    if (!from_pinned || !to_pinned) return HXT_EINVAL;
+    HopJob *j = new (std::nothrow) HopJob{plan, lane, from_pinned, to_pinned, n_threads};
+    if (!j) return HXT_ENOMEM;
+    hipError_t e = hipLaunchHostFunc(static_cast<hipStream_t>(stream), run_hop, j);
+    if (e != hipSuccess) {
+        delete j;
+        return hip_fail(e);
+    }
+    return HXT_OK;
 }
 
 int hxt_unpack_accumulate(const hxt_plan_t *plan, const void *packed, void *const *dst, uint64_t *sums,

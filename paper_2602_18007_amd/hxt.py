@@ -30,6 +30,7 @@ EXPORTS = (
     "hxt_plan_num_tensors", "hxt_plan_chunk_info", "hxt_plan_lane_info", "hxt_plan_tensor_unpack_safe",
     "hxt_plan_tensor_kind", "hxt_pack", "hxt_stage_d2h", "hxt_stage_h2d", "hxt_unpack", "hxt_checksum",
     "hxt_pack_batch", "hxt_unpack_batch", "hxt_exchange_stream", "hxt_unpack_accumulate",
+    "hxt_host_forward", "hxt_stage_hop",
     "hxt_strerror", "hxt_last_hip_error", "hxt_version",
 )
 
@@ -108,6 +109,8 @@ def lib():
             "hxt_stage_h2d": (i, [vp, i, vp, vp, vp]),
             "hxt_unpack": (i, [vp, vp, C.POINTER(vp), u64p, vp]),
             "hxt_checksum": (i, [vp, vp, u64p, vp]),
+            "hxt_host_forward": (i, [vp, i, vp, vp, i]),
+            "hxt_stage_hop": (i, [vp, i, vp, vp, i, vp]),
             "hxt_unpack_accumulate": (i, [vp, vp, C.POINTER(vp), u64p, vp]),
             "hxt_pack_batch": (i, [i, C.POINTER(vp), C.POINTER(C.POINTER(vp)), C.POINTER(vp), C.POINTER(vp), vp]),
             "hxt_unpack_batch": (i, [i, C.POINTER(vp), C.POINTER(vp), C.POINTER(C.POINTER(vp)), C.POINTER(vp), vp]),
@@ -250,6 +253,22 @@ def hxt_pack(plan: Plan, src: Sequence, packed, sums=None, stream=None) -> None:
 
 def hxt_unpack(plan: Plan, packed, dst: Sequence, sums=None, stream=None) -> None:
     _check(lib().hxt_unpack(plan.handle, _ptr(packed), _ptr_array(dst), _ptr(sums), _stream(stream)), "hxt_unpack")
+
+
+def _host_ptr(x) -> Optional[int]:
+    """Address of a host buffer: a CPU torch tensor, a NumPy array, or an integer."""
+    if x is None or isinstance(x, (int, torch.Tensor)):
+        return _ptr(x)
+    return int(x.ctypes.data)
+
+
+def hxt_host_forward(plan: Plan, lane: int, src, dst, n_threads: int = 0) -> None:
+    _check(lib().hxt_host_forward(plan.handle, lane, _host_ptr(src), _host_ptr(dst), n_threads), "hxt_host_forward")
+
+
+def hxt_stage_hop(plan: Plan, lane: int, from_pinned, to_pinned, n_threads: int = 0, stream=None) -> None:
+    _check(lib().hxt_stage_hop(plan.handle, lane, _ptr(from_pinned), _ptr(to_pinned), n_threads, _stream(stream)),
+           "hxt_stage_hop")
 
 
 def hxt_unpack_accumulate(plan: Plan, packed, dst: Sequence, sums=None, stream=None) -> None:

@@ -278,6 +278,53 @@ def test_staging_lane_by_lane_and_all_lanes(name):
             assert np.array_equal(b.cpu().numpy(), a)
 
 
+@pytest.mark.parametrize("name", ["contig_1MB_ragged", "multi_mid"])
+def test_cpu_forwarding_chain_with_host_hop(name):
+    # D2H into the sender's pinned buffer, host-to-host hop (stream ordered), H2D from the receiver's pinned
+    # buffer, unpack; once on one stream, once lane by lane over three streams chained with events
+    case = [c for c in MID_CASES if c.name == name][0]
+    say("host hop", name)
+    raws = make_storages(case, 71)
+    m = oracle_msg(case)
+    p, packed, want, want_sums = round_trip_check(case, raws)
+    n = want.size
+    dst_o = [np.zeros(r.size, np.uint8) for r in raws]
+    ho.unpack(m, want, case.B, case.k, dst_o)
+    for pipelined in (False, True):
+        h_send = torch.full((n,), 0x11, dtype=torch.uint8).pin_memory()
+        h_recv = torch.full((n,), 0x22, dtype=torch.uint8).pin_memory()
+        recv = torch.full((n,), 0x33, dtype=torch.uint8, device=DEV)
+        if not pipelined:
+            s = torch.cuda.Stream()
+            s.wait_stream(torch.cuda.current_stream())
+            hxt.hxt_stage_d2h(p, -1, packed, h_send, s)
+            hxt.hxt_stage_hop(p, -1, h_send, h_recv, 0, s)
+            hxt.hxt_stage_h2d(p, -1, h_recv, recv, s)
+            last = s
+        else:
+            s1, s2, s3 = (torch.cuda.Stream() for _ in range(3))
+            s1.wait_stream(torch.cuda.current_stream())
+            for l in range(case.k):
+                hxt.hxt_stage_d2h(p, l, packed, h_send, s1)
+                e1 = torch.cuda.Event(); e1.record(s1); s2.wait_event(e1)
+                hxt.hxt_stage_hop(p, l, h_send, h_recv, 1, s2)
+                e2 = torch.cuda.Event(); e2.record(s2); s3.wait_event(e2)
+                hxt.hxt_stage_h2d(p, l, h_recv, recv, s3)
+            last = s3
+        dst = [torch.zeros(r.size, dtype=torch.uint8, device=DEV) for r in raws]
+        rs = torch.zeros(p.num_chunks, dtype=torch.int64, device=DEV)
+        last.wait_stream(torch.cuda.current_stream())       # the zero fills above ran on the current stream
+        hxt.hxt_unpack(p, recv, dst, rs, last)
+        torch.cuda.synchronize()
+        expect = np.full(n, 0x22, np.uint8)
+        for l in range(case.k):
+            ho.stage_lane(m, case.B, case.k, l, want, expect)
+        assert np.array_equal(h_recv.numpy(), expect)
+        assert np.array_equal(rs.cpu().numpy().view(np.uint64), want_sums)
+        for a, b in zip(dst_o, dst):
+            assert np.array_equal(b.cpu().numpy(), a)
+
+
 def test_bit_flip_in_host_buffer_shows_in_exactly_one_checksum():
     case = Case("flip", (contig((40000,), 2),), 3, 8192)
     raws = make_storages(case, 23)

@@ -304,3 +304,29 @@ def test_unpack_safety_flag_never_accepts_an_aliasing_view():
                 idx = idx[..., None] + np.arange(s_, dtype=np.int64) * st
             assert np.unique(idx).size == idx.size, (shape, strides)
     assert accepted > 50
+
+
+# ---- host-side hop of the CPU-forwarding path (pure host code) ------------------------
+
+@pytest.mark.parametrize("name", ["ragged_last_chunk_2p5", "fewer_chunks_than_lanes", "three_tensors_with_gaps",
+                                  "mixed_dtypes_multi", "empty_tensor"])
+@pytest.mark.parametrize("threads", [0, 1, 3])
+def test_host_forward_copies_the_used_bytes_of_the_lanes(name, threads):
+    case = [c for c in SMALL_CASES if c.name == name][0]
+    m, p = oracle_msg(case), plan_of(case)
+    raws = make_storages(case, 91)
+    packed = ho.pack(m, raws, case.B, case.k, fill=0xB7)
+    n = max(packed.size, 1)
+    for lanes in ([-1], list(range(case.k))):
+        got = np.full(n, 0x11, np.uint8)
+        want = np.full(n, 0x11, np.uint8)
+        for l in lanes:
+            hxt.hxt_host_forward(p, l, packed if packed.size else want, got, threads)
+        for l in range(case.k):
+            if packed.size:
+                ho.stage_lane(m, case.B, case.k, l, packed, want)
+        assert np.array_equal(got, want)          # used bytes moved, everything else (unspecified tail) untouched
+    L = hxt.lib()
+    assert L.hxt_host_forward(p.handle, case.k, 256, 256, 1) == hxt.HXT_EINVAL
+    if packed.size:
+        assert L.hxt_host_forward(p.handle, 0, None, 256, 1) == hxt.HXT_EINVAL
