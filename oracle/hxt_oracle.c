@@ -348,6 +348,33 @@ int hxo_checksum(int64_t L, int64_t B, int k, const uint8_t *packed, uint64_t *s
     return 0;
 }
 
+/* ---- widening: a second, position-weighted sum per chunk -----------------------
+ * The plain sum cannot see words that changed places inside a chunk.  With the chunk's words
+ * w_0 .. w_{W-1} (little-endian, W = padded length / 4), out[2c] = sum_j w_j and
+ * out[2c+1] = sum_j (j+1) * w_j, both mod 2^64.  Swapping words i and j changes the second
+ * sum by (j - i) * (w_i - w_j), which is non-zero mod 2^64 whenever the words differ. */
+int hxo_checksum2(int64_t L, int64_t B, int k, const uint8_t *packed, uint64_t *out, int nthreads)
+{
+    if (k < 1 || B <= 0 || B % HXO_ALIGN) return -1;
+    int64_t C = hxo_num_chunks(L, B);
+    (void)nthreads;
+#pragma omp parallel for num_threads(nthreads) schedule(dynamic, 1)
+    for (int64_t c = 0; c < C; ++c) {
+        const uint8_t *p = packed + hxo_chunk_packed_offset(L, B, k, c);
+        int64_t words = hxo_chunk_padded(L, B, c) / 4;
+        uint64_t s1 = 0, s2 = 0;
+        for (int64_t j = 0; j < words; ++j) {
+            uint64_t w = (uint64_t)p[4 * j] | (uint64_t)p[4 * j + 1] << 8 |
+                         (uint64_t)p[4 * j + 2] << 16 | (uint64_t)p[4 * j + 3] << 24;
+            s1 += w;
+            s2 += (uint64_t)(j + 1) * w;
+        }
+        out[2 * c] = s1;
+        out[2 * c + 1] = s2;
+    }
+    return 0;
+}
+
 /* ---- inverse map, for sampled checks at sizes too big to pack on the CPU ---
  * Given a packed byte position p, say where it comes from:
  *   returns  1 and sets (*t, *storage_off): byte storage_off of tensor t's storage

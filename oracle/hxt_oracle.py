@@ -96,6 +96,7 @@ def lib():
             "hxo_unpack": (i32, [M, p, i64, i32, p, i32]),
             "hxo_stage_lane": (i32, [i64, i64, i32, i32, p, p]),
             "hxo_checksum": (i32, [i64, i64, i32, p, p, i32]),
+            "hxo_checksum2": (i32, [i64, i64, i32, p, p, i32]),
             "hxo_packed_origin": (i32, [M, i64, i32, i64, C.POINTER(C.c_int32), C.POINTER(C.c_int64)]),
             "hxo_max_threads": (i32, []),
             "hxo_round_to_bf16": (C.c_uint16, [C.c_float]),
@@ -246,6 +247,15 @@ def checksum(msg: Message, packed: np.ndarray, B: int, k: int, nthreads: int = 1
     if rc:
         raise ValueError("hxo_checksum rejected the arguments")
     return sums
+
+
+def checksum2(msg: Message, packed: np.ndarray, B: int, k: int, nthreads: int = 1) -> np.ndarray:
+    """[C, 2] array: plain sum and position-weighted sum of every chunk."""
+    out = np.zeros((num_chunks(msg, B), 2), dtype=np.uint64)
+    rc = lib().hxo_checksum2(msg.L, B, k, packed.ctypes.data, out.ctypes.data, nthreads)
+    if rc:
+        raise ValueError("hxo_checksum2 rejected the arguments")
+    return out
 
 
 def packed_origin(msg: Message, B: int, k: int, p: int):

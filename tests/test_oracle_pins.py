@@ -343,3 +343,50 @@ def test_empty_message():
     m = msg_of(case)
     assert (m.N, m.L, ho.num_chunks(m, case.B), ho.packed_bytes(m, case.B, case.k)) == (0, 0, 0, 0)
     assert ho.checksum(m, np.zeros(0, np.uint8), case.B, case.k).size == 0
+
+
+# ---------------------------------------------------------------------------
+# 7. position-weighted second sum
+# ---------------------------------------------------------------------------
+
+def test_checksum2_big_integer_brute_force_and_closed_form():
+    case = case_by_name("three_tensors_with_gaps")
+    m = msg_of(case)
+    packed = ho.pack(m, make_storages(case, 61), case.B, case.k)
+    both = ho.checksum2(m, packed, case.B, case.k)
+    assert np.array_equal(both[:, 0], ho.checksum(m, packed, case.B, case.k))
+    for c in range(ho.num_chunks(m, case.B)):
+        info = ho.chunk_info(m, case.B, case.k, c)
+        raw = packed[info["packed_off"]:info["packed_off"] + info["padded"]].tobytes()
+        big = sum((j + 1) * int.from_bytes(raw[4 * j:4 * j + 4], "little") for j in range(len(raw) // 4))
+        assert int(both[c, 1]) == big % (1 << 64)
+    # all-0xFF chunk of W words: (2^32 - 1) * W (W + 1) / 2
+    B, k = 2048, 2
+    z = Case("z", (contig((3 * B,), 1),), k, B)
+    mz = msg_of(z)
+    ones = ho.checksum2(mz, ho.pack(mz, [np.full(3 * B, 0xFF, np.uint8)], B, k), B, k)
+    W = B // 4
+    assert [int(x) for x in ones[:, 1]] == [((2**32 - 1) * W * (W + 1) // 2) % 2**64] * 3
+    # one byte set in word j of chunk 1 (byte 1 of the word): weight (j + 1) * 256
+    raw = np.zeros(3 * B, np.uint8)
+    raw[B + 4 * 37 + 1] = 1
+    one = ho.checksum2(mz, ho.pack(mz, [raw], B, k), B, k)
+    assert [[int(a), int(b)] for a, b in one] == [[0, 0], [256, 38 * 256], [0, 0]]
+
+
+def test_checksum2_sees_words_that_changed_places():
+    case = case_by_name("ragged_last_chunk_2p5")
+    m = msg_of(case)
+    packed = ho.pack(m, make_storages(case, 62), case.B, case.k)
+    before = ho.checksum2(m, packed, case.B, case.k)
+    info = ho.chunk_info(m, case.B, case.k, 1)
+    w = packed[info["packed_off"]:info["packed_off"] + info["padded"]].view("<u4")
+    i, j = 5, 200
+    wi, wj = int(w[i]), int(w[j])
+    assert wi != wj
+    w[i], w[j] = wj, wi
+    after = ho.checksum2(m, packed, case.B, case.k)
+    assert np.array_equal(after[:, 0], before[:, 0])                    # the plain sum is blind to it
+    diff = (int(after[1, 1]) - int(before[1, 1])) % 2**64
+    assert diff == ((j - i) * (wi - wj)) % 2**64 and diff != 0
+    assert np.array_equal(after[[0, 2], 1], before[[0, 2], 1])
