@@ -241,6 +241,14 @@ int hxt_exchange_stream(const hxt_plan_t *plan, const hxt_exchange_t *x);
 /* ---- step 5: stand-alone per-chunk checksum of a packed buffer --------------- */
 int hxt_checksum(const hxt_plan_t *plan, const void *packed, uint64_t *sums, void *stream);
 
+/* ---- widening of step 5: a check that also sees words that changed places --------
+ * The plain sum is blind to a permutation of words inside a chunk.  For chunk c with
+ * words w_0 .. w_{W-1} this writes sums2[2c] = sum_j w_j and sums2[2c+1] =
+ * sum_j (j+1) * w_j, both mod 2^64 (swapping words i and j changes the second by
+ * (j-i) * (w_i - w_j) != 0).  Stand-alone pass over a packed buffer (reads N bytes).
+ * sums2: device array of 2 * num_chunks uint64. */
+int hxt_checksum2(const hxt_plan_t *plan, const void *packed, uint64_t *sums2, void *stream);
+
 /* ---- diagnostics -------------------------------------------------------------- */
 const char *hxt_strerror(int status);
 int hxt_last_hip_error(void);    /* hipError_t of the last failing HIP call on this thread */

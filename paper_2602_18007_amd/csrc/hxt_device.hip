@@ -590,12 +590,104 @@ __global__ __launch_bounds__(kThreads) void k_checksum(ChunkGeom g, const uint8_
     chunk_commit(acc, t.chunk, t.ordinal, t.expected, cx);
 }
 
+// ---- stand-alone strong check: plain sum and position-weighted sum of every chunk -------
+// out[2c] = sum of the chunk's words, out[2c+1] = sum of (j+1) * word j, both mod 2^64.
+// A logical accumulator is a pair of slots (2s: plain sum and arrival count, 2s+1: weighted
+// sum); the ticket is taken after both additions have returned.  Same two-level fan-out as
+// chunk_commit: first-level pairs C*fan, then one second-level pair per chunk.
+__device__ __forceinline__ bool pair_arrive(uint8_t *acc, uint32_t stride, size_t s, unsigned long long &a,
+                                            unsigned long long &b, uint32_t expected)
+{
+    if (expected == 1) return true;
+    Acc *sa = reinterpret_cast<Acc *>(acc + (2 * s) * stride);
+    Acc *sb = reinterpret_cast<Acc *>(acc + (2 * s + 1) * stride);
+    const unsigned long long ra = __hip_atomic_fetch_add(&sa->sum, a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long rb = __hip_atomic_fetch_add(&sb->sum, b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("s_waitcnt vmcnt(0)" ::"v"(uint32_t(ra)), "v"(uint32_t(rb)) : "memory");
+    const uint32_t ticket = __hip_atomic_fetch_add(&sa->cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (ticket != expected - 1) return false;
+    a = __hip_atomic_exchange(&sa->sum, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    b = __hip_atomic_exchange(&sb->sum, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(&sa->cnt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return true;
+}
+
+// Word j of the chunk sits at tile word i = j - j0.  A thread's vectors start at tile words
+// 4 * (tid + 256 * n), n = 0, 1, ...; with S_n the sum of vector n's words and I_n = y + 2z + 3w,
+//   sum (j+1) w_j = (j0 + 4 tid + 1) * sum_n S_n + 1024 * sum_n n S_n + sum_n I_n,
+// so the loop needs additions only (sum_n n S_n is kept as a running suffix sum) and each
+// thread multiplies once.
+template <bool NTP>
+__global__ __launch_bounds__(kThreads) void k_checksum2(ChunkGeom g, const uint8_t *__restrict__ packed,
+                                                        uint64_t *__restrict__ out, uint8_t *acc, uint32_t stride,
+                                                        uint32_t fan)
+{
+    const TileSpan t = locate_tile(g, blockIdx.x);
+    const u32x4 *s = reinterpret_cast<const u32x4 *>(packed + t.packed_off);
+    const uint64_t j0 = (t.stream_off - uint64_t(t.chunk) * g.B) >> 2;
+    const uint32_t nvec = t.len >> 4;
+    uint64_t S = 0, nS = 0, I = 0;          // sum_n S_n, sum_n n*S_n, sum_n I_n
+    uint64_t n0 = 0;                         // n of the current block of vectors
+    for (uint32_t v = threadIdx.x; v < nvec; v += kThreads * kUnroll, n0 += kUnroll) {
+        u32x4 r[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u)
+            r[u] = (v + u * kThreads < nvec) ? load16<NTP>(s + v + u * kThreads) : u32x4{0, 0, 0, 0};
+        uint64_t blockS = 0, blockN = 0;     // this block's sum_u S_u and sum_u u*S_u
+#pragma unroll
+        for (int u = kUnroll - 1; u >= 0; --u) {
+            const uint64_t zw = uint64_t(r[u].z) + r[u].w;
+            const uint64_t yzw = zw + r[u].y;
+            blockN += blockS;                // after the loop: sum_u u * S_u
+            blockS += yzw + r[u].x;
+            I += yzw + zw + r[u].w;
+        }
+        S += blockS;
+        nS += blockN + n0 * blockS;
+    }
+    unsigned long long a = S;
+    unsigned long long b = (j0 + 4ull * threadIdx.x + 1) * S + 4ull * kThreads * nS + I;
+    __shared__ uint64_t part[2][kThreads / 64];
+    for (int o = 32; o > 0; o >>= 1) {
+        a += __shfl_down(a, o, 64);
+        b += __shfl_down(b, o, 64);
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) {
+        part[0][wave] = a;
+        part[1][wave] = b;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        a = b = 0;
+#pragma unroll
+        for (int w = 0; w < kThreads / 64; ++w) {
+            a += part[0][w];
+            b += part[1][w];
+        }
+        const size_t top = size_t(g.C) * fan + t.chunk;
+        bool last;
+        if (fan == 1 || t.expected < 2 * fan) {
+            last = pair_arrive(acc, stride, top, a, b, t.expected);
+        } else {
+            const uint32_t sub = t.ordinal & (fan - 1);
+            const uint32_t share = t.expected / fan + (sub < (t.expected & (fan - 1)) ? 1u : 0u);
+            last = pair_arrive(acc, stride, size_t(t.chunk) * fan + sub, a, b, share) &&
+                   pair_arrive(acc, stride, top, a, b, fan);
+        }
+        if (last) {
+            out[2 * size_t(t.chunk)] = a;
+            out[2 * size_t(t.chunk) + 1] = b;
+        }
+    }
+}
+
 }  // namespace hxt
 
 using namespace hxt;
 
 // The plan: host tables, their device copies, and the checksum accumulators.
-enum Op { OP_PACK = 0, OP_UNPACK = 1, OP_CHECKSUM = 2, OP_COUNT = 3 };
+enum Op { OP_PACK = 0, OP_UNPACK = 1, OP_CHECKSUM = 2, OP_CHECKSUM2 = 3, OP_COUNT = 4 };
 
 struct OpState {              // accumulator slots of one operation and who used them last
     uint8_t *acc = nullptr;
@@ -942,9 +1034,10 @@ int upload(hxt_plan_t &pl)
     const size_t slots = size_t(p.C) * (pl.fan + 1);
     pl.acc_stride = slots <= 65536 ? 256 : uint32_t(sizeof(Acc));
     const size_t bytes = slots * pl.acc_stride;
-    for (OpState &o : pl.ops) {
-        HXT_HIP(hipMalloc(reinterpret_cast<void **>(&o.acc), bytes));
-        HXT_HIP(hipMemset(o.acc, 0, bytes));
+    for (int i = 0; i < OP_COUNT; ++i) {
+        const size_t n = i == OP_CHECKSUM2 ? 2 * bytes : bytes;      // that op keeps pairs of slots
+        HXT_HIP(hipMalloc(reinterpret_cast<void **>(&pl.ops[i].acc), n));
+        HXT_HIP(hipMemset(pl.ops[i].acc, 0, n));
     }
     HXT_HIP(hipDeviceSynchronize());
     return HXT_OK;
@@ -1423,6 +1516,24 @@ int hxt_checksum(const hxt_plan_t *plan, const void *packed, uint64_t *sums, voi
         k_checksum<true><<<pl.p.geom.ntiles, kThreads, 0, st>>>(pl.p.geom, pk, cx);
     else
         k_checksum<false><<<pl.p.geom.ntiles, kThreads, 0, st>>>(pl.p.geom, pk, cx);
+    HXT_HIP(hipGetLastError());
+    return HXT_OK;
+}
+
+int hxt_checksum2(const hxt_plan_t *plan, const void *packed, uint64_t *sums2, void *stream)
+{
+    int rc = check_common(plan, packed);
+    if (rc != HXT_OK || plan->p.C == 0) return rc;
+    if (!sums2) return HXT_EINVAL;
+    hxt_plan_t &pl = *const_cast<hxt_plan_t *>(plan);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};
+    if ((rc = claim_slots(pl, OP_CHECKSUM2, st, cx, sums2)) != HXT_OK) return rc;
+    const uint8_t *pk = static_cast<const uint8_t *>(packed);
+    if (packed_nontemporal(pl.p.C * pl.p.B))
+        k_checksum2<true><<<pl.p.geom.ntiles, kThreads, 0, st>>>(pl.p.geom, pk, sums2, cx.acc, cx.stride, cx.fan);
+    else
+        k_checksum2<false><<<pl.p.geom.ntiles, kThreads, 0, st>>>(pl.p.geom, pk, sums2, cx.acc, cx.stride, cx.fan);
     HXT_HIP(hipGetLastError());
     return HXT_OK;
 }

@@ -30,7 +30,7 @@ EXPORTS = (
     "hxt_plan_num_tensors", "hxt_plan_chunk_info", "hxt_plan_lane_info", "hxt_plan_tensor_unpack_safe",
     "hxt_plan_tensor_kind", "hxt_pack", "hxt_stage_d2h", "hxt_stage_h2d", "hxt_unpack", "hxt_checksum",
     "hxt_pack_batch", "hxt_unpack_batch", "hxt_exchange_stream", "hxt_unpack_accumulate",
-    "hxt_host_forward", "hxt_stage_hop",
+    "hxt_host_forward", "hxt_stage_hop", "hxt_checksum2",
     "hxt_strerror", "hxt_last_hip_error", "hxt_version",
 )
 
@@ -109,6 +109,7 @@ def lib():
             "hxt_stage_h2d": (i, [vp, i, vp, vp, vp]),
             "hxt_unpack": (i, [vp, vp, C.POINTER(vp), u64p, vp]),
             "hxt_checksum": (i, [vp, vp, u64p, vp]),
+            "hxt_checksum2": (i, [vp, vp, u64p, vp]),
             "hxt_host_forward": (i, [vp, i, vp, vp, i]),
             "hxt_stage_hop": (i, [vp, i, vp, vp, i, vp]),
             "hxt_unpack_accumulate": (i, [vp, vp, C.POINTER(vp), u64p, vp]),
@@ -321,6 +322,10 @@ def hxt_exchange_stream(plan: Plan, x: Exchange) -> None:
 
 def hxt_checksum(plan: Plan, packed, sums, stream=None) -> None:
     _check(lib().hxt_checksum(plan.handle, _ptr(packed), _ptr(sums), _stream(stream)), "hxt_checksum")
+
+
+def hxt_checksum2(plan: Plan, packed, sums2, stream=None) -> None:
+    _check(lib().hxt_checksum2(plan.handle, _ptr(packed), _ptr(sums2), _stream(stream)), "hxt_checksum2")
 
 
 def hxt_stage_d2h(plan: Plan, lane: int, packed_dev, host_pinned, stream=None) -> None:

@@ -85,6 +85,10 @@ def round_trip_check(case, raws, tile_bytes=None, base_offset=0, nthreads=1, two
     sums2 = torch.full_like(sums, 7)
     hxt.hxt_checksum(p, packed, sums2)
     assert np.array_equal(sums2.cpu().numpy().view(np.uint64)[:want_sums.size], want_sums)
+    # the position-weighted pair of sums
+    strong = torch.full((max(want_sums.size, 1), 2), 9, dtype=torch.int64, device=DEV)
+    hxt.hxt_checksum2(p, packed, strong)
+    assert np.array_equal(strong.cpu().numpy().view(np.uint64)[:want_sums.size], ho.checksum2(m, want, B, k, nthreads=nthreads))
 
     if all(p.tensor_unpack_safe(t) for t in range(len(case.tensors))):
         dst_o = [np.full(r.size, 0x3C, np.uint8) for r in raws]
@@ -130,6 +134,7 @@ def test_base_pointers_that_are_only_element_aligned(name):
 MID_CASES = [
     Case("contig_1MB_ragged", (contig((1_000_001,), 1),), 3, 65536),
     Case("contig_bf16_5MiB_tail", (contig((5 * 1024 * 1024 // 2 + 24,), 2),), 4, 1 << 20),
+    Case("contig_chunks_of_256_tiles", (contig((9 * 1024 * 1024 // 2 + 40,), 2),), 2, 4 << 20),   # fanned-out commit
     Case("rows_mid", (((300, 2, 112), (112, 300 * 112, 1), 2),), 3, 4096),
     Case("rows_big_rows", (((96, 2, 3584), (3584, 96 * 3584, 1), 2),), 8, 65536),
     Case("rows_padded_pitch", (((1000, 256), (320, 1), 4),), 5, 32768),
@@ -389,6 +394,35 @@ def test_bit_flip_in_host_buffer_shows_in_exactly_one_checksum():
     assert diff == [0, 0, 0, 0, (-delta if was_set else delta)] + [0] * (len(diff) - 5)
 
 
+def test_words_that_change_places_show_only_in_the_weighted_sum():
+    """Two unequal words of one chunk swapped on the host: the plain sum stays, the weighted sum moves by
+    (j - i) * (w_i - w_j) in that chunk alone; repeated calls leave the accumulators clean."""
+    case = Case("swap", (contig((600000,), 2),), 2, 262144)          # 16 tiles per full chunk, ragged last chunk
+    raws = make_storages(case, 29)
+    p, packed, want, want_sums = round_trip_check(case, raws)
+    m = oracle_msg(case)
+    host = packed.cpu().numpy().copy()
+    c = 2
+    base = p.chunk_info(c)["packed_off"]
+    words = host[base:base + case.B].view("<u4")
+    i, j = 5, 40001                                                  # different tiles of the chunk
+    assert words[i] != words[j]
+    wi, wj = int(words[i]), int(words[j])
+    words[i], words[j] = wj, wi
+    want2 = ho.checksum2(m, host, case.B, case.k)
+    clean2 = ho.checksum2(m, want, case.B, case.k)
+    assert np.array_equal(want2[:, 0], clean2[:, 0])
+    assert (int(want2[c, 1]) - int(clean2[c, 1])) % 2**64 == ((j - i) * (wi - wj)) % 2**64
+    dev = to_dev(host)
+    for rep in range(3):
+        got = torch.full((p.num_chunks, 2), rep, dtype=torch.int64, device=DEV)
+        hxt.hxt_checksum2(p, dev, got)
+        assert np.array_equal(got.cpu().numpy().view(np.uint64), want2)
+    plain = torch.zeros(p.num_chunks, dtype=torch.int64, device=DEV)
+    hxt.hxt_checksum(p, dev, plain)
+    assert np.array_equal(plain.cpu().numpy().view(np.uint64), want_sums)   # blind to the swap
+
+
 def test_data_plane_argument_errors():
     case = case_by_name("single_lane")
     p = plan_of(case)
@@ -409,6 +443,8 @@ def test_data_plane_argument_errors():
         hxt.hxt_stage_d2h(p, 1, packed, packed)                          # lane out of range (k = 1)
     assert e.value.status == hxt.HXT_EINVAL
     assert L.hxt_checksum(p.handle, packed.data_ptr(), None, None) == hxt.HXT_EINVAL
+    assert L.hxt_checksum2(p.handle, packed.data_ptr(), None, None) == hxt.HXT_EINVAL
+    assert L.hxt_checksum2(p.handle, None, packed.data_ptr(), None) == hxt.HXT_EINVAL
     torch.cuda.synchronize()
 
 
@@ -640,6 +676,9 @@ def test_config_grad_buckets_full_size_both_paths():
     assert np.array_equal(got, want)
     assert np.array_equal(sums.cpu().numpy().view(np.uint64), want_sums)
     del got
+    strong = torch.zeros(C, 2, dtype=torch.int64, device=DEV)
+    hxt.hxt_checksum2(p, packed, strong)
+    assert np.array_equal(strong.cpu().numpy().view(np.uint64), ho.checksum2(m, want, w.chunk_bytes, w.n_lanes, nthreads=NT))
     say("grad buckets: cpu-forward leg")
     host = torch.zeros(nb, dtype=torch.uint8).pin_memory()
     recv = torch.full((nb,), 0x5A, dtype=torch.uint8, device=DEV)
