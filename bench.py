@@ -27,7 +27,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0     # MI355X HBM3E vendor peak
 # HBM-side bytes per k_uniform launch on the default workload from rocprofv3 counter passes
 # (FETCH_SIZE, WRITE_SIZE, scaled by a plain copy of known size); None = not measured for this build.
-TRAFFIC_BYTES_PER_LAUNCH = 134495043
+TRAFFIC_BYTES_PER_LAUNCH = 134489378
 
 
 def parse():
