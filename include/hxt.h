@@ -30,6 +30,8 @@
  *     written to outputs on error.  No function throws or aborts.
  *   - "device" pointers are HIP device addresses on the current device, "host"
  *     pointers ordinary process memory, "pinned" host memory from hipHostMalloc.
+ *     A plan belongs to the device that was current when it was created; a
+ *     data-plane call made with another device current returns HXT_EHIP.
  *   - The caller owns every data buffer and every stream.  The library owns only
  *     the plan (host tables plus one small device copy of its work tables,
  *     allocated by hxt_plan*, released by hxt_plan_destroy).

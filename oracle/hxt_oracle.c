@@ -30,6 +30,8 @@
  *  5. Staging a lane = copying that lane's used region unchanged.
  *  6. Unpack = the inverse of 1-4 for every tensor byte; pad bytes are dropped.
  *  7. Checksum of chunk c = sum of its little-endian 32-bit words, mod 2^64.
+ *  Widenings, each stated where it is defined below: receive-and-accumulate, a second
+ *  position-weighted sum per chunk, and a 64-byte tag per chunk (seal / verify).
  *
  * Style: one element at a time, every position recomputed from the formulas
  * above; no chunk table, no dimension merging, no blocking.  The counting
@@ -38,7 +40,9 @@
  * Pins (see tests/test_oracle_pins.py): hand-written chunk orders and sizes in
  * tests/golden/, NumPy's own strided-view flattening as the logical stream,
  * memcpy for the k=1 contiguous case, closed-form checksums, Python big-int
- * sums, round-trip identity, forward map vs inverse map.  The end-to-end
+ * sums, round-trip identity, forward map vs inverse map; the accumulate arithmetic in
+ * tests/test_oracle_accumulate_pins.py, the chunk tags in tests/test_oracle_tag_pins.py
+ * (hand-written record bytes, planted faults).  The end-to-end
  * training throughput and loss results of the paper's Section 3 are not
  * reproduced by anything here: parity unpinned, out of scope.
  */
@@ -372,6 +376,116 @@ int hxo_checksum2(int64_t L, int64_t B, int k, const uint8_t *packed, uint64_t *
         out[2 * c] = s1;
         out[2 * c + 1] = s2;
     }
+    return 0;
+}
+
+/* ---- widening: chunk tags (a header per chunk that travels beside the lanes) ----------
+ * The paper reports that mixed-vendor runs kept hanging until the transfer code was debugged
+ * (subsection "Engineering Challenges"); a receiver that can tell WHICH message and which chunk
+ * sits in a buffer turns a stale or misrouted ping-pong buffer into an error instead of a hang
+ * or a silent mismatch.  The paper defines no header; this one is this repository's contract.
+ *
+ * One 64-byte record per chunk, all fields little-endian.  The record of chunk c is number
+ * s(c) = packed offset of c / B in the tag array, i.e. the tags are in the order of the packed
+ * slots, so that a lane's tags are one contiguous run like its chunks:
+ *    byte  0  u32 magic = 0x31545848 (the bytes 'H','X','T','1')
+ *    byte  4  u32 chunk index c
+ *    byte  8  u32 lane(c)
+ *    byte 12  u32 slot(c)
+ *    byte 16  u64 seq          sender's running message number
+ *    byte 24  u32 micro_batch  sender's micro-batch id
+ *    byte 28  u32 C            chunks in the message
+ *    byte 32  u64 padded(c)    bytes of the chunk that are transferred
+ *    byte 40  u64 plain sum of the chunk's words      (as hxo_checksum2)
+ *    byte 48  u64 position-weighted sum of its words  (as hxo_checksum2)
+ *    byte 56  u64 zero
+ * Verification of chunk c against the tag found at s(c) yields a bit mask, 0 = accepted: */
+enum {
+    HXO_TAG_BAD_MAGIC = 1,       /* magic differs */
+    HXO_TAG_BAD_PLACE = 2,       /* chunk, lane, slot, C or padded differ from the receiver's own layout */
+    HXO_TAG_BAD_SEQ = 4,         /* seq differs from the expected one */
+    HXO_TAG_BAD_MICRO_BATCH = 8, /* micro_batch differs from the expected one */
+    HXO_TAG_BAD_SUM = 16,        /* plain sum of the received bytes differs from the tag's */
+    HXO_TAG_BAD_WSUM = 32,       /* weighted sum differs */
+    HXO_TAG_BAD_RESERVED = 64    /* last field not zero */
+};
+
+static void hxo_put_le(uint8_t *p, int nbytes, uint64_t v)
+{
+    for (int i = 0; i < nbytes; ++i) p[i] = (uint8_t)(v >> (8 * i));
+}
+
+static uint64_t hxo_get_le(const uint8_t *p, int nbytes)
+{
+    uint64_t v = 0;
+    for (int i = 0; i < nbytes; ++i) v |= (uint64_t)p[i] << (8 * i);
+    return v;
+}
+
+/* tags: C * 64 bytes. */
+int hxo_seal(int64_t L, int64_t B, int k, const uint8_t *packed, uint64_t seq, uint32_t micro_batch,
+             uint8_t *tags)
+{
+    if (k < 1 || B <= 0 || B % HXO_ALIGN) return -1;
+    int64_t C = hxo_num_chunks(L, B);
+    for (int64_t c = 0; c < C; ++c) {
+        const uint8_t *p = packed + hxo_chunk_packed_offset(L, B, k, c);
+        int64_t words = hxo_chunk_padded(L, B, c) / 4;
+        uint64_t s1 = 0, s2 = 0;
+        for (int64_t j = 0; j < words; ++j) {
+            uint64_t w = hxo_get_le(p + 4 * j, 4);
+            s1 += w;
+            s2 += (uint64_t)(j + 1) * w;
+        }
+        uint8_t *t = tags + 64 * (hxo_chunk_packed_offset(L, B, k, c) / B);
+        hxo_put_le(t + 0, 4, 0x31545848u);
+        hxo_put_le(t + 4, 4, (uint64_t)c);
+        hxo_put_le(t + 8, 4, (uint64_t)hxo_chunk_lane(c, k));
+        hxo_put_le(t + 12, 4, (uint64_t)hxo_chunk_slot(c, k));
+        hxo_put_le(t + 16, 8, seq);
+        hxo_put_le(t + 24, 4, micro_batch);
+        hxo_put_le(t + 28, 4, (uint64_t)C);
+        hxo_put_le(t + 32, 8, (uint64_t)hxo_chunk_padded(L, B, c));
+        hxo_put_le(t + 40, 8, s1);
+        hxo_put_le(t + 48, 8, s2);
+        hxo_put_le(t + 56, 8, 0);
+    }
+    return 0;
+}
+
+/* status: C + 1 entries; status[c] = bit mask for chunk c, status[C] = number of chunks whose
+ * mask is not zero. */
+int hxo_verify(int64_t L, int64_t B, int k, const uint8_t *packed, const uint8_t *tags, uint64_t seq,
+               uint32_t micro_batch, uint32_t *status)
+{
+    if (k < 1 || B <= 0 || B % HXO_ALIGN) return -1;
+    int64_t C = hxo_num_chunks(L, B);
+    uint32_t bad = 0;
+    for (int64_t c = 0; c < C; ++c) {
+        const uint8_t *p = packed + hxo_chunk_packed_offset(L, B, k, c);
+        int64_t words = hxo_chunk_padded(L, B, c) / 4;
+        uint64_t s1 = 0, s2 = 0;
+        for (int64_t j = 0; j < words; ++j) {
+            uint64_t w = hxo_get_le(p + 4 * j, 4);
+            s1 += w;
+            s2 += (uint64_t)(j + 1) * w;
+        }
+        const uint8_t *t = tags + 64 * (hxo_chunk_packed_offset(L, B, k, c) / B);
+        uint32_t m = 0;
+        if (hxo_get_le(t + 0, 4) != 0x31545848u) m |= HXO_TAG_BAD_MAGIC;
+        if (hxo_get_le(t + 4, 4) != (uint64_t)c || hxo_get_le(t + 8, 4) != (uint64_t)hxo_chunk_lane(c, k) ||
+            hxo_get_le(t + 12, 4) != (uint64_t)hxo_chunk_slot(c, k) || hxo_get_le(t + 28, 4) != (uint64_t)C ||
+            hxo_get_le(t + 32, 8) != (uint64_t)hxo_chunk_padded(L, B, c))
+            m |= HXO_TAG_BAD_PLACE;
+        if (hxo_get_le(t + 16, 8) != seq) m |= HXO_TAG_BAD_SEQ;
+        if (hxo_get_le(t + 24, 4) != micro_batch) m |= HXO_TAG_BAD_MICRO_BATCH;
+        if (hxo_get_le(t + 40, 8) != s1) m |= HXO_TAG_BAD_SUM;
+        if (hxo_get_le(t + 48, 8) != s2) m |= HXO_TAG_BAD_WSUM;
+        if (hxo_get_le(t + 56, 8) != 0) m |= HXO_TAG_BAD_RESERVED;
+        status[c] = m;
+        if (m) ++bad;
+    }
+    status[C] = bad;
     return 0;
 }
 

@@ -97,6 +97,8 @@ def lib():
             "hxo_stage_lane": (i32, [i64, i64, i32, i32, p, p]),
             "hxo_checksum": (i32, [i64, i64, i32, p, p, i32]),
             "hxo_checksum2": (i32, [i64, i64, i32, p, p, i32]),
+            "hxo_seal": (i32, [i64, i64, i32, p, C.c_uint64, C.c_uint32, p]),
+            "hxo_verify": (i32, [i64, i64, i32, p, p, C.c_uint64, C.c_uint32, p]),
             "hxo_packed_origin": (i32, [M, i64, i32, i64, C.POINTER(C.c_int32), C.POINTER(C.c_int64)]),
             "hxo_max_threads": (i32, []),
             "hxo_round_to_bf16": (C.c_uint16, [C.c_float]),
@@ -256,6 +258,30 @@ def checksum2(msg: Message, packed: np.ndarray, B: int, k: int, nthreads: int = 
     if rc:
         raise ValueError("hxo_checksum2 rejected the arguments")
     return out
+
+
+TAG_BYTES = 64
+TAG_BAD_MAGIC, TAG_BAD_PLACE, TAG_BAD_SEQ, TAG_BAD_MICRO_BATCH, TAG_BAD_SUM, TAG_BAD_WSUM, TAG_BAD_RESERVED = \
+    1, 2, 4, 8, 16, 32, 64
+
+
+def seal(msg: Message, packed: np.ndarray, B: int, k: int, seq: int, micro_batch: int) -> np.ndarray:
+    """[C, 64] uint8: the chunk tags in packed-slot order."""
+    tags = np.zeros((num_chunks(msg, B), TAG_BYTES), dtype=np.uint8)
+    rc = lib().hxo_seal(msg.L, B, k, packed.ctypes.data, seq, micro_batch, tags.ctypes.data)
+    if rc:
+        raise ValueError("hxo_seal rejected the arguments")
+    return tags
+
+
+def verify(msg: Message, packed: np.ndarray, tags: np.ndarray, B: int, k: int, seq: int, micro_batch: int) -> np.ndarray:
+    """uint32[C + 1]: per-chunk bit masks, then the number of rejected chunks."""
+    assert tags.dtype == np.uint8 and tags.flags.c_contiguous and tags.size == num_chunks(msg, B) * TAG_BYTES
+    status = np.zeros(num_chunks(msg, B) + 1, dtype=np.uint32)
+    rc = lib().hxo_verify(msg.L, B, k, packed.ctypes.data, tags.ctypes.data, seq, micro_batch, status.ctypes.data)
+    if rc:
+        raise ValueError("hxo_verify rejected the arguments")
+    return status
 
 
 def packed_origin(msg: Message, B: int, k: int, p: int):

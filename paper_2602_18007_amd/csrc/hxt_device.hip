@@ -979,6 +979,12 @@ int check_common(const hxt_plan_t *plan, const void *packed)
         g_last_hip = int(hipErrorNoDevice);
         return HXT_EHIP;
     }
+    int cur = -1;
+    if (hipGetDevice(&cur) != hipSuccess || cur != plan->device) {     // the work tables live on the plan's device
+        (void)hipGetLastError();
+        g_last_hip = int(hipErrorInvalidDevice);
+        return HXT_EHIP;
+    }
     return HXT_OK;
 }
 

@@ -1,6 +1,7 @@
 """GPU parity: the HIP path, called through the C ABI, against the CPU oracle,
 byte for byte, on the same seeded inputs.  Integer/byte work: the bar is bit-exact."""
 import os
+import zlib
 
 import numpy as np
 import pytest
@@ -421,6 +422,23 @@ def test_words_that_change_places_show_only_in_the_weighted_sum():
     plain = torch.zeros(p.num_chunks, dtype=torch.int64, device=DEV)
     hxt.hxt_checksum(p, dev, plain)
     assert np.array_equal(plain.cpu().numpy().view(np.uint64), want_sums)   # blind to the swap
+
+
+@pytest.mark.parametrize("case", [
+    Case("beyond_4GiB_one_tensor", (contig((2**32 + 3 * 2**20 + 24,), 1),), 3, 32 << 20),
+    Case("beyond_4GiB_table", (contig((2**32 + 4096,), 1), ((1000, 256), (320, 1), 4), ((512, 384), (1, 512), 2),
+                               contig((70001,), 1)), 4, 16 << 20),
+], ids=lambda c: c.name)
+def test_offsets_beyond_32_bits(case):
+    """Stream, packed and storage offsets past 2^32: the closed-form kernel, and the table-driven kernels
+    whose tiles start beyond 4 GiB."""
+    rng = np.random.default_rng(zlib.crc32(case.name.encode()))
+    raws = []
+    for t in case.tensors:
+        n = storage_bytes(*t)
+        raws.append(rng.integers(0, 2**63, size=n // 8 + 1, dtype=np.int64).view(np.uint8)[:n].copy())
+    say("drawn", [r.size for r in raws])
+    round_trip_check(case, raws, nthreads=NT)
 
 
 def test_data_plane_argument_errors():
