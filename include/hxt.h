@@ -251,6 +251,54 @@ int hxt_checksum(const hxt_plan_t *plan, const void *packed, uint64_t *sums, voi
  * sums2: device array of 2 * num_chunks uint64. */
 int hxt_checksum2(const hxt_plan_t *plan, const void *packed, uint64_t *sums2, void *stream);
 
+/* ---- widening: chunk tags (subsection "Engineering Challenges": the hangs met while
+ * bringing up the mixed-vendor transfer) -------------------------------------------
+ * The paper defines no header; this one is this library's contract.  A tag says which
+ * message and which chunk a packed slot holds and carries both sums, so that a stale
+ * ping-pong buffer, a misrouted lane or damaged bytes are reported by the receiver
+ * instead of being unpacked.  Tags are kept beside the packed buffer (its layout does
+ * not change): one 64-byte record per chunk, in packed-slot order (the tag of chunk c
+ * is number packed_off(c) / chunk_bytes, so a lane's tags are one contiguous run that
+ * can travel with the lane).  All fields little-endian. */
+typedef struct {
+    uint32_t magic;        /* HXT_TAG_MAGIC */
+    uint32_t chunk;        /* c */
+    uint32_t lane, slot;   /* c mod k, c div k */
+    uint64_t seq;          /* sender's running message number */
+    uint32_t micro_batch;  /* sender's micro-batch id */
+    uint32_t n_chunks;     /* C */
+    uint64_t padded;       /* bytes of the chunk that are transferred */
+    uint64_t sum;          /* as hxt_checksum2 */
+    uint64_t wsum;
+    uint64_t zero;
+} hxt_chunk_tag_t;
+#define HXT_TAG_MAGIC 0x31545848u /* bytes 'H','X','T','1' */
+
+enum hxt_tag_status {            /* bits of a chunk's verification result, 0 = accepted */
+    HXT_TAG_BAD_MAGIC = 1,
+    HXT_TAG_BAD_PLACE = 2,       /* chunk, lane, slot, n_chunks or padded differ from the receiver's plan */
+    HXT_TAG_BAD_SEQ = 4,
+    HXT_TAG_BAD_MICRO_BATCH = 8,
+    HXT_TAG_BAD_SUM = 16,        /* the received bytes do not add up to the tag's plain sum */
+    HXT_TAG_BAD_WSUM = 32,       /* ... to its position-weighted sum */
+    HXT_TAG_BAD_RESERVED = 64    /* last field not zero */
+};
+
+/* Sender: one pass over `packed` (reads N bytes) that writes the num_chunks tags.
+ * tags: device, num_chunks * 64 bytes, 16-byte aligned (HXT_EALIGN otherwise). */
+int hxt_seal(const hxt_plan_t *plan, const void *packed, uint64_t seq, uint32_t micro_batch,
+             hxt_chunk_tag_t *tags, void *stream);
+
+/* Receiver: one pass over the received `packed` that recomputes both sums of every
+ * chunk and checks the tag found at the chunk's slot against the receiver's own plan,
+ * the expected seq / micro_batch and the recomputed sums.
+ * status: device, num_chunks + 1 uint32; status[c] = OR of hxt_tag_status bits for chunk
+ * c, status[num_chunks] = number of chunks with a non-zero mask (written by a second,
+ * one-workgroup kernel on the same stream).  The caller reads status back and decides;
+ * nothing is compared on the host by the library. */
+int hxt_verify(const hxt_plan_t *plan, const void *packed, const hxt_chunk_tag_t *tags, uint64_t seq,
+               uint32_t micro_batch, uint32_t *status, void *stream);
+
 /* ---- diagnostics -------------------------------------------------------------- */
 const char *hxt_strerror(int status);
 int hxt_last_hip_error(void);    /* hipError_t of the last failing HIP call on this thread */

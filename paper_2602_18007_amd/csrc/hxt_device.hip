@@ -30,6 +30,7 @@ namespace hxt {
 
 constexpr int kThreads = 256;
 constexpr int kUnroll = 4;
+constexpr uint32_t kTagMagic = 0x31545848u;     // 'H','X','T','1' in memory order
 
 struct BasePtrs {
     uint8_t *p[kMaxGroupTensors];
@@ -617,10 +618,63 @@ __device__ __forceinline__ bool pair_arrive(uint8_t *acc, uint32_t stride, size_
 //   sum (j+1) w_j = (j0 + 4 tid + 1) * sum_n S_n + 1024 * sum_n n S_n + sum_n I_n,
 // so the loop needs additions only (sum_n n S_n is kept as a running suffix sum) and each
 // thread multiplies once.
-template <bool NTP>
+//
+// MODE says what the workgroup that completes a chunk does with the two sums:
+//   SUMS   out = uint64[2C]: writes the pair.
+//   SEAL   out = C tags: writes the chunk's 64-byte tag (hxt_chunk_tag_t) at its packed-slot index.
+//   VERIFY out = uint32[C + 1], tags = C tags: compares the tag found at the chunk's slot with the
+//          receiver's own layout, the expected message identity and the recomputed sums, and
+//          writes the bit mask to out[chunk].
+enum Sum2Mode { SUM2_SUMS = 0, SUM2_SEAL = 1, SUM2_VERIFY = 2 };
+
+struct TagWork {
+    const uint8_t *tags;     // VERIFY: the received tags
+    uint64_t seq;            // SEAL: value to write; VERIFY: value expected
+    uint32_t micro_batch;
+};
+
+__device__ __forceinline__ void finish_chunk(int mode, const ChunkGeom &g, const TileSpan &t, uint64_t sum,
+                                             uint64_t wsum, void *out, const TagWork &w)
+{
+    const uint32_t c = t.chunk;
+    if (mode == SUM2_SUMS) {
+        uint64_t *o = static_cast<uint64_t *>(out);
+        o[2 * size_t(c)] = sum;
+        o[2 * size_t(c) + 1] = wsum;
+        return;
+    }
+    const uint32_t slot = fast_div(c, g.div_k), lane = c - slot * g.k;
+    const uint64_t place = uint64_t(lane) * g.q + (lane < g.r ? lane : g.r) + slot;      // packed offset / B
+    const uint64_t padded = (c + 1 == g.C) ? g.L - uint64_t(c) * g.B : g.B;
+    const u32x4 q0{kTagMagic, c, lane, slot};
+    const u32x4 q1{uint32_t(w.seq), uint32_t(w.seq >> 32), w.micro_batch, g.C};
+    const u32x4 q2{uint32_t(padded), uint32_t(padded >> 32), uint32_t(sum), uint32_t(sum >> 32)};
+    const u32x4 q3{uint32_t(wsum), uint32_t(wsum >> 32), 0u, 0u};
+    if (mode == SUM2_SEAL) {
+        u32x4 *tag = reinterpret_cast<u32x4 *>(static_cast<uint8_t *>(out) + place * 64);
+        tag[0] = q0;
+        tag[1] = q1;
+        tag[2] = q2;
+        tag[3] = q3;
+        return;
+    }
+    const u32x4 *tag = reinterpret_cast<const u32x4 *>(w.tags + place * 64);
+    const u32x4 r0 = tag[0], r1 = tag[1], r2 = tag[2], r3 = tag[3];
+    uint32_t m = 0;
+    if (r0.x != q0.x) m |= HXT_TAG_BAD_MAGIC;
+    if (r0.y != q0.y || r0.z != q0.z || r0.w != q0.w || r1.w != q1.w || r2.x != q2.x || r2.y != q2.y) m |= HXT_TAG_BAD_PLACE;
+    if (r1.x != q1.x || r1.y != q1.y) m |= HXT_TAG_BAD_SEQ;
+    if (r1.z != q1.z) m |= HXT_TAG_BAD_MICRO_BATCH;
+    if (r2.z != q2.z || r2.w != q2.w) m |= HXT_TAG_BAD_SUM;
+    if (r3.x != q3.x || r3.y != q3.y) m |= HXT_TAG_BAD_WSUM;
+    if (r3.z != 0 || r3.w != 0) m |= HXT_TAG_BAD_RESERVED;
+    static_cast<uint32_t *>(out)[c] = m;
+}
+
+template <int MODE, bool NTP>
 __global__ __launch_bounds__(kThreads) void k_checksum2(ChunkGeom g, const uint8_t *__restrict__ packed,
-                                                        uint64_t *__restrict__ out, uint8_t *acc, uint32_t stride,
-                                                        uint32_t fan)
+                                                        void *__restrict__ out, uint8_t *acc, uint32_t stride,
+                                                        uint32_t fan, TagWork work)
 {
     const TileSpan t = locate_tile(g, blockIdx.x);
     const u32x4 *s = reinterpret_cast<const u32x4 *>(packed + t.packed_off);
@@ -675,10 +729,24 @@ __global__ __launch_bounds__(kThreads) void k_checksum2(ChunkGeom g, const uint8
             last = pair_arrive(acc, stride, size_t(t.chunk) * fan + sub, a, b, share) &&
                    pair_arrive(acc, stride, top, a, b, fan);
         }
-        if (last) {
-            out[2 * size_t(t.chunk)] = a;
-            out[2 * size_t(t.chunk) + 1] = b;
-        }
+        if (last) finish_chunk(MODE, g, t, a, b, out, work);
+    }
+}
+
+// status[C] = number of chunks of status[0 .. C) that were rejected.  One workgroup.
+__global__ __launch_bounds__(kThreads) void k_count_rejected(uint32_t *status, uint32_t C)
+{
+    __shared__ uint32_t part[kThreads / 64];
+    uint32_t n = 0;
+    for (uint32_t c = threadIdx.x; c < C; c += kThreads) n += status[c] != 0;
+    for (int o = 32; o > 0; o >>= 1) n += __shfl_down(n, o, 64);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = n;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t total = 0;
+#pragma unroll
+        for (int w = 0; w < kThreads / 64; ++w) total += part[w];
+        status[C] = total;
     }
 }
 
@@ -1526,22 +1594,73 @@ int hxt_checksum(const hxt_plan_t *plan, const void *packed, uint64_t *sums, voi
     return HXT_OK;
 }
 
-int hxt_checksum2(const hxt_plan_t *plan, const void *packed, uint64_t *sums2, void *stream)
+namespace {
+// The three users of the pair-of-sums pass.
+int run_sum2(const hxt_plan_t *plan, const void *packed, int mode, void *out, const TagWork &work, void *stream)
 {
     int rc = check_common(plan, packed);
-    if (rc != HXT_OK || plan->p.C == 0) return rc;
-    if (!sums2) return HXT_EINVAL;
+    if (rc != HXT_OK) return rc;
+    if (!out || (mode == SUM2_VERIFY && !work.tags)) return HXT_EINVAL;
+    const uintptr_t align = mode == SUM2_SEAL ? 16 : (mode == SUM2_VERIFY ? 4 : 8);
+    if (reinterpret_cast<uintptr_t>(out) % align) return HXT_EALIGN;
+    if (mode == SUM2_VERIFY && reinterpret_cast<uintptr_t>(work.tags) % 16) return HXT_EALIGN;
     hxt_plan_t &pl = *const_cast<hxt_plan_t *>(plan);
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (pl.p.C == 0) {
+        if (mode == SUM2_VERIFY) {
+            k_count_rejected<<<1, kThreads, 0, st>>>(static_cast<uint32_t *>(out), 0);
+            HXT_HIP(hipGetLastError());
+        }
+        return HXT_OK;
+    }
     SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};
-    if ((rc = claim_slots(pl, OP_CHECKSUM2, st, cx, sums2)) != HXT_OK) return rc;
+    if ((rc = claim_slots(pl, OP_CHECKSUM2, st, cx, nullptr)) != HXT_OK) return rc;
     const uint8_t *pk = static_cast<const uint8_t *>(packed);
-    if (packed_nontemporal(pl.p.C * pl.p.B))
-        k_checksum2<true><<<pl.p.geom.ntiles, kThreads, 0, st>>>(pl.p.geom, pk, sums2, cx.acc, cx.stride, cx.fan);
-    else
-        k_checksum2<false><<<pl.p.geom.ntiles, kThreads, 0, st>>>(pl.p.geom, pk, sums2, cx.acc, cx.stride, cx.fan);
+    const bool ntp = packed_nontemporal(pl.p.C * pl.p.B);
+    auto launch = [&]<int MODE>() {
+        if (ntp) k_checksum2<MODE, true><<<pl.p.geom.ntiles, kThreads, 0, st>>>(pl.p.geom, pk, out, cx.acc, cx.stride, cx.fan, work);
+        else k_checksum2<MODE, false><<<pl.p.geom.ntiles, kThreads, 0, st>>>(pl.p.geom, pk, out, cx.acc, cx.stride, cx.fan, work);
+    };
+    if (mode == SUM2_SUMS) launch.template operator()<SUM2_SUMS>();
+    else if (mode == SUM2_SEAL) launch.template operator()<SUM2_SEAL>();
+    else launch.template operator()<SUM2_VERIFY>();
     HXT_HIP(hipGetLastError());
+    if (mode == SUM2_VERIFY) {
+        k_count_rejected<<<1, kThreads, 0, st>>>(static_cast<uint32_t *>(out), uint32_t(pl.p.C));
+        HXT_HIP(hipGetLastError());
+    }
     return HXT_OK;
+}
+}  // namespace
+
+int hxt_checksum2(const hxt_plan_t *plan, const void *packed, uint64_t *sums2, void *stream)
+{
+    if (plan && plan->p.C == 0) return HXT_OK;
+    return run_sum2(plan, packed, SUM2_SUMS, sums2, TagWork{nullptr, 0, 0}, stream);
+}
+
+int hxt_seal(const hxt_plan_t *plan, const void *packed, uint64_t seq, uint32_t micro_batch, hxt_chunk_tag_t *tags,
+             void *stream)
+{
+    if (plan && plan->p.C == 0) return HXT_OK;
+    return run_sum2(plan, packed, SUM2_SEAL, tags, TagWork{nullptr, seq, micro_batch}, stream);
+}
+
+int hxt_verify(const hxt_plan_t *plan, const void *packed, const hxt_chunk_tag_t *tags, uint64_t seq,
+               uint32_t micro_batch, uint32_t *status, void *stream)
+{
+    if (!plan || !status) return HXT_EINVAL;
+    if (plan->p.C == 0) {                       // nothing to check: status[0] = 0 rejected chunks
+        if (plan->device < 0) {
+            g_last_hip = int(hipErrorNoDevice);
+            return HXT_EHIP;
+        }
+        k_count_rejected<<<1, kThreads, 0, static_cast<hipStream_t>(stream)>>>(status, 0);
+        HXT_HIP(hipGetLastError());
+        return HXT_OK;
+    }
+    return run_sum2(plan, packed, SUM2_VERIFY, status,
+                    TagWork{reinterpret_cast<const uint8_t *>(tags), seq, micro_batch}, stream);
 }
 
 int hxt_stage_d2h(const hxt_plan_t *plan, int lane, const void *packed_dev, void *host_pinned, void *stream)

@@ -30,7 +30,7 @@ EXPORTS = (
     "hxt_plan_num_tensors", "hxt_plan_chunk_info", "hxt_plan_lane_info", "hxt_plan_tensor_unpack_safe",
     "hxt_plan_tensor_kind", "hxt_pack", "hxt_stage_d2h", "hxt_stage_h2d", "hxt_unpack", "hxt_checksum",
     "hxt_pack_batch", "hxt_unpack_batch", "hxt_exchange_stream", "hxt_unpack_accumulate",
-    "hxt_host_forward", "hxt_stage_hop", "hxt_checksum2",
+    "hxt_host_forward", "hxt_stage_hop", "hxt_checksum2", "hxt_seal", "hxt_verify",
     "hxt_strerror", "hxt_last_hip_error", "hxt_version",
 )
 
@@ -110,6 +110,8 @@ def lib():
             "hxt_unpack": (i, [vp, vp, C.POINTER(vp), u64p, vp]),
             "hxt_checksum": (i, [vp, vp, u64p, vp]),
             "hxt_checksum2": (i, [vp, vp, u64p, vp]),
+            "hxt_seal": (i, [vp, vp, C.c_uint64, C.c_uint32, vp, vp]),
+            "hxt_verify": (i, [vp, vp, vp, C.c_uint64, C.c_uint32, vp, vp]),
             "hxt_host_forward": (i, [vp, i, vp, vp, i]),
             "hxt_stage_hop": (i, [vp, i, vp, vp, i, vp]),
             "hxt_unpack_accumulate": (i, [vp, vp, C.POINTER(vp), u64p, vp]),
@@ -326,6 +328,20 @@ def hxt_checksum(plan: Plan, packed, sums, stream=None) -> None:
 
 def hxt_checksum2(plan: Plan, packed, sums2, stream=None) -> None:
     _check(lib().hxt_checksum2(plan.handle, _ptr(packed), _ptr(sums2), _stream(stream)), "hxt_checksum2")
+
+
+TAG_BYTES = 64
+HXT_TAG_BAD_MAGIC, HXT_TAG_BAD_PLACE, HXT_TAG_BAD_SEQ, HXT_TAG_BAD_MICRO_BATCH = 1, 2, 4, 8
+HXT_TAG_BAD_SUM, HXT_TAG_BAD_WSUM, HXT_TAG_BAD_RESERVED = 16, 32, 64
+
+
+def hxt_seal(plan: Plan, packed, seq: int, micro_batch: int, tags, stream=None) -> None:
+    _check(lib().hxt_seal(plan.handle, _ptr(packed), seq, micro_batch, _ptr(tags), _stream(stream)), "hxt_seal")
+
+
+def hxt_verify(plan: Plan, packed, tags, seq: int, micro_batch: int, status, stream=None) -> None:
+    _check(lib().hxt_verify(plan.handle, _ptr(packed), _ptr(tags), seq, micro_batch, _ptr(status), _stream(stream)),
+           "hxt_verify")
 
 
 def hxt_stage_d2h(plan: Plan, lane: int, packed_dev, host_pinned, stream=None) -> None:

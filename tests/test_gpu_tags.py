@@ -1,0 +1,145 @@
+"""GPU parity of the chunk tags: hxt_seal / hxt_verify through the C ABI against the oracle's
+seal / verify, byte for byte and mask for mask; every fault is planted on the host."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import hxt_oracle as ho
+from paper_2602_18007_amd import hxt
+from paper_2602_18007_amd import workloads as wl
+from tests.cases import SMALL_CASES, Case, contig, make_storages
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+CASES = SMALL_CASES + [
+    Case("contig_1MB_ragged", (contig((1_000_001,), 1),), 3, 65536),
+    Case("chunks_of_256_tiles", (contig((9 * 1024 * 1024 // 2 + 40,), 2),), 2, 4 << 20),
+    Case("multi_mid", (contig((70001,), 1), ((64, 2, 128), (128, 64 * 128, 1), 2), ((96, 80), (1, 96), 4),
+                       contig((3, 1000), 8), ((33, 10), (20, 2), 2)), 4, 8192),
+]
+
+
+def setup(case, seed=3):
+    m = ho.Message([ho.TensorSpec(tuple(s), tuple(st), e) for (s, st, e) in case.tensors])
+    p = hxt.hxt_plan_multi([(s, st, e) for (s, st, e) in case.tensors], case.k, case.B)
+    raws = make_storages(case, seed)
+    packed = ho.pack(m, raws, case.B, case.k, fill=0x5C)
+    return m, p, packed
+
+
+def dev(a):
+    t = torch.empty(max(a.size, 16), dtype=torch.uint8, device=DEV)
+    t[:a.size].copy_(torch.from_numpy(a.reshape(-1)))
+    return t
+
+
+def gpu_verify(p, packed_np, tags_np, seq, mb):
+    C = p.num_chunks
+    status = torch.full((C + 1,), 0x7FFFFFFF, dtype=torch.int32, device=DEV)
+    hxt.hxt_verify(p, dev(packed_np), dev(tags_np), seq, mb, status)
+    return status.cpu().numpy().view(np.uint32)
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: c.name)
+def test_seal_and_verify_match_the_oracle(case):
+    m, p, packed = setup(case)
+    C = p.num_chunks
+    seq, mb = 0xA1B2C3D4E5F60718, 0xCAFE0001
+    want = ho.seal(m, packed, case.B, case.k, seq, mb)
+    tags = torch.full((max(C, 1) * 64,), 0xEE, dtype=torch.uint8, device=DEV)
+    d_packed = dev(packed)
+    hxt.hxt_seal(p, d_packed, seq, mb, tags)
+    got = tags.cpu().numpy()[:C * 64].reshape(C, 64)
+    assert np.array_equal(got, want)
+    for args in ((seq, mb), (seq + 1, mb), (seq, mb ^ 1)):
+        assert np.array_equal(gpu_verify(p, packed, got, *args), ho.verify(m, packed, want, case.B, case.k, *args))
+    assert not gpu_verify(p, packed, got, seq, mb).any()
+
+
+def test_planted_faults_get_the_oracles_masks():
+    case = next(c for c in CASES if c.name == "multi_mid")
+    m, p, packed = setup(case, 8)
+    C = p.num_chunks
+    seq, mb = 77, 5
+    tags = ho.seal(m, packed, case.B, case.k, seq, mb)
+    faults = []
+    bad = packed.copy()
+    bad[p.chunk_info(3)["packed_off"] + 1001] ^= 0x04
+    faults.append(("flipped bit", bad, tags))
+    sw = packed.copy()
+    w = sw[p.chunk_info(6)["packed_off"]:][:case.B].view("<u4")
+    i, j = next((i, j) for i in range(40) for j in range(1500, 1540) if w[i] != w[j])
+    w[i], w[j] = int(w[j]), int(w[i])
+    faults.append(("swapped words", sw, tags))
+    t = tags.copy()
+    t[[2, 9]] = tags[[9, 2]]
+    faults.append(("two tags exchanged", packed, t))
+    t = tags.copy()
+    t[4, 3] ^= 0x80
+    t[5, 60] = 9
+    t[7, 32:40] = 0
+    faults.append(("magic, reserved and length fields", packed, t))
+    lane = packed.copy()                                   # a whole lane region overwritten by another lane's bytes
+    a, b = p.lane_info(0), p.lane_info(1)
+    n = min(a["bytes"], b["bytes"])
+    lane[a["packed_off"]:a["packed_off"] + n] = packed[b["packed_off"]:b["packed_off"] + n]
+    faults.append(("lane 1's bytes in lane 0's region", lane, tags))
+    for name, pk, tg in faults:
+        want = ho.verify(m, pk, tg, case.B, case.k, seq, mb)
+        assert want[C] > 0, name
+        assert np.array_equal(gpu_verify(p, pk, tg, seq, mb), want), name
+    for rep in range(2):                                   # the accumulators are clean again after rejected chunks
+        assert not gpu_verify(p, packed, tags, seq, mb).any()
+
+
+def test_full_size_boundary_message_round_trip_with_tags():
+    w = wl.llama8b_boundary()
+    case = Case(w.name, tuple((t.shape, t.strides, t.esize) for t in w.tensors), w.n_lanes, w.chunk_bytes)
+    m = ho.Message([ho.TensorSpec(t.shape, t.strides, t.esize) for t in w.tensors])
+    p = hxt.hxt_plan_multi([(t.shape, t.strides, t.esize) for t in w.tensors], w.n_lanes, w.chunk_bytes)
+    raws = wl.make_storages(w, 1)
+    src = [torch.from_numpy(r).to(DEV) for r in raws]
+    packed = torch.empty(p.packed_bytes, dtype=torch.uint8, device=DEV)
+    hxt.hxt_pack(p, src, packed, None)
+    tags = torch.zeros(p.num_chunks * 64, dtype=torch.uint8, device=DEV)
+    hxt.hxt_seal(p, packed, 1234567890123, 31, tags)
+    want_packed = ho.pack(m, raws, w.chunk_bytes, w.n_lanes, fill=0, nthreads=8)
+    assert np.array_equal(tags.cpu().numpy().reshape(-1, 64), ho.seal(m, want_packed, w.chunk_bytes, w.n_lanes, 1234567890123, 31))
+    # the tags travel lane by lane with the chunks (slot order = lane order)
+    host = torch.zeros(p.packed_bytes, dtype=torch.uint8).pin_memory()
+    recv = torch.zeros_like(packed)
+    recv_tags = torch.zeros_like(tags)
+    for l in range(w.n_lanes):
+        hxt.hxt_stage_d2h(p, l, packed, host)
+        hxt.hxt_stage_h2d(p, l, host, recv)
+        li = p.lane_info(l)
+        s0 = li["packed_off"] // w.chunk_bytes
+        recv_tags[s0 * 64:(s0 + li["n_chunks"]) * 64].copy_(tags[s0 * 64:(s0 + li["n_chunks"]) * 64])
+    status = torch.full((p.num_chunks + 1,), -1, dtype=torch.int32, device=DEV)
+    hxt.hxt_verify(p, recv, recv_tags, 1234567890123, 31, status)
+    assert not status.cpu().numpy().any()
+    hxt.hxt_verify(p, recv, recv_tags, 1234567890122, 31, status)          # the previous message's number
+    st = status.cpu().numpy()
+    assert list(st[:-1]) == [hxt.HXT_TAG_BAD_SEQ] * p.num_chunks and st[-1] == p.num_chunks
+
+
+def test_empty_message_and_argument_errors():
+    p0 = hxt.hxt_plan((0, 16), None, 2, 2, 256)
+    status = torch.full((4,), 5, dtype=torch.int32, device=DEV)
+    buf = torch.zeros(1024, dtype=torch.uint8, device=DEV)
+    hxt.hxt_seal(p0, buf, 1, 1, buf)
+    hxt.hxt_verify(p0, buf, buf, 1, 1, status)
+    assert status.cpu().tolist() == [0, 5, 5, 5]
+    p = hxt.hxt_plan((1000,), None, 1, 2, 256)
+    L = hxt.lib()
+    packed = torch.zeros(p.packed_bytes, dtype=torch.uint8, device=DEV)
+    tags = torch.zeros(p.num_chunks * 64 + 64, dtype=torch.uint8, device=DEV)
+    st = torch.zeros(p.num_chunks + 1, dtype=torch.int32, device=DEV)
+    assert L.hxt_seal(p.handle, packed.data_ptr(), 1, 1, None, None) == hxt.HXT_EINVAL
+    assert L.hxt_seal(p.handle, packed.data_ptr(), 1, 1, tags.data_ptr() + 8, None) == hxt.HXT_EALIGN
+    assert L.hxt_verify(p.handle, packed.data_ptr(), None, 1, 1, st.data_ptr(), None) == hxt.HXT_EINVAL
+    assert L.hxt_verify(p.handle, packed.data_ptr(), tags.data_ptr(), 1, 1, None, None) == hxt.HXT_EINVAL
+    assert L.hxt_verify(p.handle, packed.data_ptr(), tags.data_ptr() + 4, 1, 1, st.data_ptr(), None) == hxt.HXT_EALIGN
+    assert L.hxt_verify(p.handle, None, tags.data_ptr(), 1, 1, st.data_ptr(), None) == hxt.HXT_EINVAL
+    torch.cuda.synchronize()

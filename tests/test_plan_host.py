@@ -43,6 +43,28 @@ def test_library_exports_every_declared_symbol():
     assert hxt.hxt_version().startswith("hxt")
 
 
+def test_header_is_plain_c_and_the_tag_record_has_the_documented_offsets(tmp_path):
+    """include/hxt.h must compile as C; the 64-byte tag record's field offsets are the ones the oracle documents."""
+    src = tmp_path / "abi.c"
+    src.write_text("""
+#include <stddef.h>
+#include "hxt.h"
+_Static_assert(sizeof(hxt_chunk_tag_t) == 64, "size");
+_Static_assert(offsetof(hxt_chunk_tag_t, magic) == 0 && offsetof(hxt_chunk_tag_t, chunk) == 4, "a");
+_Static_assert(offsetof(hxt_chunk_tag_t, lane) == 8 && offsetof(hxt_chunk_tag_t, slot) == 12, "b");
+_Static_assert(offsetof(hxt_chunk_tag_t, seq) == 16 && offsetof(hxt_chunk_tag_t, micro_batch) == 24, "c");
+_Static_assert(offsetof(hxt_chunk_tag_t, n_chunks) == 28 && offsetof(hxt_chunk_tag_t, padded) == 32, "d");
+_Static_assert(offsetof(hxt_chunk_tag_t, sum) == 40 && offsetof(hxt_chunk_tag_t, wsum) == 48, "e");
+_Static_assert(offsetof(hxt_chunk_tag_t, zero) == 56, "f");
+_Static_assert(HXT_TAG_MAGIC == 0x31545848u, "magic");
+_Static_assert(HXT_TAG_BAD_MAGIC == 1 && HXT_TAG_BAD_PLACE == 2 && HXT_TAG_BAD_SEQ == 4 && HXT_TAG_BAD_MICRO_BATCH == 8
+               && HXT_TAG_BAD_SUM == 16 && HXT_TAG_BAD_WSUM == 32 && HXT_TAG_BAD_RESERVED == 64, "bits");
+int main(void) { return 0; }
+""")
+    subprocess.run(["gcc", "-std=c11", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", os.path.join(ROOT, "include"),
+                    str(src)], check=True)
+
+
 @pytest.mark.parametrize("case", SMALL_CASES, ids=lambda c: c.name)
 def test_plan_queries_match_oracle(case):
     m, p = oracle_msg(case), plan_of(case)
