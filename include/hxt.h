@@ -43,7 +43,9 @@
  *     per-operation accumulators: such calls on one stream are ordered by the
  *     stream, and when consecutive calls come on different streams the library
  *     makes the later stream wait for the earlier one (an event), so they never
- *     overlap.  Messages that should overlap with checksums need a plan each.
+ *     overlap; the claim of the accumulators and the enqueue of the kernels that
+ *     use them are one critical section, so this also holds between threads.
+ *     Messages that should overlap with checksums need a plan each.
  *     Plans built from equal arguments on the sending and on the receiving side
  *     are interchangeable (the receive is symmetric).
  */

@@ -21,6 +21,7 @@
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <optional>
 #include <thread>
 #include <vector>
 
@@ -759,7 +760,6 @@ enum Op { OP_PACK = 0, OP_UNPACK = 1, OP_CHECKSUM = 2, OP_CHECKSUM2 = 3, OP_COUN
 
 struct OpState {              // accumulator slots of one operation and who used them last
     uint8_t *acc = nullptr;
-    std::mutex mu;
     bool used = false;
     hipStream_t last = nullptr;
     hipEvent_t ev = nullptr;
@@ -894,11 +894,16 @@ void launch_generic(const hxt_plan_t &pl, uint32_t first, uint32_t count, uint32
 
 // The accumulator slots of an operation are shared by all calls of that operation on this
 // plan.  Calls on one stream are ordered by the stream; when the stream changes, the new
-// stream is made to wait for everything enqueued so far on the previous one.
+// stream is made to wait for everything enqueued so far on the previous one.  That only works
+// if "enqueued so far" includes the previous claimant's kernels, so a call holds SlotsLock from
+// its first claim until its launches are enqueued (host-side enqueue time only; one lock for
+// all plans, recursive because batched calls fall back to single calls).
+std::recursive_mutex g_slots_mu;
+using SlotsLock = std::lock_guard<std::recursive_mutex>;
+
 int claim_slots(hxt_plan_t &pl, Op op, hipStream_t st, SumCtx &cx, uint64_t *sums)
 {
     OpState &o = pl.ops[op];
-    std::lock_guard<std::mutex> lock(o.mu);
     if (o.used && o.last != st) {
         if (!o.ev) HXT_HIP(hipEventCreateWithFlags(&o.ev, hipEventDisableTiming));
         if (hipEventRecord(o.ev, o.last) == hipSuccess)
@@ -939,7 +944,9 @@ int run_copy(hxt_plan_t &pl, void *const *ptrs, uint8_t *packed, uint64_t *sums,
 {
     const Plan &p = pl.p;
     SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};
+    std::optional<SlotsLock> lock;
     if constexpr (CSUM) {
+        lock.emplace(g_slots_mu);
         int rc = claim_slots(pl, UNPACK ? OP_UNPACK : OP_PACK, st, cx, sums);
         if (rc != HXT_OK) return rc;
         cx.sum_bits = pl.sum_bits_table;
@@ -997,7 +1004,9 @@ int run_accumulate(hxt_plan_t &pl, void *const *ptrs, uint8_t *packed, uint64_t 
 {
     const Plan &p = pl.p;
     SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};
+    std::optional<SlotsLock> lock;
     if constexpr (CSUM) {
+        lock.emplace(g_slots_mu);
         int rc = claim_slots(pl, OP_UNPACK, st, cx, sums);
         if (rc != HXT_OK) return rc;
         cx.sum_bits = pl.sum_bits_table;
@@ -1178,6 +1187,7 @@ int run_batch(int n, const hxt_plan_t *const *plans, void *const *const *tensors
         for (int j = 0; j < i; ++j)
             if (plans[j] == plans[i] && sums && sums[i] && sums[j]) return HXT_EINVAL;   // one accumulator set per plan
     }
+    SlotsLock lock(g_slots_mu);
     int i = 0;
     while (i < n) {
         hxt_plan_t &pl = *const_cast<hxt_plan_t *>(plans[i]);
@@ -1236,6 +1246,7 @@ int fused_direct_stream(hxt_plan_t &pl, const hxt_exchange_t &x, hipStream_t sp,
     const Plan &p = pl.p;
     const size_t T = p.tensors.size();
     const bool nt_packed = packed_nontemporal(p.C * p.B);
+    SlotsLock lock(g_slots_mu);
     for (int k = 0; k <= x.n_messages; ++k) {
         UniformArgs a;
         std::memset(&a, 0, sizeof a);
@@ -1583,6 +1594,7 @@ int hxt_checksum(const hxt_plan_t *plan, const void *packed, uint64_t *sums, voi
     hxt_plan_t &pl = *const_cast<hxt_plan_t *>(plan);
     hipStream_t st = static_cast<hipStream_t>(stream);
     SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};
+    SlotsLock lock(g_slots_mu);
     if ((rc = claim_slots(pl, OP_CHECKSUM, st, cx, sums)) != HXT_OK) return rc;
     cx.sum_bits = pl.sum_bits_geom;
     const uint8_t *pk = static_cast<const uint8_t *>(packed);
@@ -1614,6 +1626,7 @@ int run_sum2(const hxt_plan_t *plan, const void *packed, int mode, void *out, co
         return HXT_OK;
     }
     SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};
+    SlotsLock lock(g_slots_mu);
     if ((rc = claim_slots(pl, OP_CHECKSUM2, st, cx, nullptr)) != HXT_OK) return rc;
     const uint8_t *pk = static_cast<const uint8_t *>(packed);
     const bool ntp = packed_nontemporal(pl.p.C * pl.p.B);

@@ -187,6 +187,47 @@ def test_repeated_calls_leave_accumulators_clean():
         assert np.array_equal(sums.cpu().numpy().view(np.uint64), want), "call %d" % it
 
 
+def test_one_plan_used_from_several_threads_and_streams():
+    """Four host threads, a stream each, one shared plan, checksums on: the calls must queue behind each
+    other on the plan's accumulators (the claim and the launch are one critical section)."""
+    import threading
+    case = Case("threads", (contig((5 * 1024 * 1024 // 2 + 24,), 2),), 4, 1 << 20)
+    m = oracle_msg(case)
+    p = plan_of(case)
+    n_threads, iters = 4, 25
+    raws = [make_storages(case, 200 + i) for i in range(n_threads)]
+    want_sums = [ho.checksum(m, ho.pack(m, r, case.B, case.k, fill=0), case.B, case.k) for r in raws]
+    src = [[to_dev(a) for a in r] for r in raws]
+    dst = [[torch.zeros_like(a) for a in s_] for s_ in src]
+    packed = [torch.zeros(p.packed_bytes, dtype=torch.uint8, device=DEV) for _ in range(n_threads)]
+    s_send = [torch.zeros(iters, p.num_chunks, dtype=torch.int64, device=DEV) for _ in range(n_threads)]
+    s_recv = [torch.zeros(iters, p.num_chunks, dtype=torch.int64, device=DEV) for _ in range(n_threads)]
+    streams = [torch.cuda.Stream() for _ in range(n_threads)]
+    torch.cuda.synchronize()
+    errors = []
+
+    def work(i):
+        try:
+            for it in range(iters):
+                hxt.hxt_pack(p, src[i], packed[i], s_send[i][it], streams[i])
+                hxt.hxt_unpack(p, packed[i], dst[i], s_recv[i][it], streams[i])
+        except Exception as e:                                   # noqa: BLE001 - reported below
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(n_threads)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for i in range(n_threads):
+        for arr in (s_send[i], s_recv[i]):
+            got = arr.cpu().numpy().view(np.uint64)
+            assert (got == want_sums[i][None, :]).all(), "thread %d" % i
+        assert all(torch.equal(a, b) for a, b in zip(src[i], dst[i]))
+
+
 def test_batch_calls_equal_single_calls():
     # mixed batch: three uniform messages (one without checksums, so it cannot share a launch with its
     # neighbours), a strided one, an empty one and a multi-tensor one
