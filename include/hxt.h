@@ -212,7 +212,7 @@ int hxt_unpack_batch(int n, const hxt_plan_t *const *plans, const void *const *p
  * pack runs on stream_pack, the device-to-host copies on stream_stage, the
  * host-to-device copies and unpack on stream_unpack; events created by the call order
  * them (pack of message i waits until buffer set i mod n_buffers has been drained by
- * message i - n_buffers, and so on).  This is the host-side "event handling" half of
+ * message i - n_buffers, and so on).  This is the host-side event-handling half of
  * Section 2.2's control plane for a 1F1B schedule, where a stage sends one micro-batch
  * while the previous one is still in flight.
  *   path HXT_DEVICE_DIRECT: unpack reads packed_send[b] (packed_recv, host_pinned unused).
