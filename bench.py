@@ -27,7 +27,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0     # MI355X HBM3E vendor peak
 METRIC = "pack+unpack GB/s (% HBM peak); staged round-trip GB/s (% host link)"
 # HBM-side bytes per k_uniform launch on the default workload from rocprofv3 counter passes
-# (FETCH_SIZE, WRITE_SIZE, scaled by a plain copy of known size); None = not measured for this build.
+# (FETCH_SIZE, WRITE_SIZE, scaled by a plain copy of known size); None = not measured for the current kernel.
 TRAFFIC_BYTES_PER_LAUNCH = 134489378
 
 
@@ -78,7 +78,7 @@ class MessageSet:
 def main():
     a = parse()
     if a.gpus != 1:
-        print("bench.py: this build measures one GPU only (the transfer is per-GPU work with no collective); "
+        print("bench.py: this benchmark measures one GPU only (the transfer is per-GPU work with no collective); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     import torch

@@ -66,7 +66,7 @@ typedef enum {
     HXT_OK = 0,
     HXT_EINVAL = -1,       /* NULL where a pointer is required, bad count, bad lane, bad dtype ... */
     HXT_EALIGN = -2,       /* packed/pinned pointer not 256-byte aligned, tensor base not element aligned */
-    HXT_EUNSUPPORTED = -3, /* valid request this build cannot serve (size limits) */
+    HXT_EUNSUPPORTED = -3, /* valid request this library cannot serve (size limits) */
     HXT_EOVERLAP = -4,     /* hxt_unpack into a view whose elements may alias each other */
     HXT_EHIP = -5,         /* a HIP runtime call failed; hxt_last_hip_error() has the code */
     HXT_ENOMEM = -6        /* host or device allocation for the plan failed */

@@ -527,6 +527,35 @@ def test_config_llama8b_boundary_forward_and_backward():
         round_trip_check(case_of(w), wl.make_storages(w, msg), nthreads=NT)
 
 
+def test_config_llama8b_boundary_in_the_benchmarks_launch_configuration():
+    """Both messages of the step in one batched pack call and one batched unpack call, a plan each, fused
+    checksums, as the benchmark times them; every byte and every sum against the oracle."""
+    w = wl.llama8b_boundary()
+    case = case_of(w)
+    m = oracle_msg(case)
+    plans = [plan_of(case) for _ in range(w.messages)]
+    raws = [wl.make_storages(w, i) for i in range(w.messages)]
+    src = [[to_dev(r) for r in rs] for rs in raws]
+    packed = [torch.full((p.packed_bytes,), 0xA5, dtype=torch.uint8, device=DEV) for p in plans]
+    sums = [torch.full((p.num_chunks,), -1, dtype=torch.int64, device=DEV) for p in plans]
+    rsums = [torch.full((p.num_chunks,), -2, dtype=torch.int64, device=DEV) for p in plans]
+    dst = [[torch.full_like(t, 0x3C) for t in s_] for s_ in src]
+    hxt.hxt_pack_batch(hxt.Batch(plans, src, packed, sums))
+    hxt.hxt_unpack_batch(hxt.Batch(plans, dst, packed, rsums))
+    torch.cuda.synchronize()
+    for i in range(w.messages):
+        want = ho.pack(m, raws[i], w.chunk_bytes, w.n_lanes, fill=0xA5, nthreads=NT)
+        ws = ho.checksum(m, want, w.chunk_bytes, w.n_lanes, nthreads=NT)
+        assert np.array_equal(packed[i].cpu().numpy(), want), "message %d" % i
+        assert np.array_equal(sums[i].cpu().numpy().view(np.uint64), ws)
+        assert np.array_equal(rsums[i].cpu().numpy().view(np.uint64), ws)
+        dst_o = [np.full(r.size, 0x3C, np.uint8) for r in raws[i]]
+        ho.unpack(m, want, w.chunk_bytes, w.n_lanes, dst_o, nthreads=NT)
+        for a, b in zip(dst_o, dst[i]):
+            assert np.array_equal(b.cpu().numpy(), a)
+    assert not np.array_equal(raws[0][0], raws[1][0])
+
+
 def test_config_qwen2_both_paths_same_bytes():
     w = wl.qwen2_7b_boundary()
     case = case_of(w)
