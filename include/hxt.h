@@ -219,8 +219,12 @@ int hxt_unpack_batch(int n, const hxt_plan_t *const *plans, const void *const *p
  *   path HXT_CPU_FORWARD  : packed_send[b] -> host_pinned[b] -> packed_recv[b] -> unpack.
  * src/dst: n_messages * n_tensors device pointers, message-major.  send_sums/recv_sums:
  * NULL or device arrays of n_messages * num_chunks uint64, message-major.
- * The call only enqueues; when the three streams have drained, every message has
- * arrived.  HXT_EINVAL: n_messages < 0, n_buffers < 1, a NULL array that the path needs,
+ * The call only enqueues, with one exception: on the HXT_CPU_FORWARD path it waits on
+ * the host for the three streams to drain after every 12 messages (environment
+ * HXT_DRAIN_EVERY, 0 = never), because the runtime stops overlapping the two copy
+ * directions once more than about 16 messages' worth of copies and event waits are
+ * outstanding; such a call must not be made under stream capture.  When the three
+ * streams have drained, every message has arrived.  HXT_EINVAL: n_messages < 0, n_buffers < 1, a NULL array that the path needs,
  * a NULL stream handle shared by two roles is allowed (the steps then serialise). */
 typedef enum { HXT_DEVICE_DIRECT = 0, HXT_CPU_FORWARD = 1 } hxt_path_t;
 
