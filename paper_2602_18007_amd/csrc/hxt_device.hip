@@ -1625,14 +1625,7 @@ int run_sum2(const hxt_plan_t *plan, const void *packed, int mode, void *out, co
     if (mode == SUM2_VERIFY && reinterpret_cast<uintptr_t>(work.tags) % 16) return HXT_EALIGN;
     hxt_plan_t &pl = *const_cast<hxt_plan_t *>(plan);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (pl.p.C == 0) {
-        if (mode == SUM2_VERIFY) {
-            k_count_rejected<<<1, kThreads, 0, st>>>(static_cast<uint32_t *>(out), 0);
-            HXT_HIP(hipGetLastError());
-        }
-        return HXT_OK;
-    }
-    SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};
+    SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};          // callers have dealt with the empty message
     SlotsLock lock(g_slots_mu);
     if ((rc = claim_slots(pl, OP_CHECKSUM2, st, cx, nullptr)) != HXT_OK) return rc;
     const uint8_t *pk = static_cast<const uint8_t *>(packed);

@@ -55,6 +55,8 @@ SMALL_CASES: List[Case] = [
     Case("empty_tensor", (((0, 16), (16, 1), 2),), 2, 256),
     Case("empty_between", (contig((100,), 2), ((0,), (1,), 2), contig((77,), 4)), 2, 256),
     Case("inner_stride_2", (((40, 24), (48, 2), 2),), 2, 256),               # every other element
+    Case("eight_dims_permuted", (((2, 3, 2, 2, 3, 2, 2, 4), (288, 48, 2, 576, 4, 1, 144, 12), 2),), 3, 256),
+    Case("sixty_four_lanes", (contig((40000,), 2),), 64, 512),                # 157 chunks, lanes hold 3 or 2
     Case("mixed_dtypes_multi", (contig((33,), 1), ((8, 24), (32, 1), 2), ((16, 8), (1, 16), 4), contig((5,), 8)), 4, 512),
 ]
 
