@@ -216,6 +216,13 @@ int hxt_unpack_batch(int n, const hxt_plan_t *const *plans, const void *const *p
  * Section 2.2's control plane for a 1F1B schedule, where a stage sends one micro-batch
  * while the previous one is still in flight.
  *   path HXT_DEVICE_DIRECT: unpack reads packed_send[b] (packed_recv, host_pinned unused).
+ *       Which stream runs what is then the library's choice, the results and the
+ *       completion rule below being the same: with an even n_buffers and distinct
+ *       stream_pack / stream_unpack, even messages are packed and unpacked on
+ *       stream_pack and odd messages on stream_unpack (two independent chains whose
+ *       kernels overlap, no events inside); otherwise single-tensor messages go as
+ *       launches that unpack message i-1 and pack message i together, and anything
+ *       else as event-chained calls.
  *   path HXT_CPU_FORWARD  : packed_send[b] -> host_pinned[b] -> packed_recv[b] -> unpack.
  * src/dst: n_messages * n_tensors device pointers, message-major.  send_sums/recv_sums:
  * NULL or device arrays of n_messages * num_chunks uint64, message-major.

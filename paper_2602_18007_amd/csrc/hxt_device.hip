@@ -756,7 +756,9 @@ __global__ __launch_bounds__(kThreads) void k_count_rejected(uint32_t *status, u
 using namespace hxt;
 
 // The plan: host tables, their device copies, and the checksum accumulators.
-enum Op { OP_PACK = 0, OP_UNPACK = 1, OP_CHECKSUM = 2, OP_CHECKSUM2 = 3, OP_COUNT = 4 };
+// OP_PACK_B / OP_UNPACK_B: a second set of accumulators, for the second of two message chains that
+// run side by side on two streams (see chained_direct_stream).
+enum Op { OP_PACK = 0, OP_UNPACK = 1, OP_CHECKSUM = 2, OP_CHECKSUM2 = 3, OP_PACK_B = 4, OP_UNPACK_B = 5, OP_COUNT = 6 };
 
 struct OpState {              // accumulator slots of one operation and who used them last
     uint8_t *acc = nullptr;
@@ -940,14 +942,15 @@ uint32_t max_arrivals(uint32_t tiles, uint32_t fan)
 }
 
 template <bool UNPACK, bool CSUM>
-int run_copy(hxt_plan_t &pl, void *const *ptrs, uint8_t *packed, uint64_t *sums, hipStream_t st)
+int run_copy(hxt_plan_t &pl, void *const *ptrs, uint8_t *packed, uint64_t *sums, hipStream_t st, int chain = 0)
 {
     const Plan &p = pl.p;
     SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};
     std::optional<SlotsLock> lock;
     if constexpr (CSUM) {
         lock.emplace(g_slots_mu);
-        int rc = claim_slots(pl, UNPACK ? OP_UNPACK : OP_PACK, st, cx, sums);
+        const Op op = chain ? (UNPACK ? OP_UNPACK_B : OP_PACK_B) : (UNPACK ? OP_UNPACK : OP_PACK);
+        int rc = claim_slots(pl, op, st, cx, sums);
         if (rc != HXT_OK) return rc;
         cx.sum_bits = pl.sum_bits_table;
     }
@@ -1285,6 +1288,46 @@ int fused_direct_stream(hxt_plan_t &pl, const hxt_exchange_t &x, hipStream_t sp,
     return HXT_OK;
 }
 
+// Device-direct micro-batch stream as two chains: even messages on stream a, odd messages on stream
+// b, each chain packing and unpacking its own messages in stream order.  With an even number of
+// buffer sets a buffer only ever serves one chain, so the chains share nothing (each has its own
+// accumulator slots) and need no events; their kernels overlap and fill each other's ramp-up and
+// tail.  The third stream is made to wait for both, so that draining any of the three means every
+// message has arrived.
+int chained_direct_stream(hxt_plan_t &pl, const hxt_exchange_t &x, hipStream_t a, hipStream_t b, hipStream_t third)
+{
+    const Plan &p = pl.p;
+    const size_t T = p.tensors.size();
+    for (int i = 0; i < x.n_messages; ++i) {
+        const int chain = i & 1;
+        hipStream_t st = chain ? b : a;
+        uint8_t *buf = static_cast<uint8_t *>(x.packed_send[i % x.n_buffers]);
+        void *const *src = const_cast<void *const *>(x.src + i * T);
+        uint64_t *s_send = x.send_sums ? x.send_sums + size_t(i) * p.C : nullptr;
+        uint64_t *s_recv = x.recv_sums ? x.recv_sums + size_t(i) * p.C : nullptr;
+        int rc = s_send ? run_copy<false, true>(pl, src, buf, s_send, st, chain)
+                        : run_copy<false, false>(pl, src, buf, nullptr, st, chain);
+        if (rc != HXT_OK) return rc;
+        rc = s_recv ? run_copy<true, true>(pl, x.dst + i * T, buf, s_recv, st, chain)
+                    : run_copy<true, false>(pl, x.dst + i * T, buf, nullptr, st, chain);
+        if (rc != HXT_OK) return rc;
+    }
+    hipEvent_t done[2] = {nullptr, nullptr};
+    hipError_t e = hipEventCreateWithFlags(&done[0], hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&done[1], hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventRecord(done[0], a);
+    if (e == hipSuccess) e = hipEventRecord(done[1], b);
+    if (e == hipSuccess) e = hipStreamWaitEvent(b, done[0], 0);
+    if (e == hipSuccess) e = hipStreamWaitEvent(a, done[1], 0);
+    if (e == hipSuccess && third != a && third != b) {
+        e = hipStreamWaitEvent(third, done[0], 0);
+        if (e == hipSuccess) e = hipStreamWaitEvent(third, done[1], 0);
+    }
+    for (hipEvent_t ev : done)
+        if (ev) (void)hipEventDestroy(ev);
+    return e == hipSuccess ? HXT_OK : hip_fail(e);
+}
+
 }  // namespace
 
 // ---- C ABI ---------------------------------------------------------------------------
@@ -1530,7 +1573,12 @@ int hxt_exchange_stream(const hxt_plan_t *plan, const hxt_exchange_t *x)
     }
     hipStream_t sp = static_cast<hipStream_t>(x->stream_pack), ss = static_cast<hipStream_t>(x->stream_stage),
                 su = static_cast<hipStream_t>(x->stream_unpack);
-    if (!fwd && x->n_buffers >= 2 && p.uniform && !x->send_sums == !x->recv_sums && env_int("HXT_FUSED_STREAM", 1)) {
+    // HXT_STREAM_MODE: 2 = two chains on two streams (default when it applies), 1 = fused launches on one
+    // stream, 0 = event-chained calls on three streams.
+    const int mode = env_int("HXT_STREAM_MODE", 2);
+    if (!fwd && mode == 2 && x->n_buffers % 2 == 0 && sp != su)
+        return chained_direct_stream(*const_cast<hxt_plan_t *>(plan), *x, sp, su, ss);
+    if (!fwd && mode >= 1 && x->n_buffers >= 2 && p.uniform && !x->send_sums == !x->recv_sums) {
         bool aligned = true;
         for (int i = 0; i < x->n_messages; ++i)
             aligned = aligned && reinterpret_cast<uintptr_t>(x->src[i * T + p.uniform_tensor]) % 16 == 0 &&

@@ -691,13 +691,17 @@ def test_config_stream_1f1b_native_exchange(path):
                  [torch.cuda.Stream() for _ in range(3)])
 
 
-def test_exchange_stream_event_path_for_single_tensor_messages(monkeypatch):
-    # single-tensor device-direct streams normally take the fused-launch path; the event-chained
-    # path must give the same result
-    monkeypatch.setenv("HXT_FUSED_STREAM", "0")
-    case = [c for c in MID_CASES if c.name == "contig_bf16_5MiB_tail"][0]
-    run_exchange(case, [make_storages(case, 3200 + i) for i in range(6)], "device_direct", 2,
-                 [torch.cuda.Stream() for _ in range(3)])
+@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("n_buffers", [2, 4])
+def test_exchange_stream_device_direct_modes_agree(monkeypatch, mode, n_buffers):
+    # device-direct streams take two message chains on two streams by default (2); fused launches on one
+    # stream (1, single-tensor messages) and event-chained calls on three streams (0) must give the same
+    # result, for single-tensor and for multi-tensor messages
+    monkeypatch.setenv("HXT_STREAM_MODE", str(mode))
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    for name, nmsg in (("contig_bf16_5MiB_tail", 7), ("multi_mid", 6)):
+        case = [c for c in MID_CASES if c.name == name][0]
+        run_exchange(case, [make_storages(case, 3200 + i) for i in range(nmsg)], "device_direct", n_buffers, streams)
 
 
 def test_packed_buffer_in_pinned_host_memory():
