@@ -550,16 +550,52 @@ __global__ __launch_bounds__(kThreads) void k_generic(const Tile *__restrict__ t
         const uint32_t nel = t.n0 / sizeof(E);
         constexpr uint32_t PER = 16 / sizeof(E);
         const uint64_t e0 = t.src_off / sizeof(E);
+        // Coordinates of the tile's first element (the same for every thread).  When every dim fits the
+        // multiply-shift division, an element's coordinates are these plus its number within the tile,
+        // carried from the last dim upwards in 32 bits; otherwise each element is divided out in 64 bits.
+        const bool fast = td.all_div != 0;
+        const int nd = td.ndim;
+        uint32_t base[HXT_MAX_DIMS];
+        {
+            uint64_t idx = e0;
+#pragma unroll
+            for (int d = HXT_MAX_DIMS - 1; d >= 0; --d) {
+                base[d] = 0;
+                if (d < nd && fast) {
+                    const uint64_t q = idx / uint64_t(td.shape[d]);
+                    base[d] = uint32_t(idx - q * uint64_t(td.shape[d]));
+                    idx = q;
+                }
+            }
+        }
         for (uint32_t v = threadIdx.x; v * PER < nel; v += kThreads) {
 #pragma unroll
             for (uint32_t j = 0; j < PER; ++j) {
                 const uint32_t el = v * PER + j;
                 if (el < nel) {
-                    uint64_t idx = e0 + el, off = 0;
-                    for (int d = td.ndim - 1; d >= 0; --d) {
-                        const uint64_t q = idx / uint64_t(td.shape[d]);
-                        off += (idx - q * uint64_t(td.shape[d])) * uint64_t(td.stride_b[d]);
-                        idx = q;
+                    uint64_t off = 0;
+                    if (fast) {
+                        uint32_t x = el;                                   // carry into the last dim
+#pragma unroll
+                        for (int d = HXT_MAX_DIMS - 1; d >= 0; --d) {
+                            if (d < nd) {
+                                x += base[d];
+                                if (d > 0) {
+                                    const uint32_t q = fast_div(x, td.dim_div[d]);
+                                    off += uint64_t(x - q * uint32_t(td.shape[d])) * uint64_t(td.stride_b[d]);
+                                    x = q;
+                                } else {
+                                    off += uint64_t(x) * uint64_t(td.stride_b[0]);
+                                }
+                            }
+                        }
+                    } else {
+                        uint64_t idx = e0 + el;
+                        for (int d = nd - 1; d >= 0; --d) {
+                            const uint64_t q = idx / uint64_t(td.shape[d]);
+                            off += (idx - q * uint64_t(td.shape[d])) * uint64_t(td.stride_b[d]);
+                            idx = q;
+                        }
                     }
                     E *u = reinterpret_cast<E *>(user + off);
                     E *p = reinterpret_cast<E *>(pk) + el;

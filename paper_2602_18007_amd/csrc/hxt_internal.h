@@ -107,8 +107,9 @@ struct TensorDev {
     int32_t ndim;                      // merged dims; for ROWS the last one is the contiguous run
     int32_t esize;
     uint32_t row_bytes;                // ROWS: bytes of one contiguous run
+    uint32_t all_div;                  // 1: dim_div is valid for every dim and every shape[d] <= 2^30
     FastDiv row_div;                   // ROWS: division by row_bytes
-    FastDiv dim_div[HXT_MAX_DIMS];     // ROWS: division by shape[d] for the outer dims
+    FastDiv dim_div[HXT_MAX_DIMS];     // division by shape[d]: for the outer dims of a ROWS tensor, for all dims if all_div
     int64_t shape[HXT_MAX_DIMS];
     int64_t stride_b[HXT_MAX_DIMS];    // bytes
 };

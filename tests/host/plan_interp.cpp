@@ -33,12 +33,40 @@ uint64_t logical_to_storage(const TensorDev &td, uint64_t byte)
     }
     return off + b;
 }
+
+// The per-element kernel's 32-bit address arithmetic, restated for the host: coordinates of the tile's
+// first element, plus the element's number carried from the last dim upwards with the plan's
+// multiply-shift divisors.  Returns false if any intermediate leaves the range the divisors are exact for.
+bool carried_offset(const TensorDev &td, uint64_t e0, uint32_t el, uint64_t *off_out)
+{
+    uint32_t base[HXT_MAX_DIMS] = {0};
+    uint64_t idx = e0;
+    for (int d = td.ndim - 1; d >= 0; --d) {
+        base[d] = uint32_t(idx % uint64_t(td.shape[d]));
+        idx /= uint64_t(td.shape[d]);
+    }
+    uint64_t x = el, off = 0;
+    for (int d = td.ndim - 1; d >= 0; --d) {
+        x += base[d];
+        if (x >= (uint64_t(1) << 31)) return false;
+        if (d > 0) {
+            const uint32_t q = fast_div(uint32_t(x), td.dim_div[d]);
+            off += uint64_t(uint32_t(x) - q * uint32_t(td.shape[d])) * uint64_t(td.stride_b[d]);
+            x = q;
+        } else {
+            off += x * uint64_t(td.stride_b[0]);
+        }
+    }
+    *off_out = off;
+    return true;
+}
 }  // namespace
 
 // direction 0: pack (user -> packed) from the tables, 1: unpack (packed -> user) from the tables,
 // 2: pack from the tables and then, if the message is uniform, again from the closed form.  Returns 0, or a
 // negative code: -1 plan error, -2 user access out of bounds, -3 packed access out of
-// bounds, -4 tile crosses its chunk, -5 bad group bookkeeping, -6 bad closed-form geometry.
+// bounds, -4 tile crosses its chunk, -5 bad group bookkeeping, -6 bad closed-form geometry, -7 the 32-bit
+// carried address arithmetic of the per-element kernel disagrees with the plain one.
 extern "C" int plan_interp(const hxt_tensor_desc_t *descs, int n_tensors, int n_lanes, uint64_t chunk_bytes,
                            uint32_t tile_bytes, uint8_t *const *base, const uint64_t *storage_bytes,
                            uint8_t *packed, uint64_t packed_bytes, uint8_t *written, int direction,
@@ -75,6 +103,15 @@ extern "C" int plan_interp(const hxt_tensor_desc_t *descs, int n_tensors, int n_
                 return 0;
             };
             int rc = 0;
+            // tiles of these kinds go to the per-element kernel when a base pointer is not 16-byte aligned
+            if ((t.kind == K_CONTIG || t.kind == K_ROWS || t.kind == K_GENERIC) && td.all_div) {
+                if (t.src_off % td.esize || t.n0 % td.esize) return -7;
+                for (uint32_t el = 0; el < t.n0 / td.esize; ++el) {
+                    uint64_t off = 0;
+                    if (!carried_offset(td, t.src_off / td.esize, el, &off)) return -7;
+                    if (off != logical_to_storage(td, t.src_off + uint64_t(el) * td.esize)) return -7;
+                }
+            }
             switch (t.kind) {
             case K_CONTIG:
                 if (g.kernel != K_CONTIG) return -5;
