@@ -208,11 +208,37 @@ def main():
                      "launches": launches, "gpu_ms_timed_region": round(gpu_ms, 4)},
     }
     out["paper_context"] = PAPER_CONTEXT
+    out["roofline"]["plain_copy"] = plain_copy_ceiling(torch, int(launch_bytes) // 2)
     if not a.no_staged:
         out["staged"] = staged_round_trip(torch, hxt, w, plans, sets[0])
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))
+
+
+def plain_copy_ceiling(torch, nbytes):
+    """The runtime's own device-to-device copy of as many bytes as one launch of the dominant kernel reads
+    (and writes), cold (rotating buffers), back to back on one stream: the machine's practical ceiling for a
+    launch of that size, printed beside the kernel's figure."""
+    dev = "cuda:0"
+    nsets = max(2, min(8, int(3e9 // (2 * nbytes))))
+    src = [torch.empty(nbytes, dtype=torch.uint8, device=dev).fill_(i + 1) for i in range(nsets)]
+    dst = [torch.empty(nbytes, dtype=torch.uint8, device=dev) for _ in range(nsets)]
+    iters = 64
+    for i in range(8):
+        dst[i % nsets].copy_(src[i % nsets])
+    torch.cuda.synchronize()
+    best = 1e9
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(iters):
+            dst[i % nsets].copy_(src[i % nsets])
+        e1.record()
+        torch.cuda.synchronize()
+        best = min(best, e0.elapsed_time(e1) / iters)
+    return {"what": "torch device-to-device copy, same bytes per launch, cold", "bytes_read_plus_written": 2 * nbytes,
+            "avg_ms": round(best, 6), "gbps": round(2 * nbytes / (best * 1e-3) / 1e9, 1)}
 
 
 def _wall(fn):

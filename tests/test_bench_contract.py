@@ -37,6 +37,7 @@ def test_default_workload_line_has_the_contract_keys():
     assert rf["bound"] == "hbm" and rf["peak"] == 8000.0 and rf["unit"] == "GB/s"
     assert abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-3
     assert rf["traffic"] is None or rf["traffic"] >= rf["bytes_per_launch"]
+    assert rf["plain_copy"]["bytes_read_plus_written"] == rf["bytes_per_launch"] and rf["plain_copy"]["gbps"] > 0
     # whole-step throughput cannot exceed what the launches achieve back to back
     assert 0 < out["value"] <= rf["achieved"] * 1.02
     st = out["staged"]
