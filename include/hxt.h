@@ -109,7 +109,8 @@ typedef struct {
  * Rejects with HXT_EINVAL: out == NULL, shape == NULL with ndim > 0, ndim < 0 or
  * > HXT_MAX_DIMS, a negative extent or stride, unknown dtype, n_lanes < 1 or
  * > 1024, chunk_bytes == 0 or not a multiple of 256, n_tensors < 0.
- * HXT_EUNSUPPORTED: message larger than 2^40 bytes or more than 2^31 chunks. */
+ * HXT_EUNSUPPORTED: message larger than 2^40 bytes, more than 2^31 chunks, or a view
+ * whose farthest element lies 2^62 bytes or more past its base. */
 int hxt_plan(const int64_t *shape, const int64_t *strides, int ndim, hxt_dtype_t dtype,
              int n_lanes, size_t chunk_bytes, hxt_plan_t **out);
 int hxt_plan_multi(const hxt_tensor_desc_t *tensors, int n_tensors,

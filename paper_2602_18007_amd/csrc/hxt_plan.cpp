@@ -243,9 +243,12 @@ int build_plan(const hxt_tensor_desc_t *descs, int n_tensors, int n_lanes, size_
             elems *= uint64_t(d.shape[k]);
         }
         if (elems * t.esize > kMaxBytes) return HXT_EUNSUPPORTED;
-        if (d.strides)                                   // the view must stay addressable with 63 bits
+        if (d.strides && elems > 0) {                    // the view must stay addressable: its farthest byte below 2^62
+            unsigned __int128 reach = 0;
             for (int k = 0; k < d.ndim; ++k)
-                if (d.shape[k] > 1 && uint64_t(d.strides[k]) > (uint64_t(1) << 47)) return HXT_EUNSUPPORTED;
+                reach += (unsigned __int128)(uint64_t(d.shape[k]) - 1) * uint64_t(d.strides[k]);
+            if ((reach + 1) * unsigned(t.esize) > ((unsigned __int128)1 << 62)) return HXT_EUNSUPPORTED;
+        }
         t.elems = elems;
         t.bytes = elems * t.esize;
         t.stream_off = off;

@@ -129,7 +129,14 @@ def test_unpack_safety_flag():
     (dict(shape=(4, -1)), hxt.HXT_EINVAL), (dict(strides=(-2, 1)), hxt.HXT_EINVAL),
     (dict(shape=(1,) * 9, strides=(1,) * 9), hxt.HXT_EINVAL),
     (dict(shape=(1 << 30, 1 << 20), strides=None), hxt.HXT_EUNSUPPORTED),
+    (dict(shape=(4, 4), strides=(1 << 61, 1)), hxt.HXT_EUNSUPPORTED),          # farthest element past 2^62 bytes
+    (dict(shape=(3, 1 << 20), strides=((1 << 63) - 1, (1 << 43))), hxt.HXT_EUNSUPPORTED),   # products that overflow 64 bits
 ])
+def test_plan_accepts_a_far_reaching_view_below_the_limit():
+    p = hxt.hxt_plan((2, 64), (1 << 59, 1), 2, 2, 256)                         # 2^60 bytes apart: still addressable
+    assert p.message_bytes == 256 and p.tensor_unpack_safe(0)
+
+
 def test_plan_rejects_bad_arguments(kwargs, status):
     args = dict(shape=(4, 4), strides=(4, 1), dtype=2, n_lanes=2, chunk_bytes=256)
     args.update(kwargs)
