@@ -123,6 +123,11 @@ def test_unpack_safety_flag():
     assert plan_of(Case("e", (((0, 4), (0, 0), 2),), 2, 256)).tensor_unpack_safe(0)           # empty
 
 
+def test_plan_accepts_a_far_reaching_view_below_the_limit():
+    p = hxt.hxt_plan((2, 64), (1 << 59, 1), 2, 2, 256)                         # 2^60 bytes apart: still addressable
+    assert p.message_bytes == 256 and p.tensor_unpack_safe(0)
+
+
 @pytest.mark.parametrize("kwargs,status", [
     (dict(n_lanes=0), hxt.HXT_EINVAL), (dict(n_lanes=1025), hxt.HXT_EINVAL),
     (dict(chunk_bytes=0), hxt.HXT_EINVAL), (dict(chunk_bytes=1000), hxt.HXT_EINVAL),
@@ -132,11 +137,6 @@ def test_unpack_safety_flag():
     (dict(shape=(4, 4), strides=(1 << 61, 1)), hxt.HXT_EUNSUPPORTED),          # farthest element past 2^62 bytes
     (dict(shape=(3, 1 << 20), strides=((1 << 63) - 1, (1 << 43))), hxt.HXT_EUNSUPPORTED),   # products that overflow 64 bits
 ])
-def test_plan_accepts_a_far_reaching_view_below_the_limit():
-    p = hxt.hxt_plan((2, 64), (1 << 59, 1), 2, 2, 256)                         # 2^60 bytes apart: still addressable
-    assert p.message_bytes == 256 and p.tensor_unpack_safe(0)
-
-
 def test_plan_rejects_bad_arguments(kwargs, status):
     args = dict(shape=(4, 4), strides=(4, 1), dtype=2, n_lanes=2, chunk_bytes=256)
     args.update(kwargs)
