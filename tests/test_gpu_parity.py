@@ -482,6 +482,26 @@ def test_offsets_beyond_32_bits(case):
     round_trip_check(case, raws, nthreads=NT)
 
 
+def test_plans_release_their_device_memory():
+    case = [c for c in MID_CASES if c.name == "multi_mid"][0]
+    raws = make_storages(case, 4)
+    src = [to_dev(r) for r in raws]
+    torch.cuda.synchronize()
+    free0 = torch.cuda.mem_get_info()[0]
+    side = torch.cuda.Stream()
+    for i in range(200):
+        p = plan_of(case)
+        packed = torch.empty(p.packed_bytes, dtype=torch.uint8, device=DEV) if i == 0 else packed
+        sums = torch.zeros(p.num_chunks, dtype=torch.int64, device=DEV) if i == 0 else sums
+        if i == 0:
+            free0 = torch.cuda.mem_get_info()[0]                 # after the buffers of the test itself exist
+        hxt.hxt_pack(p, src, packed, sums)
+        hxt.hxt_pack(p, src, packed, sums, side)                 # another stream: the plan creates its ordering event
+        hxt.hxt_plan_destroy(p)
+    torch.cuda.synchronize()
+    assert torch.cuda.mem_get_info()[0] >= free0 - (8 << 20), "device memory of destroyed plans was not returned"
+
+
 def test_data_plane_argument_errors():
     case = case_by_name("single_lane")
     p = plan_of(case)
