@@ -43,6 +43,19 @@ def test_library_exports_every_declared_symbol():
     assert hxt.hxt_version().startswith("hxt")
 
 
+def test_a_plain_c_program_can_use_the_library(tmp_path):
+    """The boundary is a C ABI: a C11 client, compiled with gcc against include/hxt.h and linked with the
+    shared library, creates a plan and reads its geometry (control plane only, no GPU needed)."""
+    exe = tmp_path / "abi_client"
+    pkg = os.path.join(ROOT, "paper_2602_18007_amd")
+    subprocess.run(["gcc", "-std=c11", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    os.path.join(ROOT, "tests", "host", "abi_client.c"), "-o", str(exe),
+                    "-L", pkg, "-lhxt", "-Wl,-rpath," + pkg, "-Wl,-rpath-link,/opt/rocm/lib"], check=True)
+    r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "abi_client: ok" in r.stdout
+
+
 def test_header_is_plain_c_and_the_tag_record_has_the_documented_offsets(tmp_path):
     """include/hxt.h must compile as C; the 64-byte tag record's field offsets are the ones the oracle documents."""
     src = tmp_path / "abi.c"
