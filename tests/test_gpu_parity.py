@@ -605,7 +605,7 @@ def test_config_qwen2_both_paths_same_bytes():
 
 @pytest.mark.parametrize("path", ["device_direct", "cpu_forward"])
 def test_config_stream_1f1b_three_streams_ping_pong(path):
-    w = wl.stream_1f1b(8 if path == "cpu_forward" else 32)
+    w = wl.stream_1f1b(32)                      # CPU forwarding drains its streams after messages 12 and 24
     case = case_of(w)
     m = oracle_msg(case)
     p = plan_of(case)
@@ -705,7 +705,7 @@ def test_exchange_stream_small_messages(path, n_buffers):
 
 @pytest.mark.parametrize("path", ["device_direct", "cpu_forward"])
 def test_config_stream_1f1b_native_exchange(path):
-    w = wl.stream_1f1b(8 if path == "cpu_forward" else 32)
+    w = wl.stream_1f1b(32)                      # CPU forwarding drains its streams after messages 12 and 24
     say("native stream", path, "messages", w.messages)
     run_exchange(case_of(w), [wl.make_storages(w, i) for i in range(w.messages)], path, 2,
                  [torch.cuda.Stream() for _ in range(3)])
