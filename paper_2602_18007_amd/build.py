@@ -8,7 +8,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "libhxt.so")
 SOURCES = [os.path.join(PKG, "csrc", "hxt_device.hip"), os.path.join(PKG, "csrc", "hxt_plan.cpp")]
-HEADERS = [os.path.join(PKG, "csrc", "hxt_internal.h"), os.path.join(ROOT, "include", "hxt.h")]
+HEADERS = [os.path.join(PKG, "csrc", "hxt_internal.h"), os.path.join(PKG, "csrc", "hxt_kernels.h"),
+           os.path.join(ROOT, "include", "hxt.h")]
 
 
 def hipcc() -> str:

@@ -1,18 +1,9 @@
-// HIP kernels (gfx950) and the C ABI of libhxt.
+// Host side of libhxt: launch logic, accumulator bookkeeping, staging copies, the micro-batch
+// stream, and the C ABI declared in include/hxt.h.  The kernels are in hxt_kernels.h, the
+// planner (pure host, no HIP) in hxt_plan.cpp.
 //
-// Data plane of the paper's Section 2.2 transfer: user buffer -> chunk buffer on
-// the sender (pack), chunk buffer -> user buffer on the receiver (unpack), plus
-// the explicit device<->host copies of the CPU-forwarding variant (Section 2.1)
-// and a per-chunk integrity sum.  Every kernel is a pure byte mover: data is
-// handled as unsigned integers so that any bit pattern survives unchanged.
-//
-// Work decomposition: the host planner cuts the message into tiles (one per
-// workgroup, never crossing a chunk or a tensor); a workgroup reads its 64-byte
-// tile record with scalar loads and moves the bytes with 128-bit vector
-// accesses.  Checksums are accumulated per thread in 64-bit integers, reduced
-// across the 64-lane wavefront with shuffles, across the four waves through
-// LDS, and added to the chunk's total with one 64-bit atomic per workgroup;
-// integer addition makes the result independent of the order of arrival.
+// Covers the paper's Section 2.2 transfer (pack / unpack around a chunk buffer) and the
+// explicit device<->host copies of the CPU-forwarding variant (Section 2.1).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -26,768 +17,7 @@
 #include <vector>
 
 #include "hxt_internal.h"
-
-namespace hxt {
-
-constexpr int kThreads = 256;
-constexpr int kUnroll = 4;
-constexpr uint32_t kTagMagic = 0x31545848u;     // 'H','X','T','1' in memory order
-
-struct BasePtrs {
-    uint8_t *p[kMaxGroupTensors];
-};
-
-struct ElemKinds {                     // per tensor of a launch group: 1 = 32-bit float, 0 = bf16
-    uint8_t f32[kMaxGroupTensors];
-};
-
-// Per-chunk accumulator of a checksum in flight.  One per chunk and per operation
-// (pack, unpack, stand-alone checksum), kAccStride bytes apart so that neighbouring
-// chunks' atomics land in different memory channels.  Always zero between kernels.
-struct Acc {
-    unsigned long long sum;
-    uint32_t cnt;
-    uint32_t pad;
-};
-
-struct SumCtx {
-    uint64_t *sums;      // caller's array, one entry per chunk
-    uint8_t *acc;        // plan-owned Acc slots: C * fan first-level slots, then C second-level slots
-    uint32_t stride;     // bytes between slots
-    uint32_t sum_bits;   // > 0: a chunk's total fits this many bits and the arrival count rides above it
-    uint32_t fan;        // first-level slots per chunk (power of two); 1 = second level only
-    uint32_t chunks;     // C
-};
-
-// ---- small device helpers ----------------------------------------------------
-
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-template <bool NT>
-__device__ __forceinline__ u32x4 load16(const u32x4 *p)
-{
-    if constexpr (NT) return __builtin_nontemporal_load(p);
-    else return *p;
-}
-
-template <bool NT>
-__device__ __forceinline__ void store16(u32x4 *p, u32x4 v)
-{
-    if constexpr (NT) __builtin_nontemporal_store(v, p);
-    else *p = v;
-}
-
-__device__ __forceinline__ uint64_t words_sum(u32x4 v)
-{
-    return (uint64_t(v.x) + uint64_t(v.y)) + (uint64_t(v.z) + uint64_t(v.w));
-}
-
-// One arrival at an accumulator slot that expects `expected` of them: adds `value` and reports
-// whether this was the last arrival, in which case `value` becomes the slot's total and the
-// slot is zero again.  Only relaxed device-scope atomics touch a slot (no cache write-back).
-//   sum_bits > 0: totals stay below 2^sum_bits (a chunk has at most B/4 words of 32 bits) and
-//     the arrival count fits in the bits above, so one atomic adds and takes the ticket at once.
-//   sum_bits == 0: sum and ticket are two words; the ticket is taken after the wave has seen
-//     its own addition return, which orders the two.
-__device__ __forceinline__ bool slot_arrive(Acc *a, unsigned long long &value, uint32_t expected, uint32_t sum_bits)
-{
-    if (expected == 1) return true;
-    if (sum_bits) {
-        const unsigned long long one = 1ull << sum_bits;
-        const unsigned long long before = __hip_atomic_fetch_add(&a->sum, one + value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if ((before >> sum_bits) != expected - 1) return false;
-        __hip_atomic_store(&a->sum, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        value = (before + value) & (one - 1);
-        return true;
-    }
-    const unsigned long long before = __hip_atomic_fetch_add(&a->sum, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    asm volatile("s_waitcnt vmcnt(0)" ::"v"(uint32_t(before)) : "memory");
-    const uint32_t ticket = __hip_atomic_fetch_add(&a->cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (ticket != expected - 1) return false;
-    value = __hip_atomic_exchange(&a->sum, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(&a->cnt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return true;
-}
-
-// Adds this workgroup's partial sum to its chunk.  A chunk made of many tiles spreads its
-// arrivals over `fan` first-level slots (tile ordinal mod fan) so that they do not queue on
-// one address; the last arrival of a first-level slot carries that slot's total to the chunk's
-// second-level slot, and the last arrival there writes sums[chunk].
-__device__ __forceinline__ void chunk_commit(uint64_t acc, uint32_t chunk, uint32_t ordinal, uint32_t expected,
-                                             const SumCtx &cx)
-{
-    __shared__ uint64_t part[kThreads / 64];
-    for (int o = 32; o > 0; o >>= 1) acc += __shfl_down(acc, o, 64);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (lane == 0) part[wave] = acc;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        unsigned long long s = 0;
-#pragma unroll
-        for (int w = 0; w < kThreads / 64; ++w) s += part[w];
-        Acc *top = reinterpret_cast<Acc *>(cx.acc + (size_t(cx.chunks) * cx.fan + chunk) * cx.stride);
-        bool last;
-        if (cx.fan == 1 || expected < 2 * cx.fan) {
-            last = slot_arrive(top, s, expected, cx.sum_bits);
-        } else {
-            const uint32_t sub = ordinal & (cx.fan - 1);
-            const uint32_t share = expected / cx.fan + (sub < (expected & (cx.fan - 1)) ? 1u : 0u);
-            Acc *first = reinterpret_cast<Acc *>(cx.acc + (size_t(chunk) * cx.fan + sub) * cx.stride);
-            last = slot_arrive(first, s, share, cx.sum_bits) && slot_arrive(top, s, cx.fan, cx.sum_bits);
-        }
-        if (last) cx.sums[chunk] = s;
-    }
-}
-
-// Copy `bytes` contiguous bytes between a user tensor and the packed buffer (pack: user ->
-// packed, unpack: packed -> user) in 16-byte vectors, UNROLL independent loads in flight per
-// thread before the first store; a last partial vector goes byte by byte.  NTU / NTP mark
-// the user-side / packed-side accesses non-temporal.
-template <bool UNPACK, bool CSUM, bool NTU, bool NTP>
-__device__ __forceinline__ uint64_t copy_span(uint8_t *user, uint8_t *pk, uint32_t bytes)
-{
-    constexpr bool NTL = UNPACK ? NTP : NTU, NTS = UNPACK ? NTU : NTP;
-    const u32x4 *s = reinterpret_cast<const u32x4 *>(UNPACK ? pk : user);
-    u32x4 *d = reinterpret_cast<u32x4 *>(UNPACK ? user : pk);
-    const uint32_t nvec = bytes >> 4;
-    constexpr uint32_t STEP = kThreads * kUnroll;
-    const uint32_t full = nvec / STEP * STEP;            // uniform: blocks that need no bounds checks
-    uint64_t acc = 0;
-    for (uint32_t v = threadIdx.x; v < full; v += STEP) {
-        u32x4 r[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) r[u] = load16<NTL>(s + v + u * kThreads);
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            store16<NTS>(d + v + u * kThreads, r[u]);
-            if constexpr (CSUM) acc += words_sum(r[u]);
-        }
-    }
-    for (uint32_t v = full + threadIdx.x; v < nvec; v += kThreads) {
-        const u32x4 r = load16<NTL>(s + v);
-        store16<NTS>(d + v, r);
-        if constexpr (CSUM) acc += words_sum(r);
-    }
-    const uint32_t tail = bytes & 15;                    // only at the very end of a tensor
-    if (threadIdx.x < tail) {
-        const uint32_t i = (nvec << 4) + threadIdx.x;
-        const uint8_t b = (UNPACK ? pk : user)[i];
-        (UNPACK ? user : pk)[i] = b;
-        if constexpr (CSUM) acc += uint64_t(b) << (8 * (i & 3));
-    }
-    return acc;
-}
-
-// ---- receive and accumulate -----------------------------------------------------
-// new = round(old + arriving) per element.  bf16: both operands widened exactly to binary32,
-// added in binary32, the sum rounded to bf16 to nearest with ties to even.  f32: binary32
-// addition.  Every NaN result becomes the canonical quiet NaN, so that the outcome does not
-// depend on NaN payload propagation.
-__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f)
-{
-    const uint32_t u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0u;
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
-
-__device__ __forceinline__ uint32_t add_bf16x2(uint32_t old, uint32_t in)
-{
-    const float lo = __uint_as_float(old << 16) + __uint_as_float(in << 16);
-    const float hi = __uint_as_float(old & 0xFFFF0000u) + __uint_as_float(in & 0xFFFF0000u);
-    return f32_to_bf16_rne(lo) | (f32_to_bf16_rne(hi) << 16);
-}
-
-__device__ __forceinline__ uint32_t add_f32(uint32_t old, uint32_t in)
-{
-    const uint32_t u = __float_as_uint(__uint_as_float(old) + __uint_as_float(in));
-    return (u & 0x7FFFFFFFu) > 0x7F800000u ? 0x7FC00000u : u;
-}
-
-template <bool F32>
-__device__ __forceinline__ u32x4 add_vec(u32x4 old, u32x4 in)
-{
-    if constexpr (F32) return u32x4{add_f32(old.x, in.x), add_f32(old.y, in.y), add_f32(old.z, in.z), add_f32(old.w, in.w)};
-    else return u32x4{add_bf16x2(old.x, in.x), add_bf16x2(old.y, in.y), add_bf16x2(old.z, in.z), add_bf16x2(old.w, in.w)};
-}
-
-// Adds `bytes` arriving contiguous bytes at pk to the tensor bytes at user (both 16-byte aligned
-// except for a last partial vector, which goes element by element).  Returns the checksum
-// contribution of the packed bytes read.
-template <bool F32, bool CSUM, bool NTU, bool NTP>
-__device__ __forceinline__ uint64_t accumulate_span(uint8_t *user, const uint8_t *pk, uint32_t bytes)
-{
-    const u32x4 *in = reinterpret_cast<const u32x4 *>(pk);
-    u32x4 *io = reinterpret_cast<u32x4 *>(user);
-    const uint32_t nvec = bytes >> 4;
-    constexpr int U = 2;                                   // two vectors of each operand in flight per thread
-    constexpr uint32_t STEP = kThreads * U;
-    const uint32_t full = nvec / STEP * STEP;
-    uint64_t acc = 0;
-    for (uint32_t v = threadIdx.x; v < full; v += STEP) {
-        u32x4 a[U], b[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            a[u] = load16<NTP>(in + v + u * kThreads);
-            b[u] = load16<NTU>(io + v + u * kThreads);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            store16<NTU>(io + v + u * kThreads, add_vec<F32>(b[u], a[u]));
-            if constexpr (CSUM) acc += words_sum(a[u]);
-        }
-    }
-    for (uint32_t v = full + threadIdx.x; v < nvec; v += kThreads) {
-        const u32x4 a = load16<NTP>(in + v);
-        store16<NTU>(io + v, add_vec<F32>(load16<NTU>(io + v), a));
-        if constexpr (CSUM) acc += words_sum(a);
-    }
-    constexpr uint32_t ES = F32 ? 4 : 2;
-    const uint32_t tail = (bytes & 15) / ES;               // whole elements in the last partial vector
-    if (threadIdx.x < tail) {
-        const uint32_t off = (nvec << 4) + threadIdx.x * ES;
-        if constexpr (F32) {
-            const uint32_t a = *reinterpret_cast<const uint32_t *>(pk + off);
-            uint32_t *d = reinterpret_cast<uint32_t *>(user + off);
-            *d = add_f32(*d, a);
-            if constexpr (CSUM) acc += a;
-        } else {
-            const uint32_t a = *reinterpret_cast<const uint16_t *>(pk + off);
-            uint16_t *d = reinterpret_cast<uint16_t *>(user + off);
-            *d = uint16_t(add_bf16x2(*d, a));
-            if constexpr (CSUM) acc += uint64_t(a) << (8 * (off & 3));
-        }
-    }
-    return acc;
-}
-
-// Pad bytes (fewer than 256): pack writes zeros, unpack only reads them for the sum.
-// `phase` is the position of pk[0] within its 32-bit word.
-template <bool UNPACK, bool CSUM>
-__device__ __forceinline__ uint64_t pad_span(uint8_t *pk, uint32_t bytes, uint32_t phase)
-{
-    uint64_t acc = 0;
-    for (uint32_t i = threadIdx.x; i < bytes; i += kThreads) {
-        if constexpr (!UNPACK) pk[i] = 0;
-        if constexpr (UNPACK && CSUM) acc += uint64_t(pk[i]) << (8 * ((phase + i) & 3));
-    }
-    return acc;
-}
-
-// ---- uniform copy: messages that are one contiguous tensor each -------------------
-// No table: tile -> (chunk, lane, slot, offsets) in closed form from the kernel arguments.
-// One launch can serve several such messages (the forward activation and the backward
-// gradient that cross a stage boundary at the same point of the schedule): workgroups
-// [first_tile, first_tile + ntiles) belong to message i.
-constexpr int kMaxBatch = 4;
-
-struct UniformItem {
-    ChunkGeom g;
-    uint8_t *user;
-    uint8_t *packed;
-    SumCtx cx;
-    uint32_t first_tile;
-    uint32_t unpack;       // direction of this item; only read by the mixed-direction instantiation
-};
-
-enum Direction { DIR_PACK = 0, DIR_UNPACK = 1, DIR_MIXED = 2 };
-
-struct UniformArgs {
-    UniformItem it[kMaxBatch];
-    uint32_t n;
-};
-
-template <bool UNPACK, bool CSUM, bool NTU, bool NTP>
-__device__ __forceinline__ void uniform_tile(const UniformItem &it, uint32_t tile)
-{
-    const ChunkGeom &g = it.g;
-    const TileSpan t = locate_tile(g, tile);
-    const uint64_t left = g.N > t.stream_off ? g.N - t.stream_off : 0;     // tensor bytes from here on
-    const uint32_t data = left < t.len ? uint32_t(left) : t.len;
-    uint8_t *pk = it.packed + t.packed_off;
-    uint64_t acc = copy_span<UNPACK, CSUM, NTU, NTP>(it.user + t.stream_off, pk, data);
-    if (data < t.len) acc += pad_span<UNPACK, CSUM>(pk + data, t.len - data, data);
-    if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, t.expected, it.cx);
-}
-
-// DIR: all items pack, all unpack, or each item says which (a micro-batch stream overlaps the
-// unpack of one message with the pack of the next inside one launch).
-template <int DIR, bool CSUM, bool NTU, bool NTP>
-__global__ __launch_bounds__(kThreads) void k_uniform(UniformArgs a)
-{
-    uint32_t m = 0;
-#pragma unroll
-    for (uint32_t i = 1; i < kMaxBatch; ++i)
-        if (i < a.n && blockIdx.x >= a.it[i].first_tile) m = i;
-    const UniformItem &it = a.it[m];
-    const uint32_t tile = blockIdx.x - it.first_tile;
-    if constexpr (DIR == DIR_MIXED) {
-        if (it.unpack) uniform_tile<true, CSUM, NTU, NTP>(it, tile);
-        else uniform_tile<false, CSUM, NTU, NTP>(it, tile);
-    } else {
-        uniform_tile<DIR == DIR_UNPACK, CSUM, NTU, NTP>(it, tile);
-    }
-}
-
-// ---- contiguous tensors of a multi-tensor message: table driven ---------------------
-template <bool UNPACK, bool CSUM, bool NTU, bool NTP>
-__global__ __launch_bounds__(kThreads) void k_contig(const Tile *__restrict__ tiles,
-                                                     const uint32_t *__restrict__ chunk_tiles, BasePtrs bases,
-                                                     uint8_t *__restrict__ packed, SumCtx cx)
-{
-    const Tile t = tiles[blockIdx.x];
-    uint64_t acc;
-    if (t.kind == K_ZERO)
-        acc = pad_span<UNPACK, CSUM>(packed + t.packed_off, t.n0, uint32_t(t.packed_off));
-    else
-        acc = copy_span<UNPACK, CSUM, NTU, NTP>(bases.p[t.tensor] + t.src_off, packed + t.packed_off, t.n0);
-    if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, chunk_tiles[t.chunk], cx);
-}
-
-// ---- receive and accumulate: the uniform and the table-driven contiguous kernels -----
-template <bool CSUM, bool NTU, bool NTP>
-__global__ __launch_bounds__(kThreads) void k_uniform_accumulate(UniformArgs a)
-{
-    const UniformItem &it = a.it[0];
-    const ChunkGeom &g = it.g;
-    const TileSpan t = locate_tile(g, blockIdx.x);
-    const uint64_t left = g.N > t.stream_off ? g.N - t.stream_off : 0;
-    const uint32_t data = left < t.len ? uint32_t(left) : t.len;
-    uint8_t *pk = it.packed + t.packed_off;
-    uint64_t acc = it.unpack ? accumulate_span<true, CSUM, NTU, NTP>(it.user + t.stream_off, pk, data)
-                             : accumulate_span<false, CSUM, NTU, NTP>(it.user + t.stream_off, pk, data);
-    if (data < t.len) acc += pad_span<true, CSUM>(pk + data, t.len - data, data);
-    if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, t.expected, it.cx);
-}
-
-template <bool CSUM, bool NTU, bool NTP>
-__global__ __launch_bounds__(kThreads) void k_contig_accumulate(const Tile *__restrict__ tiles,
-                                                                const uint32_t *__restrict__ chunk_tiles,
-                                                                BasePtrs bases, ElemKinds kinds,
-                                                                uint8_t *__restrict__ packed, SumCtx cx)
-{
-    const Tile t = tiles[blockIdx.x];
-    uint64_t acc;
-    if (t.kind == K_ZERO)
-        acc = pad_span<true, CSUM>(packed + t.packed_off, t.n0, uint32_t(t.packed_off));
-    else if (kinds.f32[t.tensor])
-        acc = accumulate_span<true, CSUM, NTU, NTP>(bases.p[t.tensor] + t.src_off, packed + t.packed_off, t.n0);
-    else
-        acc = accumulate_span<false, CSUM, NTU, NTP>(bases.p[t.tensor] + t.src_off, packed + t.packed_off, t.n0);
-    if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, chunk_tiles[t.chunk], cx);
-}
-
-// ---- rows: innermost dimension contiguous, outer dimensions strided -------------
-// A 16-byte vector never straddles a run (run length and strides are multiples of 16).
-// Logical byte -> (row, column) and row -> outer indices use multiply-shift division.
-template <bool UNPACK, bool CSUM, bool NTU, bool NTP>
-__global__ __launch_bounds__(kThreads) void k_rows(const Tile *__restrict__ tiles,
-                                                   const uint32_t *__restrict__ chunk_tiles,
-                                                   const TensorDev *__restrict__ tensors, uint32_t tensor_base,
-                                                   BasePtrs bases, uint8_t *__restrict__ packed, SumCtx cx)
-{
-    constexpr bool NTL = UNPACK ? NTP : NTU, NTS = UNPACK ? NTU : NTP;
-    const Tile t = tiles[blockIdx.x];
-    const TensorDev &td = tensors[tensor_base + t.tensor];
-    uint8_t *user = bases.p[t.tensor];
-    uint8_t *pk = packed + t.packed_off;
-    const uint32_t row_bytes = td.row_bytes;
-    const uint64_t row0 = t.src_off / row_bytes;                    // uniform
-    const uint32_t col0 = uint32_t(t.src_off - row0 * row_bytes);
-    const int outer = td.ndim - 1;
-    const uint32_t nvec = t.n0 >> 4;
-    uint64_t acc = 0;
-    for (uint32_t v0 = threadIdx.x; v0 < nvec; v0 += kThreads * kUnroll) {
-        u32x4 r[kUnroll];
-        uint64_t off[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const uint32_t v = v0 + u * kThreads;
-            const uint32_t x = col0 + (v << 4);
-            const uint32_t dr = fast_div(x, td.row_div);
-            uint32_t row = uint32_t(row0) + dr;
-            uint64_t o = x - dr * row_bytes;
-            for (int d = outer - 1; d > 0; --d) {
-                const uint32_t q = fast_div(row, td.dim_div[d]);
-                o += uint64_t(row - q * uint32_t(td.shape[d])) * uint64_t(td.stride_b[d]);
-                row = q;
-            }
-            o += uint64_t(row) * uint64_t(td.stride_b[0]);
-            off[u] = o;
-            if (v < nvec)
-                r[u] = load16<NTL>(reinterpret_cast<const u32x4 *>(UNPACK ? pk + (uint64_t(v) << 4) : user + o));
-        }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const uint32_t v = v0 + u * kThreads;
-            if (v < nvec) {
-                store16<NTS>(reinterpret_cast<u32x4 *>(UNPACK ? user + off[u] : pk + (uint64_t(v) << 4)), r[u]);
-                if constexpr (CSUM) acc += words_sum(r[u]);
-            }
-        }
-    }
-    if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, chunk_tiles[t.chunk], cx);
-}
-
-// ---- transpose: logical inner dimension strided, the one before it contiguous ----
-// A tile is ni x nj elements (at most 128 x 128 for 1- and 2-byte elements, 64 x 64 otherwise).  Storage is read/written along i, the packed
-// stream along j, both coalesced; the swap of roles goes through a padded LDS tile.
-template <typename E>
-__device__ __forceinline__ uint64_t elem_weighted(E v, uint64_t packed_pos)
-{
-    if constexpr (sizeof(E) == 8) {
-        return uint64_t(uint32_t(v)) + uint64_t(uint32_t(uint64_t(v) >> 32));
-    } else {
-        return uint64_t(v) << (8 * (packed_pos & 3));
-    }
-}
-
-// Vector path of the transpose: src has R rows of Cc contiguous elements, dst gets Cc rows of R
-// contiguous elements, dst[c][r] = src[r][c]; R and Cc are multiples of V = 16 / sizeof(E) and
-// every row start is 16-byte aligned.  16-byte global loads along src rows land in LDS rows of
-// T elements whose 16-byte slots are XOR-swizzled with the row group, so that the V element
-// reads that assemble one dst vector (same column, V consecutive rows) and the other lanes'
-// reads of the same instruction fall into distinct banks; then 16-byte global stores along dst
-// rows.  The sum is taken on whichever side is the packed buffer.
-template <typename E, bool SRC_IS_PACKED, bool CSUM>
-__device__ __forceinline__ uint64_t transpose_vec(const uint8_t *src, uint64_t src_pitch, uint32_t R, uint32_t Cc,
-                                                  uint8_t *dst, uint64_t dst_pitch, uint8_t *lds)
-{
-    constexpr uint32_t T = transpose_tile(sizeof(E)), V = 16 / sizeof(E), ROWB = T * sizeof(E), NV = T / V;
-    uint64_t acc = 0;
-    const uint32_t nvs = Cc / V;                           // vectors per src row
-    for (uint32_t v = threadIdx.x; v < R * nvs; v += kThreads) {
-        const uint32_t r = v / nvs, cv = v - r * nvs;
-        // the user tensor is streamed once (non-temporal); the packed side stays cacheable
-        const u32x4 x = load16<!SRC_IS_PACKED>(reinterpret_cast<const u32x4 *>(src + r * src_pitch + cv * 16));
-        if constexpr (CSUM && SRC_IS_PACKED) acc += words_sum(x);
-        *reinterpret_cast<u32x4 *>(lds + r * ROWB + ((cv ^ ((r / V) % NV)) * 16)) = x;
-    }
-    __syncthreads();
-    const uint32_t nvd = R / V;                            // vectors per dst row
-    for (uint32_t v = threadIdx.x; v < Cc * nvd; v += kThreads) {
-        const uint32_t c = v / nvd, dv = v - c * nvd;
-        union {
-            E e[V];
-            u32x4 x;
-        } o;
-#pragma unroll
-        for (uint32_t q = 0; q < V; ++q) {
-            const uint32_t r = dv * V + q;
-            o.e[q] = *reinterpret_cast<const E *>(lds + r * ROWB + (((c / V) ^ ((r / V) % NV)) * 16) + (c % V) * sizeof(E));
-        }
-        if constexpr (CSUM && !SRC_IS_PACKED) acc += words_sum(o.x);
-        store16<SRC_IS_PACKED>(reinterpret_cast<u32x4 *>(dst + c * dst_pitch + dv * 16), o.x);
-    }
-    return acc;
-}
-
-template <typename E, bool UNPACK, bool CSUM>
-__global__ __launch_bounds__(kThreads) void k_transpose(const Tile *__restrict__ tiles,
-                                                        const uint32_t *__restrict__ chunk_tiles, BasePtrs bases,
-                                                        uint8_t *__restrict__ packed, SumCtx cx)
-{
-    constexpr uint32_t T = transpose_tile(sizeof(E)), V = 16 / sizeof(E);
-    __shared__ __attribute__((aligned(16))) uint8_t lds_raw[T * (T + 1) * sizeof(E)];
-    const Tile t = tiles[blockIdx.x];
-    uint8_t *user = bases.p[t.tensor] + t.src_off;
-    uint8_t *pk = packed + t.packed_off;
-    const uint32_t ni = t.n0, nj = t.n1;
-    uint64_t acc = 0;
-    const bool vec_ok = ((ni | nj) % V) == 0 &&
-                        ((reinterpret_cast<uintptr_t>(user) | reinterpret_cast<uintptr_t>(pk) | t.a | t.b) % 16) == 0;
-    if (vec_ok) {
-        // storage: nj rows (pitch a) of ni contiguous elements; packed: ni rows (pitch b) of nj elements
-        if constexpr (!UNPACK) acc = transpose_vec<E, false, CSUM>(user, t.a, nj, ni, pk, t.b, lds_raw);
-        else acc = transpose_vec<E, true, CSUM>(pk, t.b, ni, nj, user, t.a, lds_raw);
-    } else {
-        E(*lds)[T + 1] = reinterpret_cast<E(*)[T + 1]>(lds_raw);
-        const uint32_t tx = threadIdx.x & (T - 1), ty = threadIdx.x / T;
-        constexpr uint32_t TY = kThreads / T;
-        if constexpr (!UNPACK) {
-            if (tx < ni)
-                for (uint32_t j = ty; j < nj; j += TY) lds[j][tx] = *reinterpret_cast<const E *>(user + j * t.a + tx * sizeof(E));
-            __syncthreads();
-            if (tx < nj)
-                for (uint32_t i = ty; i < ni; i += TY) {
-                    const E v = lds[tx][i];
-                    const uint64_t pos = i * t.b + tx * sizeof(E);
-                    *reinterpret_cast<E *>(pk + pos) = v;
-                    if constexpr (CSUM) acc += elem_weighted(v, t.packed_off + pos);
-                }
-        } else {
-            if (tx < nj)
-                for (uint32_t i = ty; i < ni; i += TY) {
-                    const uint64_t pos = i * t.b + tx * sizeof(E);
-                    const E v = *reinterpret_cast<const E *>(pk + pos);
-                    lds[tx][i] = v;
-                    if constexpr (CSUM) acc += elem_weighted(v, t.packed_off + pos);
-                }
-            __syncthreads();
-            if (tx < ni)
-                for (uint32_t j = ty; j < nj; j += TY) *reinterpret_cast<E *>(user + j * t.a + tx * sizeof(E)) = lds[j][tx];
-        }
-    }
-    if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, chunk_tiles[t.chunk], cx);
-}
-
-// ---- generic: any strides, one element at a time -------------------------------
-// One thread per 16 packed bytes; every element's address is recomputed from its
-// logical index.  Slow, and only used for views the other kernels do not take.
-template <typename E, bool UNPACK, bool CSUM>
-__global__ __launch_bounds__(kThreads) void k_generic(const Tile *__restrict__ tiles,
-                                                      const uint32_t *__restrict__ chunk_tiles,
-                                                      const TensorDev *__restrict__ tensors, uint32_t tensor_base,
-                                                      BasePtrs bases, uint8_t *__restrict__ packed, SumCtx cx)
-{
-    const Tile t = tiles[blockIdx.x];
-    uint64_t acc = 0;
-    if (t.kind == K_ZERO) {
-        acc = pad_span<UNPACK, CSUM>(packed + t.packed_off, t.n0, uint32_t(t.packed_off));
-    } else {
-        const TensorDev &td = tensors[tensor_base + t.tensor];
-        uint8_t *user = bases.p[t.tensor];
-        uint8_t *pk = packed + t.packed_off;
-        const uint32_t nel = t.n0 / sizeof(E);
-        constexpr uint32_t PER = 16 / sizeof(E);
-        const uint64_t e0 = t.src_off / sizeof(E);
-        // Coordinates of the tile's first element (the same for every thread).  When every dim fits the
-        // multiply-shift division, an element's coordinates are these plus its number within the tile,
-        // carried from the last dim upwards in 32 bits; otherwise each element is divided out in 64 bits.
-        const bool fast = td.all_div != 0;
-        const int nd = td.ndim;
-        uint32_t base[HXT_MAX_DIMS];
-        {
-            uint64_t idx = e0;
-#pragma unroll
-            for (int d = HXT_MAX_DIMS - 1; d >= 0; --d) {
-                base[d] = 0;
-                if (d < nd && fast) {
-                    const uint64_t q = idx / uint64_t(td.shape[d]);
-                    base[d] = uint32_t(idx - q * uint64_t(td.shape[d]));
-                    idx = q;
-                }
-            }
-        }
-        for (uint32_t v = threadIdx.x; v * PER < nel; v += kThreads) {
-#pragma unroll
-            for (uint32_t j = 0; j < PER; ++j) {
-                const uint32_t el = v * PER + j;
-                if (el < nel) {
-                    uint64_t off = 0;
-                    if (fast) {
-                        uint32_t x = el;                                   // carry into the last dim
-#pragma unroll
-                        for (int d = HXT_MAX_DIMS - 1; d >= 0; --d) {
-                            if (d < nd) {
-                                x += base[d];
-                                if (d > 0) {
-                                    const uint32_t q = fast_div(x, td.dim_div[d]);
-                                    off += uint64_t(x - q * uint32_t(td.shape[d])) * uint64_t(td.stride_b[d]);
-                                    x = q;
-                                } else {
-                                    off += uint64_t(x) * uint64_t(td.stride_b[0]);
-                                }
-                            }
-                        }
-                    } else {
-                        uint64_t idx = e0 + el;
-                        for (int d = nd - 1; d >= 0; --d) {
-                            const uint64_t q = idx / uint64_t(td.shape[d]);
-                            off += (idx - q * uint64_t(td.shape[d])) * uint64_t(td.stride_b[d]);
-                            idx = q;
-                        }
-                    }
-                    E *u = reinterpret_cast<E *>(user + off);
-                    E *p = reinterpret_cast<E *>(pk) + el;
-                    const E val = UNPACK ? *p : *u;
-                    if constexpr (UNPACK) *u = val; else *p = val;
-                    if constexpr (CSUM) acc += elem_weighted(val, uint64_t(el) * sizeof(E));
-                }
-            }
-        }
-    }
-    if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, chunk_tiles[t.chunk], cx);
-}
-
-// ---- stand-alone checksum of packed chunks (closed-form geometry, no table) ----------
-template <bool NTP>
-__global__ __launch_bounds__(kThreads) void k_checksum(ChunkGeom g, const uint8_t *__restrict__ packed, SumCtx cx)
-{
-    const TileSpan t = locate_tile(g, blockIdx.x);
-    const u32x4 *s = reinterpret_cast<const u32x4 *>(packed + t.packed_off);
-    const uint32_t nvec = t.len >> 4;
-    uint64_t acc = 0;
-    for (uint32_t v = threadIdx.x; v < nvec; v += kThreads * kUnroll) {
-        u32x4 r[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u)
-            r[u] = (v + u * kThreads < nvec) ? load16<NTP>(s + v + u * kThreads) : u32x4{0, 0, 0, 0};
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) acc += words_sum(r[u]);
-    }
-    chunk_commit(acc, t.chunk, t.ordinal, t.expected, cx);
-}
-
-// ---- stand-alone strong check: plain sum and position-weighted sum of every chunk -------
-// out[2c] = sum of the chunk's words, out[2c+1] = sum of (j+1) * word j, both mod 2^64.
-// A logical accumulator is a pair of slots (2s: plain sum and arrival count, 2s+1: weighted
-// sum); the ticket is taken after both additions have returned.  Same two-level fan-out as
-// chunk_commit: first-level pairs C*fan, then one second-level pair per chunk.
-__device__ __forceinline__ bool pair_arrive(uint8_t *acc, uint32_t stride, size_t s, unsigned long long &a,
-                                            unsigned long long &b, uint32_t expected)
-{
-    if (expected == 1) return true;
-    Acc *sa = reinterpret_cast<Acc *>(acc + (2 * s) * stride);
-    Acc *sb = reinterpret_cast<Acc *>(acc + (2 * s + 1) * stride);
-    const unsigned long long ra = __hip_atomic_fetch_add(&sa->sum, a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const unsigned long long rb = __hip_atomic_fetch_add(&sb->sum, b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    asm volatile("s_waitcnt vmcnt(0)" ::"v"(uint32_t(ra)), "v"(uint32_t(rb)) : "memory");
-    const uint32_t ticket = __hip_atomic_fetch_add(&sa->cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (ticket != expected - 1) return false;
-    a = __hip_atomic_exchange(&sa->sum, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    b = __hip_atomic_exchange(&sb->sum, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(&sa->cnt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return true;
-}
-
-// Word j of the chunk sits at tile word i = j - j0.  A thread's vectors start at tile words
-// 4 * (tid + 256 * n), n = 0, 1, ...; with S_n the sum of vector n's words and I_n = y + 2z + 3w,
-//   sum (j+1) w_j = (j0 + 4 tid + 1) * sum_n S_n + 1024 * sum_n n S_n + sum_n I_n,
-// so the loop needs additions only (sum_n n S_n is kept as a running suffix sum) and each
-// thread multiplies once.
-//
-// MODE says what the workgroup that completes a chunk does with the two sums:
-//   SUMS   out = uint64[2C]: writes the pair.
-//   SEAL   out = C tags: writes the chunk's 64-byte tag (hxt_chunk_tag_t) at its packed-slot index.
-//   VERIFY out = uint32[C + 1], tags = C tags: compares the tag found at the chunk's slot with the
-//          receiver's own layout, the expected message identity and the recomputed sums, and
-//          writes the bit mask to out[chunk].
-enum Sum2Mode { SUM2_SUMS = 0, SUM2_SEAL = 1, SUM2_VERIFY = 2 };
-
-struct TagWork {
-    const uint8_t *tags;     // VERIFY: the received tags
-    uint64_t seq;            // SEAL: value to write; VERIFY: value expected
-    uint32_t micro_batch;
-};
-
-__device__ __forceinline__ void finish_chunk(int mode, const ChunkGeom &g, const TileSpan &t, uint64_t sum,
-                                             uint64_t wsum, void *out, const TagWork &w)
-{
-    const uint32_t c = t.chunk;
-    if (mode == SUM2_SUMS) {
-        uint64_t *o = static_cast<uint64_t *>(out);
-        o[2 * size_t(c)] = sum;
-        o[2 * size_t(c) + 1] = wsum;
-        return;
-    }
-    const uint32_t slot = fast_div(c, g.div_k), lane = c - slot * g.k;
-    const uint64_t place = uint64_t(lane) * g.q + (lane < g.r ? lane : g.r) + slot;      // packed offset / B
-    const uint64_t padded = (c + 1 == g.C) ? g.L - uint64_t(c) * g.B : g.B;
-    const u32x4 q0{kTagMagic, c, lane, slot};
-    const u32x4 q1{uint32_t(w.seq), uint32_t(w.seq >> 32), w.micro_batch, g.C};
-    const u32x4 q2{uint32_t(padded), uint32_t(padded >> 32), uint32_t(sum), uint32_t(sum >> 32)};
-    const u32x4 q3{uint32_t(wsum), uint32_t(wsum >> 32), 0u, 0u};
-    if (mode == SUM2_SEAL) {
-        u32x4 *tag = reinterpret_cast<u32x4 *>(static_cast<uint8_t *>(out) + place * 64);
-        tag[0] = q0;
-        tag[1] = q1;
-        tag[2] = q2;
-        tag[3] = q3;
-        return;
-    }
-    const u32x4 *tag = reinterpret_cast<const u32x4 *>(w.tags + place * 64);
-    const u32x4 r0 = tag[0], r1 = tag[1], r2 = tag[2], r3 = tag[3];
-    uint32_t m = 0;
-    if (r0.x != q0.x) m |= HXT_TAG_BAD_MAGIC;
-    if (r0.y != q0.y || r0.z != q0.z || r0.w != q0.w || r1.w != q1.w || r2.x != q2.x || r2.y != q2.y) m |= HXT_TAG_BAD_PLACE;
-    if (r1.x != q1.x || r1.y != q1.y) m |= HXT_TAG_BAD_SEQ;
-    if (r1.z != q1.z) m |= HXT_TAG_BAD_MICRO_BATCH;
-    if (r2.z != q2.z || r2.w != q2.w) m |= HXT_TAG_BAD_SUM;
-    if (r3.x != q3.x || r3.y != q3.y) m |= HXT_TAG_BAD_WSUM;
-    if (r3.z != 0 || r3.w != 0) m |= HXT_TAG_BAD_RESERVED;
-    static_cast<uint32_t *>(out)[c] = m;
-}
-
-template <int MODE, bool NTP>
-__global__ __launch_bounds__(kThreads) void k_checksum2(ChunkGeom g, const uint8_t *__restrict__ packed,
-                                                        void *__restrict__ out, uint8_t *acc, uint32_t stride,
-                                                        uint32_t fan, TagWork work)
-{
-    const TileSpan t = locate_tile(g, blockIdx.x);
-    const u32x4 *s = reinterpret_cast<const u32x4 *>(packed + t.packed_off);
-    const uint64_t j0 = (t.stream_off - uint64_t(t.chunk) * g.B) >> 2;
-    const uint32_t nvec = t.len >> 4;
-    uint64_t S = 0, nS = 0, I = 0;          // sum_n S_n, sum_n n*S_n, sum_n I_n
-    uint64_t n0 = 0;                         // n of the current block of vectors
-    for (uint32_t v = threadIdx.x; v < nvec; v += kThreads * kUnroll, n0 += kUnroll) {
-        u32x4 r[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u)
-            r[u] = (v + u * kThreads < nvec) ? load16<NTP>(s + v + u * kThreads) : u32x4{0, 0, 0, 0};
-        uint64_t blockS = 0, blockN = 0;     // this block's sum_u S_u and sum_u u*S_u
-#pragma unroll
-        for (int u = kUnroll - 1; u >= 0; --u) {
-            const uint64_t zw = uint64_t(r[u].z) + r[u].w;
-            const uint64_t yzw = zw + r[u].y;
-            blockN += blockS;                // after the loop: sum_u u * S_u
-            blockS += yzw + r[u].x;
-            I += yzw + zw + r[u].w;
-        }
-        S += blockS;
-        nS += blockN + n0 * blockS;
-    }
-    unsigned long long a = S;
-    unsigned long long b = (j0 + 4ull * threadIdx.x + 1) * S + 4ull * kThreads * nS + I;
-    __shared__ uint64_t part[2][kThreads / 64];
-    for (int o = 32; o > 0; o >>= 1) {
-        a += __shfl_down(a, o, 64);
-        b += __shfl_down(b, o, 64);
-    }
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (lane == 0) {
-        part[0][wave] = a;
-        part[1][wave] = b;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        a = b = 0;
-#pragma unroll
-        for (int w = 0; w < kThreads / 64; ++w) {
-            a += part[0][w];
-            b += part[1][w];
-        }
-        const size_t top = size_t(g.C) * fan + t.chunk;
-        bool last;
-        if (fan == 1 || t.expected < 2 * fan) {
-            last = pair_arrive(acc, stride, top, a, b, t.expected);
-        } else {
-            const uint32_t sub = t.ordinal & (fan - 1);
-            const uint32_t share = t.expected / fan + (sub < (t.expected & (fan - 1)) ? 1u : 0u);
-            last = pair_arrive(acc, stride, size_t(t.chunk) * fan + sub, a, b, share) &&
-                   pair_arrive(acc, stride, top, a, b, fan);
-        }
-        if (last) finish_chunk(MODE, g, t, a, b, out, work);
-    }
-}
-
-// status[C] = number of chunks of status[0 .. C) that were rejected.  One workgroup.
-__global__ __launch_bounds__(kThreads) void k_count_rejected(uint32_t *status, uint32_t C)
-{
-    __shared__ uint32_t part[kThreads / 64];
-    uint32_t n = 0;
-    for (uint32_t c = threadIdx.x; c < C; c += kThreads) n += status[c] != 0;
-    for (int o = 32; o > 0; o >>= 1) n += __shfl_down(n, o, 64);
-    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = n;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t total = 0;
-#pragma unroll
-        for (int w = 0; w < kThreads / 64; ++w) total += part[w];
-        status[C] = total;
-    }
-}
-
-}  // namespace hxt
+#include "hxt_kernels.h"
 
 using namespace hxt;
 
