@@ -307,11 +307,22 @@ int hxt_seal(const hxt_plan_t *plan, const void *packed, uint64_t seq, uint32_t 
  * chunk and checks the tag found at the chunk's slot against the receiver's own plan,
  * the expected seq / micro_batch and the recomputed sums.
  * status: device, num_chunks + 1 uint32; status[c] = OR of hxt_tag_status bits for chunk
- * c, status[num_chunks] = number of chunks with a non-zero mask (written by a second,
- * one-workgroup kernel on the same stream).  The caller reads status back and decides;
+ * c, status[num_chunks] = number of chunks with a non-zero mask (written by the workgroup
+ * that completes the last chunk).  The caller reads status back and decides;
  * nothing is compared on the host by the library. */
 int hxt_verify(const hxt_plan_t *plan, const void *packed, const hxt_chunk_tag_t *tags, uint64_t seq,
                uint32_t micro_batch, uint32_t *status, void *stream);
+
+/* The same, fused into the copies (no extra pass over the message when it is one
+ * contiguous 16-byte aligned tensor; otherwise the two passes run one after the other on
+ * the stream, with identical results): hxt_pack_seal = hxt_pack + hxt_seal,
+ * hxt_unpack_verify = hxt_verify + hxt_unpack.  The destination is written whatever the
+ * verdict; the caller reads `status` before using it.  Arguments as in those calls. */
+int hxt_pack_seal(const hxt_plan_t *plan, const void *const *src, void *packed, uint64_t seq,
+                  uint32_t micro_batch, hxt_chunk_tag_t *tags, void *stream);
+int hxt_unpack_verify(const hxt_plan_t *plan, const void *packed, const hxt_chunk_tag_t *tags,
+                      uint64_t seq, uint32_t micro_batch, void *const *dst, uint32_t *status,
+                      void *stream);
 
 /* ---- diagnostics -------------------------------------------------------------- */
 const char *hxt_strerror(int status);

@@ -387,7 +387,7 @@ int upload(hxt_plan_t &pl)
     pl.acc_stride = slots <= 65536 ? 256 : uint32_t(sizeof(Acc));
     const size_t bytes = slots * pl.acc_stride;
     for (int i = 0; i < OP_COUNT; ++i) {
-        const size_t n = i == OP_CHECKSUM2 ? 2 * bytes : bytes;      // that op keeps pairs of slots
+        const size_t n = i == OP_CHECKSUM2 ? 2 * bytes + 2 * pl.acc_stride : bytes;   // pairs of slots, plus one pair that counts finished chunks
         HXT_HIP(hipMalloc(reinterpret_cast<void **>(&pl.ops[i].acc), n));
         HXT_HIP(hipMemset(pl.ops[i].acc, 0, n));
     }
@@ -952,13 +952,67 @@ int run_sum2(const hxt_plan_t *plan, const void *packed, int mode, void *out, co
     else if (mode == SUM2_SEAL) launch.template operator()<SUM2_SEAL>();
     else launch.template operator()<SUM2_VERIFY>();
     HXT_HIP(hipGetLastError());
-    if (mode == SUM2_VERIFY) {
-        k_count_rejected<<<1, kThreads, 0, st>>>(static_cast<uint32_t *>(out), uint32_t(pl.p.C));
-        HXT_HIP(hipGetLastError());
-    }
     return HXT_OK;
 }
 }  // namespace
+
+extern "C++" {
+namespace {
+// pack + seal (UNPACK = false) or unpack + verify (UNPACK = true).  One pass for a message that is one
+// contiguous, 16-byte aligned tensor; otherwise the copy and the pair-of-sums pass one after the other
+// on the stream, which gives the same bytes, tags and masks.
+template <bool UNPACK>
+int run_copy_tag(const hxt_plan_t *plan, void *const *ptrs, void *packed, void *out, const TagWork &work, void *stream)
+{
+    constexpr int MODE = UNPACK ? SUM2_VERIFY : SUM2_SEAL;
+    int rc = check_common(plan, packed);
+    if (rc != HXT_OK) return rc;
+    if ((rc = check_tensor_pointers(plan->p, ptrs)) != HXT_OK) return rc;
+    if (!out || (UNPACK && !work.tags)) return HXT_EINVAL;
+    if (reinterpret_cast<uintptr_t>(out) % (UNPACK ? 4 : 16)) return HXT_EALIGN;
+    if (UNPACK && reinterpret_cast<uintptr_t>(work.tags) % 16) return HXT_EALIGN;
+    if (UNPACK && !plan->p.all_unpack_safe) return HXT_EOVERLAP;
+    hxt_plan_t &pl = *const_cast<hxt_plan_t *>(plan);
+    const Plan &p = pl.p;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint8_t *pk = static_cast<uint8_t *>(packed);
+    uint8_t *base = p.uniform ? static_cast<uint8_t *>(ptrs[p.uniform_tensor]) : nullptr;
+    if (!p.uniform || reinterpret_cast<uintptr_t>(base) % 16) {
+        if (UNPACK) {                                    // check what arrived, then scatter it
+            if ((rc = run_sum2(plan, packed, MODE, out, work, stream)) != HXT_OK) return rc;
+            return run_copy<true, false>(pl, ptrs, pk, nullptr, st);
+        }
+        if ((rc = run_copy<false, false>(pl, ptrs, pk, nullptr, st)) != HXT_OK) return rc;
+        return run_sum2(plan, packed, MODE, out, work, stream);
+    }
+    SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};
+    SlotsLock lock(g_slots_mu);
+    if ((rc = claim_slots(pl, OP_CHECKSUM2, st, cx, nullptr)) != HXT_OK) return rc;
+    with_hints(packed_nontemporal(p.C * p.B), [&]<bool NTU, bool NTP>() {
+        k_uniform_tag<UNPACK, MODE, NTU, NTP><<<p.geom.ntiles, kThreads, 0, st>>>(p.geom, base, pk, out, cx.acc, cx.stride,
+                                                                                 cx.fan, work);
+    });
+    HXT_HIP(hipGetLastError());
+    return HXT_OK;
+}
+}  // namespace
+}  // extern "C++"
+
+int hxt_pack_seal(const hxt_plan_t *plan, const void *const *src, void *packed, uint64_t seq, uint32_t micro_batch,
+                  hxt_chunk_tag_t *tags, void *stream)
+{
+    if (plan && plan->p.C == 0) return HXT_OK;
+    return run_copy_tag<false>(plan, const_cast<void *const *>(src), packed, tags, TagWork{nullptr, seq, micro_batch},
+                               stream);
+}
+
+int hxt_unpack_verify(const hxt_plan_t *plan, const void *packed, const hxt_chunk_tag_t *tags, uint64_t seq,
+                      uint32_t micro_batch, void *const *dst, uint32_t *status, void *stream)
+{
+    if (plan && plan->p.C == 0) return hxt_verify(plan, packed, tags, seq, micro_batch, status, stream);
+    return run_copy_tag<true>(plan, dst, const_cast<void *>(packed), status,
+                              TagWork{reinterpret_cast<const uint8_t *>(tags), seq, micro_batch}, stream);
+}
 
 int hxt_checksum2(const hxt_plan_t *plan, const void *packed, uint64_t *sums2, void *stream)
 {

@@ -665,7 +665,8 @@ struct TagWork {
 };
 
 __device__ __forceinline__ void finish_chunk(int mode, const ChunkGeom &g, const TileSpan &t, uint64_t sum,
-                                             uint64_t wsum, void *out, const TagWork &w)
+                                             uint64_t wsum, void *out, const TagWork &w, uint8_t *acc, uint32_t stride,
+                                             uint32_t fan)
 {
     const uint32_t c = t.chunk;
     if (mode == SUM2_SUMS) {
@@ -700,6 +701,48 @@ __device__ __forceinline__ void finish_chunk(int mode, const ChunkGeom &g, const
     if (r3.x != q3.x || r3.y != q3.y) m |= HXT_TAG_BAD_WSUM;
     if (r3.z != 0 || r3.w != 0) m |= HXT_TAG_BAD_RESERVED;
     static_cast<uint32_t *>(out)[c] = m;
+    // One more pair of slots, after the chunks' own, counts the chunks that are done and the rejected
+    // ones among them; the chunk that completes the message writes the total to out[C].
+    unsigned long long bad = m != 0, none = 0;
+    if (pair_arrive(acc, stride, size_t(g.C) * (fan + 1), bad, none, g.C)) static_cast<uint32_t *>(out)[g.C] = uint32_t(bad);
+}
+
+// Workgroup-wide: reduces every thread's (a, b), adds the pair to the chunk's accumulators (two-level
+// fan-out as in chunk_commit); the workgroup that completes the chunk finishes it.
+__device__ __forceinline__ void pair_commit(int mode, const ChunkGeom &g, const TileSpan &t, unsigned long long a,
+                                            unsigned long long b, void *out, uint8_t *acc, uint32_t stride,
+                                            uint32_t fan, const TagWork &work)
+{
+    __shared__ uint64_t part[2][kThreads / 64];
+    for (int o = 32; o > 0; o >>= 1) {
+        a += __shfl_down(a, o, 64);
+        b += __shfl_down(b, o, 64);
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) {
+        part[0][wave] = a;
+        part[1][wave] = b;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        a = b = 0;
+#pragma unroll
+        for (int w = 0; w < kThreads / 64; ++w) {
+            a += part[0][w];
+            b += part[1][w];
+        }
+        const size_t top = size_t(g.C) * fan + t.chunk;
+        bool last;
+        if (fan == 1 || t.expected < 2 * fan) {
+            last = pair_arrive(acc, stride, top, a, b, t.expected);
+        } else {
+            const uint32_t sub = t.ordinal & (fan - 1);
+            const uint32_t share = t.expected / fan + (sub < (t.expected & (fan - 1)) ? 1u : 0u);
+            last = pair_arrive(acc, stride, size_t(t.chunk) * fan + sub, a, b, share) &&
+                   pair_arrive(acc, stride, top, a, b, fan);
+        }
+        if (last) finish_chunk(mode, g, t, a, b, out, work, acc, stride, fan);
+    }
 }
 
 template <int MODE, bool NTP>
@@ -730,38 +773,96 @@ __global__ __launch_bounds__(kThreads) void k_checksum2(ChunkGeom g, const uint8
         S += blockS;
         nS += blockN + n0 * blockS;
     }
-    unsigned long long a = S;
-    unsigned long long b = (j0 + 4ull * threadIdx.x + 1) * S + 4ull * kThreads * nS + I;
-    __shared__ uint64_t part[2][kThreads / 64];
-    for (int o = 32; o > 0; o >>= 1) {
-        a += __shfl_down(a, o, 64);
-        b += __shfl_down(b, o, 64);
-    }
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (lane == 0) {
-        part[0][wave] = a;
-        part[1][wave] = b;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        a = b = 0;
+    pair_commit(MODE, g, t, S, (j0 + 4ull * threadIdx.x + 1) * S + 4ull * kThreads * nS + I, out, acc, stride, fan, work);
+}
+
+// ---- pack + seal and unpack + verify in one pass (messages that are one contiguous tensor) ----
+// The copy of k_uniform with both sums of the packed words taken on the way, so that tags cost no
+// extra pass over the message.  Weights are tile-local here (word i of the tile weighs i + 1);
+// the tile's position in its chunk is applied once per workgroup.
+struct Sums2 {
+    uint64_t s, w;
+};
+
+__device__ __forceinline__ void add_vector(Sums2 &acc, u32x4 r, uint32_t v)      // v: vector number in the tile
+{
+    const uint64_t zw = uint64_t(r.z) + r.w, yzw = zw + r.y, sv = yzw + r.x;
+    acc.s += sv;
+    acc.w += uint64_t(4 * v + 1) * sv + (yzw + zw + r.w);
+}
+
+template <bool UNPACK, bool NTU, bool NTP>
+__device__ __forceinline__ Sums2 copy_span2(uint8_t *user, uint8_t *pk, uint32_t bytes)
+{
+    constexpr bool NTL = UNPACK ? NTP : NTU, NTS = UNPACK ? NTU : NTP;
+    const u32x4 *s = reinterpret_cast<const u32x4 *>(UNPACK ? pk : user);
+    u32x4 *d = reinterpret_cast<u32x4 *>(UNPACK ? user : pk);
+    const uint32_t nvec = bytes >> 4;
+    constexpr uint32_t STEP = kThreads * kUnroll;
+    const uint32_t full = nvec / STEP * STEP;
+    Sums2 acc{0, 0};
+    for (uint32_t v = threadIdx.x; v < full; v += STEP) {
+        u32x4 r[kUnroll];
 #pragma unroll
-        for (int w = 0; w < kThreads / 64; ++w) {
-            a += part[0][w];
-            b += part[1][w];
+        for (int u = 0; u < kUnroll; ++u) r[u] = load16<NTL>(s + v + u * kThreads);
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            store16<NTS>(d + v + u * kThreads, r[u]);
+            add_vector(acc, r[u], v + u * kThreads);
         }
-        const size_t top = size_t(g.C) * fan + t.chunk;
-        bool last;
-        if (fan == 1 || t.expected < 2 * fan) {
-            last = pair_arrive(acc, stride, top, a, b, t.expected);
-        } else {
-            const uint32_t sub = t.ordinal & (fan - 1);
-            const uint32_t share = t.expected / fan + (sub < (t.expected & (fan - 1)) ? 1u : 0u);
-            last = pair_arrive(acc, stride, size_t(t.chunk) * fan + sub, a, b, share) &&
-                   pair_arrive(acc, stride, top, a, b, fan);
-        }
-        if (last) finish_chunk(MODE, g, t, a, b, out, work);
     }
+    for (uint32_t v = full + threadIdx.x; v < nvec; v += kThreads) {
+        const u32x4 r = load16<NTL>(s + v);
+        store16<NTS>(d + v, r);
+        add_vector(acc, r, v);
+    }
+    const uint32_t tail = bytes & 15;                    // only at the very end of the tensor
+    if (threadIdx.x < tail) {
+        const uint32_t i = (nvec << 4) + threadIdx.x;
+        const uint8_t b = (UNPACK ? pk : user)[i];
+        (UNPACK ? user : pk)[i] = b;
+        const uint64_t val = uint64_t(b) << (8 * (i & 3));
+        acc.s += val;
+        acc.w += uint64_t((i >> 2) + 1) * val;
+    }
+    return acc;
+}
+
+// Pad bytes after the tensor's last byte, `first` = their byte position in the tile: pack writes zeros
+// (which add nothing to either sum), unpack adds what it finds there.
+template <bool UNPACK>
+__device__ __forceinline__ Sums2 pad_span2(uint8_t *pk, uint32_t bytes, uint32_t first)
+{
+    Sums2 acc{0, 0};
+    for (uint32_t i = threadIdx.x; i < bytes; i += kThreads) {
+        if constexpr (!UNPACK) {
+            pk[i] = 0;
+        } else {
+            const uint32_t pos = first + i;
+            const uint64_t val = uint64_t(pk[i]) << (8 * (pos & 3));
+            acc.s += val;
+            acc.w += uint64_t((pos >> 2) + 1) * val;
+        }
+    }
+    return acc;
+}
+
+template <bool UNPACK, int MODE, bool NTU, bool NTP>
+__global__ __launch_bounds__(kThreads) void k_uniform_tag(ChunkGeom g, uint8_t *user, uint8_t *packed, void *out,
+                                                          uint8_t *acc, uint32_t stride, uint32_t fan, TagWork work)
+{
+    const TileSpan t = locate_tile(g, blockIdx.x);
+    const uint64_t left = g.N > t.stream_off ? g.N - t.stream_off : 0;
+    const uint32_t data = left < t.len ? uint32_t(left) : t.len;
+    uint8_t *pk = packed + t.packed_off;
+    Sums2 sums = copy_span2<UNPACK, NTU, NTP>(user + t.stream_off, pk, data);
+    if (data < t.len) {
+        const Sums2 pad = pad_span2<UNPACK>(pk + data, t.len - data, data);
+        sums.s += pad.s;
+        sums.w += pad.w;
+    }
+    const uint64_t j0 = (t.stream_off - uint64_t(t.chunk) * g.B) >> 2;       // the tile's first word in its chunk
+    pair_commit(MODE, g, t, sums.s, j0 * sums.s + sums.w, out, acc, stride, fan, work);
 }
 
 // status[C] = number of chunks of status[0 .. C) that were rejected.  One workgroup.

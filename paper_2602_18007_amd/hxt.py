@@ -30,7 +30,7 @@ EXPORTS = (
     "hxt_plan_num_tensors", "hxt_plan_chunk_info", "hxt_plan_lane_info", "hxt_plan_tensor_unpack_safe",
     "hxt_plan_tensor_kind", "hxt_pack", "hxt_stage_d2h", "hxt_stage_h2d", "hxt_unpack", "hxt_checksum",
     "hxt_pack_batch", "hxt_unpack_batch", "hxt_exchange_stream", "hxt_unpack_accumulate",
-    "hxt_host_forward", "hxt_stage_hop", "hxt_checksum2", "hxt_seal", "hxt_verify",
+    "hxt_host_forward", "hxt_stage_hop", "hxt_checksum2", "hxt_seal", "hxt_verify", "hxt_pack_seal", "hxt_unpack_verify",
     "hxt_strerror", "hxt_last_hip_error", "hxt_version",
 )
 
@@ -112,6 +112,8 @@ def lib():
             "hxt_checksum2": (i, [vp, vp, u64p, vp]),
             "hxt_seal": (i, [vp, vp, C.c_uint64, C.c_uint32, vp, vp]),
             "hxt_verify": (i, [vp, vp, vp, C.c_uint64, C.c_uint32, vp, vp]),
+            "hxt_pack_seal": (i, [vp, C.POINTER(vp), vp, C.c_uint64, C.c_uint32, vp, vp]),
+            "hxt_unpack_verify": (i, [vp, vp, vp, C.c_uint64, C.c_uint32, C.POINTER(vp), vp, vp]),
             "hxt_host_forward": (i, [vp, i, vp, vp, i]),
             "hxt_stage_hop": (i, [vp, i, vp, vp, i, vp]),
             "hxt_unpack_accumulate": (i, [vp, vp, C.POINTER(vp), u64p, vp]),
@@ -342,6 +344,16 @@ def hxt_seal(plan: Plan, packed, seq: int, micro_batch: int, tags, stream=None) 
 def hxt_verify(plan: Plan, packed, tags, seq: int, micro_batch: int, status, stream=None) -> None:
     _check(lib().hxt_verify(plan.handle, _ptr(packed), _ptr(tags), seq, micro_batch, _ptr(status), _stream(stream)),
            "hxt_verify")
+
+
+def hxt_pack_seal(plan: Plan, src: Sequence, packed, seq: int, micro_batch: int, tags, stream=None) -> None:
+    _check(lib().hxt_pack_seal(plan.handle, _ptr_array(src), _ptr(packed), seq, micro_batch, _ptr(tags),
+                               _stream(stream)), "hxt_pack_seal")
+
+
+def hxt_unpack_verify(plan: Plan, packed, tags, seq: int, micro_batch: int, dst: Sequence, status, stream=None) -> None:
+    _check(lib().hxt_unpack_verify(plan.handle, _ptr(packed), _ptr(tags), seq, micro_batch, _ptr_array(dst),
+                                   _ptr(status), _stream(stream)), "hxt_unpack_verify")
 
 
 def hxt_stage_d2h(plan: Plan, lane: int, packed_dev, host_pinned, stream=None) -> None:

@@ -124,6 +124,63 @@ def test_full_size_boundary_message_round_trip_with_tags():
     assert list(st[:-1]) == [hxt.HXT_TAG_BAD_SEQ] * p.num_chunks and st[-1] == p.num_chunks
 
 
+@pytest.mark.parametrize("case", CASES, ids=lambda c: c.name)
+def test_fused_pack_seal_and_unpack_verify_match_the_oracle(case):
+    """hxt_pack_seal = pack + seal, hxt_unpack_verify = verify + unpack: same bytes, tags and masks as the oracle's
+    composition, in one pass for single contiguous tensors and in two passes for everything else."""
+    m = ho.Message([ho.TensorSpec(tuple(s), tuple(st), e) for (s, st, e) in case.tensors])
+    p = hxt.hxt_plan_multi([(s, st, e) for (s, st, e) in case.tensors], case.k, case.B)
+    raws = make_storages(case, 12)
+    C = p.num_chunks
+    seq, mb = 0x1122334455667788, 9
+    want_packed = ho.pack(m, raws, case.B, case.k, fill=0xA5)
+    want_tags = ho.seal(m, want_packed, case.B, case.k, seq, mb)
+    src = [dev(r) for r in raws]
+    packed = torch.full((max(want_packed.size, 16),), 0xA5, dtype=torch.uint8, device=DEV)
+    tags = torch.full((max(C, 1) * 64,), 0xEE, dtype=torch.uint8, device=DEV)
+    hxt.hxt_pack_seal(p, src, packed, seq, mb, tags)
+    assert np.array_equal(packed.cpu().numpy()[:want_packed.size], want_packed)
+    assert np.array_equal(tags.cpu().numpy()[:C * 64].reshape(C, 64), want_tags)
+    if not all(p.tensor_unpack_safe(t) for t in range(len(case.tensors))):
+        return
+    # receive: intact, then with a stale sequence number, then with a damaged chunk (fault planted on the host)
+    damaged = want_packed.copy()
+    if C:
+        damaged[p.chunk_info(C - 1)["packed_off"] + 5] ^= 0x40
+    for pk, args in ((want_packed, (seq, mb)), (want_packed, (seq - 1, mb)), (damaged, (seq, mb))):
+        dst_o = [np.full(r.size, 0x3C, np.uint8) for r in raws]
+        ho.unpack(m, pk, case.B, case.k, dst_o)
+        want_status = ho.verify(m, pk, want_tags, case.B, case.k, *args)
+        dst = [dev(np.full(r.size, 0x3C, np.uint8)) for r in raws]
+        status = torch.full((C + 1,), 0x7FFFFFFF, dtype=torch.int32, device=DEV)
+        hxt.hxt_unpack_verify(p, dev(pk), dev(want_tags), *args, dst, status)
+        assert np.array_equal(status.cpu().numpy().view(np.uint32), want_status)
+        for a, b in zip(dst_o, dst):
+            assert np.array_equal(b.cpu().numpy()[:a.size], a)
+    if C:
+        assert want_status[C] == 1 and want_status[C - 1] == ho.TAG_BAD_SUM | ho.TAG_BAD_WSUM
+
+
+def test_fused_calls_on_the_full_size_boundary_message():
+    w = wl.llama8b_boundary()
+    m = ho.Message([ho.TensorSpec(t.shape, t.strides, t.esize) for t in w.tensors])
+    p = hxt.hxt_plan_multi([(t.shape, t.strides, t.esize) for t in w.tensors], w.n_lanes, w.chunk_bytes)
+    raws = wl.make_storages(w, 0)
+    src = [torch.from_numpy(r).to(DEV) for r in raws]
+    packed = torch.empty(p.packed_bytes, dtype=torch.uint8, device=DEV)
+    tags = torch.zeros(p.num_chunks * 64, dtype=torch.uint8, device=DEV)
+    dst = [torch.zeros_like(s_) for s_ in src]
+    status = torch.full((p.num_chunks + 1,), -1, dtype=torch.int32, device=DEV)
+    for rep in range(3):                                         # repeated calls leave the accumulators clean
+        hxt.hxt_pack_seal(p, src, packed, 500 + rep, 3, tags)
+        hxt.hxt_unpack_verify(p, packed, tags, 500 + rep, 3, dst, status)
+        assert not status.cpu().numpy().any()
+    want_packed = ho.pack(m, raws, w.chunk_bytes, w.n_lanes, fill=0, nthreads=8)
+    assert np.array_equal(packed.cpu().numpy(), want_packed)
+    assert np.array_equal(tags.cpu().numpy().reshape(-1, 64), ho.seal(m, want_packed, w.chunk_bytes, w.n_lanes, 502, 3))
+    assert torch.equal(src[0], dst[0])
+
+
 def test_empty_message_and_argument_errors():
     p0 = hxt.hxt_plan((0, 16), None, 2, 2, 256)
     status = torch.full((4,), 5, dtype=torch.int32, device=DEV)
@@ -142,4 +199,13 @@ def test_empty_message_and_argument_errors():
     assert L.hxt_verify(p.handle, packed.data_ptr(), tags.data_ptr(), 1, 1, None, None) == hxt.HXT_EINVAL
     assert L.hxt_verify(p.handle, packed.data_ptr(), tags.data_ptr() + 4, 1, 1, st.data_ptr(), None) == hxt.HXT_EALIGN
     assert L.hxt_verify(p.handle, None, tags.data_ptr(), 1, 1, st.data_ptr(), None) == hxt.HXT_EINVAL
+    ptrs = (hxt.C.c_void_p * 1)(packed.data_ptr())
+    assert L.hxt_pack_seal(p.handle, ptrs, packed.data_ptr(), 1, 1, None, None) == hxt.HXT_EINVAL
+    assert L.hxt_pack_seal(p.handle, None, packed.data_ptr(), 1, 1, tags.data_ptr(), None) == hxt.HXT_EINVAL
+    assert L.hxt_pack_seal(p.handle, ptrs, packed.data_ptr(), 1, 1, tags.data_ptr() + 8, None) == hxt.HXT_EALIGN
+    assert L.hxt_unpack_verify(p.handle, packed.data_ptr(), None, 1, 1, ptrs, st.data_ptr(), None) == hxt.HXT_EINVAL
+    assert L.hxt_unpack_verify(p.handle, packed.data_ptr(), tags.data_ptr(), 1, 1, ptrs, None, None) == hxt.HXT_EINVAL
+    hxt.hxt_pack_seal(p0, [buf], buf, 1, 1, buf)
+    hxt.hxt_unpack_verify(p0, buf, buf, 1, 1, [buf], status)
+    assert status.cpu().tolist()[0] == 0
     torch.cuda.synchronize()
