@@ -206,10 +206,19 @@ def test_one_plan_used_from_several_threads_and_streams():
     torch.cuda.synchronize()
     errors = []
 
+    strong = [torch.zeros(iters, p.num_chunks, 2, dtype=torch.int64, device=DEV) for _ in range(n_threads)]
+    plain = [torch.zeros(iters, p.num_chunks, dtype=torch.int64, device=DEV) for _ in range(n_threads)]
+    tags = [torch.zeros(p.num_chunks * 64, dtype=torch.uint8, device=DEV) for _ in range(n_threads)]
+    status = [torch.full((iters, p.num_chunks + 1), -1, dtype=torch.int32, device=DEV) for _ in range(n_threads)]
+
     def work(i):
         try:
             for it in range(iters):
                 hxt.hxt_pack(p, src[i], packed[i], s_send[i][it], streams[i])
+                hxt.hxt_checksum(p, packed[i], plain[i][it], streams[i])
+                hxt.hxt_checksum2(p, packed[i], strong[i][it], streams[i])
+                hxt.hxt_seal(p, packed[i], 1000 * i + it, i, tags[i], streams[i])
+                hxt.hxt_verify(p, packed[i], tags[i], 1000 * i + it, i, status[i][it], streams[i])
                 hxt.hxt_unpack(p, packed[i], dst[i], s_recv[i][it], streams[i])
         except Exception as e:                                   # noqa: BLE001 - reported below
             errors.append(e)
@@ -226,6 +235,10 @@ def test_one_plan_used_from_several_threads_and_streams():
             got = arr.cpu().numpy().view(np.uint64)
             assert (got == want_sums[i][None, :]).all(), "thread %d" % i
         assert all(torch.equal(a, b) for a, b in zip(src[i], dst[i]))
+        want2 = ho.checksum2(m, ho.pack(m, raws[i], case.B, case.k, fill=0), case.B, case.k)
+        assert (plain[i].cpu().numpy().view(np.uint64) == want_sums[i][None, :]).all()
+        assert (strong[i].cpu().numpy().view(np.uint64) == want2[None, :, :]).all()
+        assert not status[i].cpu().numpy().any()
 
 
 def test_batch_calls_equal_single_calls():
