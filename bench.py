@@ -50,6 +50,9 @@ def parse():
                     help="for --workload stream_1f1b: how the packed buffer travels")
     ap.add_argument("--accumulate", action="store_true",
                     help="receive with hxt_unpack_accumulate (old + arriving) instead of hxt_unpack; one call per message")
+    ap.add_argument("--tags", action="store_true",
+                    help="hxt_pack_seal / hxt_unpack_verify (chunk tags written and checked inside the copies) "
+                         "instead of the plain checksums; one call per message")
     ap.add_argument("--no-checksum", action="store_true", help="diagnostic only: copies without checksums")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-staged", action="store_true")
@@ -78,6 +81,8 @@ class MessageSet:
         self.packed = torch.empty(max(plan.packed_bytes, 256), dtype=torch.uint8, device=dev)
         self.send_sums = torch.zeros(max(plan.num_chunks, 1), dtype=torch.int64, device=dev)
         self.recv_sums = torch.zeros_like(self.send_sums)
+        self.tags = torch.zeros(max(plan.num_chunks, 1) * 64, dtype=torch.uint8, device=dev)
+        self.status = torch.zeros(plan.num_chunks + 1, dtype=torch.int32, device=dev)
 
 
 def main():
@@ -112,7 +117,7 @@ def main():
     streams = [torch.cuda.Stream() for _ in range(nmsg)] if a.two_streams else [main_stream] * nmsg
     use_sums = not a.no_checksum
 
-    batched = not (a.two_streams or a.unbatched or a.accumulate)
+    batched = not (a.two_streams or a.unbatched or a.accumulate or a.tags)
     pack_b = [hxt.Batch(plans, [ms.src for ms in S], [ms.packed for ms in S],
                         [ms.send_sums for ms in S] if use_sums else None) for S in sets]
     unpack_b = [hxt.Batch(plans, [ms.dst for ms in S], [ms.packed for ms in S],
@@ -125,6 +130,10 @@ def main():
             return
         for m, ms in enumerate(sets[i % a.sets]):
             st = streams[m]
+            if a.tags:                                   # sequence number = step, micro-batch id = message
+                hxt.hxt_pack_seal(plans[m], ms.src, ms.packed, i, m, ms.tags, st)
+                hxt.hxt_unpack_verify(plans[m], ms.packed, ms.tags, i, m, ms.dst, ms.status, st)
+                continue
             hxt.hxt_pack(plans[m], ms.src, ms.packed, ms.send_sums if use_sums else None, st)
             recv = hxt.hxt_unpack_accumulate if a.accumulate else hxt.hxt_unpack
             recv(plans[m], ms.packed, ms.dst, ms.recv_sums if use_sums else None, st)
@@ -163,7 +172,9 @@ def main():
         for s_, d_ in zip(ms.src, ms.dst):
             if not a.accumulate:
                 assert torch.equal(s_.view(torch.int16), d_.view(torch.int16)), "round trip mismatch in the timed run"
-        if use_sums:
+        if a.tags:
+            assert not bool(ms.status.any()), "a chunk was rejected in the timed run"
+        elif use_sums:
             assert torch.equal(ms.send_sums, ms.recv_sums), "checksum mismatch in the timed run"
 
     # dominant kernel: hxt::k_uniform (pack and unpack instantiations); a launch moves 2N algorithmic bytes
@@ -172,7 +183,7 @@ def main():
     uniform = plan.num_tensors == 1 and plan.tensor_kind(0) == "contig"
     per_launch = min(nmsg, 4) if batched and uniform else 1       # messages served by one launch
     kinds = sorted({plan.tensor_kind(t) for t in range(plan.num_tensors)} - {"none"})
-    kernel = "hxt::k_uniform" if uniform else " + ".join("hxt::k_" + k for k in kinds)
+    kernel = ("hxt::k_uniform_tag" if a.tags else "hxt::k_uniform") if uniform else " + ".join("hxt::k_" + k for k in kinds)
     default_run = w.name == "llama8b_boundary" and batched and use_sums
     launches = 2 * nmsg * a.steps // per_launch
     launch_ms = gpu_ms / (launches if not a.two_streams else launches / nmsg)
@@ -194,7 +205,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "note": w.note, "message_bytes": N, "messages_per_step": nmsg,
                    "n_lanes": w.n_lanes, "chunk_bytes": w.chunk_bytes, "path": "device_direct",
-                   "checksums": "fused send+receive" if use_sums else "off",
+                   "checksums": "chunk tags sealed and verified inside the copies" if a.tags else
+                   ("fused send+receive" if use_sums else "off"),
                    "buffer_sets": a.sets, "cache_state": "cold (rotating sets)" if a.sets * 3 * N * nmsg > 1e9 else
                    "working set %d MiB" % (a.sets * 3 * N * nmsg >> 20),
                    "streams": nmsg if a.two_streams else 1,
