@@ -181,6 +181,26 @@ def test_raw_abi_null_and_dtype_errors():
     assert b"align" in L.hxt_strerror(hxt.HXT_EALIGN)
 
 
+def test_without_a_gpu_the_data_plane_reports_an_error_instead_of_falling_back():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("needs a machine without a GPU")
+    p = hxt.hxt_plan((1000,), None, 1, 2, 256)
+    L = hxt.lib()
+    fake = 1 << 20                                            # never dereferenced: the call fails before any launch
+    ptrs = (C.c_void_p * 1)(fake)
+    assert p.num_chunks == 4                                  # queries still work
+    assert L.hxt_pack(p.handle, ptrs, fake, None, None) == hxt.HXT_EHIP
+    assert L.hxt_unpack(p.handle, fake, ptrs, None, None) == hxt.HXT_EHIP
+    assert L.hxt_checksum(p.handle, fake, fake, None) == hxt.HXT_EHIP
+    assert L.hxt_checksum2(p.handle, fake, fake, None) == hxt.HXT_EHIP
+    assert L.hxt_seal(p.handle, fake, 1, 1, fake, None) == hxt.HXT_EHIP
+    assert L.hxt_pack_seal(p.handle, ptrs, fake, 1, 1, fake, None) == hxt.HXT_EHIP
+    with pytest.raises(hxt.HxtError) as e:
+        hxt.hxt_pack(p, [fake], fake, None)
+    assert e.value.status == hxt.HXT_EHIP and "HIP" in str(e.value)
+
+
 def test_empty_message_calls_are_no_ops():
     p = hxt.hxt_plan((0, 16), None, 2, 2, 256)
     assert (p.message_bytes, p.num_chunks, p.packed_bytes) == (0, 0, 0)
