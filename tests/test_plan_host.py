@@ -201,6 +201,13 @@ def test_without_a_gpu_the_data_plane_reports_an_error_instead_of_falling_back()
     assert e.value.status == hxt.HXT_EHIP and "HIP" in str(e.value)
 
 
+def test_binding_raises_when_the_library_is_not_built(monkeypatch, tmp_path):
+    monkeypatch.setattr(hxt, "_lib", None)
+    monkeypatch.setattr(hxt, "LIB_PATH", str(tmp_path / "libhxt.so"))
+    with pytest.raises(RuntimeError, match="not built"):
+        hxt.hxt_plan((16,), None, 1, 1, 256)
+
+
 def test_empty_message_calls_are_no_ops():
     p = hxt.hxt_plan((0, 16), None, 2, 2, 256)
     assert (p.message_bytes, p.num_chunks, p.packed_bytes) == (0, 0, 0)
