@@ -737,6 +737,31 @@ def test_exchange_stream_device_direct_modes_agree(monkeypatch, mode, n_buffers)
         run_exchange(case, [make_storages(case, 3200 + i) for i in range(nmsg)], "device_direct", n_buffers, streams)
 
 
+@pytest.mark.parametrize("seed", range(3))
+def test_exchange_stream_random_shapes_many_rounds(seed):
+    """The paper's bring-up kept running into hangs (subsection "Engineering Challenges"): stress the ping-pong
+    stream with random message shapes, both paths, 1 to 4 buffer sets, several calls in a row on the same
+    streams and buffers; every call must finish and every byte and checksum must match the oracle."""
+    rng = np.random.default_rng(9100 + seed)
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    done = 0
+    while done < 6:
+        tensors = tuple(random_view(rng) for _ in range(int(rng.integers(1, 4))))
+        if not 0 < sum(storage_bytes(*t) for t in tensors) <= 1_500_000:
+            continue
+        case = Case("xrand%d_%d" % (seed, done), tensors, int(rng.integers(1, 6)), int(rng.choice([256, 4096, 65536])))
+        p = plan_of(case)
+        if not all(p.tensor_unpack_safe(t) for t in range(len(tensors))):
+            continue
+        nmsg = int(rng.integers(2, 9))
+        say("stream of", nmsg, "x", case.tensors, "lanes", case.k, "chunk", case.B)
+        for rounds in range(2):
+            for path in ("device_direct", "cpu_forward"):
+                run_exchange(case, [make_storages(case, 77 * done + i + 1000 * rounds) for i in range(nmsg)], path,
+                             int(rng.integers(1, 5)), streams)
+        done += 1
+
+
 def test_packed_buffer_in_pinned_host_memory():
     # the packed buffer may live in pinned host memory (the kernels then move the bytes over the
     # host link themselves, with no device-side staging buffer)
