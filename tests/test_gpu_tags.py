@@ -181,6 +181,37 @@ def test_fused_calls_on_the_full_size_boundary_message():
     assert torch.equal(src[0], dst[0])
 
 
+def test_a_stale_ping_pong_buffer_is_caught_by_its_tags():
+    """Six micro-batches through two buffer sets; the sender skips message 4 (a lost send), so the receiver finds
+    message 2 still sitting in the buffer: every chunk is rejected for its sequence number and micro-batch id, the
+    sums still agree (the bytes are intact, just the wrong message), and the other messages pass."""
+    case = next(c for c in CASES if c.name == "contig_1MB_ragged")
+    m = ho.Message([ho.TensorSpec(tuple(s_), tuple(st), e) for (s_, st, e) in case.tensors])
+    p = hxt.hxt_plan_multi([(s_, st, e) for (s_, st, e) in case.tensors], case.k, case.B)
+    C = p.num_chunks
+    raws = [make_storages(case, 40 + i) for i in range(6)]
+    src = [[dev(r) for r in rs] for rs in raws]
+    dst = [[torch.zeros_like(t) for t in s_] for s_ in src]
+    packed = [torch.zeros(p.packed_bytes, dtype=torch.uint8, device=DEV) for _ in range(2)]
+    tags = [torch.zeros(C * 64, dtype=torch.uint8, device=DEV) for _ in range(2)]
+    status = torch.full((6, C + 1), -1, dtype=torch.int32, device=DEV)
+    for i in range(6):
+        b = i % 2
+        if i != 4:
+            hxt.hxt_pack_seal(p, src[i], packed[b], 100 + i, i, tags[b])
+        hxt.hxt_unpack_verify(p, packed[b], tags[b], 100 + i, i, dst[i], status[i])
+    st = status.cpu().numpy().view(np.uint32)
+    for i in range(6):
+        if i == 4:
+            assert list(st[i, :C]) == [hxt.HXT_TAG_BAD_SEQ | hxt.HXT_TAG_BAD_MICRO_BATCH] * C and st[i, C] == C
+            assert torch.equal(dst[4][0], src[2][0])                 # what was delivered is message 2 again
+            want = ho.verify(m, ho.pack(m, raws[2], case.B, case.k), ho.seal(m, ho.pack(m, raws[2], case.B, case.k),
+                                                                               case.B, case.k, 102, 2), case.B, case.k, 104, 4)
+            assert np.array_equal(st[i], want)
+        else:
+            assert not st[i].any() and torch.equal(dst[i][0], src[i][0])
+
+
 def test_empty_message_and_argument_errors():
     p0 = hxt.hxt_plan((0, 16), None, 2, 2, 256)
     status = torch.full((4,), 5, dtype=torch.int32, device=DEV)
