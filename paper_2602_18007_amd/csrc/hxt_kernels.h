@@ -457,9 +457,22 @@ __device__ __forceinline__ uint64_t transpose_vec(const uint8_t *src, uint64_t s
         *reinterpret_cast<u32x4 *>(lds + r * ROWB + ((cv ^ ((r / V) % NV)) * 16)) = x;
     }
     __syncthreads();
+    // dst vectors are handed out with 8 consecutive vectors of one dst row (128 contiguous bytes) fastest,
+    // then the dst row: a half-wave then reads 8 row groups x 4 columns from LDS, which the swizzle spreads
+    // over all 32 banks (16 row groups of one column pair would hit each bank twice).
     const uint32_t nvd = R / V;                            // vectors per dst row
+    const uint32_t full8 = nvd >> 3, rem = nvd & 7, main = Cc * 8 * full8;
     for (uint32_t v = threadIdx.x; v < Cc * nvd; v += kThreads) {
-        const uint32_t c = v / nvd, dv = v - c * nvd;
+        uint32_t c, dv;
+        if (v < main) {
+            const uint32_t b = v / (Cc * 8), w = v - b * (Cc * 8);
+            c = w >> 3;
+            dv = b * 8 + (w & 7);
+        } else {
+            const uint32_t w = v - main;
+            c = w / rem;
+            dv = full8 * 8 + (w - c * rem);
+        }
         union {
             E e[V];
             u32x4 x;
