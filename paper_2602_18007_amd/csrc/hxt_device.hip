@@ -1070,6 +1070,6 @@ const char *hxt_strerror(int status)
 
 int hxt_last_hip_error(void) { return g_last_hip; }
 
-const char *hxt_version(void) { return "hxt 0.2 (gfx950)"; }
+const char *hxt_version(void) { return "hxt 0.3 (gfx950)"; }
 
 }  // extern "C"
