@@ -35,9 +35,10 @@ struct ElemKinds {                     // per tensor of a launch group: 1 = 32-b
     uint8_t f32[kMaxGroupTensors];
 };
 
-// Per-chunk accumulator of a checksum in flight.  One per chunk and per operation
-// (pack, unpack, stand-alone checksum), kAccStride bytes apart so that neighbouring
-// chunks' atomics land in different memory channels.  Always zero between kernels.
+// Accumulator slot of a checksum in flight.  Every operation of a plan (pack, unpack, the
+// stand-alone passes, ...) owns its own set of slots, SumCtx::stride bytes apart (256 unless the
+// plan has very many chunks) so that neighbouring slots' atomics land in different memory
+// channels.  Always zero between kernels.
 struct Acc {
     unsigned long long sum;
     uint32_t cnt;
