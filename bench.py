@@ -278,8 +278,16 @@ def stream_bench(torch, hxt, w, a):
     s_send = torch.zeros((nmsg, C), dtype=torch.int64, device=dev)
     s_recv = torch.zeros_like(s_send)
     streams = [torch.cuda.Stream() for _ in range(3)]
+    tag_kw = {}
+    if a.tags:                                         # chunk tags instead of the plain checksums
+        tag_dev = lambda: [torch.zeros(C * 64, dtype=torch.uint8, device=dev) for _ in range(2)]
+        status = torch.zeros((nmsg, C + 1), dtype=torch.int32, device=dev)
+        tag_kw = dict(tags_send=tag_dev(), tags_recv=tag_dev() if fwd else None,
+                      tags_pinned=[torch.zeros(C * 64, dtype=torch.uint8).pin_memory() for _ in range(2)] if fwd else None,
+                      status=status, seq_base=1)
+    plain = not (a.no_checksum or a.tags)
     x = hxt.Exchange(src, dst, send, hxt.HXT_CPU_FORWARD if fwd else hxt.HXT_DEVICE_DIRECT, recv, host,
-                     None if a.no_checksum else s_send, None if a.no_checksum else s_recv, *streams)
+                     s_send if plain else None, s_recv if plain else None, *streams, **tag_kw)
     steps = a.steps if not fwd else max(1, min(a.steps, 20))
     warm = a.warmup if not fwd else max(1, min(a.warmup, 2))
 
@@ -298,7 +306,9 @@ def stream_bench(torch, hxt, w, a):
     sec = time.perf_counter() - t0
     for s_, d_ in zip(src, dst):
         assert torch.equal(s_[0].view(torch.int16), d_[0].view(torch.int16)), "round trip mismatch"
-    if not a.no_checksum:
+    if a.tags:
+        assert not bool(status.any()), "a chunk was rejected in the timed run"
+    elif not a.no_checksum:
         assert torch.equal(s_send, s_recv)
     gbps = 4 * N * nmsg * steps / sec / 1e9
     out = {"metric": METRIC, "value": round(gbps, 1), "value_of": "pack+unpack GB/s", "unit": "GB/s", "n_gpus": 1, "steps": steps,
@@ -306,7 +316,8 @@ def stream_bench(torch, hxt, w, a):
            "vs_baseline": None, "dtype": "u32", "data": "synthetic",
            "config": {"workload": w.name, "note": w.note, "message_bytes": N, "messages_per_step": nmsg,
                       "n_lanes": w.n_lanes, "chunk_bytes": w.chunk_bytes, "path": a.path, "buffer_sets": 2,
-                      "streams": 3, "checksums": "off" if a.no_checksum else "fused send+receive",
+                      "streams": 3, "checksums": "chunk tags sealed and verified inside the copies" if a.tags else
+                      ("off" if a.no_checksum else "fused send+receive"),
                       "cache_state": "cold (%d MiB of sources per pass)" % (N * nmsg >> 20)},
            "pct_hbm_peak": round(100 * gbps / HBM_PEAK_GBPS, 2),
            "us_per_micro_batch": round(sec / steps / nmsg * 1e6, 2)}

@@ -250,6 +250,15 @@ typedef struct {
     void *stream_pack;
     void *stream_stage;
     void *stream_unpack;
+    /* Optional chunk tags (see hxt_seal / hxt_verify below): tags_send == NULL = none.  With
+     * tags, message i is sealed with seq = seq_base + i and micro_batch = i inside its pack, the
+     * tags travel with the message (through tags_pinned on the CPU-forwarding path) and are
+     * verified inside its unpack; send_sums / recv_sums must then be NULL (HXT_EINVAL). */
+    void *const *tags_send;    /* [n_buffers] device, num_chunks * 64 bytes, 16-byte aligned */
+    void *const *tags_recv;    /* [n_buffers] device (CPU forwarding) */
+    void *const *tags_pinned;  /* [n_buffers] pinned host (CPU forwarding) */
+    uint32_t *status;          /* device, n_messages * (num_chunks + 1): hxt_verify's result per message */
+    uint64_t seq_base;
 } hxt_exchange_t;
 
 int hxt_exchange_stream(const hxt_plan_t *plan, const hxt_exchange_t *x);

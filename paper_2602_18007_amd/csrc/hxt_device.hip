@@ -22,9 +22,15 @@
 using namespace hxt;
 
 // The plan: host tables, their device copies, and the checksum accumulators.
-// OP_PACK_B / OP_UNPACK_B: a second set of accumulators, for the second of two message chains that
-// run side by side on two streams (see chained_direct_stream).
-enum Op { OP_PACK = 0, OP_UNPACK = 1, OP_CHECKSUM = 2, OP_CHECKSUM2 = 3, OP_PACK_B = 4, OP_UNPACK_B = 5, OP_COUNT = 6 };
+// Sender-side and receiver-side passes have separate sets (a pack on one stream and an unpack on another
+// then never wait for each other); the _B sets serve the second of two message chains that run side by
+// side on two streams (see chained_direct_stream).  SUM2 = the pair-of-sums passes: SEND for hxt_checksum2,
+// hxt_seal and hxt_pack_seal, RECV for hxt_verify and hxt_unpack_verify.
+enum Op {
+    OP_PACK = 0, OP_UNPACK = 1, OP_CHECKSUM = 2, OP_SUM2_SEND = 3, OP_SUM2_RECV = 4,
+    OP_PACK_B = 5, OP_UNPACK_B = 6, OP_SUM2_SEND_B = 7, OP_SUM2_RECV_B = 8, OP_COUNT = 9
+};
+inline bool op_keeps_pairs(int op) { return op == OP_SUM2_SEND || op == OP_SUM2_RECV || op == OP_SUM2_SEND_B || op == OP_SUM2_RECV_B; }
 
 struct OpState {              // accumulator slots of one operation and who used them last
     uint8_t *acc = nullptr;
@@ -387,7 +393,7 @@ int upload(hxt_plan_t &pl)
     pl.acc_stride = slots <= 65536 ? 256 : uint32_t(sizeof(Acc));
     const size_t bytes = slots * pl.acc_stride;
     for (int i = 0; i < OP_COUNT; ++i) {
-        const size_t n = i == OP_CHECKSUM2 ? 2 * bytes + 2 * pl.acc_stride : bytes;   // pairs of slots, plus one pair that counts finished chunks
+        const size_t n = op_keeps_pairs(i) ? 2 * bytes + 2 * pl.acc_stride : bytes;   // pairs of slots, plus one pair that counts finished chunks
         HXT_HIP(hipMalloc(reinterpret_cast<void **>(&pl.ops[i].acc), n));
         HXT_HIP(hipMemset(pl.ops[i].acc, 0, n));
     }
@@ -505,6 +511,73 @@ int run_batch(int n, const hxt_plan_t *const *plans, void *const *const *tensors
     return HXT_OK;
 }
 
+// The three users of the pair-of-sums pass.
+int run_sum2(const hxt_plan_t *plan, const void *packed, int mode, void *out, const TagWork &work, void *stream,
+             int chain = 0)
+{
+    int rc = check_common(plan, packed);
+    if (rc != HXT_OK) return rc;
+    if (!out || (mode == SUM2_VERIFY && !work.tags)) return HXT_EINVAL;
+    const uintptr_t align = mode == SUM2_SEAL ? 16 : (mode == SUM2_VERIFY ? 4 : 8);
+    if (reinterpret_cast<uintptr_t>(out) % align) return HXT_EALIGN;
+    if (mode == SUM2_VERIFY && reinterpret_cast<uintptr_t>(work.tags) % 16) return HXT_EALIGN;
+    hxt_plan_t &pl = *const_cast<hxt_plan_t *>(plan);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};          // callers have dealt with the empty message
+    SlotsLock lock(g_slots_mu);
+    if ((rc = claim_slots(pl, mode == SUM2_VERIFY ? (chain ? OP_SUM2_RECV_B : OP_SUM2_RECV) : (chain ? OP_SUM2_SEND_B : OP_SUM2_SEND), st, cx, nullptr)) != HXT_OK) return rc;
+    const uint8_t *pk = static_cast<const uint8_t *>(packed);
+    const bool ntp = packed_nontemporal(pl.p.C * pl.p.B);
+    auto launch = [&]<int MODE>() {
+        if (ntp) k_checksum2<MODE, true><<<pl.p.geom.ntiles, kThreads, 0, st>>>(pl.p.geom, pk, out, cx.acc, cx.stride, cx.fan, work);
+        else k_checksum2<MODE, false><<<pl.p.geom.ntiles, kThreads, 0, st>>>(pl.p.geom, pk, out, cx.acc, cx.stride, cx.fan, work);
+    };
+    if (mode == SUM2_SUMS) launch.template operator()<SUM2_SUMS>();
+    else if (mode == SUM2_SEAL) launch.template operator()<SUM2_SEAL>();
+    else launch.template operator()<SUM2_VERIFY>();
+    HXT_HIP(hipGetLastError());
+    return HXT_OK;
+}
+
+// pack + seal (UNPACK = false) or unpack + verify (UNPACK = true).  One pass for a message that is one
+// contiguous, 16-byte aligned tensor; otherwise the copy and the pair-of-sums pass one after the other
+// on the stream, which gives the same bytes, tags and masks.
+template <bool UNPACK>
+int run_copy_tag(const hxt_plan_t *plan, void *const *ptrs, void *packed, void *out, const TagWork &work, void *stream,
+                 int chain = 0)
+{
+    constexpr int MODE = UNPACK ? SUM2_VERIFY : SUM2_SEAL;
+    int rc = check_common(plan, packed);
+    if (rc != HXT_OK) return rc;
+    if ((rc = check_tensor_pointers(plan->p, ptrs)) != HXT_OK) return rc;
+    if (!out || (UNPACK && !work.tags)) return HXT_EINVAL;
+    if (reinterpret_cast<uintptr_t>(out) % (UNPACK ? 4 : 16)) return HXT_EALIGN;
+    if (UNPACK && reinterpret_cast<uintptr_t>(work.tags) % 16) return HXT_EALIGN;
+    if (UNPACK && !plan->p.all_unpack_safe) return HXT_EOVERLAP;
+    hxt_plan_t &pl = *const_cast<hxt_plan_t *>(plan);
+    const Plan &p = pl.p;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint8_t *pk = static_cast<uint8_t *>(packed);
+    uint8_t *base = p.uniform ? static_cast<uint8_t *>(ptrs[p.uniform_tensor]) : nullptr;
+    if (!p.uniform || reinterpret_cast<uintptr_t>(base) % 16) {
+        if (UNPACK) {                                    // check what arrived, then scatter it
+            if ((rc = run_sum2(plan, packed, MODE, out, work, stream, chain)) != HXT_OK) return rc;
+            return run_copy<true, false>(pl, ptrs, pk, nullptr, st, chain);
+        }
+        if ((rc = run_copy<false, false>(pl, ptrs, pk, nullptr, st, chain)) != HXT_OK) return rc;
+        return run_sum2(plan, packed, MODE, out, work, stream, chain);
+    }
+    SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};
+    SlotsLock lock(g_slots_mu);
+    if ((rc = claim_slots(pl, UNPACK ? (chain ? OP_SUM2_RECV_B : OP_SUM2_RECV) : (chain ? OP_SUM2_SEND_B : OP_SUM2_SEND), st, cx, nullptr)) != HXT_OK) return rc;
+    with_hints(packed_nontemporal(p.C * p.B), [&]<bool NTU, bool NTP>() {
+        k_uniform_tag<UNPACK, MODE, NTU, NTP><<<p.geom.ntiles, kThreads, 0, st>>>(p.geom, base, pk, out, cx.acc, cx.stride,
+                                                                                 cx.fan, work);
+    });
+    HXT_HIP(hipGetLastError());
+    return HXT_OK;
+}
+
 // Device-direct micro-batch stream for single-tensor messages, without cross-stream handshakes:
 // launch k unpacks message k-1 and packs message k (different buffer sets, independent work, so
 // the two overlap inside the launch and fill each other's ramp-up and tail); consecutive launches
@@ -571,8 +644,19 @@ int chained_direct_stream(hxt_plan_t &pl, const hxt_exchange_t &x, hipStream_t a
         void *const *src = const_cast<void *const *>(x.src + i * T);
         uint64_t *s_send = x.send_sums ? x.send_sums + size_t(i) * p.C : nullptr;
         uint64_t *s_recv = x.recv_sums ? x.recv_sums + size_t(i) * p.C : nullptr;
-        int rc = s_send ? run_copy<false, true>(pl, src, buf, s_send, st, chain)
-                        : run_copy<false, false>(pl, src, buf, nullptr, st, chain);
+        int rc;
+        if (x.tags_send) {                               // sealed and verified inside the copies
+            void *tags = x.tags_send[i % x.n_buffers];
+            const uint64_t seq = x.seq_base + uint64_t(i);
+            rc = run_copy_tag<false>(&pl, src, buf, tags, TagWork{nullptr, seq, uint32_t(i)}, st, chain);
+            if (rc != HXT_OK) return rc;
+            rc = run_copy_tag<true>(&pl, x.dst + i * T, buf, x.status + size_t(i) * (p.C + 1),
+                                    TagWork{static_cast<const uint8_t *>(tags), seq, uint32_t(i)}, st, chain);
+            if (rc != HXT_OK) return rc;
+            continue;
+        }
+        rc = s_send ? run_copy<false, true>(pl, src, buf, s_send, st, chain)
+                    : run_copy<false, false>(pl, src, buf, nullptr, st, chain);
         if (rc != HXT_OK) return rc;
         rc = s_recv ? run_copy<true, true>(pl, x.dst + i * T, buf, s_recv, st, chain)
                     : run_copy<true, false>(pl, x.dst + i * T, buf, nullptr, st, chain);
@@ -832,6 +916,17 @@ int hxt_exchange_stream(const hxt_plan_t *plan, const hxt_exchange_t *x)
             if (reinterpret_cast<uintptr_t>(x->host_pinned[b]) % HXT_ALIGN) return HXT_EALIGN;
         }
     }
+    const bool tagged = x->tags_send != nullptr;
+    if (tagged) {
+        if (!x->status || x->send_sums || x->recv_sums || (fwd && (!x->tags_recv || !x->tags_pinned))) return HXT_EINVAL;
+        if (reinterpret_cast<uintptr_t>(x->status) % 4) return HXT_EALIGN;
+        for (int b = 0; b < x->n_buffers; ++b) {
+            if (!x->tags_send[b] || (fwd && (!x->tags_recv[b] || !x->tags_pinned[b]))) return HXT_EINVAL;
+            if (reinterpret_cast<uintptr_t>(x->tags_send[b]) % 16 ||
+                (fwd && (reinterpret_cast<uintptr_t>(x->tags_recv[b]) % 16 || reinterpret_cast<uintptr_t>(x->tags_pinned[b]) % 16)))
+                return HXT_EALIGN;
+        }
+    }
     if (!p.all_unpack_safe) return HXT_EOVERLAP;
     for (int i = 0; i < x->n_messages; ++i) {
         if ((rc = check_tensor_pointers(p, const_cast<void *const *>(x->src + i * T))) != HXT_OK) return rc;
@@ -844,7 +939,7 @@ int hxt_exchange_stream(const hxt_plan_t *plan, const hxt_exchange_t *x)
     const int mode = env_int("HXT_STREAM_MODE", 2);
     if (!fwd && mode == 2 && x->n_buffers % 2 == 0 && sp != su)
         return chained_direct_stream(*const_cast<hxt_plan_t *>(plan), *x, sp, su, ss);
-    if (!fwd && mode >= 1 && x->n_buffers >= 2 && p.uniform && !x->send_sums == !x->recv_sums) {
+    if (!fwd && !tagged && mode >= 1 && x->n_buffers >= 2 && p.uniform && !x->send_sums == !x->recv_sums) {
         bool aligned = true;
         for (int i = 0; i < x->n_messages; ++i)
             aligned = aligned && reinterpret_cast<uintptr_t>(x->src[i * T + p.uniform_tensor]) % 16 == 0 &&
@@ -852,8 +947,8 @@ int hxt_exchange_stream(const hxt_plan_t *plan, const hxt_exchange_t *x)
         if (aligned) return fused_direct_stream(*const_cast<hxt_plan_t *>(plan), *x, sp, ss, su);
     }
     // per buffer set: packed (pack done), drained (send buffer may be rewritten), staged (host copy
-    // complete), landed (host buffer may be rewritten)
-    enum { PACKED, DRAINED, STAGED, LANDED, KINDS };
+    // complete), landed (host buffer may be rewritten), tags read (pinned tag buffer may be rewritten)
+    enum { PACKED, DRAINED, STAGED, LANDED, TAGS_READ, KINDS };
     const int nb = x->n_buffers;
     std::vector<hipEvent_t> ev(size_t(nb) * KINDS, nullptr);
     auto at = [&](int kind, int b) -> hipEvent_t & { return ev[size_t(b) * KINDS + kind]; };
@@ -872,15 +967,30 @@ int hxt_exchange_stream(const hxt_plan_t *plan, const hxt_exchange_t *x)
         if (e != hipSuccess && rc == HXT_OK) rc = hip_fail(e);
         return e == hipSuccess;
     };
+    const uint32_t tag_vecs = uint32_t(p.C * (sizeof(hxt_chunk_tag_t) / 16));
+    auto copy_tags = [&](void *to, const void *from, hipStream_t st) {
+        k_copy_tags<<<std::min<uint32_t>((tag_vecs + kThreads - 1) / kThreads, 64u), kThreads, 0, st>>>(
+            static_cast<u32x4 *>(to), static_cast<const u32x4 *>(from), tag_vecs);
+        return hip(hipGetLastError());
+    };
     const int drain_every = env_int("HXT_DRAIN_EVERY", 12);
     for (int i = 0; i < x->n_messages && rc == HXT_OK; ++i) {
         const int b = i % nb;
         uint64_t *s_send = x->send_sums ? x->send_sums + size_t(i) * p.C : nullptr;
         uint64_t *s_recv = x->recv_sums ? x->recv_sums + size_t(i) * p.C : nullptr;
+        const uint64_t seq = x->seq_base + uint64_t(i);
         if (i >= nb && !hip(hipStreamWaitEvent(sp, at(DRAINED, b), 0))) break;
-        if ((rc = hxt_pack(plan, x->src + i * T, x->packed_send[b], s_send, sp)) != HXT_OK) break;
+        if (i >= nb && fwd && tagged && !hip(hipStreamWaitEvent(sp, at(TAGS_READ, b), 0))) break;
+        rc = tagged ? hxt_pack_seal(plan, x->src + i * T, x->packed_send[b], seq, uint32_t(i),
+                                    static_cast<hxt_chunk_tag_t *>(x->tags_send[b]), sp)
+                    : hxt_pack(plan, x->src + i * T, x->packed_send[b], s_send, sp);
+        if (rc != HXT_OK) break;
+        // The tags go to the pinned buffer from the pack stream, by a small kernel, so that the staging stream
+        // carries nothing but the large device-to-host copies.
+        if (fwd && tagged && !copy_tags(x->tags_pinned[b], x->tags_send[b], sp)) break;
         if (!hip(hipEventRecord(at(PACKED, b), sp))) break;
         const void *arrived = x->packed_send[b];
+        const void *arrived_tags = tagged ? x->tags_send[b] : nullptr;
         if (fwd) {
             if (!hip(hipStreamWaitEvent(ss, at(PACKED, b), 0))) break;
             if (i >= nb && !hip(hipStreamWaitEvent(ss, at(LANDED, b), 0))) break;
@@ -889,12 +999,17 @@ int hxt_exchange_stream(const hxt_plan_t *plan, const hxt_exchange_t *x)
             if (!hip(hipEventRecord(at(DRAINED, b), ss))) break;
             if (!hip(hipStreamWaitEvent(su, at(STAGED, b), 0))) break;
             if ((rc = hxt_stage_h2d(plan, -1, x->host_pinned[b], x->packed_recv[b], su)) != HXT_OK) break;
-            if (!hip(hipEventRecord(at(LANDED, b), su))) break;
+            if (!hip(hipEventRecord(at(LANDED, b), su))) break;       // straight after the copy: the next device-to-host copy waits on it
+            if (tagged && (!copy_tags(x->tags_recv[b], x->tags_pinned[b], su) || !hip(hipEventRecord(at(TAGS_READ, b), su)))) break;
             arrived = x->packed_recv[b];
+            if (tagged) arrived_tags = x->tags_recv[b];
         } else {
             if (!hip(hipStreamWaitEvent(su, at(PACKED, b), 0))) break;
         }
-        if ((rc = hxt_unpack(plan, arrived, x->dst + i * T, s_recv, su)) != HXT_OK) break;
+        rc = tagged ? hxt_unpack_verify(plan, arrived, static_cast<const hxt_chunk_tag_t *>(arrived_tags), seq, uint32_t(i),
+                                        x->dst + i * T, x->status + size_t(i) * (p.C + 1), su)
+                    : hxt_unpack(plan, arrived, x->dst + i * T, s_recv, su);
+        if (rc != HXT_OK) break;
         if (!fwd && !hip(hipEventRecord(at(DRAINED, b), su))) break;
         // CPU forwarding: with more than about 16 messages' worth of copies and event waits outstanding the
         // runtime stops overlapping the two copy directions (measured: 760 us per 32 MiB message up to 16
@@ -927,76 +1042,7 @@ int hxt_checksum(const hxt_plan_t *plan, const void *packed, uint64_t *sums, voi
     return HXT_OK;
 }
 
-namespace {
-// The three users of the pair-of-sums pass.
-int run_sum2(const hxt_plan_t *plan, const void *packed, int mode, void *out, const TagWork &work, void *stream)
-{
-    int rc = check_common(plan, packed);
-    if (rc != HXT_OK) return rc;
-    if (!out || (mode == SUM2_VERIFY && !work.tags)) return HXT_EINVAL;
-    const uintptr_t align = mode == SUM2_SEAL ? 16 : (mode == SUM2_VERIFY ? 4 : 8);
-    if (reinterpret_cast<uintptr_t>(out) % align) return HXT_EALIGN;
-    if (mode == SUM2_VERIFY && reinterpret_cast<uintptr_t>(work.tags) % 16) return HXT_EALIGN;
-    hxt_plan_t &pl = *const_cast<hxt_plan_t *>(plan);
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};          // callers have dealt with the empty message
-    SlotsLock lock(g_slots_mu);
-    if ((rc = claim_slots(pl, OP_CHECKSUM2, st, cx, nullptr)) != HXT_OK) return rc;
-    const uint8_t *pk = static_cast<const uint8_t *>(packed);
-    const bool ntp = packed_nontemporal(pl.p.C * pl.p.B);
-    auto launch = [&]<int MODE>() {
-        if (ntp) k_checksum2<MODE, true><<<pl.p.geom.ntiles, kThreads, 0, st>>>(pl.p.geom, pk, out, cx.acc, cx.stride, cx.fan, work);
-        else k_checksum2<MODE, false><<<pl.p.geom.ntiles, kThreads, 0, st>>>(pl.p.geom, pk, out, cx.acc, cx.stride, cx.fan, work);
-    };
-    if (mode == SUM2_SUMS) launch.template operator()<SUM2_SUMS>();
-    else if (mode == SUM2_SEAL) launch.template operator()<SUM2_SEAL>();
-    else launch.template operator()<SUM2_VERIFY>();
-    HXT_HIP(hipGetLastError());
-    return HXT_OK;
-}
-}  // namespace
 
-extern "C++" {
-namespace {
-// pack + seal (UNPACK = false) or unpack + verify (UNPACK = true).  One pass for a message that is one
-// contiguous, 16-byte aligned tensor; otherwise the copy and the pair-of-sums pass one after the other
-// on the stream, which gives the same bytes, tags and masks.
-template <bool UNPACK>
-int run_copy_tag(const hxt_plan_t *plan, void *const *ptrs, void *packed, void *out, const TagWork &work, void *stream)
-{
-    constexpr int MODE = UNPACK ? SUM2_VERIFY : SUM2_SEAL;
-    int rc = check_common(plan, packed);
-    if (rc != HXT_OK) return rc;
-    if ((rc = check_tensor_pointers(plan->p, ptrs)) != HXT_OK) return rc;
-    if (!out || (UNPACK && !work.tags)) return HXT_EINVAL;
-    if (reinterpret_cast<uintptr_t>(out) % (UNPACK ? 4 : 16)) return HXT_EALIGN;
-    if (UNPACK && reinterpret_cast<uintptr_t>(work.tags) % 16) return HXT_EALIGN;
-    if (UNPACK && !plan->p.all_unpack_safe) return HXT_EOVERLAP;
-    hxt_plan_t &pl = *const_cast<hxt_plan_t *>(plan);
-    const Plan &p = pl.p;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    uint8_t *pk = static_cast<uint8_t *>(packed);
-    uint8_t *base = p.uniform ? static_cast<uint8_t *>(ptrs[p.uniform_tensor]) : nullptr;
-    if (!p.uniform || reinterpret_cast<uintptr_t>(base) % 16) {
-        if (UNPACK) {                                    // check what arrived, then scatter it
-            if ((rc = run_sum2(plan, packed, MODE, out, work, stream)) != HXT_OK) return rc;
-            return run_copy<true, false>(pl, ptrs, pk, nullptr, st);
-        }
-        if ((rc = run_copy<false, false>(pl, ptrs, pk, nullptr, st)) != HXT_OK) return rc;
-        return run_sum2(plan, packed, MODE, out, work, stream);
-    }
-    SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};
-    SlotsLock lock(g_slots_mu);
-    if ((rc = claim_slots(pl, OP_CHECKSUM2, st, cx, nullptr)) != HXT_OK) return rc;
-    with_hints(packed_nontemporal(p.C * p.B), [&]<bool NTU, bool NTP>() {
-        k_uniform_tag<UNPACK, MODE, NTU, NTP><<<p.geom.ntiles, kThreads, 0, st>>>(p.geom, base, pk, out, cx.acc, cx.stride,
-                                                                                 cx.fan, work);
-    });
-    HXT_HIP(hipGetLastError());
-    return HXT_OK;
-}
-}  // namespace
-}  // extern "C++"
 
 int hxt_pack_seal(const hxt_plan_t *plan, const void *const *src, void *packed, uint64_t seq, uint32_t micro_batch,
                   hxt_chunk_tag_t *tags, void *stream)

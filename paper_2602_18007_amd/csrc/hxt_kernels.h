@@ -879,6 +879,14 @@ __global__ __launch_bounds__(kThreads) void k_uniform_tag(ChunkGeom g, uint8_t *
     pair_commit(MODE, g, t, sums.s, j0 * sums.s + sums.w, out, acc, stride, fan, work);
 }
 
+// A few KiB of chunk tags between device memory and pinned host memory (either direction; the pinned
+// buffer is addressed directly over the host link).  A kernel rather than a DMA copy: a launch costs
+// less than the fixed overhead of a copy command, and the DMA queues keep only the large staging copies.
+__global__ __launch_bounds__(kThreads) void k_copy_tags(u32x4 *__restrict__ to, const u32x4 *__restrict__ from, uint32_t nvec)
+{
+    for (uint32_t v = blockIdx.x * kThreads + threadIdx.x; v < nvec; v += gridDim.x * kThreads) to[v] = from[v];
+}
+
 // status[C] = number of chunks of status[0 .. C) that were rejected.  One workgroup.
 __global__ __launch_bounds__(kThreads) void k_count_rejected(uint32_t *status, uint32_t C)
 {

@@ -66,7 +66,9 @@ class _Exchange(C.Structure):
                 ("src", C.POINTER(C.c_void_p)), ("dst", C.POINTER(C.c_void_p)),
                 ("packed_send", C.POINTER(C.c_void_p)), ("packed_recv", C.POINTER(C.c_void_p)),
                 ("host_pinned", C.POINTER(C.c_void_p)), ("send_sums", C.c_void_p), ("recv_sums", C.c_void_p),
-                ("stream_pack", C.c_void_p), ("stream_stage", C.c_void_p), ("stream_unpack", C.c_void_p)]
+                ("stream_pack", C.c_void_p), ("stream_stage", C.c_void_p), ("stream_unpack", C.c_void_p),
+                ("tags_send", C.POINTER(C.c_void_p)), ("tags_recv", C.POINTER(C.c_void_p)),
+                ("tags_pinned", C.POINTER(C.c_void_p)), ("status", C.c_void_p), ("seq_base", C.c_uint64)]
 
 
 HXT_DEVICE_DIRECT, HXT_CPU_FORWARD = 0, 1
@@ -310,14 +312,18 @@ class Exchange:
     """Pre-marshalled hxt_exchange_t: src/dst are lists (one entry per message) of lists of tensors."""
 
     def __init__(self, src, dst, packed_send, path=HXT_DEVICE_DIRECT, packed_recv=None, host_pinned=None,
-                 send_sums=None, recv_sums=None, stream_pack=None, stream_stage=None, stream_unpack=None):
+                 send_sums=None, recv_sums=None, stream_pack=None, stream_stage=None, stream_unpack=None,
+                 tags_send=None, tags_recv=None, tags_pinned=None, status=None, seq_base=0):
         flat = lambda rows: [t for row in rows for t in row]
-        self._keep = (src, dst, packed_send, packed_recv, host_pinned, send_sums, recv_sums)
+        opt = lambda rows: _ptr_array(rows) if rows is not None else None
+        self._keep = (src, dst, packed_send, packed_recv, host_pinned, send_sums, recv_sums, tags_send, tags_recv,
+                      tags_pinned, status)
         self._arrays = [_ptr_array(flat(src)), _ptr_array(flat(dst)), _ptr_array(packed_send),
-                        _ptr_array(packed_recv) if packed_recv is not None else None,
-                        _ptr_array(host_pinned) if host_pinned is not None else None]
+                        opt(packed_recv), opt(host_pinned)]
+        self._tag_arrays = [opt(tags_send), opt(tags_recv), opt(tags_pinned)]
         self.c = _Exchange(len(src), len(packed_send), path, *self._arrays, _ptr(send_sums), _ptr(recv_sums),
-                           _stream(stream_pack), _stream(stream_stage), _stream(stream_unpack))
+                           _stream(stream_pack), _stream(stream_stage), _stream(stream_unpack),
+                           *self._tag_arrays, _ptr(status), seq_base)
 
 
 def hxt_exchange_stream(plan: Plan, x: Exchange) -> None:

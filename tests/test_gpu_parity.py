@@ -671,6 +671,41 @@ def test_config_stream_1f1b_three_streams_ping_pong(path):
             assert np.array_equal(ss_h[i], ho.checksum(m, want, w.chunk_bytes, w.n_lanes, nthreads=NT))
 
 
+def run_exchange_tagged(case, raws_per_msg, path, n_buffers, streams, seq_base=1 << 40):
+    """hxt_exchange_stream with chunk tags: every destination, a clean verdict for every message, and the tags
+    left in the buffers (those of the last n_buffers messages) against the oracle's."""
+    m = oracle_msg(case)
+    p = plan_of(case)
+    nmsg, C, nb = len(raws_per_msg), p.num_chunks, max(p.packed_bytes, 256)
+    fwd = path == "cpu_forward"
+    src = [[to_dev(r) for r in raws] for raws in raws_per_msg]
+    dst = [[to_dev(np.full(r.size, 0x3C, np.uint8)) for r in raws] for raws in raws_per_msg]
+    dev_bufs = lambda n, fill: [torch.full((n,), fill, dtype=torch.uint8, device=DEV) for _ in range(n_buffers)]
+    pinned = lambda n: [torch.zeros(n, dtype=torch.uint8).pin_memory() for _ in range(n_buffers)]
+    send_buf, tags_send = dev_bufs(nb, 0xEE), dev_bufs(max(C, 1) * 64, 0x11)
+    recv_buf, tags_recv = (dev_bufs(nb, 0xDD), dev_bufs(max(C, 1) * 64, 0x22)) if fwd else (None, None)
+    host_buf, tags_pinned = (pinned(nb), pinned(max(C, 1) * 64)) if fwd else (None, None)
+    status = torch.full((nmsg, C + 1), -1, dtype=torch.int32, device=DEV)
+    for s_ in streams:
+        s_.wait_stream(torch.cuda.current_stream())
+    x = hxt.Exchange(src, dst, send_buf, hxt.HXT_CPU_FORWARD if fwd else hxt.HXT_DEVICE_DIRECT, recv_buf, host_buf,
+                     None, None, *streams, tags_send=tags_send, tags_recv=tags_recv, tags_pinned=tags_pinned,
+                     status=status, seq_base=seq_base)
+    hxt.hxt_exchange_stream(p, x)
+    torch.cuda.synchronize()
+    assert not status.cpu().numpy().any(), "a chunk was rejected"
+    for i, raws in enumerate(raws_per_msg):
+        want = ho.pack(m, raws, case.B, case.k, nthreads=NT)
+        dst_o = [np.full(r.size, 0x3C, np.uint8) for r in raws]
+        ho.unpack(m, want, case.B, case.k, dst_o, nthreads=NT)
+        for a, b in zip(dst_o, dst[i]):
+            assert np.array_equal(b.cpu().numpy(), a), "message %d" % i
+        if i >= nmsg - n_buffers:
+            want_tags = ho.seal(m, want, case.B, case.k, seq_base + i, i)
+            for buf in ([tags_send, tags_recv] if fwd else [tags_send]):
+                assert np.array_equal(buf[i % n_buffers].cpu().numpy()[:C * 64].reshape(C, 64), want_tags), "message %d" % i
+
+
 def run_exchange(case, raws_per_msg, path, n_buffers, streams):
     """hxt_exchange_stream on a list of messages; checks every destination and every checksum."""
     m = oracle_msg(case)
@@ -714,6 +749,39 @@ def test_exchange_stream_small_messages(path, n_buffers):
     case = [c for c in MID_CASES if c.name == "contig_1MB_ragged"][0]
     one = torch.cuda.Stream()
     run_exchange(case, [make_storages(case, 3100 + i) for i in range(3)], path, n_buffers, [one, one, one])
+
+
+@pytest.mark.parametrize("path", ["device_direct", "cpu_forward"])
+@pytest.mark.parametrize("n_buffers", [1, 2, 3, 4])
+def test_exchange_stream_with_chunk_tags(path, n_buffers):
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    for name, nmsg in (("contig_bf16_5MiB_tail", 7), ("multi_mid", 5), ("rows_mid", 4)):
+        case = [c for c in MID_CASES if c.name == name][0]
+        run_exchange_tagged(case, [make_storages(case, 3300 + i) for i in range(nmsg)], path, n_buffers, streams)
+
+
+def test_exchange_stream_with_chunk_tags_rejects_mixed_requests():
+    case = [c for c in MID_CASES if c.name == "contig_1MB_ragged"][0]
+    p = plan_of(case)
+    raws = make_storages(case, 1)
+    src, dst = [[to_dev(r) for r in raws]], [[to_dev(r) for r in raws]]
+    buf = [torch.zeros(p.packed_bytes, dtype=torch.uint8, device=DEV)]
+    tags = [torch.zeros(p.num_chunks * 64, dtype=torch.uint8, device=DEV)]
+    sums = torch.zeros(p.num_chunks, dtype=torch.int64, device=DEV)
+    status = torch.zeros(p.num_chunks + 1, dtype=torch.int32, device=DEV)
+    for kwargs in (dict(tags_send=tags, status=None), dict(tags_send=tags, status=status, send=sums),
+                   dict(tags_send=[None], status=status)):
+        x = hxt.Exchange(src, dst, buf, hxt.HXT_DEVICE_DIRECT, None, None, kwargs.get("send"), None, None, None, None,
+                         tags_send=kwargs["tags_send"], status=kwargs["status"])
+        with pytest.raises(hxt.HxtError) as e:
+            hxt.hxt_exchange_stream(p, x)
+        assert e.value.status == hxt.HXT_EINVAL
+    x = hxt.Exchange(src, dst, buf, hxt.HXT_CPU_FORWARD, buf, [torch.zeros(p.packed_bytes, dtype=torch.uint8).pin_memory()],
+                     None, None, None, None, None, tags_send=tags, status=status)          # CPU forwarding needs the other tag buffers
+    with pytest.raises(hxt.HxtError) as e:
+        hxt.hxt_exchange_stream(p, x)
+    assert e.value.status == hxt.HXT_EINVAL
+    torch.cuda.synchronize()
 
 
 @pytest.mark.parametrize("path", ["device_direct", "cpu_forward"])
