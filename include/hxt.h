@@ -45,7 +45,10 @@
  *     makes the later stream wait for the earlier one (an event), so they never
  *     overlap; the claim of the accumulators and the enqueue of the kernels that
  *     use them are one critical section, so this also holds between threads.
- *     Messages that should overlap with checksums need a plan each.
+ *     The sets are: hxt_pack; hxt_unpack and hxt_unpack_accumulate; hxt_checksum;
+ *     hxt_checksum2, hxt_seal and hxt_pack_seal; hxt_verify and hxt_unpack_verify.
+ *     One plan can therefore serve a sending stream and a receiving stream at the
+ *     same time; messages that should overlap within one set need a plan each.
  *     Plans built from equal arguments on the sending and on the receiving side
  *     are interchangeable (the receive is symmetric).
  */
