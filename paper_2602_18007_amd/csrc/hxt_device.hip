@@ -529,8 +529,10 @@ int run_sum2(const hxt_plan_t *plan, const void *packed, int mode, void *out, co
     const uint8_t *pk = static_cast<const uint8_t *>(packed);
     const bool ntp = packed_nontemporal(pl.p.C * pl.p.B);
     auto launch = [&]<int MODE>() {
-        if (ntp) k_checksum2<MODE, true><<<pl.p.geom.ntiles, kThreads, 0, st>>>(pl.p.geom, pk, out, cx.acc, cx.stride, cx.fan, work);
-        else k_checksum2<MODE, false><<<pl.p.geom.ntiles, kThreads, 0, st>>>(pl.p.geom, pk, out, cx.acc, cx.stride, cx.fan, work);
+        TagWork w = work;
+        w.sum_bits = pl.sum_bits_geom;
+        if (ntp) k_checksum2<MODE, true><<<pl.p.geom.ntiles, kThreads, 0, st>>>(pl.p.geom, pk, out, cx.acc, cx.stride, cx.fan, w);
+        else k_checksum2<MODE, false><<<pl.p.geom.ntiles, kThreads, 0, st>>>(pl.p.geom, pk, out, cx.acc, cx.stride, cx.fan, w);
     };
     if (mode == SUM2_SUMS) launch.template operator()<SUM2_SUMS>();
     else if (mode == SUM2_SEAL) launch.template operator()<SUM2_SEAL>();
@@ -570,9 +572,11 @@ int run_copy_tag(const hxt_plan_t *plan, void *const *ptrs, void *packed, void *
     SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};
     SlotsLock lock(g_slots_mu);
     if ((rc = claim_slots(pl, UNPACK ? (chain ? OP_SUM2_RECV_B : OP_SUM2_RECV) : (chain ? OP_SUM2_SEND_B : OP_SUM2_SEND), st, cx, nullptr)) != HXT_OK) return rc;
+    TagWork w = work;
+    w.sum_bits = pl.sum_bits_geom;
     with_hints(packed_nontemporal(p.C * p.B), [&]<bool NTU, bool NTP>() {
         k_uniform_tag<UNPACK, MODE, NTU, NTP><<<p.geom.ntiles, kThreads, 0, st>>>(p.geom, base, pk, out, cx.acc, cx.stride,
-                                                                                 cx.fan, work);
+                                                                                 cx.fan, w);
     });
     HXT_HIP(hipGetLastError());
     return HXT_OK;
@@ -648,10 +652,10 @@ int chained_direct_stream(hxt_plan_t &pl, const hxt_exchange_t &x, hipStream_t a
         if (x.tags_send) {                               // sealed and verified inside the copies
             void *tags = x.tags_send[i % x.n_buffers];
             const uint64_t seq = x.seq_base + uint64_t(i);
-            rc = run_copy_tag<false>(&pl, src, buf, tags, TagWork{nullptr, seq, uint32_t(i)}, st, chain);
+            rc = run_copy_tag<false>(&pl, src, buf, tags, TagWork{nullptr, seq, uint32_t(i), 0}, st, chain);
             if (rc != HXT_OK) return rc;
             rc = run_copy_tag<true>(&pl, x.dst + i * T, buf, x.status + size_t(i) * (p.C + 1),
-                                    TagWork{static_cast<const uint8_t *>(tags), seq, uint32_t(i)}, st, chain);
+                                    TagWork{static_cast<const uint8_t *>(tags), seq, uint32_t(i), 0}, st, chain);
             if (rc != HXT_OK) return rc;
             continue;
         }
@@ -1048,7 +1052,7 @@ int hxt_pack_seal(const hxt_plan_t *plan, const void *const *src, void *packed, 
                   hxt_chunk_tag_t *tags, void *stream)
 {
     if (plan && plan->p.C == 0) return HXT_OK;
-    return run_copy_tag<false>(plan, const_cast<void *const *>(src), packed, tags, TagWork{nullptr, seq, micro_batch},
+    return run_copy_tag<false>(plan, const_cast<void *const *>(src), packed, tags, TagWork{nullptr, seq, micro_batch, 0},
                                stream);
 }
 
@@ -1057,20 +1061,20 @@ int hxt_unpack_verify(const hxt_plan_t *plan, const void *packed, const hxt_chun
 {
     if (plan && plan->p.C == 0) return hxt_verify(plan, packed, tags, seq, micro_batch, status, stream);
     return run_copy_tag<true>(plan, dst, const_cast<void *>(packed), status,
-                              TagWork{reinterpret_cast<const uint8_t *>(tags), seq, micro_batch}, stream);
+                              TagWork{reinterpret_cast<const uint8_t *>(tags), seq, micro_batch, 0}, stream);
 }
 
 int hxt_checksum2(const hxt_plan_t *plan, const void *packed, uint64_t *sums2, void *stream)
 {
     if (plan && plan->p.C == 0) return HXT_OK;
-    return run_sum2(plan, packed, SUM2_SUMS, sums2, TagWork{nullptr, 0, 0}, stream);
+    return run_sum2(plan, packed, SUM2_SUMS, sums2, TagWork{nullptr, 0, 0, 0}, stream);
 }
 
 int hxt_seal(const hxt_plan_t *plan, const void *packed, uint64_t seq, uint32_t micro_batch, hxt_chunk_tag_t *tags,
              void *stream)
 {
     if (plan && plan->p.C == 0) return HXT_OK;
-    return run_sum2(plan, packed, SUM2_SEAL, tags, TagWork{nullptr, seq, micro_batch}, stream);
+    return run_sum2(plan, packed, SUM2_SEAL, tags, TagWork{nullptr, seq, micro_batch, 0}, stream);
 }
 
 int hxt_verify(const hxt_plan_t *plan, const void *packed, const hxt_chunk_tag_t *tags, uint64_t seq,
@@ -1087,7 +1091,7 @@ int hxt_verify(const hxt_plan_t *plan, const void *packed, const hxt_chunk_tag_t
         return HXT_OK;
     }
     return run_sum2(plan, packed, SUM2_VERIFY, status,
-                    TagWork{reinterpret_cast<const uint8_t *>(tags), seq, micro_batch}, stream);
+                    TagWork{reinterpret_cast<const uint8_t *>(tags), seq, micro_batch, 0}, stream);
 }
 
 int hxt_stage_d2h(const hxt_plan_t *plan, int lane, const void *packed_dev, void *host_pinned, void *stream)

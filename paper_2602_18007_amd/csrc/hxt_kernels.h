@@ -641,14 +641,26 @@ __global__ __launch_bounds__(kThreads) void k_checksum(ChunkGeom g, const uint8_
 // A logical accumulator is a pair of slots (2s: plain sum and arrival count, 2s+1: weighted
 // sum); the ticket is taken after both additions have returned.  Same two-level fan-out as
 // chunk_commit: first-level pairs C*fan, then one second-level pair per chunk.
+// sum_bits > 0 (see slot_arrive): the plain sum and the arrival count share one word, so the arrival is
+// the weighted sum's addition, then one addition that also takes the ticket; sum_bits == 0: three steps.
 __device__ __forceinline__ bool pair_arrive(uint8_t *acc, uint32_t stride, size_t s, unsigned long long &a,
-                                            unsigned long long &b, uint32_t expected)
+                                            unsigned long long &b, uint32_t expected, uint32_t sum_bits)
 {
     if (expected == 1) return true;
     Acc *sa = reinterpret_cast<Acc *>(acc + (2 * s) * stride);
     Acc *sb = reinterpret_cast<Acc *>(acc + (2 * s + 1) * stride);
-    const unsigned long long ra = __hip_atomic_fetch_add(&sa->sum, a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const unsigned long long rb = __hip_atomic_fetch_add(&sb->sum, b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (sum_bits) {
+        asm volatile("s_waitcnt vmcnt(0)" ::"v"(uint32_t(rb)) : "memory");
+        const unsigned long long one = 1ull << sum_bits;
+        const unsigned long long before = __hip_atomic_fetch_add(&sa->sum, one + a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((before >> sum_bits) != expected - 1) return false;
+        __hip_atomic_store(&sa->sum, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        a = (before + a) & (one - 1);
+        b = __hip_atomic_exchange(&sb->sum, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return true;
+    }
+    const unsigned long long ra = __hip_atomic_fetch_add(&sa->sum, a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     asm volatile("s_waitcnt vmcnt(0)" ::"v"(uint32_t(ra)), "v"(uint32_t(rb)) : "memory");
     const uint32_t ticket = __hip_atomic_fetch_add(&sa->cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (ticket != expected - 1) return false;
@@ -676,6 +688,7 @@ struct TagWork {
     const uint8_t *tags;     // VERIFY: the received tags
     uint64_t seq;            // SEAL: value to write; VERIFY: value expected
     uint32_t micro_batch;
+    uint32_t sum_bits;       // see pair_arrive; set by the launch code
 };
 
 __device__ __forceinline__ void finish_chunk(int mode, const ChunkGeom &g, const TileSpan &t, uint64_t sum,
@@ -718,7 +731,7 @@ __device__ __forceinline__ void finish_chunk(int mode, const ChunkGeom &g, const
     // One more pair of slots, after the chunks' own, counts the chunks that are done and the rejected
     // ones among them; the chunk that completes the message writes the total to out[C].
     unsigned long long bad = m != 0, none = 0;
-    if (pair_arrive(acc, stride, size_t(g.C) * (fan + 1), bad, none, g.C)) static_cast<uint32_t *>(out)[g.C] = uint32_t(bad);
+    if (pair_arrive(acc, stride, size_t(g.C) * (fan + 1), bad, none, g.C, 0)) static_cast<uint32_t *>(out)[g.C] = uint32_t(bad);
 }
 
 // Workgroup-wide: reduces every thread's (a, b), adds the pair to the chunk's accumulators (two-level
@@ -748,12 +761,12 @@ __device__ __forceinline__ void pair_commit(int mode, const ChunkGeom &g, const 
         const size_t top = size_t(g.C) * fan + t.chunk;
         bool last;
         if (fan == 1 || t.expected < 2 * fan) {
-            last = pair_arrive(acc, stride, top, a, b, t.expected);
+            last = pair_arrive(acc, stride, top, a, b, t.expected, work.sum_bits);
         } else {
             const uint32_t sub = t.ordinal & (fan - 1);
             const uint32_t share = t.expected / fan + (sub < (t.expected & (fan - 1)) ? 1u : 0u);
-            last = pair_arrive(acc, stride, size_t(t.chunk) * fan + sub, a, b, share) &&
-                   pair_arrive(acc, stride, top, a, b, fan);
+            last = pair_arrive(acc, stride, size_t(t.chunk) * fan + sub, a, b, share, work.sum_bits) &&
+                   pair_arrive(acc, stride, top, a, b, fan, work.sum_bits);
         }
         if (last) finish_chunk(mode, g, t, a, b, out, work, acc, stride, fan);
     }
