@@ -691,9 +691,32 @@ struct TagWork {
     uint32_t sum_bits;       // see pair_arrive; set by the launch code
 };
 
+// The received tag of a workgroup's chunk, loaded by thread 0 when the workgroup starts so that the load's
+// latency is long past when (and if) this workgroup turns out to complete the chunk.
+struct TagRegs {
+    u32x4 r[4];
+};
+
+__device__ __forceinline__ uint64_t tag_place(const ChunkGeom &g, uint32_t c)     // packed offset of chunk c / B
+{
+    const uint32_t slot = fast_div(c, g.div_k), lane = c - slot * g.k;
+    return uint64_t(lane) * g.q + (lane < g.r ? lane : g.r) + slot;
+}
+
+__device__ __forceinline__ TagRegs prefetch_tag(int mode, const ChunkGeom &g, uint32_t chunk, const TagWork &w)
+{
+    TagRegs t{};
+    if (mode == SUM2_VERIFY && threadIdx.x == 0) {
+        const u32x4 *tag = reinterpret_cast<const u32x4 *>(w.tags + tag_place(g, chunk) * 64);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) t.r[i] = tag[i];
+    }
+    return t;
+}
+
 __device__ __forceinline__ void finish_chunk(int mode, const ChunkGeom &g, const TileSpan &t, uint64_t sum,
-                                             uint64_t wsum, void *out, const TagWork &w, uint8_t *acc, uint32_t stride,
-                                             uint32_t fan)
+                                             uint64_t wsum, void *out, const TagWork &w, const TagRegs &got,
+                                             uint8_t *acc, uint32_t stride, uint32_t fan)
 {
     const uint32_t c = t.chunk;
     if (mode == SUM2_SUMS) {
@@ -703,7 +726,7 @@ __device__ __forceinline__ void finish_chunk(int mode, const ChunkGeom &g, const
         return;
     }
     const uint32_t slot = fast_div(c, g.div_k), lane = c - slot * g.k;
-    const uint64_t place = uint64_t(lane) * g.q + (lane < g.r ? lane : g.r) + slot;      // packed offset / B
+    const uint64_t place = tag_place(g, c);
     const uint64_t padded = (c + 1 == g.C) ? g.L - uint64_t(c) * g.B : g.B;
     const u32x4 q0{kTagMagic, c, lane, slot};
     const u32x4 q1{uint32_t(w.seq), uint32_t(w.seq >> 32), w.micro_batch, g.C};
@@ -717,8 +740,7 @@ __device__ __forceinline__ void finish_chunk(int mode, const ChunkGeom &g, const
         tag[3] = q3;
         return;
     }
-    const u32x4 *tag = reinterpret_cast<const u32x4 *>(w.tags + place * 64);
-    const u32x4 r0 = tag[0], r1 = tag[1], r2 = tag[2], r3 = tag[3];
+    const u32x4 r0 = got.r[0], r1 = got.r[1], r2 = got.r[2], r3 = got.r[3];
     uint32_t m = 0;
     if (r0.x != q0.x) m |= HXT_TAG_BAD_MAGIC;
     if (r0.y != q0.y || r0.z != q0.z || r0.w != q0.w || r1.w != q1.w || r2.x != q2.x || r2.y != q2.y) m |= HXT_TAG_BAD_PLACE;
@@ -728,17 +750,26 @@ __device__ __forceinline__ void finish_chunk(int mode, const ChunkGeom &g, const
     if (r3.x != q3.x || r3.y != q3.y) m |= HXT_TAG_BAD_WSUM;
     if (r3.z != 0 || r3.w != 0) m |= HXT_TAG_BAD_RESERVED;
     static_cast<uint32_t *>(out)[c] = m;
-    // One more pair of slots, after the chunks' own, counts the chunks that are done and the rejected
-    // ones among them; the chunk that completes the message writes the total to out[C].
-    unsigned long long bad = m != 0, none = 0;
-    if (pair_arrive(acc, stride, size_t(g.C) * (fan + 1), bad, none, g.C, 0)) static_cast<uint32_t *>(out)[g.C] = uint32_t(bad);
+    // One more slot, after the chunks' own pairs, counts the chunks that are done (upper half of the word)
+    // and the rejected ones among them (lower half) with one addition; the chunk that completes the
+    // message writes the total to out[C] and clears the slot.
+    const unsigned long long mine = (1ull << 32) | (m != 0 ? 1u : 0u);
+    unsigned long long total = mine;
+    if (g.C > 1) {
+        Acc *done = reinterpret_cast<Acc *>(acc + 2 * (size_t(g.C) * (fan + 1)) * stride);
+        const unsigned long long before = __hip_atomic_fetch_add(&done->sum, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (uint32_t(before >> 32) != g.C - 1) return;
+        __hip_atomic_store(&done->sum, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        total = before + mine;
+    }
+    static_cast<uint32_t *>(out)[g.C] = uint32_t(total);
 }
 
 // Workgroup-wide: reduces every thread's (a, b), adds the pair to the chunk's accumulators (two-level
 // fan-out as in chunk_commit); the workgroup that completes the chunk finishes it.
 __device__ __forceinline__ void pair_commit(int mode, const ChunkGeom &g, const TileSpan &t, unsigned long long a,
                                             unsigned long long b, void *out, uint8_t *acc, uint32_t stride,
-                                            uint32_t fan, const TagWork &work)
+                                            uint32_t fan, const TagWork &work, const TagRegs &got)
 {
     __shared__ uint64_t part[2][kThreads / 64];
     for (int o = 32; o > 0; o >>= 1) {
@@ -768,7 +799,7 @@ __device__ __forceinline__ void pair_commit(int mode, const ChunkGeom &g, const 
             last = pair_arrive(acc, stride, size_t(t.chunk) * fan + sub, a, b, share, work.sum_bits) &&
                    pair_arrive(acc, stride, top, a, b, fan, work.sum_bits);
         }
-        if (last) finish_chunk(mode, g, t, a, b, out, work, acc, stride, fan);
+        if (last) finish_chunk(mode, g, t, a, b, out, work, got, acc, stride, fan);
     }
 }
 
@@ -778,6 +809,7 @@ __global__ __launch_bounds__(kThreads) void k_checksum2(ChunkGeom g, const uint8
                                                         uint32_t fan, TagWork work)
 {
     const TileSpan t = locate_tile(g, blockIdx.x);
+    const TagRegs got = prefetch_tag(MODE, g, t.chunk, work);
     const u32x4 *s = reinterpret_cast<const u32x4 *>(packed + t.packed_off);
     const uint64_t j0 = (t.stream_off - uint64_t(t.chunk) * g.B) >> 2;
     const uint32_t nvec = t.len >> 4;
@@ -800,7 +832,7 @@ __global__ __launch_bounds__(kThreads) void k_checksum2(ChunkGeom g, const uint8
         S += blockS;
         nS += blockN + n0 * blockS;
     }
-    pair_commit(MODE, g, t, S, (j0 + 4ull * threadIdx.x + 1) * S + 4ull * kThreads * nS + I, out, acc, stride, fan, work);
+    pair_commit(MODE, g, t, S, (j0 + 4ull * threadIdx.x + 1) * S + 4ull * kThreads * nS + I, out, acc, stride, fan, work, got);
 }
 
 // ---- pack + seal and unpack + verify in one pass (messages that are one contiguous tensor) ----
@@ -879,6 +911,7 @@ __global__ __launch_bounds__(kThreads) void k_uniform_tag(ChunkGeom g, uint8_t *
                                                           uint8_t *acc, uint32_t stride, uint32_t fan, TagWork work)
 {
     const TileSpan t = locate_tile(g, blockIdx.x);
+    const TagRegs got = prefetch_tag(MODE, g, t.chunk, work);
     const uint64_t left = g.N > t.stream_off ? g.N - t.stream_off : 0;
     const uint32_t data = left < t.len ? uint32_t(left) : t.len;
     uint8_t *pk = packed + t.packed_off;
@@ -889,7 +922,7 @@ __global__ __launch_bounds__(kThreads) void k_uniform_tag(ChunkGeom g, uint8_t *
         sums.w += pad.w;
     }
     const uint64_t j0 = (t.stream_off - uint64_t(t.chunk) * g.B) >> 2;       // the tile's first word in its chunk
-    pair_commit(MODE, g, t, sums.s, j0 * sums.s + sums.w, out, acc, stride, fan, work);
+    pair_commit(MODE, g, t, sums.s, j0 * sums.s + sums.w, out, acc, stride, fan, work, got);
 }
 
 // A few KiB of chunk tags between device memory and pinned host memory (either direction; the pinned
