@@ -49,6 +49,14 @@
  *     hxt_checksum2, hxt_seal and hxt_pack_seal; hxt_verify and hxt_unpack_verify.
  *     One plan can therefore serve a sending stream and a receiving stream at the
  *     same time; messages that should overlap within one set need a plan each.
+ *   - Stream capture: hxt_pack, hxt_unpack, hxt_unpack_accumulate, the batched calls,
+ *     the checksum / seal / verify passes and the fused tag calls may be captured into a
+ *     HIP graph (they record kernels only, no memset and no copy).  A call that asks for
+ *     checksums and finds its accumulator set last used on another stream inserts the
+ *     ordering event described above; make the first such call on the capture stream
+ *     before capture begins, so that none is needed inside the graph.  A replayed graph
+ *     keeps using the same accumulator set: do not run it concurrently with other calls
+ *     of that set on the same plan.
  *     Plans built from equal arguments on the sending and on the receiving side
  *     are interchangeable (the receive is symmetric).
  */
