@@ -57,7 +57,7 @@
  *     before capture begins, so that none is needed inside the graph.  A replayed graph
  *     keeps using the same accumulator set: do not run it concurrently with other calls
  *     of that set on the same plan.
- *     Plans built from equal arguments on the sending and on the receiving side
+ *   - Plans built from equal arguments on the sending and on the receiving side
  *     are interchangeable (the receive is symmetric).
  */
 #ifndef HXT_H
