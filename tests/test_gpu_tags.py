@@ -212,6 +212,58 @@ def test_a_stale_ping_pong_buffer_is_caught_by_its_tags():
             assert not st[i].any() and torch.equal(dst[i][0], src[i][0])
 
 
+def test_tag_calls_can_be_captured_in_a_hip_graph_and_replayed():
+    """pack_seal, checksum2, verify and unpack_verify recorded once (after one eager call on the capture stream)
+    and replayed on fresh inputs; every replay against the oracle, with eager work between the replays."""
+    case = next(c for c in CASES if c.name == "chunks_of_256_tiles")
+    m = ho.Message([ho.TensorSpec(tuple(s_), tuple(st), e) for (s_, st, e) in case.tensors])
+    p = hxt.hxt_plan_multi([(s_, st, e) for (s_, st, e) in case.tensors], case.k, case.B)
+    C = p.num_chunks
+    nbytes = make_storages(case, 0)[0].size
+    src = [torch.zeros(nbytes, dtype=torch.uint8, device=DEV)]
+    dst = [torch.zeros(nbytes, dtype=torch.uint8, device=DEV)]
+    packed = torch.zeros(p.packed_bytes, dtype=torch.uint8, device=DEV)
+    tags = torch.zeros(C * 64, dtype=torch.uint8, device=DEV)
+    strong = torch.zeros(C, 2, dtype=torch.int64, device=DEV)
+    st1 = torch.zeros(C + 1, dtype=torch.int32, device=DEV)
+    st2 = torch.zeros(C + 1, dtype=torch.int32, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+
+    def calls():
+        hxt.hxt_pack_seal(p, src, packed, 900, 4, tags, side)
+        hxt.hxt_checksum2(p, packed, strong, side)
+        hxt.hxt_verify(p, packed, tags, 900, 4, st1, side)
+        hxt.hxt_unpack_verify(p, packed, tags, 901, 4, dst, st2, side)      # expects the next sequence number
+
+    with torch.cuda.stream(side):
+        calls()
+    side.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        calls()
+    for rep in range(4):
+        raw = make_storages(case, 600 + rep)[0]
+        src[0].copy_(torch.from_numpy(raw))
+        for t in (dst[0], packed, tags):
+            t.zero_()
+        st1.fill_(-1)
+        st2.fill_(-1)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        want = ho.pack(m, [raw], case.B, case.k, fill=0)
+        want_tags = ho.seal(m, want, case.B, case.k, 900, 4)
+        assert np.array_equal(packed.cpu().numpy(), want), "replay %d" % rep
+        assert np.array_equal(tags.cpu().numpy().reshape(C, 64), want_tags)
+        assert np.array_equal(strong.cpu().numpy().view(np.uint64), ho.checksum2(m, want, case.B, case.k))
+        assert not st1.cpu().numpy().any()
+        assert np.array_equal(st2.cpu().numpy().view(np.uint32), ho.verify(m, want, want_tags, case.B, case.k, 901, 4))
+        assert np.array_equal(dst[0].cpu().numpy(), raw)
+        hxt.hxt_checksum2(p, packed, strong)                       # eager work of the same accumulator set in between
+        torch.cuda.synchronize()
+
+
 def test_empty_message_and_argument_errors():
     p0 = hxt.hxt_plan((0, 16), None, 2, 2, 256)
     status = torch.full((4,), 5, dtype=torch.int32, device=DEV)
