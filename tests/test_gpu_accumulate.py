@@ -117,3 +117,45 @@ def test_accumulate_gradient_bucket_shape():
     assert torch.equal(s1, s2)
     for a, b in zip(want, dst):
         assert np.array_equal(b.cpu().numpy(), a)
+
+
+def test_accumulate_can_be_captured_in_a_hip_graph_and_replayed():
+    """pack + receive-and-accumulate recorded once and replayed: every replay adds the arriving gradients again,
+    bit for bit as the oracle does when applied the same number of times."""
+    case = CASES[3]                                              # the mixed bf16 / f32 bucket
+    rng = np.random.default_rng(4242)
+    m = ho.Message([ho.TensorSpec(tuple(s), tuple(st), e) for (s, st, e) in case.tensors])
+    kinds = [ho.KIND_BF16 if e == 2 else ho.KIND_F32 for (_, _, e) in case.tensors]
+    sizes = [int(np.prod(s)) * e for (s, _, e) in case.tensors]
+    incoming = [draw(rng, n, e, "grad") for n, (_, _, e) in zip(sizes, case.tensors)]
+    local = [draw(rng, n, e, "grad") for n, (_, _, e) in zip(sizes, case.tensors)]
+    p = hxt.hxt_plan_multi([(s, st, e) for (s, st, e) in case.tensors], case.k, case.B)
+    src = [torch.from_numpy(x.copy()).to(DEV) if x.size else torch.zeros(16, dtype=torch.uint8, device=DEV) for x in incoming]
+    dst = [torch.from_numpy(x.copy()).to(DEV) if x.size else torch.zeros(16, dtype=torch.uint8, device=DEV) for x in local]
+    packed = torch.zeros(p.packed_bytes, dtype=torch.uint8, device=DEV)
+    s_send = torch.zeros(p.num_chunks, dtype=torch.int64, device=DEV)
+    s_recv = torch.zeros(p.num_chunks, dtype=torch.int64, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+
+    def calls():
+        hxt.hxt_pack(p, src, packed, s_send, side)
+        hxt.hxt_unpack_accumulate(p, packed, dst, s_recv, side)
+
+    with torch.cuda.stream(side):
+        calls()                                                  # eager once: the accumulator sets now belong to this stream
+    side.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        calls()
+    packed_o = ho.pack(m, incoming, case.B, case.k, fill=0)
+    want = [x.copy() for x in local]
+    ho.unpack_accumulate(m, kinds, packed_o, case.B, case.k, want)           # the eager call
+    for rep in range(3):
+        g.replay()
+        torch.cuda.synchronize()
+        ho.unpack_accumulate(m, kinds, packed_o, case.B, case.k, want)
+        for a, b in zip(want, dst):
+            assert np.array_equal(b.cpu().numpy()[:a.size], a), "replay %d" % rep
+        assert torch.equal(s_send, s_recv)
+        assert np.array_equal(s_recv.cpu().numpy().view(np.uint64), ho.checksum(m, packed_o, case.B, case.k))
