@@ -93,6 +93,28 @@ def test_planted_faults_get_the_oracles_masks():
         assert not gpu_verify(p, packed, tags, seq, mb).any()
 
 
+def test_every_field_of_the_tag_is_checked_on_the_device():
+    """One field of one received tag changed by one (on the host): the device reports what the oracle reports,
+    from the stand-alone pass and from the pass fused into unpack."""
+    TAG = np.dtype([("magic", "<u4"), ("chunk", "<u4"), ("lane", "<u4"), ("slot", "<u4"), ("seq", "<u8"),
+                    ("micro_batch", "<u4"), ("C", "<u4"), ("padded", "<u8"), ("sum", "<u8"), ("wsum", "<u8"), ("zero", "<u8")])
+    case = next(c for c in CASES if c.name == "contig_1MB_ragged")
+    m, p, packed = setup(case, 21)
+    C = p.num_chunks
+    tags = ho.seal(m, packed, case.B, case.k, 5, 6)
+    raws_like = [np.zeros(t[0][0] * t[2] if len(t[0]) == 1 else 0, np.uint8) for t in case.tensors]
+    for field in TAG.names:
+        t = tags.copy()
+        t.reshape(-1).view(TAG)[field][C - 1] += 1
+        want = ho.verify(m, packed, t, case.B, case.k, 5, 6)
+        assert want[C] == 1, field
+        assert np.array_equal(gpu_verify(p, packed, t, 5, 6), want), field
+        dst = [dev(r) for r in raws_like]
+        status = torch.full((C + 1,), -1, dtype=torch.int32, device=DEV)
+        hxt.hxt_unpack_verify(p, dev(packed), dev(t), 5, 6, dst, status)
+        assert np.array_equal(status.cpu().numpy().view(np.uint32), want), field
+
+
 def test_full_size_boundary_message_round_trip_with_tags():
     w = wl.llama8b_boundary()
     case = Case(w.name, tuple((t.shape, t.strides, t.esize) for t in w.tensors), w.n_lanes, w.chunk_bytes)

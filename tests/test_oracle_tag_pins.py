@@ -153,6 +153,25 @@ def test_damaged_or_misplaced_tags_are_rejected():
     assert st[int(slot_chunk[0])] == ho.TAG_BAD_PLACE and st[C] == 1
 
 
+@pytest.mark.parametrize("field,want_bit", [("chunk", "PLACE"), ("lane", "PLACE"), ("slot", "PLACE"), ("C", "PLACE"),
+                                             ("padded", "PLACE"), ("magic", "MAGIC"), ("seq", "SEQ"),
+                                             ("micro_batch", "MICRO_BATCH"), ("sum", "SUM"), ("wsum", "WSUM"),
+                                             ("zero", "RESERVED")])
+def test_every_field_of_the_tag_is_checked(field, want_bit):
+    """One field of one tag changed by one: exactly that field's bit, in exactly that chunk."""
+    case, m, packed, tags = planted()
+    C = tags.shape[0]
+    t = tags.copy()
+    rec = t.reshape(-1).view(TAG)
+    s = 1                                                              # the tag in packed slot 1
+    rec[field][s] += 1
+    st = ho.verify(m, packed, t, case.B, case.k, 41, 3)
+    c = int(tags.reshape(-1).view(TAG)["chunk"][s])
+    want = [0] * C
+    want[c] = getattr(ho, "TAG_BAD_" + want_bit)
+    assert list(st[:C]) == want and st[C] == 1
+
+
 def test_empty_message_has_no_tags():
     m = ho.Message([ho.TensorSpec((0, 16), (16, 1), 2)])
     packed = np.zeros(0, np.uint8)
