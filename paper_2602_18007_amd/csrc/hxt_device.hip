@@ -228,16 +228,17 @@ int run_copy(hxt_plan_t &pl, void *const *ptrs, uint8_t *packed, uint64_t *sums,
     }
     if (p.uniform) {
         uint8_t *base = static_cast<uint8_t *>(ptrs[p.uniform_tensor]);
-        if (reinterpret_cast<uintptr_t>(base) % 16 == 0) {
-            cx.sum_bits = pl.sum_bits_geom;
-            UniformArgs a;
-            std::memset(&a, 0, sizeof a);
-            a.n = 1;
-            a.it[0] = UniformItem{p.geom, base, packed, cx, 0, UNPACK};
+        cx.sum_bits = pl.sum_bits_geom;
+        UniformArgs a;
+        std::memset(&a, 0, sizeof a);
+        a.n = 1;
+        a.it[0] = UniformItem{p.geom, base, packed, cx, 0, UNPACK};
+        if (reinterpret_cast<uintptr_t>(base) % 16 == 0)
             launch_uniform<UNPACK ? DIR_UNPACK : DIR_PACK, CSUM>(a, p.geom.ntiles, packed_nontemporal(p.C * p.B), st);
-            HXT_HIP(hipGetLastError());
-            return HXT_OK;
-        }
+        else                                             // element aligned only: narrower accesses on the tensor side
+            k_uniform_any<UNPACK, CSUM><<<p.geom.ntiles, kThreads, 0, st>>>(a);
+        HXT_HIP(hipGetLastError());
+        return HXT_OK;
     }
     for (const Group &g : p.groups) {
         BasePtrs b;
@@ -251,6 +252,8 @@ int run_copy(hxt_plan_t &pl, void *const *ptrs, uint8_t *packed, uint64_t *sums,
         }
         if (g.kernel == K_CONTIG && fast_ok) {
             launch_contig<UNPACK, CSUM>(pl, g, b, packed, cx, st);
+        } else if (g.kernel == K_CONTIG) {               // some base is element aligned only
+            k_contig_any<UNPACK, CSUM><<<g.count, kThreads, 0, st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, b, packed, cx);
         } else if (g.kernel == K_ROWS && fast_ok) {
             launch_rows<UNPACK, CSUM>(pl, g, b, packed, cx, st);
         } else {

@@ -137,30 +137,80 @@ __device__ __forceinline__ void chunk_commit(uint64_t acc, uint32_t chunk, uint3
 // Copy `bytes` contiguous bytes between a user tensor and the packed buffer (pack: user ->
 // packed, unpack: packed -> user) in 16-byte vectors, UNROLL independent loads in flight per
 // thread before the first store; a last partial vector goes byte by byte.  NTU / NTP mark
-// the user-side / packed-side accesses non-temporal.
-template <bool UNPACK, bool CSUM, bool NTU, bool NTP>
+// the user-side / packed-side accesses non-temporal; UA is the alignment of `user`.
+// (The two blocks below are the user-side access helpers and the copy itself.)
+// 16 bytes of a user tensor that is only UA-byte aligned (UA = 16, 4, 2 or 1): the vector is put
+// together from / taken apart into naturally aligned pieces, so no access is misaligned and none
+// touches a byte outside the 16.
+template <int UA, bool NT>
+__device__ __forceinline__ u32x4 load_user(const uint8_t *p)
+{
+    if constexpr (UA == 16) {
+        return load16<NT>(reinterpret_cast<const u32x4 *>(p));
+    } else if constexpr (UA == 4) {
+        const uint32_t *q = reinterpret_cast<const uint32_t *>(p);
+        return u32x4{q[0], q[1], q[2], q[3]};
+    } else if constexpr (UA == 2) {
+        const uint16_t *q = reinterpret_cast<const uint16_t *>(p);
+        return u32x4{q[0] | uint32_t(q[1]) << 16, q[2] | uint32_t(q[3]) << 16, q[4] | uint32_t(q[5]) << 16,
+                     q[6] | uint32_t(q[7]) << 16};
+    } else {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            w[i] = p[4 * i] | uint32_t(p[4 * i + 1]) << 8 | uint32_t(p[4 * i + 2]) << 16 | uint32_t(p[4 * i + 3]) << 24;
+        return u32x4{w[0], w[1], w[2], w[3]};
+    }
+}
+
+template <int UA, bool NT>
+__device__ __forceinline__ void store_user(uint8_t *p, u32x4 v)
+{
+    if constexpr (UA == 16) {
+        store16<NT>(reinterpret_cast<u32x4 *>(p), v);
+    } else if constexpr (UA == 4) {
+        uint32_t *q = reinterpret_cast<uint32_t *>(p);
+        q[0] = v.x, q[1] = v.y, q[2] = v.z, q[3] = v.w;
+    } else if constexpr (UA == 2) {
+        uint16_t *q = reinterpret_cast<uint16_t *>(p);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) q[2 * i] = uint16_t(w[i]), q[2 * i + 1] = uint16_t(w[i] >> 16);
+    } else {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 16; ++i) p[i] = uint8_t(w[i >> 2] >> (8 * (i & 3)));
+    }
+}
+
+template <bool UNPACK, bool CSUM, bool NTU, bool NTP, int UA = 16>
 __device__ __forceinline__ uint64_t copy_span(uint8_t *user, uint8_t *pk, uint32_t bytes)
 {
-    constexpr bool NTL = UNPACK ? NTP : NTU, NTS = UNPACK ? NTU : NTP;
-    const u32x4 *s = reinterpret_cast<const u32x4 *>(UNPACK ? pk : user);
-    u32x4 *d = reinterpret_cast<u32x4 *>(UNPACK ? user : pk);
     const uint32_t nvec = bytes >> 4;
     constexpr uint32_t STEP = kThreads * kUnroll;
     const uint32_t full = nvec / STEP * STEP;            // uniform: blocks that need no bounds checks
+    auto load = [&](uint32_t v) {
+        if constexpr (UNPACK) return load16<NTP>(reinterpret_cast<const u32x4 *>(pk) + v);
+        else return load_user<UA, NTU>(user + (size_t(v) << 4));
+    };
+    auto store = [&](uint32_t v, u32x4 r) {
+        if constexpr (UNPACK) store_user<UA, NTU>(user + (size_t(v) << 4), r);
+        else store16<NTP>(reinterpret_cast<u32x4 *>(pk) + v, r);
+    };
     uint64_t acc = 0;
     for (uint32_t v = threadIdx.x; v < full; v += STEP) {
         u32x4 r[kUnroll];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) r[u] = load16<NTL>(s + v + u * kThreads);
+        for (int u = 0; u < kUnroll; ++u) r[u] = load(v + u * kThreads);
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            store16<NTS>(d + v + u * kThreads, r[u]);
+            store(v + u * kThreads, r[u]);
             if constexpr (CSUM) acc += words_sum(r[u]);
         }
     }
     for (uint32_t v = full + threadIdx.x; v < nvec; v += kThreads) {
-        const u32x4 r = load16<NTL>(s + v);
-        store16<NTS>(d + v, r);
+        const u32x4 r = load(v);
+        store(v, r);
         if constexpr (CSUM) acc += words_sum(r);
     }
     const uint32_t tail = bytes & 15;                    // only at the very end of a tensor
@@ -335,6 +385,48 @@ __global__ __launch_bounds__(kThreads) void k_contig(const Tile *__restrict__ ti
         acc = pad_span<UNPACK, CSUM>(packed + t.packed_off, t.n0, uint32_t(t.packed_off));
     else
         acc = copy_span<UNPACK, CSUM, NTU, NTP>(bases.p[t.tensor] + t.src_off, packed + t.packed_off, t.n0);
+    if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, chunk_tiles[t.chunk], cx);
+}
+
+// ---- contiguous tensors whose base pointer is only element aligned -------------------
+// The same copies with the user side accessed in pieces of its actual alignment (4, 2 or 1 bytes;
+// the packed side stays 16 bytes wide).  Separate kernels, so that the aligned ones keep their
+// register budget.
+template <bool UNPACK, bool CSUM>
+__device__ __forceinline__ uint64_t copy_span_any(uint8_t *user, uint8_t *pk, uint32_t bytes)
+{
+    const uint32_t mis = uint32_t(reinterpret_cast<uintptr_t>(user)) & 15u;          // the same for the whole workgroup
+    if (mis == 0) return copy_span<UNPACK, CSUM, false, false, 16>(user, pk, bytes);
+    if ((mis & 3u) == 0) return copy_span<UNPACK, CSUM, false, false, 4>(user, pk, bytes);
+    if ((mis & 1u) == 0) return copy_span<UNPACK, CSUM, false, false, 2>(user, pk, bytes);
+    return copy_span<UNPACK, CSUM, false, false, 1>(user, pk, bytes);
+}
+
+template <bool UNPACK, bool CSUM>
+__global__ __launch_bounds__(kThreads) void k_uniform_any(UniformArgs a)
+{
+    const UniformItem &it = a.it[0];
+    const ChunkGeom &g = it.g;
+    const TileSpan t = locate_tile(g, blockIdx.x);
+    const uint64_t left = g.N > t.stream_off ? g.N - t.stream_off : 0;
+    const uint32_t data = left < t.len ? uint32_t(left) : t.len;
+    uint8_t *pk = it.packed + t.packed_off;
+    uint64_t acc = copy_span_any<UNPACK, CSUM>(it.user + t.stream_off, pk, data);
+    if (data < t.len) acc += pad_span<UNPACK, CSUM>(pk + data, t.len - data, data);
+    if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, t.expected, it.cx);
+}
+
+template <bool UNPACK, bool CSUM>
+__global__ __launch_bounds__(kThreads) void k_contig_any(const Tile *__restrict__ tiles,
+                                                         const uint32_t *__restrict__ chunk_tiles, BasePtrs bases,
+                                                         uint8_t *__restrict__ packed, SumCtx cx)
+{
+    const Tile t = tiles[blockIdx.x];
+    uint64_t acc;
+    if (t.kind == K_ZERO)
+        acc = pad_span<UNPACK, CSUM>(packed + t.packed_off, t.n0, uint32_t(t.packed_off));
+    else
+        acc = copy_span_any<UNPACK, CSUM>(bases.p[t.tensor] + t.src_off, packed + t.packed_off, t.n0);
     if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, chunk_tiles[t.chunk], cx);
 }
 

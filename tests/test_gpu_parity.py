@@ -154,6 +154,17 @@ MID_CASES = [
 ]
 
 
+@pytest.mark.parametrize("name,offset", [("contig_1MB_ragged", 1), ("contig_1MB_ragged", 7), ("contig_1MB_ragged", 4),
+                                         ("contig_bf16_5MiB_tail", 2), ("contig_bf16_5MiB_tail", 6),
+                                         ("contig_bf16_5MiB_tail", 8), ("contig_chunks_of_256_tiles", 12),
+                                         ("multi_mid", 8), ("rows_mid", 2), ("transpose_mid", 2)])
+def test_mid_size_messages_with_element_aligned_bases(name, offset):
+    """Contiguous tensors whose base is 1, 2, 4, 8 or 12 bytes off a 16-byte boundary take the copy kernels with
+    narrower accesses on the tensor side; strided ones the per-element kernel.  Same bytes and sums either way."""
+    case = [c for c in MID_CASES if c.name == name][0]
+    round_trip_check(case, make_storages(case, 321), None, base_offset=offset)
+
+
 @pytest.mark.parametrize("case", MID_CASES, ids=lambda c: c.name)
 def test_mid_size_cases(case):
     say("case", case.name)
