@@ -146,8 +146,8 @@ int hxt_plan_tensor_kind(const hxt_plan_t *plan, int t);
 
 /* ---- step 2: pack (Section 2.2: user buffer -> chunk buffer, device to device)
  * src: host array of n_tensors device base pointers (element aligned; a contiguous
- *   tensor whose base is not 16-byte aligned is copied with narrower accesses on its
- *   side at about the same rate, a strided one by the slower per-element kernel).
+ *   tensor or row gather whose base is not 16-byte aligned is copied with narrower
+ *   accesses on its side at about the same rate, a transposed one element by element).
  * packed: device, >= packed_bytes, 256-byte aligned.  Every chunk's padded bytes
  *   are written (pad = 0); nothing else.
  * sums: NULL, or device array of num_chunks uint64 that receives the send-side

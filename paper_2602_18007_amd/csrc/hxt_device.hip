@@ -256,6 +256,9 @@ int run_copy(hxt_plan_t &pl, void *const *ptrs, uint8_t *packed, uint64_t *sums,
             k_contig_any<UNPACK, CSUM><<<g.count, kThreads, 0, st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, b, packed, cx);
         } else if (g.kernel == K_ROWS && fast_ok) {
             launch_rows<UNPACK, CSUM>(pl, g, b, packed, cx, st);
+        } else if (g.kernel == K_ROWS) {
+            k_rows_any<UNPACK, CSUM><<<g.count, kThreads, 0, st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, pl.d_tensors,
+                                                                   g.tensor_base, b, packed, cx);
         } else {
             // The transpose and per-element kernels are instantiated per element size: issue one
             // launch per run of tiles whose tensors share it (host table, same order as on the device).

@@ -466,17 +466,9 @@ __global__ __launch_bounds__(kThreads) void k_contig_accumulate(const Tile *__re
 // ---- rows: innermost dimension contiguous, outer dimensions strided -------------
 // A 16-byte vector never straddles a run (run length and strides are multiples of 16).
 // Logical byte -> (row, column) and row -> outer indices use multiply-shift division.
-template <bool UNPACK, bool CSUM, bool NTU, bool NTP>
-__global__ __launch_bounds__(kThreads) void k_rows(const Tile *__restrict__ tiles,
-                                                   const uint32_t *__restrict__ chunk_tiles,
-                                                   const TensorDev *__restrict__ tensors, uint32_t tensor_base,
-                                                   BasePtrs bases, uint8_t *__restrict__ packed, SumCtx cx)
+template <bool UNPACK, bool CSUM, bool NTU, bool NTP, int UA>
+__device__ __forceinline__ uint64_t rows_tile(const Tile &t, const TensorDev &td, uint8_t *user, uint8_t *pk)
 {
-    constexpr bool NTL = UNPACK ? NTP : NTU, NTS = UNPACK ? NTU : NTP;
-    const Tile t = tiles[blockIdx.x];
-    const TensorDev &td = tensors[tensor_base + t.tensor];
-    uint8_t *user = bases.p[t.tensor];
-    uint8_t *pk = packed + t.packed_off;
     const uint32_t row_bytes = td.row_bytes;
     const uint64_t row0 = t.src_off / row_bytes;                    // uniform
     const uint32_t col0 = uint32_t(t.src_off - row0 * row_bytes);
@@ -500,18 +492,53 @@ __global__ __launch_bounds__(kThreads) void k_rows(const Tile *__restrict__ tile
             }
             o += uint64_t(row) * uint64_t(td.stride_b[0]);
             off[u] = o;
-            if (v < nvec)
-                r[u] = load16<NTL>(reinterpret_cast<const u32x4 *>(UNPACK ? pk + (uint64_t(v) << 4) : user + o));
+            if (v < nvec) {
+                if constexpr (UNPACK) r[u] = load16<NTP>(reinterpret_cast<const u32x4 *>(pk + (uint64_t(v) << 4)));
+                else r[u] = load_user<UA, NTU>(user + o);
+            }
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const uint32_t v = v0 + u * kThreads;
             if (v < nvec) {
-                store16<NTS>(reinterpret_cast<u32x4 *>(UNPACK ? user + off[u] : pk + (uint64_t(v) << 4)), r[u]);
+                if constexpr (UNPACK) store_user<UA, NTU>(user + off[u], r[u]);
+                else store16<NTP>(reinterpret_cast<u32x4 *>(pk + (uint64_t(v) << 4)), r[u]);
                 if constexpr (CSUM) acc += words_sum(r[u]);
             }
         }
     }
+    return acc;
+}
+
+template <bool UNPACK, bool CSUM, bool NTU, bool NTP>
+__global__ __launch_bounds__(kThreads) void k_rows(const Tile *__restrict__ tiles,
+                                                   const uint32_t *__restrict__ chunk_tiles,
+                                                   const TensorDev *__restrict__ tensors, uint32_t tensor_base,
+                                                   BasePtrs bases, uint8_t *__restrict__ packed, SumCtx cx)
+{
+    const Tile t = tiles[blockIdx.x];
+    const uint64_t acc = rows_tile<UNPACK, CSUM, NTU, NTP, 16>(t, tensors[tensor_base + t.tensor], bases.p[t.tensor],
+                                                               packed + t.packed_off);
+    if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, chunk_tiles[t.chunk], cx);
+}
+
+// The same gather when a base pointer is only element aligned (all strides are multiples of 16 bytes, so
+// every vector of a tensor is off by the same amount): narrower accesses on the tensor side.
+template <bool UNPACK, bool CSUM>
+__global__ __launch_bounds__(kThreads) void k_rows_any(const Tile *__restrict__ tiles,
+                                                       const uint32_t *__restrict__ chunk_tiles,
+                                                       const TensorDev *__restrict__ tensors, uint32_t tensor_base,
+                                                       BasePtrs bases, uint8_t *__restrict__ packed, SumCtx cx)
+{
+    const Tile t = tiles[blockIdx.x];
+    const TensorDev &td = tensors[tensor_base + t.tensor];
+    uint8_t *user = bases.p[t.tensor], *pk = packed + t.packed_off;
+    const uint32_t mis = uint32_t(reinterpret_cast<uintptr_t>(user)) & 15u;
+    uint64_t acc;
+    if (mis == 0) acc = rows_tile<UNPACK, CSUM, false, false, 16>(t, td, user, pk);
+    else if ((mis & 3u) == 0) acc = rows_tile<UNPACK, CSUM, false, false, 4>(t, td, user, pk);
+    else if ((mis & 1u) == 0) acc = rows_tile<UNPACK, CSUM, false, false, 2>(t, td, user, pk);
+    else acc = rows_tile<UNPACK, CSUM, false, false, 1>(t, td, user, pk);
     if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, chunk_tiles[t.chunk], cx);
 }
 

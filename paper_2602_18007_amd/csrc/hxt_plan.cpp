@@ -121,8 +121,7 @@ static TensorDev make_tensor_dev(const TensorPlan &t)
         d.row_div = make_fastdiv(d.row_bytes);
         for (int i = 0; i < t.ndim - 1; ++i) d.dim_div[i] = make_fastdiv(uint32_t(t.shape[i]));
     }
-    // Any tensor can end up in the per-element kernel (a ROWS or TRANSPOSE tensor whose base pointer is
-    // not 16-byte aligned does): all_div says that dim_div is valid for every dim, with room for a carry.
+    // For the per-element kernel: all_div says that dim_div is valid for every dim, with room for a carry.
     bool small = t.ndim > 0;
     for (int i = 0; i < t.ndim; ++i) small = small && t.shape[i] >= 1 && t.shape[i] <= (int64_t(1) << 30);
     d.all_div = small ? 1u : 0u;

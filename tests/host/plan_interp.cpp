@@ -103,7 +103,7 @@ extern "C" int plan_interp(const hxt_tensor_desc_t *descs, int n_tensors, int n_
                 return 0;
             };
             int rc = 0;
-            // tiles of these kinds go to the per-element kernel when a base pointer is not 16-byte aligned
+            // the per-element kernel's carried arithmetic must hold for every linear tile, whichever kernel ends up serving it
             if ((t.kind == K_CONTIG || t.kind == K_ROWS || t.kind == K_GENERIC) && td.all_div) {
                 if (t.src_off % td.esize || t.n0 % td.esize) return -7;
                 for (uint32_t el = 0; el < t.n0 / td.esize; ++el) {
