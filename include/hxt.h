@@ -145,9 +145,9 @@ int hxt_plan_tensor_unpack_safe(const hxt_plan_t *plan, int t);
 int hxt_plan_tensor_kind(const hxt_plan_t *plan, int t);
 
 /* ---- step 2: pack (Section 2.2: user buffer -> chunk buffer, device to device)
- * src: host array of n_tensors device base pointers (element aligned; a contiguous
- *   tensor or row gather whose base is not 16-byte aligned is copied with narrower
- *   accesses on its side at about the same rate, a transposed one element by element).
+ * src: host array of n_tensors device base pointers (element aligned; a tensor
+ *   whose base is not 16-byte aligned is served by the same kernel with narrower
+ *   accesses on its side).
  * packed: device, >= packed_bytes, 256-byte aligned.  Every chunk's padded bytes
  *   are written (pad = 0); nothing else.
  * sums: NULL, or device array of num_chunks uint64 that receives the send-side

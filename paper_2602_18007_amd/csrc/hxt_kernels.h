@@ -562,7 +562,7 @@ __device__ __forceinline__ uint64_t elem_weighted(E v, uint64_t packed_pos)
 // reads that assemble one dst vector (same column, V consecutive rows) and the other lanes'
 // reads of the same instruction fall into distinct banks; then 16-byte global stores along dst
 // rows.  The sum is taken on whichever side is the packed buffer.
-template <typename E, bool SRC_IS_PACKED, bool CSUM>
+template <typename E, bool SRC_IS_PACKED, bool CSUM, int UA>
 __device__ __forceinline__ uint64_t transpose_vec(const uint8_t *src, uint64_t src_pitch, uint32_t R, uint32_t Cc,
                                                   uint8_t *dst, uint64_t dst_pitch, uint8_t *lds)
 {
@@ -571,8 +571,10 @@ __device__ __forceinline__ uint64_t transpose_vec(const uint8_t *src, uint64_t s
     const uint32_t nvs = Cc / V;                           // vectors per src row
     for (uint32_t v = threadIdx.x; v < R * nvs; v += kThreads) {
         const uint32_t r = v / nvs, cv = v - r * nvs;
-        // the user tensor is streamed once (non-temporal); the packed side stays cacheable
-        const u32x4 x = load16<!SRC_IS_PACKED>(reinterpret_cast<const u32x4 *>(src + r * src_pitch + cv * 16));
+        // the user tensor is streamed once (non-temporal) and may be only UA-byte aligned; the packed side stays cacheable
+        u32x4 x;
+        if constexpr (SRC_IS_PACKED) x = load16<false>(reinterpret_cast<const u32x4 *>(src + r * src_pitch + cv * 16));
+        else x = load_user<UA, true>(src + r * src_pitch + cv * 16);
         if constexpr (CSUM && SRC_IS_PACKED) acc += words_sum(x);
         *reinterpret_cast<u32x4 *>(lds + r * ROWB + ((cv ^ ((r / V) % NV)) * 16)) = x;
     }
@@ -603,7 +605,8 @@ __device__ __forceinline__ uint64_t transpose_vec(const uint8_t *src, uint64_t s
             o.e[q] = *reinterpret_cast<const E *>(lds + r * ROWB + (((c / V) ^ ((r / V) % NV)) * 16) + (c % V) * sizeof(E));
         }
         if constexpr (CSUM && !SRC_IS_PACKED) acc += words_sum(o.x);
-        store16<SRC_IS_PACKED>(reinterpret_cast<u32x4 *>(dst + c * dst_pitch + dv * 16), o.x);
+        if constexpr (SRC_IS_PACKED) store_user<UA, true>(dst + c * dst_pitch + dv * 16, o.x);
+        else store16<false>(reinterpret_cast<u32x4 *>(dst + c * dst_pitch + dv * 16), o.x);
     }
     return acc;
 }
@@ -620,12 +623,19 @@ __global__ __launch_bounds__(kThreads) void k_transpose(const Tile *__restrict__
     uint8_t *pk = packed + t.packed_off;
     const uint32_t ni = t.n0, nj = t.n1;
     uint64_t acc = 0;
-    const bool vec_ok = ((ni | nj) % V) == 0 &&
-                        ((reinterpret_cast<uintptr_t>(user) | reinterpret_cast<uintptr_t>(pk) | t.a | t.b) % 16) == 0;
+    const bool vec_ok = ((ni | nj) % V) == 0 && ((reinterpret_cast<uintptr_t>(pk) | t.a | t.b) % 16) == 0;
     if (vec_ok) {
-        // storage: nj rows (pitch a) of ni contiguous elements; packed: ni rows (pitch b) of nj elements
-        if constexpr (!UNPACK) acc = transpose_vec<E, false, CSUM>(user, t.a, nj, ni, pk, t.b, lds_raw);
-        else acc = transpose_vec<E, true, CSUM>(pk, t.b, ni, nj, user, t.a, lds_raw);
+        // storage: nj rows (pitch a) of ni contiguous elements; packed: ni rows (pitch b) of nj elements.  Every
+        // storage row of the tile is off a 16-byte boundary by the same amount (the pitch is a multiple of 16).
+        auto run = [&]<int UA>() {
+            if constexpr (!UNPACK) return transpose_vec<E, false, CSUM, UA>(user, t.a, nj, ni, pk, t.b, lds_raw);
+            else return transpose_vec<E, true, CSUM, UA>(pk, t.b, ni, nj, user, t.a, lds_raw);
+        };
+        const uint32_t mis = uint32_t(reinterpret_cast<uintptr_t>(user)) & 15u;
+        if (mis == 0) acc = run.template operator()<16>();
+        else if ((mis & 3u) == 0) acc = run.template operator()<4>();
+        else if ((mis & 1u) == 0) acc = run.template operator()<2>();
+        else acc = run.template operator()<1>();
     } else {
         E(*lds)[T + 1] = reinterpret_cast<E(*)[T + 1]>(lds_raw);
         const uint32_t tx = threadIdx.x & (T - 1), ty = threadIdx.x / T;

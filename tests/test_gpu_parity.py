@@ -158,10 +158,12 @@ MID_CASES = [
                                          ("contig_bf16_5MiB_tail", 2), ("contig_bf16_5MiB_tail", 6),
                                          ("contig_bf16_5MiB_tail", 8), ("contig_chunks_of_256_tiles", 12),
                                          ("multi_mid", 8), ("rows_mid", 2), ("rows_mid", 4), ("rows_big_rows", 6),
-                                         ("rows_padded_pitch", 4), ("rows_4d", 2), ("transpose_mid", 2), ("generic_mid", 2)])
+                                         ("rows_padded_pitch", 4), ("rows_4d", 2), ("transpose_mid", 2), ("transpose_512", 6),
+                                         ("transpose_f32_vec_batched", 4), ("transpose_f64", 8), ("transpose_u8_vec", 1),
+                                         ("transpose_u8_vec", 4), ("transpose_bf16_vec_partial", 2), ("generic_mid", 2)])
 def test_mid_size_messages_with_element_aligned_bases(name, offset):
     """Contiguous tensors and row gathers whose base is 1, 2, 4, 8 or 12 bytes off a 16-byte boundary take their
-    kernels with narrower accesses on the tensor side; transposes their element-wise path.  Same bytes and sums."""
+    kernels, with narrower accesses on the tensor side, and so do transposes.  Same bytes and sums."""
     case = [c for c in MID_CASES if c.name == name][0]
     round_trip_check(case, make_storages(case, 321), None, base_offset=offset)
 
