@@ -7,7 +7,7 @@ import torch
 from oracle import hxt_oracle as ho
 from paper_2602_18007_amd import hxt
 from paper_2602_18007_amd import workloads as wl
-from tests.cases import SMALL_CASES, Case, contig, make_storages
+from tests.cases import SMALL_CASES, Case, contig, make_storages, random_view, storage_bytes
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -284,6 +284,66 @@ def test_tag_calls_can_be_captured_in_a_hip_graph_and_replayed():
         assert np.array_equal(dst[0].cpu().numpy(), raw)
         hxt.hxt_checksum2(p, packed, strong)                       # eager work of the same accumulator set in between
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("block", range(3))
+def test_fused_tag_calls_on_random_messages(block):
+    """Random messages (single contiguous tensors of random length, and random strided views), random lanes and
+    chunk sizes, element-aligned base offsets, and one planted fault per message (a flipped payload bit, a flipped
+    tag bit or a stale sequence number): tags, masks and destinations against the oracle."""
+    done = 0
+    seed = 1000 * block
+    while done < 40:
+        seed += 1
+        rng = np.random.default_rng(77000 + seed)
+        if rng.random() < 0.5:
+            tensors = (contig((int(rng.integers(1, 400000)),), int(rng.choice([1, 2, 4, 8]))),)
+        else:
+            tensors = tuple(random_view(rng) for _ in range(int(rng.integers(1, 4))))
+        if not 0 < sum(storage_bytes(*t) for t in tensors) <= 4_000_000:
+            continue
+        case = Case("ft%d" % seed, tensors, int(rng.integers(1, 9)), int(rng.choice([256, 1024, 4096, 65536, 262144])))
+        m = ho.Message([ho.TensorSpec(tuple(s_), tuple(st), e) for (s_, st, e) in case.tensors])
+        p = hxt.hxt_plan_multi([(s_, st, e) for (s_, st, e) in case.tensors], case.k, case.B)
+        C = p.num_chunks
+        if C == 0 or not all(p.tensor_unpack_safe(t) for t in range(len(tensors))):
+            continue
+        raws = make_storages(case, seed)
+        off = int(rng.choice([0, 0, 8, 16]))
+
+        def shifted(a):
+            t = torch.empty(max(a.size, 16) + off + 16, dtype=torch.uint8, device=DEV)
+            v = t[off:off + a.size]
+            v.copy_(torch.from_numpy(a.reshape(-1)))
+            return v
+
+        seq, mb = int(rng.integers(0, 2**62)), int(rng.integers(0, 2**31))
+        want = ho.pack(m, raws, case.B, case.k, fill=0x77)
+        want_tags = ho.seal(m, want, case.B, case.k, seq, mb)
+        packed = torch.full((want.size,), 0x77, dtype=torch.uint8, device=DEV)
+        tags = torch.zeros(C * 64, dtype=torch.uint8, device=DEV)
+        hxt.hxt_pack_seal(p, [shifted(r) for r in raws], packed, seq, mb, tags)
+        assert np.array_equal(packed.cpu().numpy(), want), case
+        assert np.array_equal(tags.cpu().numpy().reshape(C, 64), want_tags), case
+        pk, tg = want.copy(), want_tags.copy()
+        kind = int(rng.integers(0, 4))
+        info = p.chunk_info(int(rng.integers(0, C)))
+        if kind == 1:
+            pk[info["packed_off"] + int(rng.integers(0, info["padded"]))] ^= 1 << int(rng.integers(0, 8))
+        if kind == 2:
+            tg[int(rng.integers(0, C)), int(rng.integers(0, 64))] ^= 1 << int(rng.integers(0, 8))
+        eseq = seq + (1 if kind == 3 else 0)
+        want_status = ho.verify(m, pk, tg, case.B, case.k, eseq, mb)
+        dst_o = [np.full(r.size, 0x3C, np.uint8) for r in raws]
+        ho.unpack(m, pk, case.B, case.k, dst_o)
+        dst = [shifted(np.full(r.size, 0x3C, np.uint8)) for r in raws]
+        status = torch.full((C + 1,), -1, dtype=torch.int32, device=DEV)
+        hxt.hxt_unpack_verify(p, dev(pk), dev(tg), eseq, mb, dst, status)
+        assert np.array_equal(status.cpu().numpy().view(np.uint32), want_status), (case, kind)
+        for a, b in zip(dst_o, dst):
+            assert np.array_equal(b.cpu().numpy(), a), case
+        assert np.array_equal(gpu_verify(p, pk, tg, eseq, mb), want_status), (case, kind)
+        done += 1
 
 
 def test_empty_message_and_argument_errors():
