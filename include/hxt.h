@@ -197,7 +197,7 @@ int hxt_unpack(const hxt_plan_t *plan, const void *packed, void *const *dst,
  *   HXT_F32 : IEEE binary32 addition.
  * A NaN result is stored as the canonical quiet NaN (0x7FC0 / 0x7FC00000).
  * Supported for plans whose non-empty tensors are all contiguous and of those two
- * dtypes (HXT_EUNSUPPORTED otherwise), with 16-byte aligned destinations (HXT_EALIGN).
+ * dtypes (HXT_EUNSUPPORTED otherwise); destinations element aligned, as in hxt_unpack.
  * sums: as in hxt_unpack (checksums of the packed bytes as read). */
 int hxt_unpack_accumulate(const hxt_plan_t *plan, const void *packed, void *const *dst,
                           uint64_t *sums, void *stream);

@@ -302,9 +302,12 @@ int run_accumulate(hxt_plan_t &pl, void *const *ptrs, uint8_t *packed, uint64_t 
         // `unpack` carries the element kind here: 1 = f32, 0 = bf16
         a.it[0] = UniformItem{p.geom, static_cast<uint8_t *>(ptrs[p.uniform_tensor]), packed, cx, 0,
                               tp.dtype == HXT_F32 ? 1u : 0u};
-        with_hints(ntp, [&]<bool NTU, bool NTP>() {
-            k_uniform_accumulate<CSUM, NTU, NTP><<<p.geom.ntiles, kThreads, 0, st>>>(a);
-        });
+        if (reinterpret_cast<uintptr_t>(ptrs[p.uniform_tensor]) % 16 == 0)
+            with_hints(ntp, [&]<bool NTU, bool NTP>() {
+                k_uniform_accumulate<CSUM, NTU, NTP><<<p.geom.ntiles, kThreads, 0, st>>>(a);
+            });
+        else
+            k_uniform_accumulate_any<CSUM><<<p.geom.ntiles, kThreads, 0, st>>>(a);
         HXT_HIP(hipGetLastError());
         return HXT_OK;
     }
@@ -313,14 +316,20 @@ int run_accumulate(hxt_plan_t &pl, void *const *ptrs, uint8_t *packed, uint64_t 
         ElemKinds kinds;
         std::memset(&b, 0, sizeof b);
         std::memset(&kinds, 0, sizeof kinds);
+        bool aligned = true;
         for (uint32_t i = 0; i < g.n_tensors; ++i) {
             b.p[i] = static_cast<uint8_t *>(ptrs[g.tensor_base + i]);
             kinds.f32[i] = p.tensors[g.tensor_base + i].dtype == HXT_F32;
+            if (p.tensors[g.tensor_base + i].bytes && reinterpret_cast<uintptr_t>(b.p[i]) % 16) aligned = false;
         }
-        with_hints(ntp, [&]<bool NTU, bool NTP>() {
-            k_contig_accumulate<CSUM, NTU, NTP><<<g.count, kThreads, 0, st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, b,
-                                                                              kinds, packed, cx);
-        });
+        if (aligned)
+            with_hints(ntp, [&]<bool NTU, bool NTP>() {
+                k_contig_accumulate<CSUM, NTU, NTP><<<g.count, kThreads, 0, st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles,
+                                                                                  b, kinds, packed, cx);
+            });
+        else
+            k_contig_accumulate_any<CSUM><<<g.count, kThreads, 0, st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, b, kinds,
+                                                                        packed, cx);
         HXT_HIP(hipGetLastError());
     }
     return HXT_OK;
@@ -900,8 +909,6 @@ int hxt_unpack_accumulate(const hxt_plan_t *plan, const void *packed, void *cons
     if ((rc = check_tensor_pointers(plan->p, dst)) != HXT_OK) return rc;
     const Plan &p = plan->p;
     if (!p.can_accumulate) return HXT_EUNSUPPORTED;
-    for (size_t i = 0; i < p.tensors.size(); ++i)
-        if (p.tensors[i].bytes && reinterpret_cast<uintptr_t>(dst[i]) % 16) return HXT_EALIGN;
     hxt_plan_t &pl = *const_cast<hxt_plan_t *>(plan);
     hipStream_t st = static_cast<hipStream_t>(stream);
     uint8_t *pk = const_cast<uint8_t *>(static_cast<const uint8_t *>(packed));

@@ -258,11 +258,10 @@ __device__ __forceinline__ u32x4 add_vec(u32x4 old, u32x4 in)
 // Adds `bytes` arriving contiguous bytes at pk to the tensor bytes at user (both 16-byte aligned
 // except for a last partial vector, which goes element by element).  Returns the checksum
 // contribution of the packed bytes read.
-template <bool F32, bool CSUM, bool NTU, bool NTP>
+template <bool F32, bool CSUM, bool NTU, bool NTP, int UA = 16>
 __device__ __forceinline__ uint64_t accumulate_span(uint8_t *user, const uint8_t *pk, uint32_t bytes)
 {
     const u32x4 *in = reinterpret_cast<const u32x4 *>(pk);
-    u32x4 *io = reinterpret_cast<u32x4 *>(user);
     const uint32_t nvec = bytes >> 4;
     constexpr int U = 2;                                   // two vectors of each operand in flight per thread
     constexpr uint32_t STEP = kThreads * U;
@@ -273,17 +272,18 @@ __device__ __forceinline__ uint64_t accumulate_span(uint8_t *user, const uint8_t
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             a[u] = load16<NTP>(in + v + u * kThreads);
-            b[u] = load16<NTU>(io + v + u * kThreads);
+            b[u] = load_user<UA, NTU>(user + (size_t(v + u * kThreads) << 4));
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            store16<NTU>(io + v + u * kThreads, add_vec<F32>(b[u], a[u]));
+            store_user<UA, NTU>(user + (size_t(v + u * kThreads) << 4), add_vec<F32>(b[u], a[u]));
             if constexpr (CSUM) acc += words_sum(a[u]);
         }
     }
     for (uint32_t v = full + threadIdx.x; v < nvec; v += kThreads) {
         const u32x4 a = load16<NTP>(in + v);
-        store16<NTU>(io + v, add_vec<F32>(load16<NTU>(io + v), a));
+        uint8_t *at = user + (size_t(v) << 4);
+        store_user<UA, NTU>(at, add_vec<F32>(load_user<UA, NTU>(at), a));
         if constexpr (CSUM) acc += words_sum(a);
     }
     constexpr uint32_t ES = F32 ? 4 : 2;
@@ -444,6 +444,48 @@ __global__ __launch_bounds__(kThreads) void k_uniform_accumulate(UniformArgs a)
                              : accumulate_span<false, CSUM, NTU, NTP>(it.user + t.stream_off, pk, data);
     if (data < t.len) acc += pad_span<true, CSUM>(pk + data, t.len - data, data);
     if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, t.expected, it.cx);
+}
+
+// The same for destinations whose base is only element aligned.
+template <bool F32, bool CSUM>
+__device__ __forceinline__ uint64_t accumulate_span_any(uint8_t *user, const uint8_t *pk, uint32_t bytes)
+{
+    const uint32_t mis = uint32_t(reinterpret_cast<uintptr_t>(user)) & 15u;
+    if (mis == 0) return accumulate_span<F32, CSUM, false, false, 16>(user, pk, bytes);
+    if ((mis & 3u) == 0) return accumulate_span<F32, CSUM, false, false, 4>(user, pk, bytes);
+    return accumulate_span<F32, CSUM, false, false, 2>(user, pk, bytes);      // bf16 on an odd element
+}
+
+template <bool CSUM>
+__global__ __launch_bounds__(kThreads) void k_uniform_accumulate_any(UniformArgs a)
+{
+    const UniformItem &it = a.it[0];
+    const ChunkGeom &g = it.g;
+    const TileSpan t = locate_tile(g, blockIdx.x);
+    const uint64_t left = g.N > t.stream_off ? g.N - t.stream_off : 0;
+    const uint32_t data = left < t.len ? uint32_t(left) : t.len;
+    uint8_t *pk = it.packed + t.packed_off;
+    uint64_t acc = it.unpack ? accumulate_span_any<true, CSUM>(it.user + t.stream_off, pk, data)
+                             : accumulate_span_any<false, CSUM>(it.user + t.stream_off, pk, data);
+    if (data < t.len) acc += pad_span<true, CSUM>(pk + data, t.len - data, data);
+    if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, t.expected, it.cx);
+}
+
+template <bool CSUM>
+__global__ __launch_bounds__(kThreads) void k_contig_accumulate_any(const Tile *__restrict__ tiles,
+                                                                    const uint32_t *__restrict__ chunk_tiles,
+                                                                    BasePtrs bases, ElemKinds kinds,
+                                                                    uint8_t *__restrict__ packed, SumCtx cx)
+{
+    const Tile t = tiles[blockIdx.x];
+    uint64_t acc;
+    if (t.kind == K_ZERO)
+        acc = pad_span<true, CSUM>(packed + t.packed_off, t.n0, uint32_t(t.packed_off));
+    else if (kinds.f32[t.tensor])
+        acc = accumulate_span_any<true, CSUM>(bases.p[t.tensor] + t.src_off, packed + t.packed_off, t.n0);
+    else
+        acc = accumulate_span_any<false, CSUM>(bases.p[t.tensor] + t.src_off, packed + t.packed_off, t.n0);
+    if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, chunk_tiles[t.chunk], cx);
 }
 
 template <bool CSUM, bool NTU, bool NTP>

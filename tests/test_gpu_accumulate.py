@@ -86,9 +86,42 @@ def test_accumulate_refuses_what_it_does_not_support():
         assert e.value.status == hxt.HXT_EUNSUPPORTED
     ok = hxt.hxt_plan((64,), None, 2, 2, 256)
     with pytest.raises(hxt.HxtError) as e:
-        hxt.hxt_unpack_accumulate(ok, buf, [buf[2:]], None)              # element aligned only
+        hxt.hxt_unpack_accumulate(ok, buf, [buf[1:]], None)              # not even element aligned
     assert e.value.status == hxt.HXT_EALIGN
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("offset", [2, 4, 8, 12, 6])
+@pytest.mark.parametrize("case", CASES, ids=lambda c: c.name)
+def test_accumulate_into_element_aligned_destinations(case, offset):
+    """Destinations that start 2 to 12 bytes off a 16-byte boundary (slices of a larger gradient buffer): same
+    arithmetic, narrower accesses on the destination side."""
+    if offset % max(e for (_, _, e) in case.tensors):
+        pytest.skip("offset is not a multiple of the element size")
+    rng = np.random.default_rng(zlib.crc32((case.name + str(offset)).encode()))
+    m = ho.Message([ho.TensorSpec(tuple(s), tuple(st), e) for (s, st, e) in case.tensors])
+    kinds = [ho.KIND_BF16 if e == 2 else ho.KIND_F32 for (_, _, e) in case.tensors]
+    sizes = [int(np.prod(s)) * e for (s, _, e) in case.tensors]
+    incoming = [draw(rng, n, e, "near") for n, (_, _, e) in zip(sizes, case.tensors)]
+    local = [draw(rng, n, e, "near") for n, (_, _, e) in zip(sizes, case.tensors)]
+    packed_o = ho.pack(m, incoming, case.B, case.k, fill=0)
+    want = [x.copy() for x in local]
+    ho.unpack_accumulate(m, kinds, packed_o, case.B, case.k, want)
+    p = hxt.hxt_plan_multi([(s, st, e) for (s, st, e) in case.tensors], case.k, case.B)
+    dst = []
+    for x in local:
+        buf = torch.full((x.size + offset + 32,), 0x3C, dtype=torch.uint8, device=DEV)
+        buf[offset:offset + x.size].copy_(torch.from_numpy(x))
+        dst.append(buf)
+    views = [b[offset:offset + x.size] for b, x in zip(dst, local)]
+    sums = torch.zeros(p.num_chunks, dtype=torch.int64, device=DEV)
+    hxt.hxt_unpack_accumulate(p, torch.from_numpy(packed_o).to(DEV), views, sums)
+    torch.cuda.synchronize()
+    for a, b, x in zip(want, dst, local):
+        got = b.cpu().numpy()
+        assert np.array_equal(got[offset:offset + x.size], a)
+        assert (got[:offset] == 0x3C).all() and (got[offset + x.size:] == 0x3C).all(), "bytes outside the tensor were touched"
+    assert np.array_equal(sums.cpu().numpy().view(np.uint64), ho.checksum(m, packed_o, case.B, case.k))
 
 
 def test_accumulate_gradient_bucket_shape():
