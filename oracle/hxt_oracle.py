@@ -189,6 +189,11 @@ def chunk_info(msg: Message, B: int, k: int, c: int) -> dict:
     )
 
 
+def stream_to_packed(L_: int, B: int, k: int, s: int) -> int:
+    """Packed position of stream byte s of a stream of L_ bytes."""
+    return lib().hxo_stream_to_packed(L_, B, k, s)
+
+
 def lane_info(msg: Message, B: int, k: int, lane: int) -> dict:
     L_ = msg.L
     l = lib()

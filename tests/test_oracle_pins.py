@@ -74,6 +74,28 @@ def test_packed_chunk_order_matches_hand_written(C, k, order):
     assert deal_order(C, k) == order          # the helper used below agrees with the fixture
 
 
+@pytest.mark.parametrize("C,k,order", golden_orders())
+def test_stream_byte_to_packed_position_matches_hand_written_orders(C, k, order):
+    # The hand-dealt order says in which slot of the packed buffer a chunk sits; a stream byte keeps its
+    # position inside its chunk.  Also with a short last chunk (it still owns a whole slot).
+    B = 512
+    for L_ in (C * B, (C - 1) * B + 256):
+        for c in range(C):
+            last = min((c + 1) * B, L_) - 1
+            for s in (c * B, c * B + 77, last):
+                assert ho.stream_to_packed(L_, B, k, s) == order.index(c) * B + (s - c * B)
+
+
+def test_stream_byte_to_packed_position_agrees_with_pack():
+    # pack moves stream byte s of a one-tensor byte message to exactly that position
+    case = Case("g", (contig((7 * 256 + 100,), 1),), 3, 512)
+    m = msg_of(case)
+    raw = np.arange(case.tensors[0][0][0], dtype=np.uint32).astype(np.uint8)
+    packed = ho.pack(m, [raw], 512, 3, fill=0xEE)
+    for s in range(raw.size):
+        assert packed[ho.stream_to_packed(m.L, 512, 3, s)] == raw[s]
+
+
 def test_short_last_chunk_keeps_its_full_slot():
     # 5 chunks over 2 lanes, last chunk 256 of 512 bytes: lane 0 holds chunks 0,2,4 and the
     # short chunk 4 still occupies a whole slot, so lane 1 starts at 3*512.
