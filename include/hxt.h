@@ -345,6 +345,31 @@ int hxt_unpack_verify(const hxt_plan_t *plan, const void *packed, const hxt_chun
                       uint64_t seq, uint32_t micro_batch, void *const *dst, uint32_t *status,
                       void *stream);
 
+/* ---- for callers that cannot allocate ----------------------------------------------
+ * Code under HIP graph capture, tight serving loops and harnesses that forbid allocation
+ * cannot create a plan (hxt_plan* allocates device memory).  hxt_pack_noalloc is hxt_pack for
+ * a message that is ONE contiguous tensor of message_bytes bytes at `src` (device, any
+ * alignment; 16-byte aligned is the fast path), with the same layout contract, the same
+ * packed bytes and the same checksums as hxt_pack on hxt_plan({message_bytes}, NULL, 1,
+ * HXT_U8, n_lanes, chunk_bytes).  It needs no plan, and neither it nor anything it calls
+ * allocates host or device memory: the geometry is computed on the stack, and the checksum
+ * accumulators live in a fixed 1 MiB device array that is part of the library image (each
+ * GPU the library runs on holds its copy until the process ends).
+ *   packed: device, >= ceil(L / chunk_bytes) * chunk_bytes with L = message_bytes rounded up
+ *           to 256; 256-byte aligned.
+ *   sums:   NULL, or device array of ceil(L / chunk_bytes) uint64.
+ * Limit: with checksums, num_chunks * (f + 1) <= 4096, where f = 1 for chunks of fewer than
+ * 128 tiles of 16 KiB (chunk_bytes < 2 MiB), else the largest power of two <= min(16,
+ * tiles per chunk / 64); HXT_EUNSUPPORTED beyond (nothing is enqueued).  Other errors as
+ * hxt_plan / hxt_pack.  message_bytes == 0 is a no-op.
+ * All calls on one GPU share that array (the call zero-fills the part it uses, with a
+ * kernel, on `stream` first): calls that ask for checksums and overlap in time on one GPU,
+ * on different streams or from a replayed graph, race; order them.  The device address of
+ * the array is looked up on the first call on each device: make that call before stream
+ * capture begins. */
+int hxt_pack_noalloc(const void *src, size_t message_bytes, int n_lanes, size_t chunk_bytes,
+                     void *packed, uint64_t *sums, void *stream);
+
 /* ---- diagnostics -------------------------------------------------------------- */
 const char *hxt_strerror(int status);
 int hxt_last_hip_error(void);    /* hipError_t of the last failing HIP call on this thread */

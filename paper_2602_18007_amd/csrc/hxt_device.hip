@@ -51,6 +51,15 @@ struct hxt_plan {
     OpState ops[OP_COUNT];
 };
 
+// Accumulator slots for the entry point that may not allocate (hxt_pack_noalloc).  Every GPU the library
+// runs on holds its own copy of this array until the process ends.  In host code the name is only a
+// stand-in for the symbol: its device address is asked for once per device (scratch_on_device) and that
+// pointer, never the name, is what kernels and fills receive.
+constexpr size_t kScratchBytes = size_t(1) << 20;
+constexpr uint32_t kScratchSlotStride = 256;
+constexpr size_t kScratchSlots = kScratchBytes / kScratchSlotStride;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 namespace {
 
 // ---- host side --------------------------------------------------------------------
@@ -211,6 +220,39 @@ uint32_t single_word_bits(uint64_t chunk_bytes, uint32_t arrivals)
 uint32_t max_arrivals(uint32_t tiles, uint32_t fan)
 {
     return fan == 1 ? tiles : std::max((tiles + fan - 1) / fan, 2 * fan);
+}
+
+// First-level accumulator slots per chunk for chunks of up to `most` tiles: chunks of 128 tiles or more fan
+// out over up to 16 slots so that a few dozen arrivals at most queue on one address (measured: a 25 MiB
+// chunk of 1600 tiles loses 20 % without it, a 1 MiB chunk of 64 tiles is faster with a single slot).
+uint32_t choose_fan(uint32_t most)
+{
+    uint32_t fan = 1;
+    while (fan < 16 && most >= 128 * fan) fan *= 2;
+    fan = uint32_t(std::max(1, std::min<int>(int(fan), env_int("HXT_FAN", 16))));
+    while (fan & (fan - 1)) fan &= fan - 1;                               // keep a power of two
+    return fan;
+}
+
+// Device address of this GPU's copy of `scratch`, looked up once per device with that device current.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+uint8_t *g_scratch_ptr[kMaxDevices] = {nullptr};
+
+int scratch_on_device(uint8_t **out)
+{
+    int dev = -1;
+    HXT_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return HXT_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        HXT_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return hip_fail(hipErrorInvalidSymbol);
+        g_scratch_ptr[dev] = static_cast<uint8_t *>(ptr);
+    }
+    *out = g_scratch_ptr[dev];
+    return HXT_OK;
 }
 
 template <bool UNPACK, bool CSUM>
@@ -389,16 +431,11 @@ int upload(hxt_plan_t &pl)
     if ((rc = to_device(&pl.d_tiles, p.tiles)) != HXT_OK) return rc;
     if ((rc = to_device(&pl.d_chunk_tiles, p.chunk_tiles)) != HXT_OK) return rc;
     if ((rc = to_device(&pl.d_tensors, p.tdev)) != HXT_OK) return rc;
-    // Accumulator slots.  Chunks of 128 tiles or more fan out over up to 16 first-level slots so
-    // that a few dozen arrivals at most queue on one address (measured: a 25 MiB chunk of 1600
-    // tiles loses 20 % without it, a 1 MiB chunk of 64 tiles is faster with a single slot); slots
-    // are 256 bytes apart (separate memory channels) unless that would be large.
+    // Accumulator slots: fan-out as choose_fan says; slots are 256 bytes apart (separate memory
+    // channels) unless that would be large.
     uint32_t most = p.geom.tpc;
     for (uint32_t n : p.chunk_tiles) most = std::max(most, n);
-    pl.fan = 1;
-    while (pl.fan < 16 && most >= 128 * pl.fan) pl.fan *= 2;
-    pl.fan = uint32_t(std::max(1, std::min<int>(int(pl.fan), env_int("HXT_FAN", 16))));
-    while (pl.fan & (pl.fan - 1)) pl.fan &= pl.fan - 1;                    // keep a power of two
+    pl.fan = choose_fan(most);
     const bool two_word = env_int("HXT_TWO_WORD_COMMIT", 0) != 0;
     uint32_t most_table = 0;
     for (uint32_t n : p.chunk_tiles) most_table = std::max(most_table, n);
@@ -1037,6 +1074,61 @@ int hxt_exchange_stream(const hxt_plan_t *plan, const hxt_exchange_t *x)
     }
     cleanup();
     return rc;
+}
+
+// hxt_pack for a message that is one contiguous tensor, with no plan and no allocation: the geometry is
+// closed form (host arithmetic on the stack) and the checksum accumulators live in this GPU's `scratch`.
+int hxt_pack_noalloc(const void *src, size_t message_bytes, int n_lanes, size_t chunk_bytes, void *packed,
+                     uint64_t *sums, void *stream)
+{
+    if (n_lanes < 1 || n_lanes > 1024 || chunk_bytes == 0 || chunk_bytes % HXT_ALIGN) return HXT_EINVAL;
+    if (message_bytes > (uint64_t(1) << 40)) return HXT_EUNSUPPORTED;
+    if (message_bytes == 0) return HXT_OK;
+    if (!src || !packed) return HXT_EINVAL;
+    if (reinterpret_cast<uintptr_t>(packed) % HXT_ALIGN) return HXT_EALIGN;
+    const uint32_t tile = uint32_t(env_int("HXT_TILE_BYTES", int(kDefaultTileBytes)));
+    if (tile == 0 || tile % HXT_ALIGN || tile > (1u << 24)) return HXT_EINVAL;
+    const uint64_t L = (uint64_t(message_bytes) + HXT_ALIGN - 1) / HXT_ALIGN * HXT_ALIGN;
+    UniformArgs a;
+    std::memset(&a, 0, sizeof a);
+    ChunkGeom &g = a.it[0].g;
+    int rc = make_geom(message_bytes, L, chunk_bytes, uint32_t(n_lanes), tile, g);
+    if (rc != HXT_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};
+    if (sums) {
+        const uint32_t fan = choose_fan(g.tpc);
+        const size_t slots = size_t(g.C) * (fan + 1);
+        if (slots > kScratchSlots) return HXT_EUNSUPPORTED;           // more chunks than the fixed scratch serves
+        uint8_t *ptr = nullptr;
+        if ((rc = scratch_on_device(&ptr)) != HXT_OK) return rc;
+        const bool two_word = env_int("HXT_TWO_WORD_COMMIT", 0) != 0;
+        cx = SumCtx{sums, ptr, kScratchSlotStride, two_word ? 0 : single_word_bits(chunk_bytes, max_arrivals(g.tpc, fan)),
+                    fan, g.C};
+        // The array keeps whatever the last call on this GPU left: the slots this call uses start at zero.
+        const uint32_t nvec = uint32_t(slots * kScratchSlotStride / 16);
+        k_fill_zero<<<std::min<uint32_t>((nvec + kThreads - 1) / kThreads, 256u), kThreads, 0, st>>>(
+            reinterpret_cast<u32x4 *>(ptr), nvec);
+        HXT_HIP(hipGetLastError());
+    }
+    uint8_t *user = const_cast<uint8_t *>(static_cast<const uint8_t *>(src));
+    a.n = 1;
+    a.it[0].user = user;
+    a.it[0].packed = static_cast<uint8_t *>(packed);
+    a.it[0].cx = cx;
+    a.it[0].first_tile = 0;
+    a.it[0].unpack = 0;
+    const bool ntp = packed_nontemporal(uint64_t(g.C) * g.B);
+    if (reinterpret_cast<uintptr_t>(user) % 16 == 0) {
+        if (sums) launch_uniform<DIR_PACK, true>(a, g.ntiles, ntp, st);
+        else launch_uniform<DIR_PACK, false>(a, g.ntiles, ntp, st);
+    } else if (sums) {
+        k_uniform_any<false, true><<<g.ntiles, kThreads, 0, st>>>(a);
+    } else {
+        k_uniform_any<false, false><<<g.ntiles, kThreads, 0, st>>>(a);
+    }
+    HXT_HIP(hipGetLastError());
+    return HXT_OK;
 }
 
 int hxt_checksum(const hxt_plan_t *plan, const void *packed, uint64_t *sums, void *stream)

@@ -156,6 +156,9 @@ struct Plan {
     uint64_t chunk_packed_off(uint64_t c) const { return lane_off[c % k] + (c / k) * B; }
 };
 
+// Host-only, allocation-free: the closed-form geometry alone.  Returns an hxt_status.
+int make_geom(uint64_t N, uint64_t L, uint64_t B, uint32_t k, uint32_t tile_bytes, ChunkGeom &g);
+
 // Host-only construction of every table (no HIP call).  Returns an hxt_status.
 int build_plan(const hxt_tensor_desc_t *tensors, int n_tensors, int n_lanes, size_t chunk_bytes,
                uint32_t tile_bytes, Plan &out);

@@ -1104,6 +1104,12 @@ __global__ __launch_bounds__(kThreads) void k_copy_tags(u32x4 *__restrict__ to, 
     for (uint32_t v = blockIdx.x * kThreads + threadIdx.x; v < nvec; v += gridDim.x * kThreads) to[v] = from[v];
 }
 
+// Zero-fill of nvec 16-byte vectors (a kernel, so that it can be recorded where a memset node cannot).
+__global__ __launch_bounds__(kThreads) void k_fill_zero(u32x4 *__restrict__ p, uint32_t nvec)
+{
+    for (uint32_t v = blockIdx.x * kThreads + threadIdx.x; v < nvec; v += gridDim.x * kThreads) p[v] = u32x4{0, 0, 0, 0};
+}
+
 // status[C] = number of chunks of status[0 .. C) that were rejected.  One workgroup.
 __global__ __launch_bounds__(kThreads) void k_count_rejected(uint32_t *status, uint32_t C)
 {

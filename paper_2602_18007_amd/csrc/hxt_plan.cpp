@@ -22,6 +22,32 @@ FastDiv make_fastdiv(uint32_t d)
     return FastDiv{uint32_t(mul), s};
 }
 
+// Closed-form geometry of a packed stream of L bytes (a multiple of 256) cut into chunks of B bytes over k
+// lanes, with tiles of tile_bytes; N = tensor bytes when the stream is one contiguous tensor, else 0.
+int make_geom(uint64_t N, uint64_t L, uint64_t B, uint32_t k, uint32_t tile_bytes, ChunkGeom &g)
+{
+    std::memset(&g, 0, sizeof g);
+    const uint64_t C = (L + B - 1) / B;
+    if (C >= (uint64_t(1) << 31)) return HXT_EUNSUPPORTED;
+    g.N = N;
+    g.L = L;
+    g.B = B;
+    g.k = k;
+    g.C = uint32_t(C);
+    g.tile = tile_bytes;
+    const uint64_t tpc = (B + tile_bytes - 1) / tile_bytes;
+    if (tpc * std::max<uint64_t>(C, 1) >= (uint64_t(1) << 31)) return HXT_EUNSUPPORTED;
+    g.tpc = uint32_t(tpc);
+    g.q = uint32_t(C / k);
+    g.r = uint32_t(C % k);
+    const uint64_t last = C ? L - (C - 1) * B : 0;
+    g.last_tiles = uint32_t((last + tile_bytes - 1) / tile_bytes);
+    g.ntiles = C ? uint32_t((C - 1) * tpc) + g.last_tiles : 0;
+    g.div_tpc = make_fastdiv(g.tpc);
+    g.div_k = make_fastdiv(g.k);
+    return HXT_OK;
+}
+
 static int dtype_size(hxt_dtype_t dt)
 {
     switch (dt) {
@@ -313,21 +339,7 @@ int build_plan(const hxt_tensor_desc_t *descs, int n_tensors, int n_lanes, size_
     }
     // closed-form geometry of the packed stream (stand-alone checksum; uniform copy)
     ChunkGeom &g = p.geom;
-    std::memset(&g, 0, sizeof g);
-    g.L = p.L;
-    g.B = p.B;
-    g.k = uint32_t(p.k);
-    g.C = uint32_t(p.C);
-    g.tile = tile_bytes;
-    const uint64_t tpc = (p.B + tile_bytes - 1) / tile_bytes;
-    if (tpc * std::max<uint64_t>(p.C, 1) >= (uint64_t(1) << 31)) return HXT_EUNSUPPORTED;
-    g.tpc = uint32_t(tpc);
-    g.q = uint32_t(p.C / p.k);
-    g.r = uint32_t(p.C % p.k);
-    g.last_tiles = p.C ? uint32_t((p.chunk_padded(p.C - 1) + tile_bytes - 1) / tile_bytes) : 0;
-    g.ntiles = p.C ? uint32_t((p.C - 1) * tpc) + g.last_tiles : 0;
-    g.div_tpc = make_fastdiv(g.tpc);
-    g.div_k = make_fastdiv(g.k);
+    if (int rc = make_geom(0, p.L, p.B, uint32_t(p.k), tile_bytes, g); rc != HXT_OK) return rc;
     int live = 0;
     for (int i = 0; i < n_tensors; ++i)
         if (p.tensors[i].bytes) {

@@ -31,6 +31,7 @@ EXPORTS = (
     "hxt_plan_tensor_kind", "hxt_pack", "hxt_stage_d2h", "hxt_stage_h2d", "hxt_unpack", "hxt_checksum",
     "hxt_pack_batch", "hxt_unpack_batch", "hxt_exchange_stream", "hxt_unpack_accumulate",
     "hxt_host_forward", "hxt_stage_hop", "hxt_checksum2", "hxt_seal", "hxt_verify", "hxt_pack_seal", "hxt_unpack_verify",
+    "hxt_pack_noalloc",
     "hxt_strerror", "hxt_last_hip_error", "hxt_version",
 )
 
@@ -122,6 +123,7 @@ def lib():
             "hxt_pack_batch": (i, [i, C.POINTER(vp), C.POINTER(C.POINTER(vp)), C.POINTER(vp), C.POINTER(vp), vp]),
             "hxt_unpack_batch": (i, [i, C.POINTER(vp), C.POINTER(vp), C.POINTER(C.POINTER(vp)), C.POINTER(vp), vp]),
             "hxt_exchange_stream": (i, [vp, C.POINTER(_Exchange)]),
+            "hxt_pack_noalloc": (i, [vp, sz, i, sz, vp, u64p, vp]),
             "hxt_strerror": (C.c_char_p, [i]),
             "hxt_last_hip_error": (i, []),
             "hxt_version": (C.c_char_p, []),
@@ -360,6 +362,11 @@ def hxt_pack_seal(plan: Plan, src: Sequence, packed, seq: int, micro_batch: int,
 def hxt_unpack_verify(plan: Plan, packed, tags, seq: int, micro_batch: int, dst: Sequence, status, stream=None) -> None:
     _check(lib().hxt_unpack_verify(plan.handle, _ptr(packed), _ptr(tags), seq, micro_batch, _ptr_array(dst),
                                    _ptr(status), _stream(stream)), "hxt_unpack_verify")
+
+
+def hxt_pack_noalloc(src, message_bytes: int, n_lanes: int, chunk_bytes: int, packed, sums=None, stream=None) -> None:
+    _check(lib().hxt_pack_noalloc(_ptr(src), message_bytes, n_lanes, chunk_bytes, _ptr(packed), _ptr(sums),
+                                  _stream(stream)), "hxt_pack_noalloc")
 
 
 def hxt_stage_d2h(plan: Plan, lane: int, packed_dev, host_pinned, stream=None) -> None:
