@@ -128,6 +128,18 @@ int hxt_plan_multi(const hxt_tensor_desc_t *tensors, int n_tensors,
                    int n_lanes, size_t chunk_bytes, hxt_plan_t **out);
 int hxt_plan_destroy(hxt_plan_t *plan); /* NULL is allowed */
 
+/* ---- per-plan options (host only; not in the paper: tuning switches of this library) --
+ * HXT_OPT_PACKED_HINT: cache hint of the packed-buffer side of every copy and pass of this plan.
+ *   -1 (default) by size: cacheable while packed_bytes <= 128 MiB, so that a packed buffer that is
+ *      re-read soon (by the wire, or by hxt_unpack on the same GPU) can be served from the 256 MB
+ *      last-level cache; non-temporal above;
+ *    0 always cacheable;  1 always non-temporal (every byte goes to and comes from HBM).
+ *   The environment variable HXT_NT_PACKED (0/1), read when a plan is created, sets the initial value.
+ * Takes effect for calls made afterwards; do not change it while calls on the plan are being issued
+ * from other threads.  HXT_EINVAL for an unknown option or value. */
+typedef enum { HXT_OPT_PACKED_HINT = 1 } hxt_option_t;
+int hxt_plan_set_option(hxt_plan_t *plan, int option, int value);
+
 /* ---- queries (host only) ---------------------------------------------------- */
 size_t hxt_plan_message_bytes(const hxt_plan_t *plan); /* N */
 size_t hxt_plan_stream_bytes(const hxt_plan_t *plan);  /* L */

@@ -48,6 +48,7 @@ struct hxt_plan {
     uint32_t fan = 1;                           // first-level accumulator slots per chunk
     uint32_t sum_bits_table = 0, sum_bits_geom = 0;   // see slot_arrive: table-driven copies / closed-form kernels
     int device = -1;
+    int nt_packed = -1;                         // HXT_OPT_PACKED_HINT: -1 by size, 0 cacheable, 1 non-temporal
     OpState ops[OP_COUNT];
 };
 
@@ -107,6 +108,11 @@ inline bool packed_nontemporal(uint64_t packed_bytes)
     return o >= 0 ? o != 0 : packed_bytes > kCacheablePackedLimit;
 }
 
+inline bool packed_nontemporal(const hxt_plan_t &pl)
+{
+    return pl.nt_packed >= 0 ? pl.nt_packed != 0 : packed_nontemporal(pl.p.C * pl.p.B);
+}
+
 // Calls f.template operator()<NTU, NTP>() for the chosen cache hints.
 template <typename F>
 void with_hints(bool nt_packed, F &&f)
@@ -131,7 +137,7 @@ template <bool UNPACK, bool CSUM>
 void launch_contig(const hxt_plan_t &pl, const Group &g, const BasePtrs &b, uint8_t *packed, const SumCtx &cx,
                    hipStream_t st)
 {
-    with_hints(packed_nontemporal(pl.p.C * pl.p.B), [&]<bool NTU, bool NTP>() {
+    with_hints(packed_nontemporal(pl), [&]<bool NTU, bool NTP>() {
         k_contig<UNPACK, CSUM, NTU, NTP><<<g.count, kThreads, 0, st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, b, packed, cx);
     });
 }
@@ -140,7 +146,7 @@ template <bool UNPACK, bool CSUM>
 void launch_rows(const hxt_plan_t &pl, const Group &g, const BasePtrs &b, uint8_t *packed, const SumCtx &cx,
                  hipStream_t st)
 {
-    with_hints(packed_nontemporal(pl.p.C * pl.p.B), [&]<bool NTU, bool NTP>() {
+    with_hints(packed_nontemporal(pl), [&]<bool NTU, bool NTP>() {
         k_rows<UNPACK, CSUM, NTU, NTP><<<g.count, kThreads, 0, st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, pl.d_tensors,
                                                                      g.tensor_base, b, packed, cx);
     });
@@ -276,7 +282,7 @@ int run_copy(hxt_plan_t &pl, void *const *ptrs, uint8_t *packed, uint64_t *sums,
         a.n = 1;
         a.it[0] = UniformItem{p.geom, base, packed, cx, 0, UNPACK};
         if (reinterpret_cast<uintptr_t>(base) % 16 == 0)
-            launch_uniform<UNPACK ? DIR_UNPACK : DIR_PACK, CSUM>(a, p.geom.ntiles, packed_nontemporal(p.C * p.B), st);
+            launch_uniform<UNPACK ? DIR_UNPACK : DIR_PACK, CSUM>(a, p.geom.ntiles, packed_nontemporal(pl), st);
         else                                             // element aligned only: narrower accesses on the tensor side
             k_uniform_any<UNPACK, CSUM><<<p.geom.ntiles, kThreads, 0, st>>>(a);
         HXT_HIP(hipGetLastError());
@@ -334,7 +340,7 @@ int run_accumulate(hxt_plan_t &pl, void *const *ptrs, uint8_t *packed, uint64_t 
         if (rc != HXT_OK) return rc;
         cx.sum_bits = pl.sum_bits_table;
     }
-    const bool ntp = packed_nontemporal(p.C * p.B);
+    const bool ntp = packed_nontemporal(pl);
     if (p.uniform) {
         const TensorPlan &tp = p.tensors[p.uniform_tensor];
         UniformArgs a;
@@ -419,6 +425,7 @@ int to_device(T **dst, const std::vector<T> &src)
 
 int upload(hxt_plan_t &pl)
 {
+    pl.nt_packed = tuning().nt_packed;
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess) {
         (void)hipGetLastError();
@@ -555,8 +562,10 @@ int run_batch(int n, const hxt_plan_t *const *plans, void *const *const *tensors
             ++j;
         }
         constexpr int DIR = UNPACK ? DIR_UNPACK : DIR_PACK;
-        if (sm) launch_uniform<DIR, true>(a, uint32_t(tiles), packed_nontemporal(bytes), st);
-        else launch_uniform<DIR, false>(a, uint32_t(tiles), packed_nontemporal(bytes), st);
+        // cache hint of the launch: the first message's plan decides if it has been told to, else the bytes of the launch
+        const bool ntp = plans[i]->nt_packed >= 0 ? plans[i]->nt_packed != 0 : packed_nontemporal(bytes);
+        if (sm) launch_uniform<DIR, true>(a, uint32_t(tiles), ntp, st);
+        else launch_uniform<DIR, false>(a, uint32_t(tiles), ntp, st);
         HXT_HIP(hipGetLastError());
         i = j;
     }
@@ -579,7 +588,7 @@ int run_sum2(const hxt_plan_t *plan, const void *packed, int mode, void *out, co
     SlotsLock lock(g_slots_mu);
     if ((rc = claim_slots(pl, mode == SUM2_VERIFY ? (chain ? OP_SUM2_RECV_B : OP_SUM2_RECV) : (chain ? OP_SUM2_SEND_B : OP_SUM2_SEND), st, cx, nullptr)) != HXT_OK) return rc;
     const uint8_t *pk = static_cast<const uint8_t *>(packed);
-    const bool ntp = packed_nontemporal(pl.p.C * pl.p.B);
+    const bool ntp = packed_nontemporal(pl);
     auto launch = [&]<int MODE>() {
         TagWork w = work;
         w.sum_bits = pl.sum_bits_geom;
@@ -626,7 +635,7 @@ int run_copy_tag(const hxt_plan_t *plan, void *const *ptrs, void *packed, void *
     if ((rc = claim_slots(pl, UNPACK ? (chain ? OP_SUM2_RECV_B : OP_SUM2_RECV) : (chain ? OP_SUM2_SEND_B : OP_SUM2_SEND), st, cx, nullptr)) != HXT_OK) return rc;
     TagWork w = work;
     w.sum_bits = pl.sum_bits_geom;
-    with_hints(packed_nontemporal(p.C * p.B), [&]<bool NTU, bool NTP>() {
+    with_hints(packed_nontemporal(pl), [&]<bool NTU, bool NTP>() {
         k_uniform_tag<UNPACK, MODE, NTU, NTP><<<p.geom.ntiles, kThreads, 0, st>>>(p.geom, base, pk, out, cx.acc, cx.stride,
                                                                                  cx.fan, w);
     });
@@ -643,7 +652,7 @@ int fused_direct_stream(hxt_plan_t &pl, const hxt_exchange_t &x, hipStream_t sp,
 {
     const Plan &p = pl.p;
     const size_t T = p.tensors.size();
-    const bool nt_packed = packed_nontemporal(p.C * p.B);
+    const bool nt_packed = packed_nontemporal(pl);
     SlotsLock lock(g_slots_mu);
     for (int k = 0; k <= x.n_messages; ++k) {
         UniformArgs a;
@@ -787,6 +796,18 @@ int hxt_plan_destroy(hxt_plan_t *plan)
     return rc;
 }
 
+int hxt_plan_set_option(hxt_plan_t *plan, int option, int value)
+{
+    if (!plan) return HXT_EINVAL;
+    switch (option) {
+    case HXT_OPT_PACKED_HINT:
+        if (value < -1 || value > 1) return HXT_EINVAL;
+        plan->nt_packed = value;
+        return HXT_OK;
+    }
+    return HXT_EINVAL;
+}
+
 size_t hxt_plan_message_bytes(const hxt_plan_t *plan) { return plan ? plan->p.N : 0; }
 size_t hxt_plan_stream_bytes(const hxt_plan_t *plan) { return plan ? plan->p.L : 0; }
 size_t hxt_plan_packed_bytes(const hxt_plan_t *plan) { return plan ? plan->p.C * plan->p.B : 0; }
@@ -893,16 +914,21 @@ int hxt_host_forward(const hxt_plan_t *plan, int lane, const void *from, void *t
         for (int l : lanes) copy_lane(l);
         return HXT_OK;
     }
+    // A worker takes lanes w, w + workers, ...  If a thread cannot be created, the threads that did start
+    // are joined and the lanes of the missing workers are copied here: the copy still completes.
+    std::thread pool[64];
+    const size_t n_pool = std::min<size_t>(workers, 64);
+    auto work = [&](size_t w) {
+        for (size_t i = w; i < lanes.size(); i += n_pool) copy_lane(lanes[i]);
+    };
+    size_t started = 0;
     try {
-        std::vector<std::thread> pool;
-        for (size_t w = 0; w < workers; ++w)
-            pool.emplace_back([&, w] {
-                for (size_t i = w; i < lanes.size(); i += workers) copy_lane(lanes[i]);
-            });
-        for (std::thread &t : pool) t.join();
-    } catch (const std::exception &) {
-        return HXT_ENOMEM;                         // thread creation failed
+        for (; started + 1 < n_pool; ++started) pool[started] = std::thread(work, started + 1);
+    } catch (...) {
     }
+    work(0);                                         // the calling thread is worker 0
+    for (size_t w = 0; w < started; ++w) pool[w].join();
+    for (size_t w = started + 1; w < n_pool; ++w) work(w);      // workers that never started
     return HXT_OK;
 }
 
@@ -1143,7 +1169,7 @@ int hxt_checksum(const hxt_plan_t *plan, const void *packed, uint64_t *sums, voi
     if ((rc = claim_slots(pl, OP_CHECKSUM, st, cx, sums)) != HXT_OK) return rc;
     cx.sum_bits = pl.sum_bits_geom;
     const uint8_t *pk = static_cast<const uint8_t *>(packed);
-    if (packed_nontemporal(pl.p.C * pl.p.B))
+    if (packed_nontemporal(pl))
         k_checksum<true><<<pl.p.geom.ntiles, kThreads, 0, st>>>(pl.p.geom, pk, cx);
     else
         k_checksum<false><<<pl.p.geom.ntiles, kThreads, 0, st>>>(pl.p.geom, pk, cx);

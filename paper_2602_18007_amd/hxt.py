@@ -31,7 +31,7 @@ EXPORTS = (
     "hxt_plan_tensor_kind", "hxt_pack", "hxt_stage_d2h", "hxt_stage_h2d", "hxt_unpack", "hxt_checksum",
     "hxt_pack_batch", "hxt_unpack_batch", "hxt_exchange_stream", "hxt_unpack_accumulate",
     "hxt_host_forward", "hxt_stage_hop", "hxt_checksum2", "hxt_seal", "hxt_verify", "hxt_pack_seal", "hxt_unpack_verify",
-    "hxt_pack_noalloc",
+    "hxt_pack_noalloc", "hxt_plan_set_option",
     "hxt_strerror", "hxt_last_hip_error", "hxt_version",
 )
 
@@ -96,6 +96,7 @@ def lib():
             "hxt_plan": (i, [i64p, i64p, i, i, i, sz, C.POINTER(vp)]),
             "hxt_plan_multi": (i, [C.POINTER(_TensorDesc), i, i, sz, C.POINTER(vp)]),
             "hxt_plan_destroy": (i, [vp]),
+            "hxt_plan_set_option": (i, [vp, i, i]),
             "hxt_plan_message_bytes": (sz, [vp]),
             "hxt_plan_stream_bytes": (sz, [vp]),
             "hxt_plan_packed_bytes": (sz, [vp]),
@@ -148,6 +149,12 @@ def _dtype_code(dt) -> int:
     raise ValueError("unsupported dtype %r" % (dt,))
 
 
+def _names_arithmetic(dt) -> bool:
+    """True if dt says what the bits mean as numbers (the library adds bf16 and f32 only).  An integer
+    torch dtype or a bare element size describes raw bits: such data can be moved, not added."""
+    return isinstance(dt, torch.dtype) and dt in (torch.bfloat16, torch.float32)
+
+
 def _ptr(x) -> Optional[int]:
     if x is None:
         return None
@@ -174,8 +181,9 @@ def _ptr_array(xs: Sequence):
 class Plan:
     """Owner of one hxt_plan_t handle."""
 
-    def __init__(self, handle: int):
+    def __init__(self, handle: int, arithmetic: bool = False):
         self.handle = C.c_void_p(handle)
+        self.arithmetic = arithmetic      # every tensor was described by torch.bfloat16 / torch.float32
 
     def destroy(self):
         if self.handle:
@@ -226,7 +234,7 @@ def hxt_plan(shape, strides, dtype, n_lanes: int, chunk_bytes: int) -> Plan:
     st = (C.c_int64 * max(nd, 1))(*strides) if strides is not None else None
     out = C.c_void_p()
     _check(lib().hxt_plan(shp, st, nd, _dtype_code(dtype), n_lanes, chunk_bytes, C.byref(out)), "hxt_plan")
-    return Plan(out.value)
+    return Plan(out.value, _names_arithmetic(dtype))
 
 
 def hxt_plan_multi(tensors: Sequence, n_lanes: int, chunk_bytes: int) -> Plan:
@@ -234,6 +242,7 @@ def hxt_plan_multi(tensors: Sequence, n_lanes: int, chunk_bytes: int) -> Plan:
     n = len(tensors)
     descs = (_TensorDesc * max(n, 1))()
     keep = []
+    arithmetic = True
     for j, t in enumerate(tensors):
         if isinstance(t, torch.Tensor):
             shape, strides, dt = tuple(t.shape), tuple(t.stride()), t.dtype
@@ -247,9 +256,17 @@ def hxt_plan_multi(tensors: Sequence, n_lanes: int, chunk_bytes: int) -> Plan:
         descs[j].shape = shp
         descs[j].strides = st
         descs[j].dtype = _dtype_code(dt)
+        arithmetic = arithmetic and (_names_arithmetic(dt) or 0 in shape)
     out = C.c_void_p()
     _check(lib().hxt_plan_multi(descs, n, n_lanes, chunk_bytes, C.byref(out)), "hxt_plan_multi")
-    return Plan(out.value)
+    return Plan(out.value, arithmetic)
+
+
+HXT_OPT_PACKED_HINT = 1
+
+
+def hxt_plan_set_option(plan: Plan, option: int, value: int) -> None:
+    _check(lib().hxt_plan_set_option(plan.handle, option, value), "hxt_plan_set_option")
 
 
 def hxt_plan_destroy(plan: Plan) -> None:
@@ -281,6 +298,9 @@ def hxt_stage_hop(plan: Plan, lane: int, from_pinned, to_pinned, n_threads: int 
 
 
 def hxt_unpack_accumulate(plan: Plan, packed, dst: Sequence, sums=None, stream=None) -> None:
+    if not plan.arithmetic:
+        raise ValueError("hxt_unpack_accumulate adds bf16 or f32 values: build the plan with torch.bfloat16 / "
+                         "torch.float32, not with an integer dtype or a bare element size (those only name raw bits)")
     _check(lib().hxt_unpack_accumulate(plan.handle, _ptr(packed), _ptr_array(dst), _ptr(sums), _stream(stream)),
            "hxt_unpack_accumulate")
 

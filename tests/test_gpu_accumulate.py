@@ -11,6 +11,7 @@ from paper_2602_18007_amd import hxt
 from tests.cases import Case, contig
 
 pytestmark = pytest.mark.gpu
+FLOAT_OF = {2: torch.bfloat16, 4: torch.float32}
 DEV = "cuda:0"
 
 
@@ -55,7 +56,7 @@ def test_accumulate_matches_oracle(case, mode):
     want = [x.copy() for x in local]
     ho.unpack_accumulate(m, kinds, packed_o, case.B, case.k, want)
 
-    p = hxt.hxt_plan_multi([(s, st, e) for (s, st, e) in case.tensors], case.k, case.B)
+    p = hxt.hxt_plan_multi([(s, st, FLOAT_OF[e]) for (s, st, e) in case.tensors], case.k, case.B)
     packed = torch.from_numpy(packed_o).to(DEV)
     dst = [torch.from_numpy(x.copy()).to(DEV) for x in local]
     sums = torch.full((p.num_chunks,), -1, dtype=torch.int64, device=DEV)
@@ -76,15 +77,24 @@ def test_accumulate_matches_oracle(case, mode):
 
 
 def test_accumulate_refuses_what_it_does_not_support():
-    strided = hxt.hxt_plan((8, 64), (128, 1), 2, 2, 256)
+    strided = hxt.hxt_plan((8, 64), (128, 1), torch.bfloat16, 2, 256)
     half = hxt.hxt_plan((64,), None, torch.float16, 2, 256)
     bytes_ = hxt.hxt_plan((64,), None, 1, 2, 256)
     buf = torch.zeros(4096, dtype=torch.uint8, device=DEV)
-    for p in (strided, half, bytes_):
-        with pytest.raises(hxt.HxtError) as e:
-            hxt.hxt_unpack_accumulate(p, buf, [buf], None)
-        assert e.value.status == hxt.HXT_EUNSUPPORTED
-    ok = hxt.hxt_plan((64,), None, 2, 2, 256)
+    with pytest.raises(hxt.HxtError) as e:
+        hxt.hxt_unpack_accumulate(strided, buf, [buf], None)
+    assert e.value.status == hxt.HXT_EUNSUPPORTED
+    # the library refuses element kinds it cannot add ...
+    ptrs = (hxt.C.c_void_p * 1)(buf.data_ptr())
+    for p in (half, bytes_):
+        assert hxt.lib().hxt_unpack_accumulate(p.handle, buf.data_ptr(), ptrs, None, None) == hxt.HXT_EUNSUPPORTED
+    # ... and the binding refuses plans whose dtype only names raw bits: an integer dtype or a bare element size
+    # would otherwise be added as if it were bf16 / f32
+    for dt in (2, 4, torch.int16, torch.int32, torch.float16):
+        raw_bits = hxt.hxt_plan((64,), None, dt, 2, 256)
+        with pytest.raises(ValueError):
+            hxt.hxt_unpack_accumulate(raw_bits, buf, [buf], None)
+    ok = hxt.hxt_plan((64,), None, torch.bfloat16, 2, 256)
     with pytest.raises(hxt.HxtError) as e:
         hxt.hxt_unpack_accumulate(ok, buf, [buf[1:]], None)              # not even element aligned
     assert e.value.status == hxt.HXT_EALIGN
@@ -107,7 +117,7 @@ def test_accumulate_into_element_aligned_destinations(case, offset):
     packed_o = ho.pack(m, incoming, case.B, case.k, fill=0)
     want = [x.copy() for x in local]
     ho.unpack_accumulate(m, kinds, packed_o, case.B, case.k, want)
-    p = hxt.hxt_plan_multi([(s, st, e) for (s, st, e) in case.tensors], case.k, case.B)
+    p = hxt.hxt_plan_multi([(s, st, FLOAT_OF[e]) for (s, st, e) in case.tensors], case.k, case.B)
     dst = []
     for x in local:
         buf = torch.full((x.size + offset + 32,), 0x3C, dtype=torch.uint8, device=DEV)
@@ -138,7 +148,7 @@ def test_accumulate_gradient_bucket_shape():
     packed_o = ho.pack(m, incoming, case.B, case.k, nthreads=8)
     want = [x.copy() for x in local]
     ho.unpack_accumulate(m, [ho.KIND_BF16] * 9, packed_o, case.B, case.k, want, nthreads=8)
-    p = hxt.hxt_plan_multi([(s, st, e) for (s, st, e) in case.tensors], case.k, case.B)
+    p = hxt.hxt_plan_multi([(s, st, FLOAT_OF[e]) for (s, st, e) in case.tensors], case.k, case.B)
     src = [torch.from_numpy(x).to(DEV) for x in incoming]
     packed = torch.zeros(p.packed_bytes, dtype=torch.uint8, device=DEV)
     s1 = torch.zeros(p.num_chunks, dtype=torch.int64, device=DEV)
@@ -152,6 +162,40 @@ def test_accumulate_gradient_bucket_shape():
         assert np.array_equal(b.cpu().numpy(), a)
 
 
+def test_accumulate_full_size_gradient_buckets():
+    """The real gradient message (36 tensors, 1.7 GB, 25 MiB chunks of 1600 tiles, 8 lanes): hxt_pack then
+    hxt_unpack_accumulate, every element against the oracle.  At this size the packed side is accessed with
+    non-temporal hints and every chunk's checksum commit fans out over 16 first-level slots."""
+    from paper_2602_18007_amd import workloads as wl
+    w = wl.grad_buckets()
+    T = len(w.tensors)
+    print("full-size accumulate: drawing 2 x", w.message_bytes, "bytes", flush=True)
+    incoming = wl.make_storages(w)
+    rng = np.random.default_rng(18007 + 77)
+    local = [wl.draw_u16(t.nbytes // 2, "normal", 0.02, rng).view(np.uint8) for t in w.tensors]
+    local[1][:4] = np.array([0x3F80, 0x3F81], np.uint16).view(np.uint8)      # two exact ties, as in the small cases
+    incoming[1][:4] = np.array([0x3B80, 0x3B80], np.uint16).view(np.uint8)
+    m = ho.Message([ho.TensorSpec(t.shape, t.strides, t.esize) for t in w.tensors])
+    p = hxt.hxt_plan_multi([(t.shape, t.strides, torch.bfloat16) for t in w.tensors], w.n_lanes, w.chunk_bytes)
+    src = [torch.from_numpy(x).to(DEV) for x in incoming]
+    dst = [torch.from_numpy(x).to(DEV) for x in local]
+    packed = torch.zeros(p.packed_bytes, dtype=torch.uint8, device=DEV)
+    s1 = torch.zeros(p.num_chunks, dtype=torch.int64, device=DEV)
+    s2 = torch.full_like(s1, -1)
+    hxt.hxt_pack(p, src, packed, s1)
+    hxt.hxt_unpack_accumulate(p, packed, dst, s2)
+    torch.cuda.synchronize()
+    print("full-size accumulate: oracle", flush=True)
+    nt = ho.max_threads()
+    packed_o = ho.pack(m, incoming, w.chunk_bytes, w.n_lanes, fill=0, nthreads=nt)
+    want_sums = ho.checksum(m, packed_o, w.chunk_bytes, w.n_lanes, nthreads=nt)
+    ho.unpack_accumulate(m, [ho.KIND_BF16] * T, packed_o, w.chunk_bytes, w.n_lanes, local, nthreads=nt)   # in place
+    assert np.array_equal(s1.cpu().numpy().view(np.uint64), want_sums)
+    assert np.array_equal(s2.cpu().numpy().view(np.uint64), want_sums)
+    for t, (a, b) in enumerate(zip(local, dst)):
+        assert np.array_equal(b.cpu().numpy(), a), "tensor %d differs" % t
+
+
 def test_accumulate_can_be_captured_in_a_hip_graph_and_replayed():
     """pack + receive-and-accumulate recorded once and replayed: every replay adds the arriving gradients again,
     bit for bit as the oracle does when applied the same number of times."""
@@ -162,7 +206,7 @@ def test_accumulate_can_be_captured_in_a_hip_graph_and_replayed():
     sizes = [int(np.prod(s)) * e for (s, _, e) in case.tensors]
     incoming = [draw(rng, n, e, "grad") for n, (_, _, e) in zip(sizes, case.tensors)]
     local = [draw(rng, n, e, "grad") for n, (_, _, e) in zip(sizes, case.tensors)]
-    p = hxt.hxt_plan_multi([(s, st, e) for (s, st, e) in case.tensors], case.k, case.B)
+    p = hxt.hxt_plan_multi([(s, st, FLOAT_OF[e]) for (s, st, e) in case.tensors], case.k, case.B)
     src = [torch.from_numpy(x.copy()).to(DEV) if x.size else torch.zeros(16, dtype=torch.uint8, device=DEV) for x in incoming]
     dst = [torch.from_numpy(x.copy()).to(DEV) if x.size else torch.zeros(16, dtype=torch.uint8, device=DEV) for x in local]
     packed = torch.zeros(p.packed_bytes, dtype=torch.uint8, device=DEV)

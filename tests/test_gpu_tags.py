@@ -203,6 +203,67 @@ def test_fused_calls_on_the_full_size_boundary_message():
     assert torch.equal(src[0], dst[0])
 
 
+def full_size_tag_check(w, tensors, raws):
+    """seal / verify and the fused calls at full size against the oracle: tags byte for byte, masks word for word,
+    packed and destination bytes, and a bit flipped on the host that must be reported in exactly its chunk."""
+    B, k = w.chunk_bytes, w.n_lanes
+    m = ho.Message([ho.TensorSpec(t.shape, t.strides, t.esize) for t in tensors])
+    p = hxt.hxt_plan_multi([(t.shape, t.strides, t.esize) for t in tensors], k, B)
+    C = p.num_chunks
+    seq, mb = 0x0102030405060708, 17
+    print("full-size tags:", w.name, m.N, "bytes,", C, "chunks: oracle", flush=True)
+    want_packed = ho.pack(m, raws, B, k, fill=0xA5, nthreads=ho.max_threads())
+    want_tags = ho.seal(m, want_packed, B, k, seq, mb)
+    src = [torch.from_numpy(r).to(DEV) for r in raws]
+    packed = torch.full((p.packed_bytes,), 0xA5, dtype=torch.uint8, device=DEV)
+    tags = torch.full((C * 64,), 0xEE, dtype=torch.uint8, device=DEV)
+    hxt.hxt_pack_seal(p, src, packed, seq, mb, tags)
+    assert np.array_equal(packed.cpu().numpy(), want_packed), "fused pack+seal: packed bytes"
+    assert np.array_equal(tags.cpu().numpy().reshape(C, 64), want_tags), "fused pack+seal: tags"
+    tags2 = torch.full_like(tags, 0x11)
+    hxt.hxt_seal(p, packed, seq, mb, tags2)
+    assert torch.equal(tags, tags2), "stand-alone seal"
+    status = torch.full((C + 1,), 0x7FFFFFFF, dtype=torch.int32, device=DEV)
+    hxt.hxt_verify(p, packed, tags, seq, mb, status)
+    assert not status.cpu().numpy().any()
+    dst = [torch.zeros_like(s_) for s_ in src]
+    status.fill_(0x7FFFFFFF)
+    hxt.hxt_unpack_verify(p, packed, tags, seq, mb, dst, status)
+    assert not status.cpu().numpy().any()
+    for t, (a, b) in enumerate(zip(src, dst)):
+        assert torch.equal(a, b), "tensor %d after unpack+verify" % t
+    # damage planted from the host: one bit of a chunk in the middle, one byte of the last chunk
+    hit = sorted({C // 2, C - 1})
+    for c in hit:
+        off = p.chunk_info(c)["packed_off"] + 4 * 1000 + 2
+        packed[off] = int(want_packed[off]) ^ 0x10
+        want_packed[off] ^= 0x10
+    want_status = ho.verify(m, want_packed, want_tags, B, k, seq, mb)
+    assert int(want_status[C]) == len(hit)
+    for fused in (False, True):
+        status.fill_(0x7FFFFFFF)
+        if fused:
+            hxt.hxt_unpack_verify(p, packed, tags, seq, mb, dst, status)
+        else:
+            hxt.hxt_verify(p, packed, tags, seq, mb, status)
+        assert np.array_equal(status.cpu().numpy().view(np.uint32), want_status), "masks, fused=%s" % fused
+    torch.cuda.synchronize()
+
+
+def test_tags_on_the_full_size_gradient_buckets():
+    w = wl.grad_buckets()
+    full_size_tag_check(w, w.tensors, wl.make_storages(w))
+
+
+def test_tags_on_a_single_tensor_larger_than_the_cacheable_limit():
+    # one contiguous bf16 tensor of 160 MiB + 4 KiB + 6 bytes (above 128 MiB the packed side is non-temporal),
+    # 4 lanes, 4 MiB chunks of 256 tiles (fanned-out commits), ragged last chunk
+    n = (160 << 20) + 4096 + 6
+    t = wl.TensorDesc.contiguous((n // 2,))
+    w = wl.Workload("single_160MiB", (t,), 4, 4 << 20, "bits16", seed=18007 + 91)
+    full_size_tag_check(w, w.tensors, wl.make_storages(w))
+
+
 def test_a_stale_ping_pong_buffer_is_caught_by_its_tags():
     """Six micro-batches through two buffer sets; the sender skips message 4 (a lost send), so the receiver finds
     message 2 still sitting in the buffer: every chunk is rejected for its sequence number and micro-batch id, the
