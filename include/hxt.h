@@ -241,24 +241,34 @@ int hxt_unpack_batch(int n, const hxt_plan_t *const *plans, const void *const *p
  * Section 2.2's control plane for a 1F1B schedule, where a stage sends one micro-batch
  * while the previous one is still in flight.
  *   path HXT_DEVICE_DIRECT: unpack reads packed_send[b] (packed_recv, host_pinned unused).
- *       Which stream runs what is then the library's choice, the results and the
- *       completion rule below being the same: with an even n_buffers and distinct
- *       stream_pack / stream_unpack, even messages are packed and unpacked on
- *       stream_pack and odd messages on stream_unpack (two independent chains whose
- *       kernels overlap, no events inside); otherwise single-tensor messages go as
- *       launches that unpack message i-1 and pack message i together, and anything
- *       else as event-chained calls.
+ *       Which stream runs what is then chosen by direct_mode, the results and the
+ *       completion rule below being the same:
+ *       HXT_DIRECT_TWO_CHAINS  even messages are packed and unpacked on stream_pack and odd
+ *           messages on stream_unpack (two independent chains whose kernels overlap, no events
+ *           inside); needs an even n_buffers and distinct stream_pack / stream_unpack.  This
+ *           is loopback-shaped: a message is unpacked right behind its own pack.
+ *       HXT_DIRECT_FUSED  launches on stream_pack that unpack message i-1 and pack message i
+ *           together; needs n_buffers >= 2, single-tensor 16-byte aligned messages, no tags.
+ *       HXT_DIRECT_EVENTS  pack on stream_pack, unpack on stream_unpack after an event, as at
+ *           a real boundary where the unpack waits for the arrival; any message.
+ *       HXT_DIRECT_AUTO  the first of the three, in that order, that the arguments allow.
  *   path HXT_CPU_FORWARD  : packed_send[b] -> host_pinned[b] -> packed_recv[b] -> unpack.
  * src/dst: n_messages * n_tensors device pointers, message-major.  send_sums/recv_sums:
  * NULL or device arrays of n_messages * num_chunks uint64, message-major.
- * The call only enqueues, with one exception: on the HXT_CPU_FORWARD path it waits on
- * the host for the three streams to drain after every 12 messages (environment
- * HXT_DRAIN_EVERY, 0 = never), because the runtime stops overlapping the two copy
- * directions once more than about 16 messages' worth of copies and event waits are
- * outstanding; such a call must not be made under stream capture.  When the three
- * streams have drained, every message has arrived.  HXT_EINVAL: n_messages < 0, n_buffers < 1, a NULL array that the path needs,
+ * The call only enqueues and never waits on the host, unless the caller asks for it with
+ * drain_every > 0 (HXT_CPU_FORWARD only): the call then waits for the three streams to run empty
+ * after every drain_every messages.  That is a workaround for the HIP runtime on this machine,
+ * which stops overlapping the two copy directions once more than about 16 messages' worth of copies
+ * and event waits are outstanding (12 is the measured best); such a call blocks the calling thread
+ * and must not be made under stream capture.  With drain_every == 0 a caller can get the same
+ * effect without blocking inside the library by issuing the stream in windows of its own
+ * (n_messages <= 12 per call, waiting for the streams between calls).  When the three streams have
+ * drained, every message has arrived.
+ * HXT_EINVAL: n_messages < 0, n_buffers < 1, drain_every < 0, an unknown direct_mode or one that the
+ * arguments do not allow, a NULL array that the path needs;
  * a NULL stream handle shared by two roles is allowed (the steps then serialise). */
 typedef enum { HXT_DEVICE_DIRECT = 0, HXT_CPU_FORWARD = 1 } hxt_path_t;
+typedef enum { HXT_DIRECT_AUTO = 0, HXT_DIRECT_TWO_CHAINS = 1, HXT_DIRECT_FUSED = 2, HXT_DIRECT_EVENTS = 3 } hxt_direct_mode_t;
 
 typedef struct {
     int n_messages;
@@ -283,6 +293,8 @@ typedef struct {
     void *const *tags_pinned;  /* [n_buffers] pinned host (CPU forwarding) */
     uint32_t *status;          /* device, n_messages * (num_chunks + 1): hxt_verify's result per message */
     uint64_t seq_base;
+    int direct_mode;           /* hxt_direct_mode_t; HXT_DEVICE_DIRECT only */
+    int drain_every;           /* 0 = enqueue only; > 0: wait on the host after every so many messages (HXT_CPU_FORWARD) */
 } hxt_exchange_t;
 
 int hxt_exchange_stream(const hxt_plan_t *plan, const hxt_exchange_t *x);
@@ -346,9 +358,10 @@ int hxt_seal(const hxt_plan_t *plan, const void *packed, uint64_t seq, uint32_t 
 int hxt_verify(const hxt_plan_t *plan, const void *packed, const hxt_chunk_tag_t *tags, uint64_t seq,
                uint32_t micro_batch, uint32_t *status, void *stream);
 
-/* The same, fused into the copies (no extra pass over the message when it is one
- * contiguous 16-byte aligned tensor; otherwise the two passes run one after the other on
- * the stream, with identical results): hxt_pack_seal = hxt_pack + hxt_seal,
+/* The same, fused into the copies (no extra pass over the message when all its tensors
+ * are contiguous and 16-byte aligned: one activation, or a bucket of gradients; otherwise
+ * the two passes run one after the other on the stream, with identical results):
+ * hxt_pack_seal = hxt_pack + hxt_seal,
  * hxt_unpack_verify = hxt_verify + hxt_unpack.  The destination is written whatever the
  * verdict; the caller reads `status` before using it.  Arguments as in those calls. */
 int hxt_pack_seal(const hxt_plan_t *plan, const void *const *src, void *packed, uint64_t seq,
@@ -381,6 +394,19 @@ int hxt_unpack_verify(const hxt_plan_t *plan, const void *packed, const hxt_chun
  * capture begins. */
 int hxt_pack_noalloc(const void *src, size_t message_bytes, int n_lanes, size_t chunk_bytes,
                      void *packed, uint64_t *sums, void *stream);
+
+/* The fused tag calls for several messages at once, as hxt_pack_batch / hxt_unpack_batch are for
+ * the plain sums: exactly the result of n hxt_pack_seal / hxt_unpack_verify calls on `stream` in
+ * order; messages that consist of one contiguous 16-byte aligned tensor share launches (up to 4 per
+ * launch).  seq[i], micro_batch[i], tags[i], status[i] belong to message i.  HXT_EINVAL also if a
+ * plan appears twice.  Nothing is enqueued on error. */
+int hxt_pack_seal_batch(int n, const hxt_plan_t *const *plans, const void *const *const *src,
+                        void *const *packed, const uint64_t *seq, const uint32_t *micro_batch,
+                        hxt_chunk_tag_t *const *tags, void *stream);
+int hxt_unpack_verify_batch(int n, const hxt_plan_t *const *plans, const void *const *packed,
+                            const hxt_chunk_tag_t *const *tags, const uint64_t *seq,
+                            const uint32_t *micro_batch, void *const *const *dst,
+                            uint32_t *const *status, void *stream);
 
 /* ---- diagnostics -------------------------------------------------------------- */
 const char *hxt_strerror(int status);

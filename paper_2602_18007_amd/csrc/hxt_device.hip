@@ -307,6 +307,9 @@ int run_copy(hxt_plan_t &pl, void *const *ptrs, uint8_t *packed, uint64_t *sums,
         } else if (g.kernel == K_ROWS) {
             k_rows_any<UNPACK, CSUM><<<g.count, kThreads, 0, st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, pl.d_tensors,
                                                                    g.tensor_base, b, packed, cx);
+        } else if (g.kernel == K_ROWS_SPLIT) {
+            k_rows_split<UNPACK, CSUM><<<g.count, kThreads, 0, st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, pl.d_tensors,
+                                                                     g.tensor_base, b, packed, cx);
         } else {
             // The transpose and per-element kernels are instantiated per element size: issue one
             // launch per run of tiles whose tensors share it (host table, same order as on the device).
@@ -622,7 +625,11 @@ int run_copy_tag(const hxt_plan_t *plan, void *const *ptrs, void *packed, void *
     hipStream_t st = static_cast<hipStream_t>(stream);
     uint8_t *pk = static_cast<uint8_t *>(packed);
     uint8_t *base = p.uniform ? static_cast<uint8_t *>(ptrs[p.uniform_tensor]) : nullptr;
-    if (!p.uniform || reinterpret_cast<uintptr_t>(base) % 16) {
+    bool aligned = true;                                 // every live tensor's base on a 16-byte boundary
+    for (size_t i = 0; i < p.tensors.size(); ++i)
+        aligned = aligned && (p.tensors[i].bytes == 0 || reinterpret_cast<uintptr_t>(ptrs[i]) % 16 == 0);
+    const bool one_pass = aligned && (p.uniform || p.all_contig);
+    if (!one_pass) {
         if (UNPACK) {                                    // check what arrived, then scatter it
             if ((rc = run_sum2(plan, packed, MODE, out, work, stream, chain)) != HXT_OK) return rc;
             return run_copy<true, false>(pl, ptrs, pk, nullptr, st, chain);
@@ -634,12 +641,103 @@ int run_copy_tag(const hxt_plan_t *plan, void *const *ptrs, void *packed, void *
     SlotsLock lock(g_slots_mu);
     if ((rc = claim_slots(pl, UNPACK ? (chain ? OP_SUM2_RECV_B : OP_SUM2_RECV) : (chain ? OP_SUM2_SEND_B : OP_SUM2_SEND), st, cx, nullptr)) != HXT_OK) return rc;
     TagWork w = work;
-    w.sum_bits = pl.sum_bits_geom;
-    with_hints(packed_nontemporal(pl), [&]<bool NTU, bool NTP>() {
-        k_uniform_tag<UNPACK, MODE, NTU, NTP><<<p.geom.ntiles, kThreads, 0, st>>>(p.geom, base, pk, out, cx.acc, cx.stride,
-                                                                                 cx.fan, w);
-    });
-    HXT_HIP(hipGetLastError());
+    if (p.uniform) {
+        w.sum_bits = pl.sum_bits_geom;
+        UniformTagArgs a;
+        std::memset(&a, 0, sizeof a);
+        a.n = 1;
+        a.it[0] = UniformTagItem{p.geom, base, pk, out, cx.acc, cx.stride, cx.fan, w, 0};
+        with_hints(packed_nontemporal(pl), [&]<bool NTU, bool NTP>() {
+            k_uniform_tag<UNPACK, MODE, NTU, NTP><<<p.geom.ntiles, kThreads, 0, st>>>(a);
+        });
+        HXT_HIP(hipGetLastError());
+        return HXT_OK;
+    }
+    // contiguous tensors of a multi-tensor message: the table-driven copy with both sums taken on the way; the
+    // chunks' accumulators carry over from one launch group to the next
+    w.sum_bits = pl.sum_bits_table;
+    for (const Group &g : p.groups) {
+        BasePtrs b;
+        std::memset(&b, 0, sizeof b);
+        for (uint32_t i = 0; i < g.n_tensors; ++i) b.p[i] = static_cast<uint8_t *>(ptrs[g.tensor_base + i]);
+        with_hints(packed_nontemporal(pl), [&]<bool NTU, bool NTP>() {
+            k_contig_tag<UNPACK, MODE, NTU, NTP><<<g.count, kThreads, 0, st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, b, pk,
+                                                                               p.geom, out, cx.acc, cx.stride, cx.fan, w);
+        });
+        HXT_HIP(hipGetLastError());
+    }
+    return HXT_OK;
+}
+
+// Batched pack + seal / unpack + verify: messages that are one contiguous 16-byte aligned tensor share
+// launches (up to kMaxBatch each), the rest go one by one.
+template <bool UNPACK>
+int run_tag_batch(int n, const hxt_plan_t *const *plans, void *const *const *tensors, void *const *packed,
+                  void *const *outs, const hxt_chunk_tag_t *const *tags_in, const uint64_t *seq,
+                  const uint32_t *micro_batch, hipStream_t st)
+{
+    constexpr int MODE = UNPACK ? SUM2_VERIFY : SUM2_SEAL;
+    if (n < 0 || (n > 0 && (!plans || !tensors || !packed || !outs || !seq || !micro_batch || (UNPACK && !tags_in))))
+        return HXT_EINVAL;
+    for (int i = 0; i < n; ++i) {                      // validate everything before enqueuing anything
+        if (!plans[i]) return HXT_EINVAL;
+        if (plans[i]->p.C == 0) {
+            if (UNPACK && !outs[i]) return HXT_EINVAL;
+            continue;
+        }
+        int rc = check_common(plans[i], packed[i]);
+        if (rc != HXT_OK) return rc;
+        if ((rc = check_tensor_pointers(plans[i]->p, tensors[i])) != HXT_OK) return rc;
+        if (!outs[i] || (UNPACK && !tags_in[i])) return HXT_EINVAL;
+        if (reinterpret_cast<uintptr_t>(outs[i]) % (UNPACK ? 4 : 16)) return HXT_EALIGN;
+        if (UNPACK && reinterpret_cast<uintptr_t>(tags_in[i]) % 16) return HXT_EALIGN;
+        if (UNPACK && !plans[i]->p.all_unpack_safe) return HXT_EOVERLAP;
+        for (int j = 0; j < i; ++j)
+            if (plans[j] == plans[i]) return HXT_EINVAL;     // one accumulator set per plan
+    }
+    SlotsLock lock(g_slots_mu);
+    int i = 0;
+    while (i < n) {
+        auto work_of = [&](int j) {
+            return TagWork{UNPACK ? reinterpret_cast<const uint8_t *>(tags_in[j]) : nullptr, seq[j], micro_batch[j], 0};
+        };
+        auto fusable = [&](int j) {
+            const Plan &q = plans[j]->p;
+            return q.C != 0 && q.uniform && reinterpret_cast<uintptr_t>(tensors[j][q.uniform_tensor]) % 16 == 0;
+        };
+        if (!fusable(i)) {
+            int rc;
+            if (plans[i]->p.C == 0)
+                rc = UNPACK ? hxt_verify(plans[i], packed[i], tags_in[i], seq[i], micro_batch[i], static_cast<uint32_t *>(outs[i]), st)
+                            : HXT_OK;
+            else
+                rc = run_copy_tag<UNPACK>(plans[i], tensors[i], packed[i], outs[i], work_of(i), st);
+            if (rc != HXT_OK) return rc;
+            ++i;
+            continue;
+        }
+        UniformTagArgs a;
+        std::memset(&a, 0, sizeof a);
+        uint64_t tiles = 0, bytes = 0;
+        int j = i;
+        while (j < n && a.n < uint32_t(kMaxBatch) && fusable(j) && tiles + plans[j]->p.geom.ntiles < (uint64_t(1) << 31)) {
+            hxt_plan_t &pj = *const_cast<hxt_plan_t *>(plans[j]);
+            SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};
+            int rc = claim_slots(pj, UNPACK ? OP_SUM2_RECV : OP_SUM2_SEND, st, cx, nullptr);
+            if (rc != HXT_OK) return rc;
+            TagWork w = work_of(j);
+            w.sum_bits = pj.sum_bits_geom;
+            a.it[a.n++] = UniformTagItem{pj.p.geom, static_cast<uint8_t *>(tensors[j][pj.p.uniform_tensor]),
+                                         static_cast<uint8_t *>(packed[j]), outs[j], cx.acc, cx.stride, cx.fan, w, uint32_t(tiles)};
+            tiles += pj.p.geom.ntiles;
+            bytes += pj.p.C * pj.p.B;
+            ++j;
+        }
+        const bool ntp = plans[i]->nt_packed >= 0 ? plans[i]->nt_packed != 0 : packed_nontemporal(bytes);
+        with_hints(ntp, [&]<bool NTU, bool NTP>() { k_uniform_tag<UNPACK, MODE, NTU, NTP><<<uint32_t(tiles), kThreads, 0, st>>>(a); });
+        HXT_HIP(hipGetLastError());
+        i = j;
+    }
     return HXT_OK;
 }
 
@@ -855,7 +953,8 @@ int hxt_plan_tensor_unpack_safe(const hxt_plan_t *plan, int t)
 int hxt_plan_tensor_kind(const hxt_plan_t *plan, int t)
 {
     if (!plan || t < 0 || size_t(t) >= plan->p.tensors.size()) return HXT_EINVAL;
-    return int(plan->p.tensors[t].kind);
+    const Kind k = plan->p.tensors[t].kind;
+    return k == K_ROWS_SPLIT ? int(K_ROWS) : int(k);          // both are the row gather
 }
 
 int hxt_pack(const hxt_plan_t *plan, const void *const *src, void *packed, uint64_t *sums, void *stream)
@@ -1014,17 +1113,23 @@ int hxt_exchange_stream(const hxt_plan_t *plan, const hxt_exchange_t *x)
     }
     hipStream_t sp = static_cast<hipStream_t>(x->stream_pack), ss = static_cast<hipStream_t>(x->stream_stage),
                 su = static_cast<hipStream_t>(x->stream_unpack);
-    // HXT_STREAM_MODE: 2 = two chains on two streams (default when it applies), 1 = fused launches on one
-    // stream, 0 = event-chained calls on three streams.
-    const int mode = env_int("HXT_STREAM_MODE", 2);
-    if (!fwd && mode == 2 && x->n_buffers % 2 == 0 && sp != su)
-        return chained_direct_stream(*const_cast<hxt_plan_t *>(plan), *x, sp, su, ss);
-    if (!fwd && !tagged && mode >= 1 && x->n_buffers >= 2 && p.uniform && !x->send_sums == !x->recv_sums) {
-        bool aligned = true;
-        for (int i = 0; i < x->n_messages; ++i)
-            aligned = aligned && reinterpret_cast<uintptr_t>(x->src[i * T + p.uniform_tensor]) % 16 == 0 &&
-                      reinterpret_cast<uintptr_t>(x->dst[i * T + p.uniform_tensor]) % 16 == 0;
-        if (aligned) return fused_direct_stream(*const_cast<hxt_plan_t *>(plan), *x, sp, ss, su);
+    if (x->drain_every < 0 || x->direct_mode < HXT_DIRECT_AUTO || x->direct_mode > HXT_DIRECT_EVENTS) return HXT_EINVAL;
+    if (!fwd) {
+        const bool chains_ok = x->n_buffers % 2 == 0 && sp != su;
+        bool fused_ok = !tagged && x->n_buffers >= 2 && p.uniform && !x->send_sums == !x->recv_sums;
+        for (int i = 0; fused_ok && i < x->n_messages; ++i)
+            fused_ok = reinterpret_cast<uintptr_t>(x->src[i * T + p.uniform_tensor]) % 16 == 0 &&
+                       reinterpret_cast<uintptr_t>(x->dst[i * T + p.uniform_tensor]) % 16 == 0;
+        int mode = x->direct_mode;
+        if (mode == HXT_DIRECT_AUTO) mode = chains_ok ? HXT_DIRECT_TWO_CHAINS : (fused_ok ? HXT_DIRECT_FUSED : HXT_DIRECT_EVENTS);
+        if (mode == HXT_DIRECT_TWO_CHAINS) {
+            if (!chains_ok) return HXT_EINVAL;
+            return chained_direct_stream(*const_cast<hxt_plan_t *>(plan), *x, sp, su, ss);
+        }
+        if (mode == HXT_DIRECT_FUSED) {
+            if (!fused_ok) return HXT_EINVAL;
+            return fused_direct_stream(*const_cast<hxt_plan_t *>(plan), *x, sp, ss, su);
+        }
     }
     // per buffer set: packed (pack done), drained (send buffer may be rewritten), staged (host copy
     // complete), landed (host buffer may be rewritten), tags read (pinned tag buffer may be rewritten)
@@ -1053,7 +1158,7 @@ int hxt_exchange_stream(const hxt_plan_t *plan, const hxt_exchange_t *x)
             static_cast<u32x4 *>(to), static_cast<const u32x4 *>(from), tag_vecs);
         return hip(hipGetLastError());
     };
-    const int drain_every = env_int("HXT_DRAIN_EVERY", 12);
+    const int drain_every = x->drain_every;
     for (int i = 0; i < x->n_messages && rc == HXT_OK; ++i) {
         const int b = i % nb;
         uint64_t *s_send = x->send_sums ? x->send_sums + size_t(i) * p.C : nullptr;
@@ -1091,10 +1196,10 @@ int hxt_exchange_stream(const hxt_plan_t *plan, const hxt_exchange_t *x)
                     : hxt_unpack(plan, arrived, x->dst + i * T, s_recv, su);
         if (rc != HXT_OK) break;
         if (!fwd && !hip(hipEventRecord(at(DRAINED, b), su))) break;
-        // CPU forwarding: with more than about 16 messages' worth of copies and event waits outstanding the
-        // runtime stops overlapping the two copy directions (measured: 760 us per 32 MiB message up to 16
-        // enqueued, 1300-1900 us beyond; waiting on an older message's event does not help, an empty
-        // queue does), so the three streams are drained every few messages.  The host blocks here.
+        // CPU forwarding, on request only: with more than about 16 messages' worth of copies and event waits
+        // outstanding the runtime stops overlapping the two copy directions (measured: 760 us per 32 MiB
+        // message up to 16 enqueued, 1300-1900 us beyond; waiting on an older message's event does not help,
+        // an empty queue does), so a caller may have the three streams drained every few messages.
         if (fwd && drain_every > 0 && (i + 1) % drain_every == 0 && i + 1 < x->n_messages)
             if (!hip(hipStreamSynchronize(su)) || !hip(hipStreamSynchronize(ss)) || !hip(hipStreamSynchronize(sp))) break;
     }
@@ -1193,6 +1298,22 @@ int hxt_unpack_verify(const hxt_plan_t *plan, const void *packed, const hxt_chun
     if (plan && plan->p.C == 0) return hxt_verify(plan, packed, tags, seq, micro_batch, status, stream);
     return run_copy_tag<true>(plan, dst, const_cast<void *>(packed), status,
                               TagWork{reinterpret_cast<const uint8_t *>(tags), seq, micro_batch, 0}, stream);
+}
+
+int hxt_pack_seal_batch(int n, const hxt_plan_t *const *plans, const void *const *const *src, void *const *packed,
+                        const uint64_t *seq, const uint32_t *micro_batch, hxt_chunk_tag_t *const *tags, void *stream)
+{
+    return run_tag_batch<false>(n, plans, const_cast<void *const *const *>(src), packed,
+                                reinterpret_cast<void *const *>(tags), nullptr, seq, micro_batch,
+                                static_cast<hipStream_t>(stream));
+}
+
+int hxt_unpack_verify_batch(int n, const hxt_plan_t *const *plans, const void *const *packed,
+                            const hxt_chunk_tag_t *const *tags, const uint64_t *seq, const uint32_t *micro_batch,
+                            void *const *const *dst, uint32_t *const *status, void *stream)
+{
+    return run_tag_batch<true>(n, plans, dst, const_cast<void *const *>(packed), reinterpret_cast<void *const *>(status),
+                               tags, seq, micro_batch, static_cast<hipStream_t>(stream));
 }
 
 int hxt_checksum2(const hxt_plan_t *plan, const void *packed, uint64_t *sums2, void *stream)

@@ -23,7 +23,9 @@ enum Kind : uint16_t {
     K_ROWS = 2,       // innermost dimension contiguous, 16-byte friendly rows: gather of runs
     K_TRANSPOSE = 3,  // innermost logical dim strided, second innermost contiguous: LDS tile transpose
     K_GENERIC = 4,    // anything else: one element at a time
-    K_ZERO = 5        // pad bytes between tensors / after the last one (byte granular, < 256 bytes)
+    K_ZERO = 5,       // pad bytes between tensors / after the last one (byte granular, < 256 bytes)
+    K_ROWS_SPLIT = 6  // innermost dimension contiguous, runs of 16 bytes or more whose length or pitch is not a
+                      // multiple of 16: a 16-byte packed vector may end one run and begin the next
 };
 
 // One unit of work for one workgroup.  64 bytes of 32/64-bit fields, read with scalar loads.
@@ -31,6 +33,7 @@ enum Kind : uint16_t {
 //     packed_off : first packed byte of the piece (CONTIG/ROWS/GENERIC: multiple of 256)
 //     src_off    : logical byte offset inside the tensor (equals the storage offset for CONTIG)
 //     n0         : bytes of the piece
+//     a          : byte offset of the piece inside its chunk
 //   TRANSPOSE (a 2-D block of ni logical rows x nj logical columns inside one chunk):
 //     packed_off : packed byte of element (i0, j0);  b = packed row pitch in bytes
 //     src_off    : storage byte of element (i0, j0); a = storage pitch between columns in bytes
@@ -108,6 +111,9 @@ struct TensorDev {
     int32_t esize;
     uint32_t row_bytes;                // ROWS: bytes of one contiguous run
     uint32_t all_div;                  // 1: dim_div is valid for every dim and every shape[d] <= 2^30
+    uint32_t low_or;                   // ROWS_SPLIT: OR of the run length and the outer strides in bytes (their low bits
+                                       // give the widest naturally aligned piece the tensor side can be accessed in)
+    uint32_t reserved;
     FastDiv row_div;                   // ROWS: division by row_bytes
     FastDiv dim_div[HXT_MAX_DIMS];     // division by shape[d]: for the outer dims of a ROWS tensor, for all dims if all_div
     int64_t shape[HXT_MAX_DIMS];
@@ -128,7 +134,7 @@ struct TensorPlan {
 };
 
 struct Group {          // one kernel launch
-    Kind kernel;        // K_CONTIG (serves ZERO tiles too), K_ROWS, K_TRANSPOSE, K_GENERIC
+    Kind kernel;        // K_CONTIG (serves ZERO tiles too), K_ROWS, K_ROWS_SPLIT, K_TRANSPOSE, K_GENERIC
     uint32_t first;     // first tile
     uint32_t count;
     uint32_t tensor_base;
@@ -151,6 +157,7 @@ struct Plan {
     ChunkGeom geom;                      // closed-form geometry of the packed stream
     bool uniform = false;                // the message is one contiguous tensor: geom alone describes the copy
     uint32_t uniform_tensor = 0;         // index of that tensor
+    bool all_contig = false;             // every launch group is a contiguous copy (zero pads included)
 
     uint64_t chunk_padded(uint64_t c) const;
     uint64_t chunk_packed_off(uint64_t c) const { return lane_off[c % k] + (c / k) * B; }

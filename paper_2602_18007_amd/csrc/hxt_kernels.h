@@ -584,6 +584,158 @@ __global__ __launch_bounds__(kThreads) void k_rows_any(const Tile *__restrict__ 
     if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, chunk_tiles[t.chunk], cx);
 }
 
+// ---- rows whose length or pitch is not a multiple of 16 bytes ----------------------
+// Still a gather of contiguous runs (of 16 bytes or more), but a 16-byte vector of the packed stream may end
+// one run and begin the next, and the tensor side is only G-byte aligned (G = 8 is served as 4).  A thread
+// finds (run, column) of its vector's first byte, the storage address of that run and, if the vector
+// crosses into the next run, of that one too, and moves the 16 bytes in naturally aligned pieces of G bytes;
+// the packed side stays 16 bytes wide.
+__device__ __forceinline__ uint64_t run_storage_offset(const TensorDev &td, uint32_t row)
+{
+    uint64_t o = 0;
+    for (int d = td.ndim - 2; d > 0; --d) {
+        const uint32_t q = fast_div(row, td.dim_div[d]);
+        o += uint64_t(row - q * uint32_t(td.shape[d])) * uint64_t(td.stride_b[d]);
+        row = q;
+    }
+    return o + uint64_t(row) * uint64_t(td.stride_b[0]);
+}
+
+// Piece p (G bytes) of a 16-byte vector whose first n1 bytes are at a and the rest at b.
+template <int G>
+__device__ __forceinline__ uint8_t *piece_at(uint8_t *a, uint8_t *b, uint32_t n1, uint32_t p)
+{
+    return p * G < n1 ? a + p * G : b + (p * G - n1);
+}
+
+template <int G, bool NT>
+__device__ __forceinline__ u32x4 load_split(uint8_t *a, uint8_t *b, uint32_t n1)
+{
+    uint32_t w[4];
+    if constexpr (G == 4) {
+#pragma unroll
+        for (uint32_t p = 0; p < 4; ++p) w[p] = *reinterpret_cast<const uint32_t *>(piece_at<4>(a, b, n1, p));
+    } else if constexpr (G == 2) {
+#pragma unroll
+        for (uint32_t p = 0; p < 4; ++p)
+            w[p] = uint32_t(*reinterpret_cast<const uint16_t *>(piece_at<2>(a, b, n1, 2 * p))) |
+                   uint32_t(*reinterpret_cast<const uint16_t *>(piece_at<2>(a, b, n1, 2 * p + 1))) << 16;
+    } else {
+#pragma unroll
+        for (uint32_t p = 0; p < 4; ++p) {
+            w[p] = 0;
+#pragma unroll
+            for (uint32_t q = 0; q < 4; ++q) w[p] |= uint32_t(*piece_at<1>(a, b, n1, 4 * p + q)) << (8 * q);
+        }
+    }
+    return u32x4{w[0], w[1], w[2], w[3]};
+}
+
+template <int G>
+__device__ __forceinline__ void store_split(uint8_t *a, uint8_t *b, uint32_t n1, u32x4 v)
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    if constexpr (G == 4) {
+#pragma unroll
+        for (uint32_t p = 0; p < 4; ++p) *reinterpret_cast<uint32_t *>(piece_at<4>(a, b, n1, p)) = w[p];
+    } else if constexpr (G == 2) {
+#pragma unroll
+        for (uint32_t p = 0; p < 8; ++p)
+            *reinterpret_cast<uint16_t *>(piece_at<2>(a, b, n1, p)) = uint16_t(w[p >> 1] >> (16 * (p & 1)));
+    } else {
+#pragma unroll
+        for (uint32_t p = 0; p < 16; ++p) *piece_at<1>(a, b, n1, p) = uint8_t(w[p >> 2] >> (8 * (p & 3)));
+    }
+}
+
+template <bool UNPACK, bool CSUM, int G>
+__device__ __forceinline__ uint64_t rows_split_tile(const Tile &t, const TensorDev &td, uint8_t *user, uint8_t *pk)
+{
+    const uint32_t row_bytes = td.row_bytes;
+    const uint64_t row0 = t.src_off / row_bytes;                    // uniform
+    const uint32_t col0 = uint32_t(t.src_off - row0 * row_bytes);
+    const uint32_t nvec = t.n0 >> 4;
+    constexpr int U = 2;                                            // vectors in flight per thread
+    uint64_t acc = 0;
+    auto locate = [&](uint32_t byte, uint8_t *&a, uint32_t &n1) {   // tile byte -> address of its run position, bytes left in the run
+        const uint32_t x = col0 + byte;
+        const uint32_t dr = fast_div(x, td.row_div);
+        const uint32_t col = x - dr * row_bytes;
+        a = user + run_storage_offset(td, uint32_t(row0) + dr) + col;
+        n1 = row_bytes - col;
+        return uint32_t(row0) + dr;
+    };
+    for (uint32_t v0 = threadIdx.x; v0 < nvec; v0 += kThreads * U) {
+        u32x4 r[U];
+        uint8_t *a[U], *b[U];
+        uint32_t n1[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t v = v0 + u * kThreads;
+            a[u] = b[u] = user;
+            n1[u] = 16;
+            if (v < nvec) {
+                const uint32_t row = locate(v << 4, a[u], n1[u]);
+                if (n1[u] < 16) b[u] = user + run_storage_offset(td, row + 1);
+                else n1[u] = 16;
+                if constexpr (UNPACK) r[u] = *(reinterpret_cast<const u32x4 *>(pk) + v);
+                else r[u] = load_split<G, true>(a[u], b[u], n1[u]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t v = v0 + u * kThreads;
+            if (v < nvec) {
+                if constexpr (UNPACK) store_split<G>(a[u], b[u], n1[u], r[u]);
+                else *(reinterpret_cast<u32x4 *>(pk) + v) = r[u];
+                if constexpr (CSUM) acc += words_sum(r[u]);
+            }
+        }
+    }
+    // the last few bytes of the tensor (fewer than 16), piece by piece
+    const uint32_t tail = (t.n0 & 15u) / G;
+    if (threadIdx.x < tail) {
+        const uint32_t byte = (nvec << 4) + threadIdx.x * G;
+        uint8_t *a;
+        uint32_t n1;
+        locate(byte, a, n1);
+        uint32_t val;
+        if constexpr (G == 4) {
+            uint32_t *u = reinterpret_cast<uint32_t *>(a), *p = reinterpret_cast<uint32_t *>(pk + byte);
+            val = UNPACK ? *p : *u;
+            if constexpr (UNPACK) *u = val; else *p = val;
+        } else if constexpr (G == 2) {
+            uint16_t *u = reinterpret_cast<uint16_t *>(a), *p = reinterpret_cast<uint16_t *>(pk + byte);
+            val = UNPACK ? *p : *u;
+            if constexpr (UNPACK) *u = uint16_t(val); else *p = uint16_t(val);
+        } else {
+            uint8_t *p = pk + byte;
+            val = UNPACK ? *p : *a;
+            if constexpr (UNPACK) *a = uint8_t(val); else *p = uint8_t(val);
+        }
+        if constexpr (CSUM) acc += uint64_t(val) << (8 * (byte & 3));
+    }
+    return acc;
+}
+
+template <bool UNPACK, bool CSUM>
+__global__ __launch_bounds__(kThreads) void k_rows_split(const Tile *__restrict__ tiles,
+                                                         const uint32_t *__restrict__ chunk_tiles,
+                                                         const TensorDev *__restrict__ tensors, uint32_t tensor_base,
+                                                         BasePtrs bases, uint8_t *__restrict__ packed, SumCtx cx)
+{
+    const Tile t = tiles[blockIdx.x];
+    const TensorDev &td = tensors[tensor_base + t.tensor];
+    uint8_t *user = bases.p[t.tensor], *pk = packed + t.packed_off;
+    // widest piece that is naturally aligned everywhere: low bits of the base address, the run length and the pitches
+    const uint32_t low = (uint32_t(reinterpret_cast<uintptr_t>(user)) | td.low_or) & 15u;
+    uint64_t acc;
+    if ((low & 3u) == 0) acc = rows_split_tile<UNPACK, CSUM, 4>(t, td, user, pk);
+    else if ((low & 1u) == 0) acc = rows_split_tile<UNPACK, CSUM, 2>(t, td, user, pk);
+    else acc = rows_split_tile<UNPACK, CSUM, 1>(t, td, user, pk);
+    if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, chunk_tiles[t.chunk], cx);
+}
+
 // ---- transpose: logical inner dimension strided, the one before it contiguous ----
 // A tile is ni x nj elements (at most 128 x 128 for 1- and 2-byte elements, 64 x 64 otherwise).  Storage is read/written along i, the packed
 // stream along j, both coalesced; the swap of roles goes through a padded LDS tile.
@@ -1061,14 +1213,14 @@ __device__ __forceinline__ Sums2 copy_span2(uint8_t *user, uint8_t *pk, uint32_t
 // Pad bytes after the tensor's last byte, `first` = their byte position in the tile: pack writes zeros
 // (which add nothing to either sum), unpack adds what it finds there.
 template <bool UNPACK>
-__device__ __forceinline__ Sums2 pad_span2(uint8_t *pk, uint32_t bytes, uint32_t first)
+__device__ __forceinline__ Sums2 pad_span2(uint8_t *pk, uint32_t bytes, uint64_t first)
 {
     Sums2 acc{0, 0};
     for (uint32_t i = threadIdx.x; i < bytes; i += kThreads) {
         if constexpr (!UNPACK) {
             pk[i] = 0;
         } else {
-            const uint32_t pos = first + i;
+            const uint64_t pos = first + i;
             const uint64_t val = uint64_t(pk[i]) << (8 * (pos & 3));
             acc.s += val;
             acc.w += uint64_t((pos >> 2) + 1) * val;
@@ -1077,23 +1229,71 @@ __device__ __forceinline__ Sums2 pad_span2(uint8_t *pk, uint32_t bytes, uint32_t
     return acc;
 }
 
+// One launch serves up to kMaxBatch such messages (workgroups [first_tile, first_tile + ntiles) belong to
+// message i), as k_uniform does for the plain sums.
+struct UniformTagItem {
+    ChunkGeom g;
+    uint8_t *user;
+    uint8_t *packed;
+    void *out;             // SEAL: the message's tags; VERIFY: its status words
+    uint8_t *acc;          // the plan's pair-of-sums accumulator slots
+    uint32_t stride, fan;
+    TagWork work;
+    uint32_t first_tile;
+};
+
+struct UniformTagArgs {
+    UniformTagItem it[kMaxBatch];
+    uint32_t n;
+};
+
 template <bool UNPACK, int MODE, bool NTU, bool NTP>
-__global__ __launch_bounds__(kThreads) void k_uniform_tag(ChunkGeom g, uint8_t *user, uint8_t *packed, void *out,
-                                                          uint8_t *acc, uint32_t stride, uint32_t fan, TagWork work)
+__global__ __launch_bounds__(kThreads) void k_uniform_tag(UniformTagArgs a)
 {
-    const TileSpan t = locate_tile(g, blockIdx.x);
-    const TagRegs got = prefetch_tag(MODE, g, t.chunk, work);
+    uint32_t m = 0;
+#pragma unroll
+    for (uint32_t i = 1; i < kMaxBatch; ++i)
+        if (i < a.n && blockIdx.x >= a.it[i].first_tile) m = i;
+    const UniformTagItem &it = a.it[m];
+    const ChunkGeom &g = it.g;
+    const TileSpan t = locate_tile(g, blockIdx.x - it.first_tile);
+    const TagRegs got = prefetch_tag(MODE, g, t.chunk, it.work);
     const uint64_t left = g.N > t.stream_off ? g.N - t.stream_off : 0;
     const uint32_t data = left < t.len ? uint32_t(left) : t.len;
-    uint8_t *pk = packed + t.packed_off;
-    Sums2 sums = copy_span2<UNPACK, NTU, NTP>(user + t.stream_off, pk, data);
+    uint8_t *pk = it.packed + t.packed_off;
+    Sums2 sums = copy_span2<UNPACK, NTU, NTP>(it.user + t.stream_off, pk, data);
     if (data < t.len) {
         const Sums2 pad = pad_span2<UNPACK>(pk + data, t.len - data, data);
         sums.s += pad.s;
         sums.w += pad.w;
     }
     const uint64_t j0 = (t.stream_off - uint64_t(t.chunk) * g.B) >> 2;       // the tile's first word in its chunk
-    pair_commit(MODE, g, t, sums.s, j0 * sums.s + sums.w, out, acc, stride, fan, work, got);
+    pair_commit(MODE, g, t, sums.s, j0 * sums.s + sums.w, it.out, it.acc, it.stride, it.fan, it.work, got);
+}
+
+// The same for the contiguous tensors of a multi-tensor message (gradient buckets): the table-driven copy
+// of k_contig with both sums taken on the way.  A tile's record says where it starts inside its chunk.
+template <bool UNPACK, int MODE, bool NTU, bool NTP>
+__global__ __launch_bounds__(kThreads) void k_contig_tag(const Tile *__restrict__ tiles,
+                                                         const uint32_t *__restrict__ chunk_tiles, BasePtrs bases,
+                                                         uint8_t *__restrict__ packed, ChunkGeom g, void *out,
+                                                         uint8_t *acc, uint32_t stride, uint32_t fan, TagWork work)
+{
+    const Tile t = tiles[blockIdx.x];
+    const TagRegs got = prefetch_tag(MODE, g, t.chunk, work);
+    TileSpan span{};
+    span.chunk = t.chunk;
+    span.ordinal = t.ordinal;
+    span.expected = chunk_tiles[t.chunk];
+    Sums2 sums;
+    uint64_t j0 = 0;
+    if (t.kind == K_ZERO) {                                  // byte granular: weights taken from the chunk's start
+        sums = pad_span2<UNPACK>(packed + t.packed_off, t.n0, t.a);
+    } else {
+        sums = copy_span2<UNPACK, NTU, NTP>(bases.p[t.tensor] + t.src_off, packed + t.packed_off, t.n0);
+        j0 = t.a >> 2;
+    }
+    pair_commit(MODE, g, span, sums.s, j0 * sums.s + sums.w, out, acc, stride, fan, work, got);
 }
 
 // A few KiB of chunk tags between device memory and pinned host memory (either direction; the pinned

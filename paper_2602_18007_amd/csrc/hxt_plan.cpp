@@ -126,7 +126,12 @@ static Kind classify(const TensorPlan &t)
         bool ok = row_bytes % 16 == 0 && row_bytes < (1u << 30) && rows < (1u << 31);
         for (int d = 0; d < last; ++d)
             ok = ok && (uint64_t(t.stride[d]) * t.esize) % 16 == 0 && t.shape[d] < (int64_t(1) << 31);
-        return ok ? K_ROWS : K_GENERIC;
+        if (ok) return K_ROWS;
+        // runs or pitches that are not multiples of 16 bytes: still a gather of runs, with the tensor side
+        // accessed in narrower pieces, as long as a 16-byte vector meets at most one run boundary
+        bool split = row_bytes >= 16 && row_bytes < (1u << 30) && rows < (1u << 31);
+        for (int d = 0; d < last; ++d) split = split && t.shape[d] < (int64_t(1) << 31);
+        return split ? K_ROWS_SPLIT : K_GENERIC;
     }
     if (t.ndim >= 2 && t.stride[last] > 1 && t.stride[last - 1] == 1) return K_TRANSPOSE;
     return K_GENERIC;
@@ -142,8 +147,10 @@ static TensorDev make_tensor_dev(const TensorPlan &t)
         d.shape[i] = t.shape[i];
         d.stride_b[i] = t.stride[i] * t.esize;
     }
-    if (t.kind == K_ROWS) {
+    if (t.kind == K_ROWS || t.kind == K_ROWS_SPLIT) {
         d.row_bytes = uint32_t(t.shape[t.ndim - 1] * t.esize);
+        d.low_or = d.row_bytes;
+        for (int i = 0; i < t.ndim - 1; ++i) d.low_or |= uint32_t(uint64_t(d.stride_b[i]) & 0xFFu);
         d.row_div = make_fastdiv(d.row_bytes);
         for (int i = 0; i < t.ndim - 1; ++i) d.dim_div[i] = make_fastdiv(uint32_t(t.shape[i]));
     }
@@ -164,7 +171,7 @@ struct RawTile {
 
 struct Builder {
     Plan &p;
-    std::vector<RawTile> by_kernel[5];   // indexed by kernel kind 1..4
+    std::vector<RawTile> by_kernel[7];   // indexed by kernel kind (1..4 and 6)
     explicit Builder(Plan &plan) : p(plan) {}
 
     void add(Kind kernel, Kind kind, uint32_t tensor, uint64_t packed_off, uint64_t src_off, uint64_t a,
@@ -184,7 +191,7 @@ struct Builder {
         while (s < s1) {
             uint64_t c = s / p.B;
             uint64_t end = std::min({(c + 1) * p.B, s1, s + step});
-            add(kernel, kind, ti, p.chunk_packed_off(c) + (s - c * p.B), lo0 + (s - s0), 0, 0, uint32_t(c),
+            add(kernel, kind, ti, p.chunk_packed_off(c) + (s - c * p.B), lo0 + (s - s0), s - c * p.B, 0, uint32_t(c),
                 uint32_t(end - s), 0);
             s = end;
         }
@@ -309,6 +316,7 @@ int build_plan(const hxt_tensor_desc_t *descs, int n_tensors, int n_lanes, size_
         switch (t.kind) {
         case K_CONTIG: b.linear(K_CONTIG, K_CONTIG, i, t.stream_off, data_end, 0, tile_bytes); break;
         case K_ROWS: b.linear(K_ROWS, K_ROWS, i, t.stream_off, data_end, 0, tile_bytes); break;
+        case K_ROWS_SPLIT: b.linear(K_ROWS_SPLIT, K_ROWS_SPLIT, i, t.stream_off, data_end, 0, tile_bytes); break;
         case K_GENERIC: b.linear(K_GENERIC, K_GENERIC, i, t.stream_off, data_end, 0, tile_bytes); break;
         case K_TRANSPOSE: b.transpose(i); break;
         default: break;
@@ -320,7 +328,7 @@ int build_plan(const hxt_tensor_desc_t *descs, int n_tensors, int n_lanes, size_
     if (total >= (uint64_t(1) << 31)) return HXT_EUNSUPPORTED;
     p.tiles.reserve(total);
     p.chunk_tiles.assign(p.C, 0);
-    for (Kind kern : {K_CONTIG, K_ROWS, K_TRANSPOSE, K_GENERIC}) {
+    for (Kind kern : {K_CONTIG, K_ROWS, K_ROWS_SPLIT, K_TRANSPOSE, K_GENERIC}) {
         auto &v = b.by_kernel[kern];
         size_t i = 0;
         while (i < v.size()) {
@@ -347,6 +355,8 @@ int build_plan(const hxt_tensor_desc_t *descs, int n_tensors, int n_lanes, size_
             p.uniform_tensor = uint32_t(i);
         }
     p.uniform = live == 1 && p.tensors[p.uniform_tensor].kind == K_CONTIG;
+    p.all_contig = true;
+    for (const Group &gr : p.groups) p.all_contig = p.all_contig && gr.kernel == K_CONTIG;
     g.N = p.uniform ? p.tensors[p.uniform_tensor].bytes : 0;
     return HXT_OK;
 }

@@ -31,7 +31,7 @@ EXPORTS = (
     "hxt_plan_tensor_kind", "hxt_pack", "hxt_stage_d2h", "hxt_stage_h2d", "hxt_unpack", "hxt_checksum",
     "hxt_pack_batch", "hxt_unpack_batch", "hxt_exchange_stream", "hxt_unpack_accumulate",
     "hxt_host_forward", "hxt_stage_hop", "hxt_checksum2", "hxt_seal", "hxt_verify", "hxt_pack_seal", "hxt_unpack_verify",
-    "hxt_pack_noalloc", "hxt_plan_set_option",
+    "hxt_pack_noalloc", "hxt_plan_set_option", "hxt_pack_seal_batch", "hxt_unpack_verify_batch",
     "hxt_strerror", "hxt_last_hip_error", "hxt_version",
 )
 
@@ -69,10 +69,12 @@ class _Exchange(C.Structure):
                 ("host_pinned", C.POINTER(C.c_void_p)), ("send_sums", C.c_void_p), ("recv_sums", C.c_void_p),
                 ("stream_pack", C.c_void_p), ("stream_stage", C.c_void_p), ("stream_unpack", C.c_void_p),
                 ("tags_send", C.POINTER(C.c_void_p)), ("tags_recv", C.POINTER(C.c_void_p)),
-                ("tags_pinned", C.POINTER(C.c_void_p)), ("status", C.c_void_p), ("seq_base", C.c_uint64)]
+                ("tags_pinned", C.POINTER(C.c_void_p)), ("status", C.c_void_p), ("seq_base", C.c_uint64),
+                ("direct_mode", C.c_int), ("drain_every", C.c_int)]
 
 
 HXT_DEVICE_DIRECT, HXT_CPU_FORWARD = 0, 1
+HXT_DIRECT_AUTO, HXT_DIRECT_TWO_CHAINS, HXT_DIRECT_FUSED, HXT_DIRECT_EVENTS = 0, 1, 2, 3
 
 
 class LaneInfo(C.Structure):
@@ -124,6 +126,10 @@ def lib():
             "hxt_pack_batch": (i, [i, C.POINTER(vp), C.POINTER(C.POINTER(vp)), C.POINTER(vp), C.POINTER(vp), vp]),
             "hxt_unpack_batch": (i, [i, C.POINTER(vp), C.POINTER(vp), C.POINTER(C.POINTER(vp)), C.POINTER(vp), vp]),
             "hxt_exchange_stream": (i, [vp, C.POINTER(_Exchange)]),
+            "hxt_pack_seal_batch": (i, [i, C.POINTER(vp), C.POINTER(C.POINTER(vp)), C.POINTER(vp), C.POINTER(C.c_uint64),
+                                        C.POINTER(C.c_uint32), C.POINTER(vp), vp]),
+            "hxt_unpack_verify_batch": (i, [i, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(C.c_uint64),
+                                            C.POINTER(C.c_uint32), C.POINTER(C.POINTER(vp)), C.POINTER(vp), vp]),
             "hxt_pack_noalloc": (i, [vp, sz, i, sz, vp, u64p, vp]),
             "hxt_strerror": (C.c_char_p, [i]),
             "hxt_last_hip_error": (i, []),
@@ -335,7 +341,8 @@ class Exchange:
 
     def __init__(self, src, dst, packed_send, path=HXT_DEVICE_DIRECT, packed_recv=None, host_pinned=None,
                  send_sums=None, recv_sums=None, stream_pack=None, stream_stage=None, stream_unpack=None,
-                 tags_send=None, tags_recv=None, tags_pinned=None, status=None, seq_base=0):
+                 tags_send=None, tags_recv=None, tags_pinned=None, status=None, seq_base=0,
+                 direct_mode=HXT_DIRECT_AUTO, drain_every=0):
         flat = lambda rows: [t for row in rows for t in row]
         opt = lambda rows: _ptr_array(rows) if rows is not None else None
         self._keep = (src, dst, packed_send, packed_recv, host_pinned, send_sums, recv_sums, tags_send, tags_recv,
@@ -345,7 +352,7 @@ class Exchange:
         self._tag_arrays = [opt(tags_send), opt(tags_recv), opt(tags_pinned)]
         self.c = _Exchange(len(src), len(packed_send), path, *self._arrays, _ptr(send_sums), _ptr(recv_sums),
                            _stream(stream_pack), _stream(stream_stage), _stream(stream_unpack),
-                           *self._tag_arrays, _ptr(status), seq_base)
+                           *self._tag_arrays, _ptr(status), seq_base, direct_mode, drain_every)
 
 
 def hxt_exchange_stream(plan: Plan, x: Exchange) -> None:
@@ -387,6 +394,39 @@ def hxt_unpack_verify(plan: Plan, packed, tags, seq: int, micro_batch: int, dst:
 def hxt_pack_noalloc(src, message_bytes: int, n_lanes: int, chunk_bytes: int, packed, sums=None, stream=None) -> None:
     _check(lib().hxt_pack_noalloc(_ptr(src), message_bytes, n_lanes, chunk_bytes, _ptr(packed), _ptr(sums),
                                   _stream(stream)), "hxt_pack_noalloc")
+
+
+class TagBatch:
+    """Pre-marshalled arguments of hxt_pack_seal_batch / hxt_unpack_verify_batch for a fixed set of messages;
+    sequence numbers and micro-batch ids are given per call."""
+
+    def __init__(self, plans: Sequence[Plan], tensors: Sequence[Sequence], packed: Sequence, tags: Sequence,
+                 status: Optional[Sequence] = None):
+        n = len(plans)
+        assert len(tensors) == n and len(packed) == n and len(tags) == n and (status is None or len(status) == n)
+        self.n = n
+        self.plans = (C.c_void_p * max(n, 1))(*[p.handle.value for p in plans])
+        self._rows = [_ptr_array(t) for t in tensors]
+        self.tensors = (C.POINTER(C.c_void_p) * max(n, 1))(*[C.cast(r, C.POINTER(C.c_void_p)) for r in self._rows])
+        self.packed = _ptr_array(packed)
+        self.tags = _ptr_array(tags)
+        self.status = _ptr_array(status) if status is not None else None
+        self._keep = (plans, tensors, packed, tags, status)
+
+    def ids(self, seq: Sequence[int], micro_batch: Sequence[int]):
+        return (C.c_uint64 * max(self.n, 1))(*seq), (C.c_uint32 * max(self.n, 1))(*micro_batch)
+
+
+def hxt_pack_seal_batch(batch: TagBatch, seq: Sequence[int], micro_batch: Sequence[int], stream=None) -> None:
+    s_, m_ = batch.ids(seq, micro_batch)
+    _check(lib().hxt_pack_seal_batch(batch.n, batch.plans, batch.tensors, batch.packed, s_, m_, batch.tags,
+                                     _stream(stream)), "hxt_pack_seal_batch")
+
+
+def hxt_unpack_verify_batch(batch: TagBatch, seq: Sequence[int], micro_batch: Sequence[int], stream=None) -> None:
+    s_, m_ = batch.ids(seq, micro_batch)
+    _check(lib().hxt_unpack_verify_batch(batch.n, batch.plans, batch.packed, batch.tags, s_, m_, batch.tensors,
+                                         batch.status, _stream(stream)), "hxt_unpack_verify_batch")
 
 
 def hxt_stage_d2h(plan: Plan, lane: int, packed_dev, host_pinned, stream=None) -> None:

@@ -66,7 +66,8 @@ bool carried_offset(const TensorDev &td, uint64_t e0, uint32_t el, uint64_t *off
 // 2: pack from the tables and then, if the message is uniform, again from the closed form.  Returns 0, or a
 // negative code: -1 plan error, -2 user access out of bounds, -3 packed access out of
 // bounds, -4 tile crosses its chunk, -5 bad group bookkeeping, -6 bad closed-form geometry, -7 the 32-bit
-// carried address arithmetic of the per-element kernel disagrees with the plain one.
+// carried address arithmetic of the per-element kernel disagrees with the plain one, -8 a linear tile's
+// recorded offset inside its chunk is wrong.
 extern "C" int plan_interp(const hxt_tensor_desc_t *descs, int n_tensors, int n_lanes, uint64_t chunk_bytes,
                            uint32_t tile_bytes, uint8_t *const *base, const uint64_t *storage_bytes,
                            uint8_t *packed, uint64_t packed_bytes, uint8_t *written, int direction,
@@ -103,8 +104,10 @@ extern "C" int plan_interp(const hxt_tensor_desc_t *descs, int n_tensors, int n_
                 return 0;
             };
             int rc = 0;
+            // linear tiles record where they start inside their chunk (the fused tag kernels weigh words by it)
+            if (t.kind != K_TRANSPOSE && t.a != t.packed_off - c_lo) return -8;
             // the per-element kernel's carried arithmetic must hold for every linear tile, whichever kernel ends up serving it
-            if ((t.kind == K_CONTIG || t.kind == K_ROWS || t.kind == K_GENERIC) && td.all_div) {
+            if ((t.kind == K_CONTIG || t.kind == K_ROWS || t.kind == K_ROWS_SPLIT || t.kind == K_GENERIC) && td.all_div) {
                 if (t.src_off % td.esize || t.n0 % td.esize) return -7;
                 for (uint32_t el = 0; el < t.n0 / td.esize; ++el) {
                     uint64_t off = 0;
@@ -122,9 +125,11 @@ extern "C" int plan_interp(const hxt_tensor_desc_t *descs, int n_tensors, int n_
                 for (uint64_t b = 0; b < t.n0 && !rc; ++b) rc = put(t.packed_off + b, 0, true);
                 break;
             case K_ROWS:
+            case K_ROWS_SPLIT:
             case K_GENERIC:
                 if (g.kernel != t.kind) return -5;
                 if (t.kind == K_ROWS && (t.n0 % 16 || td.row_bytes % 16)) return -5;
+                if (t.kind == K_ROWS_SPLIT && (td.row_bytes < 16 || t.src_off % 16)) return -5;
                 for (uint64_t b = 0; b < t.n0 && !rc; ++b)
                     rc = put(t.packed_off + b, logical_to_storage(td, t.src_off + b), false);
                 break;

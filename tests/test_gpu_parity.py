@@ -720,7 +720,7 @@ def run_exchange_tagged(case, raws_per_msg, path, n_buffers, streams, seq_base=1
                 assert np.array_equal(buf[i % n_buffers].cpu().numpy()[:C * 64].reshape(C, 64), want_tags), "message %d" % i
 
 
-def run_exchange(case, raws_per_msg, path, n_buffers, streams):
+def run_exchange(case, raws_per_msg, path, n_buffers, streams, **how):
     """hxt_exchange_stream on a list of messages; checks every destination and every checksum."""
     m = oracle_msg(case)
     p = plan_of(case)
@@ -736,7 +736,7 @@ def run_exchange(case, raws_per_msg, path, n_buffers, streams):
     for s_ in streams:
         s_.wait_stream(torch.cuda.current_stream())
     x = hxt.Exchange(src, dst, send_buf, hxt.HXT_CPU_FORWARD if fwd else hxt.HXT_DEVICE_DIRECT, recv_buf, host_buf,
-                     send_sums, recv_sums, *streams)
+                     send_sums, recv_sums, *streams, **how)
     hxt.hxt_exchange_stream(p, x)
     torch.cuda.synchronize()
     ss_h = send_sums.cpu().numpy().view(np.uint64)[:, :C]
@@ -798,25 +798,43 @@ def test_exchange_stream_with_chunk_tags_rejects_mixed_requests():
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("path", ["device_direct", "cpu_forward"])
-def test_config_stream_1f1b_native_exchange(path):
-    w = wl.stream_1f1b(32)                      # CPU forwarding drains its streams after messages 12 and 24
-    say("native stream", path, "messages", w.messages)
+@pytest.mark.parametrize("path,how", [("device_direct", {}), ("cpu_forward", {}), ("cpu_forward", {"drain_every": 12})],
+                         ids=["device_direct", "cpu_forward_enqueue_only", "cpu_forward_drained_every_12"])
+def test_config_stream_1f1b_native_exchange(path, how):
+    w = wl.stream_1f1b(32)                      # with drain_every = 12 the call waits after messages 12 and 24
+    say("native stream", path, how, "messages", w.messages)
     run_exchange(case_of(w), [wl.make_storages(w, i) for i in range(w.messages)], path, 2,
-                 [torch.cuda.Stream() for _ in range(3)])
+                 [torch.cuda.Stream() for _ in range(3)], **how)
 
 
-@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("mode", [hxt.HXT_DIRECT_AUTO, hxt.HXT_DIRECT_TWO_CHAINS, hxt.HXT_DIRECT_FUSED, hxt.HXT_DIRECT_EVENTS])
 @pytest.mark.parametrize("n_buffers", [2, 4])
-def test_exchange_stream_device_direct_modes_agree(monkeypatch, mode, n_buffers):
-    # device-direct streams take two message chains on two streams by default (2); fused launches on one
-    # stream (1, single-tensor messages) and event-chained calls on three streams (0) must give the same
-    # result, for single-tensor and for multi-tensor messages
-    monkeypatch.setenv("HXT_STREAM_MODE", str(mode))
+def test_exchange_stream_device_direct_modes_agree(mode, n_buffers):
+    # device-direct streams: two message chains on two streams, fused launches on one stream (single-tensor
+    # messages only) and event-chained calls on three streams must give the same result, for single-tensor
+    # and for multi-tensor messages
     streams = [torch.cuda.Stream() for _ in range(3)]
     for name, nmsg in (("contig_bf16_5MiB_tail", 7), ("multi_mid", 6)):
         case = [c for c in MID_CASES if c.name == name][0]
-        run_exchange(case, [make_storages(case, 3200 + i) for i in range(nmsg)], "device_direct", n_buffers, streams)
+        raws = [make_storages(case, 3200 + i) for i in range(nmsg)]
+        if mode == hxt.HXT_DIRECT_FUSED and name == "multi_mid":          # not a single-tensor message: refused
+            with pytest.raises(hxt.HxtError) as e:
+                run_exchange(case, raws, "device_direct", n_buffers, streams, direct_mode=mode)
+            assert e.value.status == hxt.HXT_EINVAL
+            continue
+        run_exchange(case, raws, "device_direct", n_buffers, streams, direct_mode=mode)
+
+
+def test_exchange_stream_refuses_modes_the_arguments_do_not_allow():
+    case = [c for c in MID_CASES if c.name == "contig_1MB_ragged"][0]
+    raws = [make_storages(case, 1), make_storages(case, 2)]
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    for n_buffers, how in ((3, dict(direct_mode=hxt.HXT_DIRECT_TWO_CHAINS)), (1, dict(direct_mode=hxt.HXT_DIRECT_FUSED)),
+                           (2, dict(direct_mode=7)), (2, dict(drain_every=-1))):
+        with pytest.raises(hxt.HxtError) as e:
+            run_exchange(case, raws, "device_direct", n_buffers, streams, **how)
+        assert e.value.status == hxt.HXT_EINVAL
+    torch.cuda.synchronize()
 
 
 @pytest.mark.parametrize("seed", range(3))

@@ -203,6 +203,100 @@ def test_fused_calls_on_the_full_size_boundary_message():
     assert torch.equal(src[0], dst[0])
 
 
+BATCH_MESSAGES = [
+    Case("uniform_a", (contig((5 * 1024 * 1024 // 2 + 24,), 2),), 4, 1 << 20),
+    Case("uniform_b_fanned_out", (contig((9 * 1024 * 1024 // 2 + 40,), 2),), 2, 4 << 20),
+    Case("bucket_all_contig", (contig((4096,), 2), contig((1000, 37), 2), contig((511,), 4), contig((0,), 2),
+                               contig((300, 300), 4), contig((5,), 1)), 4, 16384),
+    Case("strided_two_pass", (((300, 2, 112), (112, 300 * 112, 1), 2),), 3, 4096),
+    Case("empty", (contig((0,), 2),), 2, 256),
+    Case("uniform_c_small", (contig((1000,), 1),), 8, 256),
+]
+
+
+@pytest.mark.parametrize("offset", [0, 4])
+def test_batched_fused_tag_calls_match_the_oracle(offset):
+    """hxt_pack_seal_batch / hxt_unpack_verify_batch over a mixed set of messages (single tensors that share
+    launches, a bucket of contiguous tensors served by the table-driven fused kernel, a strided message that
+    takes two passes, an empty one): tags, packed bytes, destinations and masks against the oracle, with one
+    message's sequence number stale and one message damaged on the host.  offset 4: bases that are only
+    element aligned (every message falls back to its own call)."""
+    cases = BATCH_MESSAGES
+    n = len(cases)
+    ms = [ho.Message([ho.TensorSpec(tuple(s), tuple(st), e) for (s, st, e) in c.tensors]) for c in cases]
+    plans = [hxt.hxt_plan_multi([(s, st, e) for (s, st, e) in c.tensors], c.k, c.B) for c in cases]
+    raws = [make_storages(c, 40 + i) for i, c in enumerate(cases)]
+    seqs = [(1 << 50) + 3 * i for i in range(n)]
+    mbs = [100 + i for i in range(n)]
+    want_packed = [ho.pack(m, r, c.B, c.k, fill=0xA5) for m, r, c in zip(ms, raws, cases)]
+    want_tags = [ho.seal(m, pk, c.B, c.k, sq, mb) for m, pk, c, sq, mb in zip(ms, want_packed, cases, seqs, mbs)]
+
+    def at(a):
+        t = torch.empty(max(a.size, 1) + 64, dtype=torch.uint8, device=DEV)
+        v = t[offset:offset + a.size] if a.size else t[:0]
+        v.copy_(torch.from_numpy(a))
+        return v
+
+    src = [[at(r) for r in rs] for rs in raws]
+    packed = [torch.full((max(pk.size, 16),), 0xA5, dtype=torch.uint8, device=DEV) for pk in want_packed]
+    tags = [torch.full((max(p.num_chunks, 1) * 64,), 0xEE, dtype=torch.uint8, device=DEV) for p in plans]
+    status = [torch.full((p.num_chunks + 1,), 0x7FFFFFFF, dtype=torch.int32, device=DEV) for p in plans]
+    dst = [[at(np.full(r.size, 0x3C, np.uint8)) for r in rs] for rs in raws]
+    hxt.hxt_pack_seal_batch(hxt.TagBatch(plans, src, packed, tags), seqs, mbs)
+    for i, c in enumerate(cases):
+        C = plans[i].num_chunks
+        assert np.array_equal(packed[i].cpu().numpy()[:want_packed[i].size], want_packed[i]), c.name
+        assert np.array_equal(tags[i].cpu().numpy()[:C * 64].reshape(C, 64), want_tags[i]), c.name
+    # receive side: message 1 is expected under another sequence number, message 2 was damaged on the way
+    seqs_r = list(seqs)
+    seqs_r[1] += 1
+    hit = plans[2].chunk_info(plans[2].num_chunks - 1)["packed_off"] + 9
+    packed[2][hit] = int(want_packed[2][hit]) ^ 0x04
+    want_packed[2][hit] ^= 0x04
+    hxt.hxt_unpack_verify_batch(hxt.TagBatch(plans, dst, packed, tags, status), seqs_r, mbs)
+    for i, c in enumerate(cases):
+        want_status = ho.verify(ms[i], want_packed[i], want_tags[i], c.B, c.k, seqs_r[i], mbs[i])
+        assert np.array_equal(status[i].cpu().numpy().view(np.uint32), want_status), c.name
+        dst_o = [np.full(r.size, 0x3C, np.uint8) for r in raws[i]]
+        ho.unpack(ms[i], want_packed[i], c.B, c.k, dst_o)
+        for a, b in zip(dst_o, dst[i]):
+            assert np.array_equal(b.cpu().numpy(), a), c.name
+    assert int(status[1][-1]) == plans[1].num_chunks and int(status[2][-1]) == 1 and int(status[0][-1]) == 0
+    # a plan may appear only once in a batch
+    with pytest.raises(hxt.HxtError) as e:
+        hxt.hxt_pack_seal_batch(hxt.TagBatch([plans[0], plans[0]], [src[0], src[0]], [packed[0], packed[0]], [tags[0], tags[0]]),
+                                [1, 2], [0, 0])
+    assert e.value.status == hxt.HXT_EINVAL
+    torch.cuda.synchronize()
+
+
+def test_batched_fused_tag_calls_on_the_full_size_boundary_step():
+    """The benchmark's tagged step: both LLaMA-shaped messages sealed inside one batched pack launch and verified
+    inside one batched unpack launch."""
+    w = wl.llama8b_boundary()
+    m = ho.Message([ho.TensorSpec(t.shape, t.strides, t.esize) for t in w.tensors])
+    plans = [hxt.hxt_plan_multi([(t.shape, t.strides, t.esize) for t in w.tensors], w.n_lanes, w.chunk_bytes) for _ in range(2)]
+    raws = [wl.make_storages(w, i) for i in range(2)]
+    src = [[torch.from_numpy(r).to(DEV) for r in rs] for rs in raws]
+    dst = [[torch.zeros_like(t) for t in ts] for ts in src]
+    C = plans[0].num_chunks
+    packed = [torch.empty(plans[0].packed_bytes, dtype=torch.uint8, device=DEV) for _ in range(2)]
+    tags = [torch.zeros(C * 64, dtype=torch.uint8, device=DEV) for _ in range(2)]
+    status = [torch.full((C + 1,), -1, dtype=torch.int32, device=DEV) for _ in range(2)]
+    send = hxt.TagBatch(plans, src, packed, tags)
+    recv = hxt.TagBatch(plans, dst, packed, tags, status)
+    for rep in range(3):
+        hxt.hxt_pack_seal_batch(send, [700 + rep, 800 + rep], [0, 1])
+        hxt.hxt_unpack_verify_batch(recv, [700 + rep, 800 + rep], [0, 1])
+        assert not status[0].cpu().numpy().any() and not status[1].cpu().numpy().any()
+    for i in range(2):
+        want_packed = ho.pack(m, raws[i], w.chunk_bytes, w.n_lanes, fill=0, nthreads=8)
+        assert np.array_equal(packed[i].cpu().numpy(), want_packed)
+        assert np.array_equal(tags[i].cpu().numpy().reshape(-1, 64),
+                              ho.seal(m, want_packed, w.chunk_bytes, w.n_lanes, [702, 802][i], i))
+        assert torch.equal(src[i][0], dst[i][0])
+
+
 def full_size_tag_check(w, tensors, raws):
     """seal / verify and the fused calls at full size against the oracle: tags byte for byte, masks word for word,
     packed and destination bytes, and a bit flipped on the host that must be reported in exactly its chunk."""
