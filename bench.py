@@ -9,13 +9,14 @@ with receive-side checksums by another.  Inputs are resident in HBM before the t
 The step is timed in several regions, each `repeats` blocks of `steps` steps back to back between
 one pair of host synchronisations (HIP events between the blocks give every block's GPU time):
   cold          one stream, every access non-temporal: all 4N bytes per message come from and go
-                to HBM.  `value`, `ms_per_step` and `roofline` are this region's.
+                to HBM, and a kernel has the machine to itself.  `roofline` is this region's.
   llc           one stream, packed buffer cacheable: unpack re-reads it from the 256 MB
                 last-level cache ~25 us after pack wrote it (loopback only: at a real boundary the
                 reader of a packed buffer is the NIC or the peer).  Reported, never the headline.
   chains_*      the same steps dealt alternately onto two streams with a plan set each, so that the
-                kernels of consecutive steps overlap (throughput figure; kernel durations are not
-                comparable with a roofline because the kernels share the machine).
+                kernels of consecutive steps overlap and fill each other's ramp-up and tail.  `value` and
+                `ms_per_step` are chains_cold's: whole-job throughput, all-cold (kernel durations in these
+                regions are not comparable with a roofline because the kernels share the machine).
 Then every other benchmark message is timed once (`configs`), the CPU-forwarding path is timed
 against a pinned-copy probe taken in the same run (`staged`), and the CPU oracle is timed on the
 host cores (`cpu_baseline`).  Prints ONE JSON line.
@@ -65,6 +66,10 @@ def parse():
     ap.add_argument("--no-checksum", action="store_true", help="diagnostic only: copies without checksums")
     ap.add_argument("--path", default="device_direct", choices=["device_direct", "cpu_forward"],
                     help="for --workload stream_1f1b")
+    ap.add_argument("--window", type=int, default=-1,
+                    help="for --workload stream_1f1b --path cpu_forward: micro-batches per hxt_exchange_stream call, the "
+                         "streams being drained between calls (0: all at once; default 12)")
+    ap.add_argument("--direct-mode", type=int, default=0, help="for --workload stream_1f1b: hxt_direct_mode_t (0 automatic)")
     ap.add_argument("--no-configs", action="store_true", help="skip the per-message entries")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-staged", action="store_true")
@@ -215,8 +220,10 @@ class DirectStep:
         for back in (0, 1):
             for ms in self.S[(self.last_step - back) % self.sets]:
                 if self.mode != "accumulate":
-                    for s_, d_ in zip(ms.src, ms.dst):
-                        assert torch.equal(s_.view(torch.int16), d_.view(torch.int16)), "round trip mismatch in the timed run"
+                    for t, s_, d_ in zip(self.w.tensors, ms.src, ms.dst):       # the elements the view addresses
+                        a = s_.view(torch.int16).as_strided(t.shape, t.strides)
+                        b = d_.view(torch.int16).as_strided(t.shape, t.strides)
+                        assert torch.equal(a, b), "round trip mismatch in the timed run"
                 if self.mode == "tags":
                     assert not bool(ms.status.any()), "a chunk was rejected in the timed run"
                 elif self.mode != "none":
@@ -477,8 +484,10 @@ def cpu_baseline(w, budget_s=10.0, max_tensors=None, one_core=True):
             break
     sec = time.perf_counter() - t0
     assert np.array_equal(s_send, s_recv)
-    if all(len(set(t.strides)) == len(t.strides) and 0 not in t.strides for t in tensors):
-        assert all(np.array_equal(a, b) for a, b in zip(raws, dst))
+    for t, a_, b_ in zip(tensors, raws, dst):             # round trip: the elements the view addresses
+        el = np.dtype("u%d" % t.esize)
+        view = lambda x: np.lib.stride_tricks.as_strided(x.view(el), t.shape, [st * t.esize for st in t.strides])
+        assert np.array_equal(view(a_), view(b_)), "oracle round trip"
     out = {"value": round(4 * m.N * reps / sec / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
            "sample": "%d pass(es) over %s (%d bytes): pack + checksum + unpack + checksum, %.1f s"
                      % (reps, "the whole message" if not max_tensors else "the first %d tensors of the message" % len(tensors),
@@ -582,7 +591,7 @@ def config_entries(torch, hxt, wl, a, link, headline_regions):
     # supplementary strided views
     direct("qwen_rows_view")
     direct("transpose_view")
-    direct("rows_split_view", note="bf16 [32768, 100] rows of 200 bytes at a pitch of 256 bytes")
+    direct("rows_split_view", note="bf16 [327680, 100]: runs of 200 bytes at a pitch of 256 bytes")
     return out
 
 
@@ -604,12 +613,14 @@ def main():
     torch.cuda.set_device(0)
     w = wl.ALL[a.workload]()
     if w.name == "stream_1f1b":
-        r = stream_passes(torch, hxt, w, a.path, window=12 if a.path == "cpu_forward" else 0, tags=a.tags,
+        window = (12 if a.path == "cpu_forward" else 0) if a.window < 0 else a.window
+        r = stream_passes(torch, hxt, w, a.path, direct_mode=a.direct_mode, window=window, tags=a.tags,
                           checksums=not a.no_checksum, passes=max(1, min(a.steps, 20)), warm=max(1, min(a.warmup, 2)))
         out = {"metric": METRIC, "value": r["pack_unpack_gbps"], "value_of": "pack+unpack GB/s", "unit": "GB/s", "n_gpus": 1,
                "steps": r["passes"], "warmup": max(1, min(a.warmup, 2)), "ms_per_step": r["ms_per_pass"],
                "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32", "data": "synthetic",
-               "config": {"workload": w.name, "note": w.note, "path": a.path, "buffer_sets": 2, "streams": 3}}
+               "config": {"workload": w.name, "note": w.note, "path": a.path, "buffer_sets": 2, "streams": 3,
+                          "window": window, "direct_mode": a.direct_mode}}
         out.update(r)
         print(json.dumps(out))
         return
@@ -636,7 +647,10 @@ def main():
                                   if name.startswith("chains") else "one stream, launches back to back")
     if a.accumulate:
         accumulate_check(torch, hxt, d)
-    head_name = "cold" if "cold" in regions else next(iter(regions))
+    # value: whole-job throughput of the all-cold step as the library is meant to be driven (independent steps on two
+    # streams); roofline: the dominant kernel's launches alone on the machine, back to back on one stream, all-cold
+    head_name = next(n for n in ("chains_cold", "cold", "chains_llc", "llc") if n in regions)
+    roof_name = next((n for n in ("cold", "llc") if n in regions), None)
     head = regions[head_name]
     out = {
         "metric": METRIC if not a.accumulate else "pack+accumulate GB/s",
@@ -658,7 +672,8 @@ def main():
                    "n_lanes": w.n_lanes, "chunk_bytes": w.chunk_bytes, "path": "device_direct",
                    "checks": {"sums": "fused send+receive checksums", "tags": "chunk tags sealed and verified inside the copies",
                               "accumulate": "receive-and-accumulate, fused checksums", "none": "off"}[mode],
-                   "buffer_sets": d.sets, "cache_state": head["cache_state"], "streams": 1,
+                   "buffer_sets": d.sets, "cache_state": head["cache_state"],
+                   "streams": 2 if head_name.startswith("chains") else 1,
                    "issue": ("batched calls (one launch packs all messages of the step, one unpacks them)"
                              if d.batched and d.per_launch > 1 else "one call per message") + "; " + head["issue"],
                    "timing": "%d blocks of %d steps between one pair of host synchronisations; value = bytes / wall time of the "
@@ -666,20 +681,22 @@ def main():
         "pct_hbm_peak": head["pct_hbm_peak"],
         "regions": regions,
     }
-    if "avg_launch_ms" in head:
+    roof = regions.get(roof_name) if roof_name else None
+    if roof and "avg_launch_ms" in roof:
         out["roofline"] = {"bound": "hbm", "kernel": d.kernel + " (pack and unpack instantiations%s)"
-                           % ("" if mode == "none" else ", checks fused"), "region": head_name,
-                           "achieved": head["launch_gbps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": head["frac"],
-                           "traffic": traffic_from_profile(hxt.hxt_version()) if (head_name == "cold" and mode == "sums"
+                           % ("" if mode == "none" else ", checks fused"), "region": roof_name,
+                           "region_is": "one stream, launches back to back (a kernel has the machine to itself), " + roof["cache_state"],
+                           "achieved": roof["launch_gbps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": roof["frac"],
+                           "traffic": traffic_from_profile(hxt.hxt_version()) if (roof_name == "cold" and mode == "sums"
                                                                                   and w.name == "llama8b_boundary" and d.batched) else None,
-                           "traffic_is": "L2<->fabric bytes per launch (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy); "
-                                         "counts last-level-cache hits as traffic",
-                           "bytes_per_launch": head["bytes_per_launch"], "avg_launch_ms": head["avg_launch_ms"],
+                           "traffic_is": "L2<->fabric bytes per launch (FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy of known "
+                                         "size); last-level-cache hits are not separated from HBM accesses",
+                           "bytes_per_launch": roof["bytes_per_launch"], "avg_launch_ms": roof["avg_launch_ms"],
                            "launches": a.steps * repeats * d.launches_per_step,
-                           "gpu_ms_median_block": head["median_block_ms"]}
+                           "gpu_ms_median_block": roof["median_block_ms"]}
         if not a.calibration_copies:        # a counter pass must see no other copy kernels than its calibration copies
-            out["roofline"]["plain_copy"] = plain_copy_ceiling(torch, head["bytes_per_launch"] // 2)
-        if "llc" in regions and "frac" in regions["llc"]:
+            out["roofline"]["plain_copy"] = plain_copy_ceiling(torch, roof["bytes_per_launch"] // 2)
+        if roof_name == "cold" and "llc" in regions and "frac" in regions["llc"]:
             out["roofline_llc_assisted"] = {k: regions["llc"][k] for k in ("launch_gbps", "frac", "avg_launch_ms", "cache_state")}
     out["paper_context"] = PAPER_CONTEXT
     if not a.no_staged:

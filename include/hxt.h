@@ -49,6 +49,10 @@
  *     hxt_checksum2, hxt_seal and hxt_pack_seal; hxt_verify and hxt_unpack_verify.
  *     One plan can therefore serve a sending stream and a receiving stream at the
  *     same time; messages that should overlap within one set need a plan each.
+ *     The library remembers the stream that used a set last (it records the ordering
+ *     event on it when the next call comes on another stream): a stream that has been
+ *     given to such a call must stay alive until the plan is destroyed or until a later
+ *     call of the same set has been made on another stream.
  *   - Stream capture: hxt_pack, hxt_unpack, hxt_unpack_accumulate, the batched calls,
  *     the checksum / seal / verify passes and the fused tag calls may be captured into a
  *     HIP graph (they record kernels only, no memset and no copy).  A call that asks for
@@ -184,7 +188,8 @@ int hxt_stage_h2d(const hxt_plan_t *plan, int lane, const void *host_pinned,
  *   hxt_host_forward: synchronous, pure host (no GPU needed).  Copies the used bytes of
  *     lane `lane` (or of every lane, lane == -1) from `from` to `to` at the same offsets,
  *     with up to n_threads threads (one lane per thread at a time; n_threads < 1 = one per
- *     lane).  Both buffers >= packed_bytes; they must not overlap.
+ *     lane; never more than 64, the calling thread included; if a thread cannot be started its
+ *     lanes are copied by the calling thread).  Both buffers >= packed_bytes; they must not overlap.
  *   hxt_stage_hop: the same copy enqueued on `stream` (it runs on a host thread once the
  *     work enqueued before it has finished, and later work on the stream waits for it).
  * HXT_EINVAL for NULL buffers or a bad lane. */

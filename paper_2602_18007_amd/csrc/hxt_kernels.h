@@ -756,21 +756,42 @@ __device__ __forceinline__ uint64_t elem_weighted(E v, uint64_t packed_pos)
 // reads that assemble one dst vector (same column, V consecutive rows) and the other lanes'
 // reads of the same instruction fall into distinct banks; then 16-byte global stores along dst
 // rows.  The sum is taken on whichever side is the packed buffer.
-template <typename E, bool SRC_IS_PACKED, bool CSUM, int UA>
-__device__ __forceinline__ uint64_t transpose_vec(const uint8_t *src, uint64_t src_pitch, uint32_t R, uint32_t Cc,
+// FULL: the tile is T x T, so every index computation folds to shifts and masks and each thread moves exactly
+// T * T / (V * kThreads) vectors per phase, all of whose global loads are issued before the first LDS store
+// (measured with counters: with run-time extents the kernel was bound by its integer divisions, not by memory).
+template <typename E, bool SRC_IS_PACKED, bool CSUM, int UA, bool FULL>
+__device__ __forceinline__ uint64_t transpose_vec(const uint8_t *src, uint64_t src_pitch, uint32_t R_in, uint32_t Cc_in,
                                                   uint8_t *dst, uint64_t dst_pitch, uint8_t *lds)
 {
     constexpr uint32_t T = transpose_tile(sizeof(E)), V = 16 / sizeof(E), ROWB = T * sizeof(E), NV = T / V;
+    const uint32_t R = FULL ? T : R_in, Cc = FULL ? T : Cc_in;
     uint64_t acc = 0;
     const uint32_t nvs = Cc / V;                           // vectors per src row
-    for (uint32_t v = threadIdx.x; v < R * nvs; v += kThreads) {
+    auto load_src = [&](uint32_t v, uint32_t &slot) {
         const uint32_t r = v / nvs, cv = v - r * nvs;
+        slot = r * ROWB + ((cv ^ ((r / V) % NV)) * 16);
         // the user tensor is streamed once (non-temporal) and may be only UA-byte aligned; the packed side stays cacheable
-        u32x4 x;
-        if constexpr (SRC_IS_PACKED) x = load16<false>(reinterpret_cast<const u32x4 *>(src + r * src_pitch + cv * 16));
-        else x = load_user<UA, true>(src + r * src_pitch + cv * 16);
-        if constexpr (CSUM && SRC_IS_PACKED) acc += words_sum(x);
-        *reinterpret_cast<u32x4 *>(lds + r * ROWB + ((cv ^ ((r / V) % NV)) * 16)) = x;
+        if constexpr (SRC_IS_PACKED) return load16<false>(reinterpret_cast<const u32x4 *>(src + r * src_pitch + cv * 16));
+        else return load_user<UA, true>(src + r * src_pitch + cv * 16);
+    };
+    if constexpr (FULL) {
+        constexpr uint32_t PER = T * T / (V * kThreads);   // 8 vectors per thread (4 for 1-byte elements)
+        u32x4 x[PER];
+        uint32_t slot[PER];
+#pragma unroll
+        for (uint32_t u = 0; u < PER; ++u) x[u] = load_src(threadIdx.x + u * kThreads, slot[u]);
+#pragma unroll
+        for (uint32_t u = 0; u < PER; ++u) {
+            if constexpr (CSUM && SRC_IS_PACKED) acc += words_sum(x[u]);
+            *reinterpret_cast<u32x4 *>(lds + slot[u]) = x[u];
+        }
+    } else {
+        for (uint32_t v = threadIdx.x; v < R * nvs; v += kThreads) {
+            uint32_t slot;
+            const u32x4 x = load_src(v, slot);
+            if constexpr (CSUM && SRC_IS_PACKED) acc += words_sum(x);
+            *reinterpret_cast<u32x4 *>(lds + slot) = x;
+        }
     }
     __syncthreads();
     // dst vectors are handed out with 8 consecutive vectors of one dst row (128 contiguous bytes) fastest,
@@ -778,13 +799,13 @@ __device__ __forceinline__ uint64_t transpose_vec(const uint8_t *src, uint64_t s
     // over all 32 banks (16 row groups of one column pair would hit each bank twice).
     const uint32_t nvd = R / V;                            // vectors per dst row
     const uint32_t full8 = nvd >> 3, rem = nvd & 7, main = Cc * 8 * full8;
-    for (uint32_t v = threadIdx.x; v < Cc * nvd; v += kThreads) {
+    auto move_dst = [&](uint32_t v) {
         uint32_t c, dv;
-        if (v < main) {
+        if (FULL || v < main) {                            // a full tile's dst rows are whole groups of 8 vectors
             const uint32_t b = v / (Cc * 8), w = v - b * (Cc * 8);
             c = w >> 3;
             dv = b * 8 + (w & 7);
-        } else {
+        } else if constexpr (!FULL) {
             const uint32_t w = v - main;
             c = w / rem;
             dv = full8 * 8 + (w - c * rem);
@@ -801,6 +822,14 @@ __device__ __forceinline__ uint64_t transpose_vec(const uint8_t *src, uint64_t s
         if constexpr (CSUM && !SRC_IS_PACKED) acc += words_sum(o.x);
         if constexpr (SRC_IS_PACKED) store_user<UA, true>(dst + c * dst_pitch + dv * 16, o.x);
         else store16<false>(reinterpret_cast<u32x4 *>(dst + c * dst_pitch + dv * 16), o.x);
+    };
+    if constexpr (FULL) {
+        static_assert(NV % 8 == 0, "a full tile's dst rows must be whole groups of 8 vectors");
+        constexpr uint32_t PER = T * T / (V * kThreads);
+#pragma unroll
+        for (uint32_t u = 0; u < PER; ++u) move_dst(threadIdx.x + u * kThreads);
+    } else {
+        for (uint32_t v = threadIdx.x; v < Cc * nvd; v += kThreads) move_dst(v);
     }
     return acc;
 }
@@ -821,12 +850,13 @@ __global__ __launch_bounds__(kThreads) void k_transpose(const Tile *__restrict__
     if (vec_ok) {
         // storage: nj rows (pitch a) of ni contiguous elements; packed: ni rows (pitch b) of nj elements.  Every
         // storage row of the tile is off a 16-byte boundary by the same amount (the pitch is a multiple of 16).
-        auto run = [&]<int UA>() {
-            if constexpr (!UNPACK) return transpose_vec<E, false, CSUM, UA>(user, t.a, nj, ni, pk, t.b, lds_raw);
-            else return transpose_vec<E, true, CSUM, UA>(pk, t.b, ni, nj, user, t.a, lds_raw);
+        auto run = [&]<int UA, bool FULL = false>() {
+            if constexpr (!UNPACK) return transpose_vec<E, false, CSUM, UA, FULL>(user, t.a, nj, ni, pk, t.b, lds_raw);
+            else return transpose_vec<E, true, CSUM, UA, FULL>(pk, t.b, ni, nj, user, t.a, lds_raw);
         };
         const uint32_t mis = uint32_t(reinterpret_cast<uintptr_t>(user)) & 15u;
-        if (mis == 0) acc = run.template operator()<16>();
+        if (mis == 0 && ni == T && nj == T) acc = run.template operator()<16, true>();      // the common case
+        else if (mis == 0) acc = run.template operator()<16>();
         else if ((mis & 3u) == 0) acc = run.template operator()<4>();
         else if ((mis & 1u) == 0) acc = run.template operator()<2>();
         else acc = run.template operator()<1>();

@@ -132,10 +132,17 @@ def transpose_view() -> Workload:
                     note="bf16 logical [4096,4096] with strides (1,4096)")
 
 
+def rows_split_view() -> Workload:
+    """Supplementary: rows whose length is not a multiple of 16 bytes (200-byte runs at a pitch of 256 bytes)."""
+    t = TensorDesc((327680, 100), (128, 1))
+    return Workload("rows_split_view", (t,), 4, 1 * MiB, "normal", 1.0, seed=BASE_SEED + 7,
+                    note="bf16 [327680,100] view with a row pitch of 128 elements (62.5 MiB)")
+
+
 ALL = {
     "tiny": tiny, "llama8b_boundary": llama8b_boundary, "qwen2_7b_boundary": qwen2_7b_boundary,
     "stream_1f1b": stream_1f1b, "grad_buckets": grad_buckets,
-    "qwen_rows_view": qwen_rows_view, "transpose_view": transpose_view,
+    "qwen_rows_view": qwen_rows_view, "transpose_view": transpose_view, "rows_split_view": rows_split_view,
 }
 
 

@@ -137,6 +137,9 @@ MID_CASES = [
     Case("contig_bf16_5MiB_tail", (contig((5 * 1024 * 1024 // 2 + 24,), 2),), 4, 1 << 20),
     Case("contig_chunks_of_256_tiles", (contig((9 * 1024 * 1024 // 2 + 40,), 2),), 2, 4 << 20),   # fanned-out commit
     Case("rows_mid", (((300, 2, 112), (112, 300 * 112, 1), 2),), 3, 4096),
+    Case("rows_200_byte_runs", (((4096, 100), (128, 1), 2),), 4, 65536),          # runs that are not 16-byte multiples
+    Case("rows_31_byte_runs_3d", (((50, 3, 31), (100, 5000, 1), 1),), 2, 1024),
+    Case("rows_f32_odd_pitch", (((700, 37), (41, 1), 4),), 3, 8192),
     Case("rows_big_rows", (((96, 2, 3584), (3584, 96 * 3584, 1), 2),), 8, 65536),
     Case("rows_padded_pitch", (((1000, 256), (320, 1), 4),), 5, 32768),
     Case("rows_4d", (((5, 7, 3, 64), (64, 5 * 3 * 64, 5 * 64, 1), 2),), 2, 2048),
@@ -160,7 +163,9 @@ MID_CASES = [
                                          ("multi_mid", 8), ("rows_mid", 2), ("rows_mid", 4), ("rows_big_rows", 6),
                                          ("rows_padded_pitch", 4), ("rows_4d", 2), ("transpose_mid", 2), ("transpose_512", 6),
                                          ("transpose_f32_vec_batched", 4), ("transpose_f64", 8), ("transpose_u8_vec", 1),
-                                         ("transpose_u8_vec", 4), ("transpose_bf16_vec_partial", 2), ("generic_mid", 2)])
+                                         ("transpose_u8_vec", 4), ("transpose_bf16_vec_partial", 2), ("generic_mid", 2),
+                                         ("rows_200_byte_runs", 2), ("rows_200_byte_runs", 4), ("rows_200_byte_runs", 8),
+                                         ("rows_31_byte_runs_3d", 1), ("rows_31_byte_runs_3d", 3), ("rows_f32_odd_pitch", 4)])
 def test_mid_size_messages_with_element_aligned_bases(name, offset):
     """Contiguous tensors and row gathers whose base is 1, 2, 4, 8 or 12 bytes off a 16-byte boundary take their
     kernels, with narrower accesses on the tensor side, and so do transposes.  Same bytes and sums."""
@@ -951,7 +956,7 @@ def test_config_grad_buckets_full_size_both_paths():
     assert bool((host[tail0:tail1] == 0).all())
 
 
-@pytest.mark.parametrize("name", ["qwen_rows_view", "transpose_view"])
+@pytest.mark.parametrize("name", ["qwen_rows_view", "transpose_view", "rows_split_view"])
 def test_supplementary_strided_messages_full_size(name):
     w = wl.ALL[name]()
     say("supplementary", name)
