@@ -330,6 +330,21 @@ int hxo_stage_lane(int64_t L, int64_t B, int k, int l, const uint8_t *from, uint
     return 0;
 }
 
+/* Staging a run of slots of one lane: slots [first, first + count) of lane l, each up to the
+ * padded end of the chunk it holds; slots past the lane's last chunk do not exist (-1). */
+int hxo_stage_slots(int64_t L, int64_t B, int k, int l, int64_t first, int64_t count, const uint8_t *from, uint8_t *to)
+{
+    if (l < 0 || l >= k || first < 0 || count < 0) return -1;
+    if (first + count > hxo_lane_chunks(L, B, k, l)) return -1;
+    int64_t lane = hxo_lane_offset(L, B, k, l);
+    for (int64_t s = first; s < first + count; ++s) {
+        int64_t c = s * k + l;                        /* the chunk in slot s of lane l */
+        int64_t off = lane + s * B, n = hxo_chunk_padded(L, B, c);
+        for (int64_t i = 0; i < n; ++i) to[off + i] = from[off + i];
+    }
+    return 0;
+}
+
 /* ---- step 5: per-chunk checksum -------------------------------------------- */
 
 int hxo_checksum(int64_t L, int64_t B, int k, const uint8_t *packed, uint64_t *sums, int nthreads)

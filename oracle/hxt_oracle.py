@@ -95,6 +95,7 @@ def lib():
             "hxo_pack": (i32, [M, p, i64, i32, p, i32]),
             "hxo_unpack": (i32, [M, p, i64, i32, p, i32]),
             "hxo_stage_lane": (i32, [i64, i64, i32, i32, p, p]),
+            "hxo_stage_slots": (i32, [i64, i64, i32, i32, i64, i64, p, p]),
             "hxo_checksum": (i32, [i64, i64, i32, p, p, i32]),
             "hxo_checksum2": (i32, [i64, i64, i32, p, p, i32]),
             "hxo_seal": (i32, [i64, i64, i32, p, C.c_uint64, C.c_uint32, p]),
@@ -246,6 +247,12 @@ def stage_lane(msg: Message, B: int, k: int, lane: int, src: np.ndarray, dst: np
     rc = lib().hxo_stage_lane(msg.L, B, k, lane, src.ctypes.data, dst.ctypes.data)
     if rc:
         raise ValueError("bad lane")
+
+
+def stage_slots(msg: Message, B: int, k: int, lane: int, first: int, count: int, src: np.ndarray, dst: np.ndarray) -> None:
+    rc = lib().hxo_stage_slots(msg.L, B, k, lane, first, count, src.ctypes.data, dst.ctypes.data)
+    if rc:
+        raise ValueError("bad lane or slots")
 
 
 def checksum(msg: Message, packed: np.ndarray, B: int, k: int, nthreads: int = 1) -> np.ndarray:

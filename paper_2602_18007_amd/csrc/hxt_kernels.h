@@ -586,10 +586,11 @@ __global__ __launch_bounds__(kThreads) void k_rows_any(const Tile *__restrict__ 
 
 // ---- rows whose length or pitch is not a multiple of 16 bytes ----------------------
 // Still a gather of contiguous runs (of 16 bytes or more), but a 16-byte vector of the packed stream may end
-// one run and begin the next, and the tensor side is only G-byte aligned (G = 8 is served as 4).  A thread
-// finds (run, column) of its vector's first byte, the storage address of that run and, if the vector
-// crosses into the next run, of that one too, and moves the 16 bytes in naturally aligned pieces of G bytes;
-// the packed side stays 16 bytes wide.
+// one run and begin the next, and the tensor side is only G-byte aligned (G = 4, 2 or 1; 8 is served as 4).
+// Work is dealt in pieces of G bytes, consecutive lanes taking consecutive pieces of the tile: a wave's access
+// is then contiguous on the packed side and contiguous within each run on the tensor side (64 lanes x 4 bytes
+// = 256 bytes per instruction), whatever the run length; each piece finds its run with one multiply-shift
+// division and the run's storage offset from the outer indices.
 __device__ __forceinline__ uint64_t run_storage_offset(const TensorDev &td, uint32_t row)
 {
     uint64_t o = 0;
@@ -601,119 +602,47 @@ __device__ __forceinline__ uint64_t run_storage_offset(const TensorDev &td, uint
     return o + uint64_t(row) * uint64_t(td.stride_b[0]);
 }
 
-// Piece p (G bytes) of a 16-byte vector whose first n1 bytes are at a and the rest at b.
-template <int G>
-__device__ __forceinline__ uint8_t *piece_at(uint8_t *a, uint8_t *b, uint32_t n1, uint32_t p)
-{
-    return p * G < n1 ? a + p * G : b + (p * G - n1);
-}
-
-template <int G, bool NT>
-__device__ __forceinline__ u32x4 load_split(uint8_t *a, uint8_t *b, uint32_t n1)
-{
-    uint32_t w[4];
-    if constexpr (G == 4) {
-#pragma unroll
-        for (uint32_t p = 0; p < 4; ++p) w[p] = *reinterpret_cast<const uint32_t *>(piece_at<4>(a, b, n1, p));
-    } else if constexpr (G == 2) {
-#pragma unroll
-        for (uint32_t p = 0; p < 4; ++p)
-            w[p] = uint32_t(*reinterpret_cast<const uint16_t *>(piece_at<2>(a, b, n1, 2 * p))) |
-                   uint32_t(*reinterpret_cast<const uint16_t *>(piece_at<2>(a, b, n1, 2 * p + 1))) << 16;
-    } else {
-#pragma unroll
-        for (uint32_t p = 0; p < 4; ++p) {
-            w[p] = 0;
-#pragma unroll
-            for (uint32_t q = 0; q < 4; ++q) w[p] |= uint32_t(*piece_at<1>(a, b, n1, 4 * p + q)) << (8 * q);
-        }
-    }
-    return u32x4{w[0], w[1], w[2], w[3]};
-}
-
-template <int G>
-__device__ __forceinline__ void store_split(uint8_t *a, uint8_t *b, uint32_t n1, u32x4 v)
-{
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-    if constexpr (G == 4) {
-#pragma unroll
-        for (uint32_t p = 0; p < 4; ++p) *reinterpret_cast<uint32_t *>(piece_at<4>(a, b, n1, p)) = w[p];
-    } else if constexpr (G == 2) {
-#pragma unroll
-        for (uint32_t p = 0; p < 8; ++p)
-            *reinterpret_cast<uint16_t *>(piece_at<2>(a, b, n1, p)) = uint16_t(w[p >> 1] >> (16 * (p & 1)));
-    } else {
-#pragma unroll
-        for (uint32_t p = 0; p < 16; ++p) *piece_at<1>(a, b, n1, p) = uint8_t(w[p >> 2] >> (8 * (p & 3)));
-    }
-}
+template <int G> struct PieceOf;
+template <> struct PieceOf<4> { using type = uint32_t; };
+template <> struct PieceOf<2> { using type = uint16_t; };
+template <> struct PieceOf<1> { using type = uint8_t; };
 
 template <bool UNPACK, bool CSUM, int G>
 __device__ __forceinline__ uint64_t rows_split_tile(const Tile &t, const TensorDev &td, uint8_t *user, uint8_t *pk)
 {
+    using P = typename PieceOf<G>::type;
     const uint32_t row_bytes = td.row_bytes;
     const uint64_t row0 = t.src_off / row_bytes;                    // uniform
     const uint32_t col0 = uint32_t(t.src_off - row0 * row_bytes);
-    const uint32_t nvec = t.n0 >> 4;
-    constexpr int U = 2;                                            // vectors in flight per thread
+    const uint32_t npiece = t.n0 / G;
+    constexpr int U = 8;                                            // pieces in flight per thread
     uint64_t acc = 0;
-    auto locate = [&](uint32_t byte, uint8_t *&a, uint32_t &n1) {   // tile byte -> address of its run position, bytes left in the run
-        const uint32_t x = col0 + byte;
+    auto user_piece = [&](uint32_t i) {                             // piece i of the tile -> its place in storage
+        const uint32_t x = col0 + i * G;
         const uint32_t dr = fast_div(x, td.row_div);
-        const uint32_t col = x - dr * row_bytes;
-        a = user + run_storage_offset(td, uint32_t(row0) + dr) + col;
-        n1 = row_bytes - col;
-        return uint32_t(row0) + dr;
+        return reinterpret_cast<P *>(user + run_storage_offset(td, uint32_t(row0) + dr) + (x - dr * row_bytes));
     };
-    for (uint32_t v0 = threadIdx.x; v0 < nvec; v0 += kThreads * U) {
-        u32x4 r[U];
-        uint8_t *a[U], *b[U];
-        uint32_t n1[U];
+    P *pieces = reinterpret_cast<P *>(pk);
+    for (uint32_t i0 = threadIdx.x; i0 < npiece; i0 += kThreads * U) {
+        P r[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const uint32_t v = v0 + u * kThreads;
-            a[u] = b[u] = user;
-            n1[u] = 16;
-            if (v < nvec) {
-                const uint32_t row = locate(v << 4, a[u], n1[u]);
-                if (n1[u] < 16) b[u] = user + run_storage_offset(td, row + 1);
-                else n1[u] = 16;
-                if constexpr (UNPACK) r[u] = *(reinterpret_cast<const u32x4 *>(pk) + v);
-                else r[u] = load_split<G, true>(a[u], b[u], n1[u]);
+            const uint32_t i = i0 + u * kThreads;
+            r[u] = 0;
+            if (i < npiece) {
+                if constexpr (UNPACK) r[u] = pieces[i];
+                else r[u] = __builtin_nontemporal_load(user_piece(i));
             }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const uint32_t v = v0 + u * kThreads;
-            if (v < nvec) {
-                if constexpr (UNPACK) store_split<G>(a[u], b[u], n1[u], r[u]);
-                else *(reinterpret_cast<u32x4 *>(pk) + v) = r[u];
-                if constexpr (CSUM) acc += words_sum(r[u]);
+            const uint32_t i = i0 + u * kThreads;
+            if (i < npiece) {
+                if constexpr (UNPACK) __builtin_nontemporal_store(r[u], user_piece(i));
+                else pieces[i] = r[u];
+                if constexpr (CSUM) acc += uint64_t(r[u]) << (8 * ((i * G) & 3));
             }
         }
-    }
-    // the last few bytes of the tensor (fewer than 16), piece by piece
-    const uint32_t tail = (t.n0 & 15u) / G;
-    if (threadIdx.x < tail) {
-        const uint32_t byte = (nvec << 4) + threadIdx.x * G;
-        uint8_t *a;
-        uint32_t n1;
-        locate(byte, a, n1);
-        uint32_t val;
-        if constexpr (G == 4) {
-            uint32_t *u = reinterpret_cast<uint32_t *>(a), *p = reinterpret_cast<uint32_t *>(pk + byte);
-            val = UNPACK ? *p : *u;
-            if constexpr (UNPACK) *u = val; else *p = val;
-        } else if constexpr (G == 2) {
-            uint16_t *u = reinterpret_cast<uint16_t *>(a), *p = reinterpret_cast<uint16_t *>(pk + byte);
-            val = UNPACK ? *p : *u;
-            if constexpr (UNPACK) *u = uint16_t(val); else *p = uint16_t(val);
-        } else {
-            uint8_t *p = pk + byte;
-            val = UNPACK ? *p : *a;
-            if constexpr (UNPACK) *a = uint8_t(val); else *p = uint8_t(val);
-        }
-        if constexpr (CSUM) acc += uint64_t(val) << (8 * (byte & 3));
     }
     return acc;
 }

@@ -321,6 +321,32 @@ def test_staging_copies_used_bytes_of_one_lane_only():
         assert (info["packed_off"], info["bytes"]) == (lo, hi - lo)
 
 
+def test_staging_a_run_of_slots_copies_exactly_those_chunks():
+    # 7 chunks of 512 bytes over 2 lanes, last chunk 256 bytes: lane 0 holds chunks 0,2,4,6 at 0,512,1024,1536
+    # (the last one short), lane 1 holds chunks 1,3,5 at 2048,2560,3072.  Ranges written out by hand.
+    case = Case("g", (contig((6 * 512 + 256,), 1),), 2, 512)
+    m = msg_of(case)
+    packed = ho.pack(m, make_storages(case, 43), case.B, case.k, fill=0x77)
+    hand = {(0, 0, 1): [(0, 512)], (0, 1, 2): [(512, 1536)], (0, 2, 2): [(1024, 1536 + 256)], (0, 3, 1): [(1536, 1536 + 256)],
+            (1, 0, 3): [(2048, 3584)], (1, 2, 1): [(3072, 3584)], (0, 0, 0): [], (0, 0, 4): [(0, 1536 + 256)]}
+    for (lane, first, count), ranges in hand.items():
+        host = np.full(packed.size, 0x11, np.uint8)
+        ho.stage_slots(m, case.B, case.k, lane, first, count, packed, host)
+        touched = np.zeros(packed.size, bool)
+        for lo, hi in ranges:
+            touched[lo:hi] = True
+        assert np.array_equal(host[touched], packed[touched]) and np.all(host[~touched] == 0x11), (lane, first, count)
+    for bad in ((0, 3, 2), (1, 0, 4), (2, 0, 1), (0, -1, 1)):
+        with pytest.raises(ValueError):
+            ho.stage_slots(m, case.B, case.k, *bad, packed, np.zeros_like(packed))
+    # all slots of a lane = the lane
+    for lane, n in ((0, 4), (1, 3)):
+        a, b = np.full(packed.size, 0x22, np.uint8), np.full(packed.size, 0x22, np.uint8)
+        ho.stage_slots(m, case.B, case.k, lane, 0, n, packed, a)
+        ho.stage_lane(m, case.B, case.k, lane, packed, b)
+        assert np.array_equal(a, b)
+
+
 @pytest.mark.parametrize("name", ["mixed_dtypes_multi", "four_d_mixed", "ragged_last_chunk_2p5", "fewer_chunks_than_lanes"])
 def test_inverse_map_agrees_with_forward_pack(name):
     case = case_by_name(name)
