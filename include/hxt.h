@@ -139,9 +139,18 @@ int hxt_plan_destroy(hxt_plan_t *plan); /* NULL is allowed */
  *      last-level cache; non-temporal above;
  *    0 always cacheable;  1 always non-temporal (every byte goes to and comes from HBM).
  *   The environment variable HXT_NT_PACKED (0/1), read when a plan is created, sets the initial value.
- * Takes effect for calls made afterwards; do not change it while calls on the plan are being issued
- * from other threads.  HXT_EINVAL for an unknown option or value. */
-typedef enum { HXT_OPT_PACKED_HINT = 1 } hxt_option_t;
+ * HXT_OPT_STAGE_D2H: how hxt_stage_d2h* and the CPU-forwarding path of hxt_exchange_stream move
+ *   the packed buffer to pinned host memory.
+ *    0 (default) a copy command (hipMemcpyAsync: the runtime picks a DMA engine or a blit kernel of
+ *      its own, depending on what is outstanding when the call is made);
+ *    1 the library's copy kernel (64 workgroups that store straight into the pinned buffer; the host
+ *      buffer must then be device-accessible pinned memory, which hipHostMalloc memory is).  Same
+ *      rate alone (55 GB/s); beside a host-to-device DMA copy it reaches 44 GB/s per direction where
+ *      two DMA engines reach 49.
+ *   Host-to-device staging always uses a copy command (a DMA engine).
+ * Options take effect for calls made afterwards; do not change them while calls on the plan are being
+ * issued from other threads.  HXT_EINVAL for an unknown option or value. */
+typedef enum { HXT_OPT_PACKED_HINT = 1, HXT_OPT_STAGE_D2H = 2 } hxt_option_t;
 int hxt_plan_set_option(hxt_plan_t *plan, int option, int value);
 
 /* ---- queries (host only) ---------------------------------------------------- */
@@ -179,6 +188,15 @@ int hxt_stage_d2h(const hxt_plan_t *plan, int lane, const void *packed_dev,
                   void *host_pinned, void *stream);
 int hxt_stage_h2d(const hxt_plan_t *plan, int lane, const void *host_pinned,
                   void *packed_dev, void *stream);
+
+/* The same for a run of slots of one lane: slots [first_slot, first_slot + n_slots) of lane `lane`
+ * (slot s of lane l holds chunk s * n_lanes + l), each up to its chunk's padded end, so that a lane
+ * can be staged in pieces and the two directions pipelined chunk by chunk.  HXT_EINVAL if lane < 0
+ * or the run reaches past the lane's last chunk; n_slots == 0 is a no-op. */
+int hxt_stage_d2h_slots(const hxt_plan_t *plan, int lane, int first_slot, int n_slots,
+                        const void *packed_dev, void *host_pinned, void *stream);
+int hxt_stage_h2d_slots(const hxt_plan_t *plan, int lane, int first_slot, int n_slots,
+                        const void *host_pinned, void *packed_dev, void *stream);
 
 /* ---- widening of step 3: the host-side hop of the CPU-forwarding path ------------
  * Section 2.1: in the compatibility path the data travels between the two hosts through

@@ -49,6 +49,7 @@ struct hxt_plan {
     uint32_t sum_bits_table = 0, sum_bits_geom = 0;   // see slot_arrive: table-driven copies / closed-form kernels
     int device = -1;
     int nt_packed = -1;                         // HXT_OPT_PACKED_HINT: -1 by size, 0 cacheable, 1 non-temporal
+    int stage_d2h_kernel = 0;                   // HXT_OPT_STAGE_D2H: 0 copy command, 1 the library's copy kernel
     OpState ops[OP_COUNT];
 };
 
@@ -500,19 +501,47 @@ int stage_ranges(const Plan &p, int lane, uint64_t (*r)[2])
     return 2;
 }
 
-int stage(const hxt_plan_t *plan, int lane, const void *from, void *to, hipMemcpyKind kind, void *stream)
+// Workgroups of the staging copy kernel: enough to keep the host link busy (it needs about 100 KB in flight;
+// measured 55 GB/s with 16 workgroups and with 4096), few enough to leave the chip to the kernels beside it.
+constexpr uint32_t kStageCopyGroups = 64;
+
+int copy_range(const void *from, void *to, uint64_t off, uint64_t bytes, hipMemcpyKind kind, bool by_kernel, hipStream_t st)
+{
+    const uint8_t *f = static_cast<const uint8_t *>(from) + off;
+    uint8_t *t = static_cast<uint8_t *>(to) + off;
+    if (by_kernel) {                                   // offsets and lengths are multiples of 256
+        static const uint32_t groups = uint32_t(std::max(1, std::min(4096, env_int("HXT_STAGE_GROUPS", int(kStageCopyGroups)))));
+        k_stage_copy<<<groups, kThreads, 0, st>>>(reinterpret_cast<u32x4 *>(t), reinterpret_cast<const u32x4 *>(f), bytes / 16);
+        HXT_HIP(hipGetLastError());
+        return HXT_OK;
+    }
+    HXT_HIP(hipMemcpyAsync(t, f, bytes, kind, st));
+    return HXT_OK;
+}
+
+int stage(const hxt_plan_t *plan, int lane, int64_t first_slot, int64_t n_slots, const void *from, void *to, hipMemcpyKind kind,
+          void *stream)
 {
     if (!plan) return HXT_EINVAL;
     const Plan &p = plan->p;
     if (lane < -1 || lane >= p.k) return HXT_EINVAL;
-    if (p.C == 0) return HXT_OK;
+    if (n_slots >= 0 && (lane < 0 || first_slot < 0 || uint64_t(first_slot) + uint64_t(n_slots) > p.lane_chunks[lane])) return HXT_EINVAL;
+    if (p.C == 0 || n_slots == 0) return HXT_OK;
     if (!from || !to) return HXT_EINVAL;
     if (reinterpret_cast<uintptr_t>(from) % HXT_ALIGN || reinterpret_cast<uintptr_t>(to) % HXT_ALIGN) return HXT_EALIGN;
+    const bool by_kernel = kind == hipMemcpyDeviceToHost && plan->stage_d2h_kernel > 0;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (n_slots > 0) {                                 // a run of slots of one lane: full slots, the lane's last one up to its padded end
+        const uint64_t last = uint64_t(first_slot + n_slots - 1) * p.k + lane;       // the chunk in the run's last slot
+        const uint64_t bytes = uint64_t(n_slots - 1) * p.B + p.chunk_padded(last);
+        return copy_range(from, to, p.lane_off[lane] + uint64_t(first_slot) * p.B, bytes, kind, by_kernel, st);
+    }
     uint64_t r[2][2];
     const int n = stage_ranges(p, lane, r);
-    for (int i = 0; i < n; ++i)
-        HXT_HIP(hipMemcpyAsync(static_cast<uint8_t *>(to) + r[i][0], static_cast<const uint8_t *>(from) + r[i][0],
-                               r[i][1], kind, static_cast<hipStream_t>(stream)));
+    for (int i = 0; i < n; ++i) {
+        int rc = copy_range(from, to, r[i][0], r[i][1], kind, by_kernel, st);
+        if (rc != HXT_OK) return rc;
+    }
     return HXT_OK;
 }
 
@@ -909,6 +938,10 @@ int hxt_plan_set_option(hxt_plan_t *plan, int option, int value)
     case HXT_OPT_PACKED_HINT:
         if (value < -1 || value > 1) return HXT_EINVAL;
         plan->nt_packed = value;
+        return HXT_OK;
+    case HXT_OPT_STAGE_D2H:
+        if (value < 0 || value > 1) return HXT_EINVAL;
+        plan->stage_d2h_kernel = value;
         return HXT_OK;
     }
     return HXT_EINVAL;
@@ -1356,12 +1389,26 @@ int hxt_verify(const hxt_plan_t *plan, const void *packed, const hxt_chunk_tag_t
 
 int hxt_stage_d2h(const hxt_plan_t *plan, int lane, const void *packed_dev, void *host_pinned, void *stream)
 {
-    return stage(plan, lane, packed_dev, host_pinned, hipMemcpyDeviceToHost, stream);
+    return stage(plan, lane, 0, -1, packed_dev, host_pinned, hipMemcpyDeviceToHost, stream);
 }
 
 int hxt_stage_h2d(const hxt_plan_t *plan, int lane, const void *host_pinned, void *packed_dev, void *stream)
 {
-    return stage(plan, lane, host_pinned, packed_dev, hipMemcpyHostToDevice, stream);
+    return stage(plan, lane, 0, -1, host_pinned, packed_dev, hipMemcpyHostToDevice, stream);
+}
+
+int hxt_stage_d2h_slots(const hxt_plan_t *plan, int lane, int first_slot, int n_slots, const void *packed_dev,
+                        void *host_pinned, void *stream)
+{
+    if (n_slots < 0) return HXT_EINVAL;
+    return stage(plan, lane, first_slot, n_slots, packed_dev, host_pinned, hipMemcpyDeviceToHost, stream);
+}
+
+int hxt_stage_h2d_slots(const hxt_plan_t *plan, int lane, int first_slot, int n_slots, const void *host_pinned,
+                        void *packed_dev, void *stream)
+{
+    if (n_slots < 0) return HXT_EINVAL;
+    return stage(plan, lane, first_slot, n_slots, host_pinned, packed_dev, hipMemcpyHostToDevice, stream);
 }
 
 const char *hxt_strerror(int status)

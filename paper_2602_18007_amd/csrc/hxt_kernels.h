@@ -1263,6 +1263,23 @@ __global__ __launch_bounds__(kThreads) void k_copy_tags(u32x4 *__restrict__ to, 
     for (uint32_t v = blockIdx.x * kThreads + threadIdx.x; v < nvec; v += gridDim.x * kThreads) to[v] = from[v];
 }
 
+// Plain copy of nvec 16-byte vectors by a small grid (grid-stride), for staging between device memory and
+// pinned host memory over the host link: a few dozen workgroups keep the link busy and leave the rest of the
+// chip to other kernels.  The device side is streamed (non-temporal), four vectors in flight per thread.
+__global__ __launch_bounds__(kThreads) void k_stage_copy(u32x4 *__restrict__ to, const u32x4 *__restrict__ from, uint64_t nvec)
+{
+    const uint64_t step = uint64_t(gridDim.x) * kThreads;
+    uint64_t v = uint64_t(blockIdx.x) * kThreads + threadIdx.x;
+    for (; v + 3 * step < nvec; v += 4 * step) {
+        u32x4 r[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) r[u] = __builtin_nontemporal_load(from + v + u * step);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) __builtin_nontemporal_store(r[u], to + v + u * step);
+    }
+    for (; v < nvec; v += step) __builtin_nontemporal_store(__builtin_nontemporal_load(from + v), to + v);
+}
+
 // Zero-fill of nvec 16-byte vectors (a kernel, so that it can be recorded where a memset node cannot).
 __global__ __launch_bounds__(kThreads) void k_fill_zero(u32x4 *__restrict__ p, uint32_t nvec)
 {

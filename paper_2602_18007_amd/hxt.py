@@ -32,6 +32,7 @@ EXPORTS = (
     "hxt_pack_batch", "hxt_unpack_batch", "hxt_exchange_stream", "hxt_unpack_accumulate",
     "hxt_host_forward", "hxt_stage_hop", "hxt_checksum2", "hxt_seal", "hxt_verify", "hxt_pack_seal", "hxt_unpack_verify",
     "hxt_pack_noalloc", "hxt_plan_set_option", "hxt_pack_seal_batch", "hxt_unpack_verify_batch",
+    "hxt_stage_d2h_slots", "hxt_stage_h2d_slots",
     "hxt_strerror", "hxt_last_hip_error", "hxt_version",
 )
 
@@ -113,6 +114,8 @@ def lib():
             "hxt_pack": (i, [vp, C.POINTER(vp), vp, u64p, vp]),
             "hxt_stage_d2h": (i, [vp, i, vp, vp, vp]),
             "hxt_stage_h2d": (i, [vp, i, vp, vp, vp]),
+            "hxt_stage_d2h_slots": (i, [vp, i, i, i, vp, vp, vp]),
+            "hxt_stage_h2d_slots": (i, [vp, i, i, i, vp, vp, vp]),
             "hxt_unpack": (i, [vp, vp, C.POINTER(vp), u64p, vp]),
             "hxt_checksum": (i, [vp, vp, u64p, vp]),
             "hxt_checksum2": (i, [vp, vp, u64p, vp]),
@@ -268,7 +271,7 @@ def hxt_plan_multi(tensors: Sequence, n_lanes: int, chunk_bytes: int) -> Plan:
     return Plan(out.value, arithmetic)
 
 
-HXT_OPT_PACKED_HINT = 1
+HXT_OPT_PACKED_HINT, HXT_OPT_STAGE_D2H = 1, 2
 
 
 def hxt_plan_set_option(plan: Plan, option: int, value: int) -> None:
@@ -437,6 +440,16 @@ def hxt_stage_d2h(plan: Plan, lane: int, packed_dev, host_pinned, stream=None) -
 def hxt_stage_h2d(plan: Plan, lane: int, host_pinned, packed_dev, stream=None) -> None:
     _check(lib().hxt_stage_h2d(plan.handle, lane, _ptr(host_pinned), _ptr(packed_dev), _stream(stream)),
            "hxt_stage_h2d")
+
+
+def hxt_stage_d2h_slots(plan: Plan, lane: int, first_slot: int, n_slots: int, packed_dev, host_pinned, stream=None) -> None:
+    _check(lib().hxt_stage_d2h_slots(plan.handle, lane, first_slot, n_slots, _ptr(packed_dev), _ptr(host_pinned),
+                                     _stream(stream)), "hxt_stage_d2h_slots")
+
+
+def hxt_stage_h2d_slots(plan: Plan, lane: int, first_slot: int, n_slots: int, host_pinned, packed_dev, stream=None) -> None:
+    _check(lib().hxt_stage_h2d_slots(plan.handle, lane, first_slot, n_slots, _ptr(host_pinned), _ptr(packed_dev),
+                                     _stream(stream)), "hxt_stage_h2d_slots")
 
 
 def hxt_version() -> str:

@@ -84,6 +84,14 @@ static void run(const view *vs, int T, int64_t B, int k, int aliasing)
     }
     EXPECT(hxo_verify(L, B, k, recv, tags, 77, 5, status) == 0);
     EXPECT(status[C] == 0);
+    memset(recv, 0x5A, (size_t)(P > 0 ? P : 1));         /* and slot by slot */
+    for (int l = 0; l < k; ++l) {
+        int64_t n = hxo_lane_chunks(L, B, k, l);
+        for (int64_t s = 0; s < n; ++s) EXPECT(hxo_stage_slots(L, B, k, l, s, 1, host, recv) == 0);
+        EXPECT(hxo_stage_slots(L, B, k, l, n, 1, host, recv) == -1);
+    }
+    EXPECT(hxo_verify(L, B, k, recv, tags, 77, 5, status) == 0);
+    EXPECT(status[C] == 0);
     for (int64_t p = 0; p < P; ++p) {                   /* every packed byte has an origin, and it is the right one */
         int32_t t = -1;
         int64_t off = -1;

@@ -399,6 +399,49 @@ def test_staging_lane_by_lane_and_all_lanes(name):
             assert np.array_equal(b.cpu().numpy(), a)
 
 
+@pytest.mark.parametrize("d2h", [0, 1], ids=["copy_command", "copy_kernel"])
+@pytest.mark.parametrize("name", ["ragged_last_chunk_2p5", "fewer_chunks_than_lanes", "sixty_four_lanes", "contig_1MB_ragged",
+                                  "multi_mid"])
+def test_staging_in_runs_of_slots(name, d2h):
+    """A lane staged in pieces (runs of slots), each piece down by the copy command or by the library's copy kernel
+    and up by a copy command: exactly the oracle's bytes move, untouched bytes keep their canaries."""
+    case = ([c for c in MID_CASES if c.name == name] or [None])[0] or case_by_name(name)
+    say("slot staging", name, "d2h mode", d2h)
+    raws = make_storages(case, 19)
+    m = oracle_msg(case)
+    p, packed, want, _ = round_trip_check(case, raws)
+    hxt.hxt_plan_set_option(p, hxt.HXT_OPT_STAGE_D2H, d2h)
+    n = want.size
+    rng = np.random.default_rng(5)
+    host = torch.full((n,), 0x11, dtype=torch.uint8).pin_memory()
+    recv = torch.full((n,), 0x22, dtype=torch.uint8, device=DEV)
+    expect_host, expect_recv = np.full(n, 0x11, np.uint8), np.full(n, 0x22, np.uint8)
+    for lane in range(case.k):
+        slots = p.lane_info(lane)["n_chunks"]
+        s = 0
+        while s < slots:                                   # random cuts, the empty run included
+            cnt = int(rng.integers(0, slots - s + 1)) if rng.random() < 0.8 else 0
+            hxt.hxt_stage_d2h_slots(p, lane, s, cnt, packed, host)
+            hxt.hxt_stage_h2d_slots(p, lane, s, cnt, host, recv)
+            ho.stage_slots(m, case.B, case.k, lane, s, cnt, want, expect_host)
+            ho.stage_slots(m, case.B, case.k, lane, s, cnt, expect_host, expect_recv)
+            s += cnt
+        with pytest.raises(hxt.HxtError) as e:
+            hxt.hxt_stage_d2h_slots(p, lane, slots, 1, packed, host)
+        assert e.value.status == hxt.HXT_EINVAL
+    torch.cuda.synchronize()
+    assert np.array_equal(host.numpy(), expect_host)
+    assert np.array_equal(recv.cpu().numpy(), expect_recv)
+    # whole lanes and the whole buffer through the copy kernel too
+    host2 = torch.full((n,), 0x11, dtype=torch.uint8).pin_memory()
+    hxt.hxt_stage_d2h(p, -1, packed, host2)
+    torch.cuda.synchronize()
+    assert np.array_equal(host2.numpy(), expect_host)
+    with pytest.raises(hxt.HxtError) as e:
+        hxt.hxt_stage_d2h_slots(p, -1, 0, 1, packed, host)
+    assert e.value.status == hxt.HXT_EINVAL
+
+
 @pytest.mark.parametrize("name", ["contig_1MB_ragged", "multi_mid"])
 def test_cpu_forwarding_chain_with_host_hop(name):
     # D2H into the sender's pinned buffer, host-to-host hop (stream ordered), H2D from the receiver's pinned
