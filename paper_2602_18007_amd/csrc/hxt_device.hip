@@ -128,17 +128,26 @@ void with_hints(bool nt_packed, F &&f)
     }
 }
 
-// The uniform copy is launched with 32 KiB of (unused) dynamic LDS per workgroup, which caps residency at 5
+// The streaming copies are launched with 32 KiB of (unused) dynamic LDS per workgroup, which caps residency at 5
 // workgroups per CU instead of 8: with 8 the memory system holds twice the bytes it needs to stay busy, every
-// request queues for longer and the launch's tail grows (measured on 2 x 32 MiB, sums on: 26.1 -> 25.3 us per
-// launch all-cold, 23.9 -> 23.3 us with the packed side cacheable; 4 per CU is no better, 6 gives half the gain).
+// request queues for longer and the launch's tail grows.  Measured per launch, all-cold, checks on: k_uniform on
+// 2 x 32 MiB 26.1 -> 25.3 us (23.9 -> 23.3 us with the packed side cacheable); k_contig on the 1.7 GB message 587 ->
+// 557 us (6 per CU 574, 4 per CU 564, 3 per CU 563, 2 per CU 618); k_contig_tag 571 -> 559 us; k_contig_accumulate
+// 717 -> 701 us; k_rows_split 35.3 -> 33.2 us.  Not applied where it does not pay: k_rows (23.1 -> 23.8 us),
+// k_uniform_tag (27.3 vs 27.4 us all-cold, 25.5 vs 24.6 us cacheable), k_uniform_accumulate (no change).
 // HXT_UNIFORM_LDS overrides (bytes, 0 = no cap).
 constexpr int kUniformLdsPad = 32768;
+
+inline size_t residency_cap_lds()
+{
+    static const size_t lds = size_t(std::max(0, std::min(65536, env_int("HXT_UNIFORM_LDS", kUniformLdsPad))));
+    return lds;
+}
 
 template <int DIR, bool CSUM>
 void launch_uniform(const UniformArgs &a, uint32_t tiles, bool nt_packed, hipStream_t st)
 {
-    static const size_t lds = size_t(std::max(0, std::min(65536, env_int("HXT_UNIFORM_LDS", kUniformLdsPad))));
+    const size_t lds = residency_cap_lds();
     with_hints(nt_packed, [&]<bool NTU, bool NTP>() { k_uniform<DIR, CSUM, NTU, NTP><<<tiles, kThreads, lds, st>>>(a); });
 }
 
@@ -147,7 +156,7 @@ void launch_contig(const hxt_plan_t &pl, const Group &g, const BasePtrs &b, uint
                    hipStream_t st)
 {
     with_hints(packed_nontemporal(pl), [&]<bool NTU, bool NTP>() {
-        k_contig<UNPACK, CSUM, NTU, NTP><<<g.count, kThreads, 0, st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, b, packed, cx);
+        k_contig<UNPACK, CSUM, NTU, NTP><<<g.count, kThreads, residency_cap_lds(), st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, b, packed, cx);
     });
 }
 
@@ -317,7 +326,7 @@ int run_copy(hxt_plan_t &pl, void *const *ptrs, uint8_t *packed, uint64_t *sums,
             k_rows_any<UNPACK, CSUM><<<g.count, kThreads, 0, st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, pl.d_tensors,
                                                                    g.tensor_base, b, packed, cx);
         } else if (g.kernel == K_ROWS_SPLIT) {
-            k_rows_split<UNPACK, CSUM><<<g.count, kThreads, 0, st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, pl.d_tensors,
+            k_rows_split<UNPACK, CSUM><<<g.count, kThreads, residency_cap_lds(), st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, pl.d_tensors,
                                                                      g.tensor_base, b, packed, cx);
         } else {
             // The transpose and per-element kernels are instantiated per element size: issue one
@@ -384,7 +393,7 @@ int run_accumulate(hxt_plan_t &pl, void *const *ptrs, uint8_t *packed, uint64_t 
         }
         if (aligned)
             with_hints(ntp, [&]<bool NTU, bool NTP>() {
-                k_contig_accumulate<CSUM, NTU, NTP><<<g.count, kThreads, 0, st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles,
+                k_contig_accumulate<CSUM, NTU, NTP><<<g.count, kThreads, residency_cap_lds(), st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles,
                                                                                   b, kinds, packed, cx);
             });
         else
@@ -698,7 +707,7 @@ int run_copy_tag(const hxt_plan_t *plan, void *const *ptrs, void *packed, void *
         std::memset(&b, 0, sizeof b);
         for (uint32_t i = 0; i < g.n_tensors; ++i) b.p[i] = static_cast<uint8_t *>(ptrs[g.tensor_base + i]);
         with_hints(packed_nontemporal(pl), [&]<bool NTU, bool NTP>() {
-            k_contig_tag<UNPACK, MODE, NTU, NTP><<<g.count, kThreads, 0, st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, b, pk,
+            k_contig_tag<UNPACK, MODE, NTU, NTP><<<g.count, kThreads, residency_cap_lds(), st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, b, pk,
                                                                                p.geom, out, cx.acc, cx.stride, cx.fan, w);
         });
         HXT_HIP(hipGetLastError());

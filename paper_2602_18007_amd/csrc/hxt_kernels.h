@@ -1125,12 +1125,20 @@ struct Sums2 {
     uint64_t s, w;
 };
 
-__device__ __forceinline__ void add_vector(Sums2 &acc, u32x4 r, uint32_t v)      // v: vector number in the tile
-{
-    const uint64_t zw = uint64_t(r.z) + r.w, yzw = zw + r.y, sv = yzw + r.x;
-    acc.s += sv;
-    acc.w += uint64_t(4 * v + 1) * sv + (yzw + zw + r.w);
-}
+// A thread's vectors are numbers tid + 256 n (n = 0, 1, ...) of the tile; with S_n the sum of vector n's words and
+// I_n = y + 2z + 3w, the tile-local weighted sum is
+//   sum (i + 1) w_i = (4 tid + 1) * sum_n S_n + 1024 * sum_n n S_n + sum_n I_n,
+// so the loop only adds (as in k_checksum2) and each thread multiplies once at the end.
+struct Partial2 {
+    uint64_t S, nS, I;
+    __device__ __forceinline__ void add(u32x4 r, uint64_t n)
+    {
+        const uint64_t zw = uint64_t(r.z) + r.w, yzw = zw + r.y, sv = yzw + r.x;
+        S += sv;
+        nS += n * sv;
+        I += yzw + zw + r.w;
+    }
+};
 
 template <bool UNPACK, bool NTU, bool NTP>
 __device__ __forceinline__ Sums2 copy_span2(uint8_t *user, uint8_t *pk, uint32_t bytes)
@@ -1141,22 +1149,32 @@ __device__ __forceinline__ Sums2 copy_span2(uint8_t *user, uint8_t *pk, uint32_t
     const uint32_t nvec = bytes >> 4;
     constexpr uint32_t STEP = kThreads * kUnroll;
     const uint32_t full = nvec / STEP * STEP;
-    Sums2 acc{0, 0};
-    for (uint32_t v = threadIdx.x; v < full; v += STEP) {
+    Partial2 p{0, 0, 0};
+    uint64_t n0 = 0;                                     // n of the current block's first vector
+    uint32_t v = threadIdx.x;
+    for (; v < full; v += STEP, n0 += kUnroll) {
         u32x4 r[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) r[u] = load16<NTL>(s + v + u * kThreads);
+        uint64_t blockS = 0, blockN = 0, blockI = 0;     // this block's sum_u S_u, sum_u u * S_u, sum_u I_u
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
+        for (int u = kUnroll - 1; u >= 0; --u) {
             store16<NTS>(d + v + u * kThreads, r[u]);
-            add_vector(acc, r[u], v + u * kThreads);
+            const uint64_t zw = uint64_t(r[u].z) + r[u].w, yzw = zw + r[u].y;
+            blockN += blockS;                            // after the loop: sum_u u * S_u
+            blockS += yzw + r[u].x;
+            blockI += yzw + zw + r[u].w;
         }
+        p.S += blockS;
+        p.nS += blockN + n0 * blockS;
+        p.I += blockI;
     }
-    for (uint32_t v = full + threadIdx.x; v < nvec; v += kThreads) {
+    for (; v < nvec; v += kThreads, ++n0) {
         const u32x4 r = load16<NTL>(s + v);
         store16<NTS>(d + v, r);
-        add_vector(acc, r, v);
+        p.add(r, n0);
     }
+    Sums2 acc{p.S, uint64_t(4 * threadIdx.x + 1) * p.S + 4ull * kThreads * p.nS + p.I};
     const uint32_t tail = bytes & 15;                    // only at the very end of the tensor
     if (threadIdx.x < tail) {
         const uint32_t i = (nvec << 4) + threadIdx.x;
