@@ -1003,8 +1003,7 @@ int hxt_plan_tensor_unpack_safe(const hxt_plan_t *plan, int t)
 int hxt_plan_tensor_kind(const hxt_plan_t *plan, int t)
 {
     if (!plan || t < 0 || size_t(t) >= plan->p.tensors.size()) return HXT_EINVAL;
-    const Kind k = plan->p.tensors[t].kind;
-    return k == K_ROWS_SPLIT ? int(K_ROWS) : int(k);          // both are the row gather
+    return int(plan->p.tensors[t].kind);
 }
 
 int hxt_pack(const hxt_plan_t *plan, const void *const *src, void *packed, uint64_t *sums, void *stream)

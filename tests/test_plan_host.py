@@ -119,8 +119,8 @@ def test_kernel_family_per_view():
     assert kinds["rows_interleaved_3d"] == ["rows"]
     assert kinds["true_transpose_64x48"] == ["transpose"]
     assert kinds["transpose_batched"] == ["transpose"]
-    assert kinds["rows_not_16B_multiple"] == ["rows"]         # 200-byte runs: the row gather with narrower pieces
-    assert kinds["esize1_2d_strided"] == ["rows"]             # 31-byte runs
+    assert kinds["rows_not_16B_multiple"] == ["rows_split"]   # 200-byte runs: the row gather in narrower pieces
+    assert kinds["esize1_2d_strided"] == ["rows_split"]       # 31-byte runs
     assert kinds["four_d_mixed"] == ["generic"]               # 12-byte runs are too short for it
     assert kinds["inner_stride_2"] == ["generic"]
     assert kinds["size_one_dims"] == ["contig"]
