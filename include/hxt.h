@@ -153,7 +153,8 @@ int hxt_plan_destroy(hxt_plan_t *plan); /* NULL is allowed */
 typedef enum { HXT_OPT_PACKED_HINT = 1, HXT_OPT_STAGE_D2H = 2 } hxt_option_t;
 int hxt_plan_set_option(hxt_plan_t *plan, int option, int value);
 
-/* ---- queries (host only) ---------------------------------------------------- */
+/* ---- queries (host only; not in the paper: what a caller needs to size its buffers and to
+ * check the layout contract stated at the top of this file) -------------------------- */
 size_t hxt_plan_message_bytes(const hxt_plan_t *plan); /* N */
 size_t hxt_plan_stream_bytes(const hxt_plan_t *plan);  /* L */
 size_t hxt_plan_packed_bytes(const hxt_plan_t *plan);  /* num_chunks * chunk_bytes */
@@ -323,7 +324,9 @@ typedef struct {
 
 int hxt_exchange_stream(const hxt_plan_t *plan, const hxt_exchange_t *x);
 
-/* ---- step 5: stand-alone per-chunk checksum of a packed buffer --------------- */
+/* ---- step 5: stand-alone per-chunk checksum of a packed buffer (not in the paper: the
+ * integrity check of this library's contract, also available fused into hxt_pack /
+ * hxt_unpack through their `sums` argument) ------------------------------------------ */
 int hxt_checksum(const hxt_plan_t *plan, const void *packed, uint64_t *sums, void *stream);
 
 /* ---- widening of step 5: a check that also sees words that changed places --------
