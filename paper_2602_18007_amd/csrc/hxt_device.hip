@@ -133,7 +133,7 @@ void with_hints(bool nt_packed, F &&f)
 // request queues for longer and the launch's tail grows.  Measured per launch, all-cold, checks on: k_uniform on
 // 2 x 32 MiB 26.1 -> 25.3 us (23.9 -> 23.3 us with the packed side cacheable); k_contig on the 1.7 GB message 587 ->
 // 557 us (6 per CU 574, 4 per CU 564, 3 per CU 563, 2 per CU 618); k_contig_tag 571 -> 559 us; k_contig_accumulate
-// 717 -> 701 us; k_rows_split 35.3 -> 33.2 us.  Not applied where it does not pay: k_rows (23.1 -> 23.8 us),
+// 717 -> 701 us.  Not applied where it does not pay: k_rows (23.1 -> 23.8 us), k_rows_split (30.7 -> 31.7 us),
 // k_uniform_tag (27.3 vs 27.4 us all-cold, 25.5 vs 24.6 us cacheable), k_uniform_accumulate (no change).
 // HXT_UNIFORM_LDS overrides (bytes, 0 = no cap).
 constexpr int kUniformLdsPad = 32768;
@@ -326,7 +326,7 @@ int run_copy(hxt_plan_t &pl, void *const *ptrs, uint8_t *packed, uint64_t *sums,
             k_rows_any<UNPACK, CSUM><<<g.count, kThreads, 0, st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, pl.d_tensors,
                                                                    g.tensor_base, b, packed, cx);
         } else if (g.kernel == K_ROWS_SPLIT) {
-            k_rows_split<UNPACK, CSUM><<<g.count, kThreads, residency_cap_lds(), st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, pl.d_tensors,
+            k_rows_split<UNPACK, CSUM><<<g.count, kThreads, 0, st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, pl.d_tensors,
                                                                      g.tensor_base, b, packed, cx);
         } else {
             // The transpose and per-element kernels are instantiated per element size: issue one

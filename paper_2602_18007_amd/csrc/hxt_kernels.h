@@ -586,7 +586,7 @@ __global__ __launch_bounds__(kThreads) void k_rows_any(const Tile *__restrict__ 
 
 // ---- rows whose length or pitch is not a multiple of 16 bytes ----------------------
 // Still a gather of contiguous runs (of 16 bytes or more), but a 16-byte vector of the packed stream may end
-// one run and begin the next, and the tensor side is only G-byte aligned (G = 4, 2 or 1; 8 is served as 4).
+// one run and begin the next, and the tensor side is only G-byte aligned (G = 8, 4, 2 or 1).
 // Work is dealt in pieces of G bytes, consecutive lanes taking consecutive pieces of the tile: a wave's access
 // is then contiguous on the packed side and contiguous within each run on the tensor side (64 lanes x 4 bytes
 // = 256 bytes per instruction), whatever the run length; each piece finds its run with one multiply-shift
@@ -603,6 +603,7 @@ __device__ __forceinline__ uint64_t run_storage_offset(const TensorDev &td, uint
 }
 
 template <int G> struct PieceOf;
+template <> struct PieceOf<8> { using type = uint64_t; };
 template <> struct PieceOf<4> { using type = uint32_t; };
 template <> struct PieceOf<2> { using type = uint16_t; };
 template <> struct PieceOf<1> { using type = uint8_t; };
@@ -615,11 +616,18 @@ __device__ __forceinline__ uint64_t rows_split_tile(const Tile &t, const TensorD
     const uint64_t row0 = t.src_off / row_bytes;                    // uniform
     const uint32_t col0 = uint32_t(t.src_off - row0 * row_bytes);
     const uint32_t npiece = t.n0 / G;
-    constexpr int U = 8;                                            // pieces in flight per thread
+    constexpr int U = G == 8 ? 8 : 16;                              // pieces in flight per thread: a 16 KiB tile in one go
     uint64_t acc = 0;
+    // Two-dimensional views (the usual padded-pitch matrix) need no index decomposition: run row0 + dr starts
+    // (row0 + dr) * pitch into the storage, so byte x of the tile's first run sits at x + dr * (pitch - run length)
+    // from that run's start.
+    const bool two_d = td.ndim == 2;
+    uint8_t *const first_run = user + row0 * uint64_t(td.stride_b[0]);                   // uniform
+    const int64_t slack = td.stride_b[0] - int64_t(row_bytes);
     auto user_piece = [&](uint32_t i) {                             // piece i of the tile -> its place in storage
         const uint32_t x = col0 + i * G;
         const uint32_t dr = fast_div(x, td.row_div);
+        if (two_d) return reinterpret_cast<P *>(first_run + (int64_t(x) + int64_t(dr) * slack));
         return reinterpret_cast<P *>(user + run_storage_offset(td, uint32_t(row0) + dr) + (x - dr * row_bytes));
     };
     P *pieces = reinterpret_cast<P *>(pk);
@@ -640,7 +648,8 @@ __device__ __forceinline__ uint64_t rows_split_tile(const Tile &t, const TensorD
             if (i < npiece) {
                 if constexpr (UNPACK) __builtin_nontemporal_store(r[u], user_piece(i));
                 else pieces[i] = r[u];
-                if constexpr (CSUM) acc += uint64_t(r[u]) << (8 * ((i * G) & 3));
+                if constexpr (CSUM && G == 8) acc += (uint64_t(r[u]) & 0xFFFFFFFFull) + (uint64_t(r[u]) >> 32);
+                if constexpr (CSUM && G < 8) acc += uint64_t(r[u]) << (8 * ((i * G) & 3));
             }
         }
     }
@@ -659,7 +668,8 @@ __global__ __launch_bounds__(kThreads) void k_rows_split(const Tile *__restrict_
     // widest piece that is naturally aligned everywhere: low bits of the base address, the run length and the pitches
     const uint32_t low = (uint32_t(reinterpret_cast<uintptr_t>(user)) | td.low_or) & 15u;
     uint64_t acc;
-    if ((low & 3u) == 0) acc = rows_split_tile<UNPACK, CSUM, 4>(t, td, user, pk);
+    if ((low & 7u) == 0) acc = rows_split_tile<UNPACK, CSUM, 8>(t, td, user, pk);
+    else if ((low & 3u) == 0) acc = rows_split_tile<UNPACK, CSUM, 4>(t, td, user, pk);
     else if ((low & 1u) == 0) acc = rows_split_tile<UNPACK, CSUM, 2>(t, td, user, pk);
     else acc = rows_split_tile<UNPACK, CSUM, 1>(t, td, user, pk);
     if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, chunk_tiles[t.chunk], cx);
