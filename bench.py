@@ -68,7 +68,7 @@ def parse():
                     help="for --workload stream_1f1b")
     ap.add_argument("--window", type=int, default=-1,
                     help="for --workload stream_1f1b --path cpu_forward: micro-batches per hxt_exchange_stream call, the "
-                         "streams being drained between calls (0: all at once; default 12)")
+                         "streams being drained between calls (0: all at once; default 16)")
     ap.add_argument("--direct-mode", type=int, default=0, help="for --workload stream_1f1b: hxt_direct_mode_t (0 automatic)")
     ap.add_argument("--no-configs", action="store_true", help="skip the per-message entries")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -579,7 +579,7 @@ def config_entries(torch, hxt, wl, a, link, headline_regions):
         e.pop("gbps_per_direction")
         out.append(e)
     if not a.no_staged:
-        for window, label in ((12, "issued in windows of 12 micro-batches, the three streams drained between windows"),
+        for window, label in ((16, "issued in windows of 16 micro-batches, the three streams drained between windows"),
                               (0, "all 32 micro-batches enqueued at once")):
             e = {"workload": w.name, "path": "cpu_forward", "issue": label}
             e.update(stream_passes(torch, hxt, w, "cpu_forward", window=window, passes=3))
@@ -625,7 +625,7 @@ def main():
     torch.cuda.set_device(0)
     w = wl.ALL[a.workload]()
     if w.name == "stream_1f1b":
-        window = (12 if a.path == "cpu_forward" else 0) if a.window < 0 else a.window
+        window = (16 if a.path == "cpu_forward" else 0) if a.window < 0 else a.window
         r = stream_passes(torch, hxt, w, a.path, direct_mode=a.direct_mode, window=window, tags=a.tags,
                           checksums=not a.no_checksum, passes=max(1, min(a.steps, 20)), warm=max(1, min(a.warmup, 2)))
         out = {"metric": METRIC, "value": r["pack_unpack_gbps"], "value_of": "pack+unpack GB/s", "unit": "GB/s", "n_gpus": 1,
