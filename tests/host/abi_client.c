@@ -42,6 +42,18 @@ int main(void)
     EXPECT(ci.payload == (1u << 20) && ci.packed_off == (2u * 8u + 1u) * (1u << 20));
     EXPECT(hxt_plan_chunk_info(plan, 32, &ci) == HXT_EINVAL);
     EXPECT(hxt_plan_lane_info(plan, 4, NULL) == HXT_EINVAL);
+    EXPECT(hxt_plan_set_option(plan, HXT_OPT_PACKED_HINT, 1) == HXT_OK);
+    EXPECT(hxt_plan_set_option(plan, HXT_OPT_STAGE_D2H, 7) == HXT_EINVAL);
+    EXPECT(hxt_stage_d2h_slots(plan, 1, 7, 2, NULL, NULL, NULL) == HXT_EINVAL);   /* lane 1 has slots 0..7 */
+    EXPECT(hxt_stage_h2d_slots(plan, 1, 8, 0, NULL, NULL, NULL) == HXT_OK);       /* the empty run */
+    hxt_exchange_t x;
+    memset(&x, 0, sizeof x);
+    x.n_messages = 1;
+    x.n_buffers = 2;
+    x.direct_mode = 9;
+    EXPECT(hxt_exchange_stream(plan, &x) == HXT_EINVAL);
+    EXPECT(hxt_pack_noalloc(NULL, 0, 4, 1u << 20, NULL, NULL, NULL) == HXT_OK);
+    EXPECT(hxt_pack_noalloc(NULL, 64, 4, 1000, NULL, NULL, NULL) == HXT_EINVAL);
     EXPECT(hxt_plan_destroy(plan) == HXT_OK);
     EXPECT(hxt_plan_destroy(NULL) == HXT_OK);
 

@@ -183,6 +183,44 @@ def test_raw_abi_null_and_dtype_errors():
     assert b"align" in L.hxt_strerror(hxt.HXT_EALIGN)
 
 
+def test_argument_errors_of_the_newer_entry_points():
+    """Options, staging in runs of slots, the batched tag calls, the stream's mode fields and the plan-free pack:
+    everything that is refused before a GPU is touched."""
+    L = hxt.lib()
+    p = hxt.hxt_plan((2560,), None, 1, 2, 1024)                       # 3 chunks: lane 0 holds 2, lane 1 holds 1
+    assert L.hxt_plan_set_option(None, hxt.HXT_OPT_PACKED_HINT, 1) == hxt.HXT_EINVAL
+    assert L.hxt_plan_set_option(p.handle, 99, 1) == hxt.HXT_EINVAL
+    assert L.hxt_plan_set_option(p.handle, hxt.HXT_OPT_PACKED_HINT, 2) == hxt.HXT_EINVAL
+    assert L.hxt_plan_set_option(p.handle, hxt.HXT_OPT_STAGE_D2H, -1) == hxt.HXT_EINVAL
+    for opt, vals in ((hxt.HXT_OPT_PACKED_HINT, (-1, 0, 1)), (hxt.HXT_OPT_STAGE_D2H, (0, 1, 0))):
+        for v in vals:
+            assert L.hxt_plan_set_option(p.handle, opt, v) == hxt.HXT_OK
+    for f in (L.hxt_stage_d2h_slots, L.hxt_stage_h2d_slots):
+        assert f(None, 0, 0, 1, 256, 256, None) == hxt.HXT_EINVAL
+        assert f(p.handle, -1, 0, 1, 256, 256, None) == hxt.HXT_EINVAL          # a run of slots belongs to one lane
+        assert f(p.handle, 2, 0, 1, 256, 256, None) == hxt.HXT_EINVAL
+        assert f(p.handle, 0, 1, 2, 256, 256, None) == hxt.HXT_EINVAL           # lane 0 has slots 0 and 1 only
+        assert f(p.handle, 1, 1, 1, 256, 256, None) == hxt.HXT_EINVAL
+        assert f(p.handle, 0, 0, -1, 256, 256, None) == hxt.HXT_EINVAL
+        assert f(p.handle, 0, -1, 1, 256, 256, None) == hxt.HXT_EINVAL
+        assert f(p.handle, 0, 2, 0, None, None, None) == hxt.HXT_OK             # the empty run
+        assert f(p.handle, 0, 0, 1, 256 + 8, 256, None) == hxt.HXT_EALIGN
+        assert f(p.handle, 0, 0, 1, None, 256, None) == hxt.HXT_EINVAL
+    assert L.hxt_pack_seal_batch(-1, None, None, None, None, None, None, None) == hxt.HXT_EINVAL
+    assert L.hxt_pack_seal_batch(1, None, None, None, None, None, None, None) == hxt.HXT_EINVAL
+    assert L.hxt_unpack_verify_batch(1, None, None, None, None, None, None, None, None) == hxt.HXT_EINVAL
+    assert L.hxt_pack_seal_batch(0, None, None, None, None, None, None, None) == hxt.HXT_OK
+    assert L.hxt_pack_noalloc(None, 100, 0, 256, None, None, None) == hxt.HXT_EINVAL
+    assert L.hxt_pack_noalloc(None, 100, 2, 100, None, None, None) == hxt.HXT_EINVAL
+    assert L.hxt_pack_noalloc(None, 100, 2, 256, None, None, None) == hxt.HXT_EINVAL      # NULL buffers
+    assert L.hxt_pack_noalloc(256, 100, 2, 256, 256 + 16, None, None) == hxt.HXT_EALIGN
+    assert L.hxt_pack_noalloc(None, 0, 2, 256, None, None, None) == hxt.HXT_OK            # empty message
+    assert L.hxt_pack_noalloc(256, (1 << 40) + 1, 2, 256, 256, None, None) == hxt.HXT_EUNSUPPORTED
+    x = hxt._Exchange()
+    x.n_messages, x.n_buffers, x.drain_every = 1, 1, -1
+    assert L.hxt_exchange_stream(p.handle, C.byref(x)) == hxt.HXT_EINVAL
+
+
 def test_without_a_gpu_the_data_plane_reports_an_error_instead_of_falling_back():
     import torch
     if torch.cuda.is_available():
@@ -198,6 +236,7 @@ def test_without_a_gpu_the_data_plane_reports_an_error_instead_of_falling_back()
     assert L.hxt_checksum2(p.handle, fake, fake, None) == hxt.HXT_EHIP
     assert L.hxt_seal(p.handle, fake, 1, 1, fake, None) == hxt.HXT_EHIP
     assert L.hxt_pack_seal(p.handle, ptrs, fake, 1, 1, fake, None) == hxt.HXT_EHIP
+    assert L.hxt_pack_noalloc(fake, 1000, 2, 256, fake, fake, None) == hxt.HXT_EHIP
     with pytest.raises(hxt.HxtError) as e:
         hxt.hxt_pack(p, [fake], fake, None)
     assert e.value.status == hxt.HXT_EHIP and "HIP" in str(e.value)

@@ -81,3 +81,34 @@ def test_no_alloc_pack_rejects_what_the_scratch_cannot_serve():
             hxt.hxt_pack_noalloc(src, n, kw["n_lanes"], kw["chunk_bytes"], packed, None)
         assert e.value.status == hxt.HXT_EINVAL
     hxt.hxt_pack_noalloc(None, 0, 2, 256, None, None)        # empty message: no-op
+
+
+def test_no_alloc_pack_can_be_captured_in_a_hip_graph_and_replayed():
+    """What the entry point is for: a caller under stream capture.  The call records kernels only (its zero-fill
+    is a kernel, not a memset node); every replay, with eager work and synchronisations between the replays, must
+    give the eager result for the source's contents at that time."""
+    n, k, B = 3 * 1024 * 1024 + 4096 + 32, 4, 1 << 20
+    plan = hxt.hxt_plan((n,), None, 1, k, B)
+    C = plan.num_chunks
+    src = torch.randint(0, 255, (n,), dtype=torch.uint8, device=DEV)
+    packed = torch.full((plan.packed_bytes,), 0xA5, dtype=torch.uint8, device=DEV)
+    sums = torch.full((C,), -1, dtype=torch.int64, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        hxt.hxt_pack_noalloc(src, n, k, B, packed, sums, side)      # first call on this device: before capture begins
+    side.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        hxt.hxt_pack_noalloc(src, n, k, B, packed, sums, side)
+    for rep in range(3):
+        src.copy_(torch.randint(0, 255, (n,), dtype=torch.uint8, device=DEV))       # eager work between the replays
+        want_packed = torch.full_like(packed, 0xA5)
+        want_sums = torch.full_like(sums, -2)
+        hxt.hxt_pack(plan, [src], want_packed, want_sums)
+        packed.fill_(0xA5)
+        sums.fill_(-1)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(packed, want_packed) and torch.equal(sums, want_sums), "replay %d" % rep
