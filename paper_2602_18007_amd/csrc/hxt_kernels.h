@@ -831,8 +831,8 @@ __global__ __launch_bounds__(kThreads) void k_transpose(const Tile *__restrict__
 }
 
 // ---- generic: any strides, one element at a time -------------------------------
-// One thread per 16 packed bytes; every element's address is recomputed from its
-// logical index.  Slow, and only used for views the other kernels do not take.
+// Every element's address is recomputed from its logical index.  Slow, and only used for
+// views the other kernels do not take.
 template <typename E, bool UNPACK, bool CSUM>
 __global__ __launch_bounds__(kThreads) void k_generic(const Tile *__restrict__ tiles,
                                                       const uint32_t *__restrict__ chunk_tiles,
@@ -848,7 +848,6 @@ __global__ __launch_bounds__(kThreads) void k_generic(const Tile *__restrict__ t
         uint8_t *user = bases.p[t.tensor];
         uint8_t *pk = packed + t.packed_off;
         const uint32_t nel = t.n0 / sizeof(E);
-        constexpr uint32_t PER = 16 / sizeof(E);
         const uint64_t e0 = t.src_off / sizeof(E);
         // Coordinates of the tile's first element (the same for every thread).  When every dim fits the
         // multiply-shift division, an element's coordinates are these plus its number within the tile,
@@ -868,40 +867,52 @@ __global__ __launch_bounds__(kThreads) void k_generic(const Tile *__restrict__ t
                 }
             }
         }
-        for (uint32_t v = threadIdx.x; v * PER < nel; v += kThreads) {
+        // Consecutive lanes take consecutive elements, U of them in flight per thread: a wave's access is contiguous
+        // on the packed side and as dense on the tensor side as the view allows (every other element of a line for
+        // an inner stride of 2), instead of eight scattered two-byte accesses per lane.
+        auto locate = [&](uint32_t el) -> E * {
+            uint64_t off = 0;
+            if (fast) {
+                uint32_t x = el;                                   // carry into the last dim
 #pragma unroll
-            for (uint32_t j = 0; j < PER; ++j) {
-                const uint32_t el = v * PER + j;
-                if (el < nel) {
-                    uint64_t off = 0;
-                    if (fast) {
-                        uint32_t x = el;                                   // carry into the last dim
-#pragma unroll
-                        for (int d = HXT_MAX_DIMS - 1; d >= 0; --d) {
-                            if (d < nd) {
-                                x += base[d];
-                                if (d > 0) {
-                                    const uint32_t q = fast_div(x, td.dim_div[d]);
-                                    off += uint64_t(x - q * uint32_t(td.shape[d])) * uint64_t(td.stride_b[d]);
-                                    x = q;
-                                } else {
-                                    off += uint64_t(x) * uint64_t(td.stride_b[0]);
-                                }
-                            }
-                        }
-                    } else {
-                        uint64_t idx = e0 + el;
-                        for (int d = nd - 1; d >= 0; --d) {
-                            const uint64_t q = idx / uint64_t(td.shape[d]);
-                            off += (idx - q * uint64_t(td.shape[d])) * uint64_t(td.stride_b[d]);
-                            idx = q;
+                for (int d = HXT_MAX_DIMS - 1; d >= 0; --d) {
+                    if (d < nd) {
+                        x += base[d];
+                        if (d > 0) {
+                            const uint32_t q = fast_div(x, td.dim_div[d]);
+                            off += uint64_t(x - q * uint32_t(td.shape[d])) * uint64_t(td.stride_b[d]);
+                            x = q;
+                        } else {
+                            off += uint64_t(x) * uint64_t(td.stride_b[0]);
                         }
                     }
-                    E *u = reinterpret_cast<E *>(user + off);
-                    E *p = reinterpret_cast<E *>(pk) + el;
-                    const E val = UNPACK ? *p : *u;
-                    if constexpr (UNPACK) *u = val; else *p = val;
-                    if constexpr (CSUM) acc += elem_weighted(val, uint64_t(el) * sizeof(E));
+                }
+            } else {
+                uint64_t idx = e0 + el;
+                for (int d = nd - 1; d >= 0; --d) {
+                    const uint64_t q = idx / uint64_t(td.shape[d]);
+                    off += (idx - q * uint64_t(td.shape[d])) * uint64_t(td.stride_b[d]);
+                    idx = q;
+                }
+            }
+            return reinterpret_cast<E *>(user + off);
+        };
+        constexpr int U = 8;
+        E *p = reinterpret_cast<E *>(pk);
+        for (uint32_t e1 = threadIdx.x; e1 < nel; e1 += kThreads * U) {
+            E val[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t el = e1 + u * kThreads;
+                val[u] = 0;
+                if (el < nel) val[u] = UNPACK ? p[el] : *locate(el);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t el = e1 + u * kThreads;
+                if (el < nel) {
+                    if constexpr (UNPACK) *locate(el) = val[u]; else p[el] = val[u];
+                    if constexpr (CSUM) acc += elem_weighted(val[u], uint64_t(el) * sizeof(E));
                 }
             }
         }
