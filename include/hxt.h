@@ -260,7 +260,8 @@ int hxt_unpack_batch(int n, const hxt_plan_t *const *plans, const void *const *p
  * Enqueues pack -> (staging) -> unpack for n_messages messages of one geometry so that
  * the steps of consecutive messages overlap: message i uses buffer set i mod n_buffers;
  * pack runs on stream_pack, the device-to-host copies on stream_stage, the
- * host-to-device copies and unpack on stream_unpack; events created by the call order
+ * host-to-device copies and unpack on stream_unpack; events owned by the plan (created the
+ * first time they are needed, released by hxt_plan_destroy) order
  * them (pack of message i waits until buffer set i mod n_buffers has been drained by
  * message i - n_buffers, and so on).  This is the host-side event-handling half of
  * Section 2.2's control plane for a 1F1B schedule, where a stage sends one micro-batch

@@ -51,6 +51,11 @@ struct hxt_plan {
     int nt_packed = -1;                         // HXT_OPT_PACKED_HINT: -1 by size, 0 cacheable, 1 non-temporal
     int stage_d2h_kernel = 0;                   // HXT_OPT_STAGE_D2H: 0 copy command, 1 the library's copy kernel
     OpState ops[OP_COUNT];
+    // Events for hxt_exchange_stream, created on first need and kept until the plan is destroyed, so that a call
+    // in steady state creates nothing.  A call borrows what it needs and hands it back when it has enqueued
+    // everything (an event may be recorded again while earlier waits on it are still pending).
+    std::mutex ev_mu;
+    std::vector<hipEvent_t> ev_free;
 };
 
 // Accumulator slots for the entry point that may not allocate (hxt_pack_noalloc).  Every GPU the library
@@ -787,6 +792,41 @@ int run_tag_batch(int n, const hxt_plan_t *const *plans, void *const *const *ten
     return HXT_OK;
 }
 
+// n events from the plan's pool (created if the pool runs short); false after a HIP error (out is then empty).
+bool borrow_events(hxt_plan_t &pl, size_t n, std::vector<hipEvent_t> &out)
+{
+    std::lock_guard<std::mutex> lock(pl.ev_mu);
+    out.clear();
+    try {                                              // room for every event on both sides: nothing below can throw
+        out.reserve(n);
+        pl.ev_free.reserve(pl.ev_free.size() + n);
+    } catch (const std::bad_alloc &) {
+        g_last_hip = int(hipErrorOutOfMemory);
+        return false;
+    }
+    while (out.size() < n) {
+        hipEvent_t e = nullptr;
+        if (!pl.ev_free.empty()) {
+            e = pl.ev_free.back();
+            pl.ev_free.pop_back();
+        } else if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
+            g_last_hip = int(hipGetLastError());
+            for (hipEvent_t b : out) pl.ev_free.push_back(b);
+            out.clear();
+            return false;
+        }
+        out.push_back(e);
+    }
+    return true;
+}
+
+void return_events(hxt_plan_t &pl, std::vector<hipEvent_t> &ev)
+{
+    std::lock_guard<std::mutex> lock(pl.ev_mu);
+    for (hipEvent_t e : ev) pl.ev_free.push_back(e);
+    ev.clear();
+}
+
 // Device-direct micro-batch stream for single-tensor messages, without cross-stream handshakes:
 // launch k unpacks message k-1 and packs message k (different buffer sets, independent work, so
 // the two overlap inside the launch and fill each other's ramp-up and tail); consecutive launches
@@ -825,12 +865,12 @@ int fused_direct_stream(hxt_plan_t &pl, const hxt_exchange_t &x, hipStream_t sp,
         HXT_HIP(hipGetLastError());
     }
     if (su != sp || ss != sp) {
-        hipEvent_t done;
-        HXT_HIP(hipEventCreateWithFlags(&done, hipEventDisableTiming));
-        hipError_t e = hipEventRecord(done, sp);
-        if (e == hipSuccess && su != sp) e = hipStreamWaitEvent(su, done, 0);
-        if (e == hipSuccess && ss != sp) e = hipStreamWaitEvent(ss, done, 0);
-        (void)hipEventDestroy(done);
+        std::vector<hipEvent_t> done;
+        if (!borrow_events(pl, 1, done)) return HXT_EHIP;
+        hipError_t e = hipEventRecord(done[0], sp);
+        if (e == hipSuccess && su != sp) e = hipStreamWaitEvent(su, done[0], 0);
+        if (e == hipSuccess && ss != sp) e = hipStreamWaitEvent(ss, done[0], 0);
+        return_events(pl, done);
         if (e != hipSuccess) return hip_fail(e);
     }
     return HXT_OK;
@@ -871,10 +911,9 @@ int chained_direct_stream(hxt_plan_t &pl, const hxt_exchange_t &x, hipStream_t a
                     : run_copy<true, false>(pl, x.dst + i * T, buf, nullptr, st, chain);
         if (rc != HXT_OK) return rc;
     }
-    hipEvent_t done[2] = {nullptr, nullptr};
-    hipError_t e = hipEventCreateWithFlags(&done[0], hipEventDisableTiming);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&done[1], hipEventDisableTiming);
-    if (e == hipSuccess) e = hipEventRecord(done[0], a);
+    std::vector<hipEvent_t> done;
+    if (!borrow_events(pl, 2, done)) return HXT_EHIP;
+    hipError_t e = hipEventRecord(done[0], a);
     if (e == hipSuccess) e = hipEventRecord(done[1], b);
     if (e == hipSuccess) e = hipStreamWaitEvent(b, done[0], 0);
     if (e == hipSuccess) e = hipStreamWaitEvent(a, done[1], 0);
@@ -882,8 +921,7 @@ int chained_direct_stream(hxt_plan_t &pl, const hxt_exchange_t &x, hipStream_t a
         e = hipStreamWaitEvent(third, done[0], 0);
         if (e == hipSuccess) e = hipStreamWaitEvent(third, done[1], 0);
     }
-    for (hipEvent_t ev : done)
-        if (ev) (void)hipEventDestroy(ev);
+    return_events(pl, done);
     return e == hipSuccess ? HXT_OK : hip_fail(e);
 }
 
@@ -936,6 +974,8 @@ int hxt_plan_destroy(hxt_plan_t *plan)
         release(o.acc);
         if (o.ev && hipEventDestroy(o.ev) != hipSuccess) rc = HXT_EHIP;
     }
+    for (hipEvent_t e : plan->ev_free)
+        if (hipEventDestroy(e) != hipSuccess) rc = HXT_EHIP;
     delete plan;
     return rc;
 }
@@ -1184,19 +1224,12 @@ int hxt_exchange_stream(const hxt_plan_t *plan, const hxt_exchange_t *x)
     // complete), landed (host buffer may be rewritten), tags read (pinned tag buffer may be rewritten)
     enum { PACKED, DRAINED, STAGED, LANDED, TAGS_READ, KINDS };
     const int nb = x->n_buffers;
-    std::vector<hipEvent_t> ev(size_t(nb) * KINDS, nullptr);
+    hxt_plan_t &pl = *const_cast<hxt_plan_t *>(plan);
+    std::vector<hipEvent_t> ev;
+    if (!borrow_events(pl, size_t(nb) * KINDS, ev)) return HXT_EHIP;
     auto at = [&](int kind, int b) -> hipEvent_t & { return ev[size_t(b) * KINDS + kind]; };
-    auto cleanup = [&]() {
-        for (hipEvent_t e : ev)
-            if (e) (void)hipEventDestroy(e);                  // pending events are released when they complete
-    };
+    auto cleanup = [&]() { return_events(pl, ev); };
     rc = HXT_OK;
-    for (hipEvent_t &e : ev)
-        if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
-            g_last_hip = int(hipGetLastError());
-            cleanup();
-            return HXT_EHIP;
-        }
     auto hip = [&](hipError_t e) {
         if (e != hipSuccess && rc == HXT_OK) rc = hip_fail(e);
         return e == hipSuccess;
