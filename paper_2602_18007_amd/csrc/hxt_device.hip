@@ -10,6 +10,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <functional>
 #include <mutex>
 #include <new>
 #include <optional>
@@ -51,6 +52,7 @@ struct hxt_plan {
     int nt_packed = -1;                         // HXT_OPT_PACKED_HINT: -1 by size, 0 cacheable, 1 non-temporal
     int stage_d2h_kernel = 0;                   // HXT_OPT_STAGE_D2H: 0 copy command, 1 the library's copy kernel
     OpState ops[OP_COUNT];
+    std::recursive_mutex slots_mu;              // see SlotsLock
     // Events for hxt_exchange_stream, created on first need and kept until the plan is destroyed, so that a call
     // in steady state creates nothing.  A call borrows what it needs and hands it back when it has enqueued
     // everything (an event may be recorded again while earlier waits on it are still pending).
@@ -207,11 +209,41 @@ void launch_generic(const hxt_plan_t &pl, uint32_t first, uint32_t count, uint32
 // The accumulator slots of an operation are shared by all calls of that operation on this
 // plan.  Calls on one stream are ordered by the stream; when the stream changes, the new
 // stream is made to wait for everything enqueued so far on the previous one.  That only works
-// if "enqueued so far" includes the previous claimant's kernels, so a call holds SlotsLock from
-// its first claim until its launches are enqueued (host-side enqueue time only; one lock for
-// all plans, recursive because batched calls fall back to single calls).
-std::recursive_mutex g_slots_mu;
+// if "enqueued so far" includes the previous claimant's kernels, so a call holds the plan's lock
+// from its first claim until its launches are enqueued (host-side enqueue time only; one lock
+// per plan, recursive because batched calls fall back to single calls).  Calls on different
+// plans do not wait for each other.
 using SlotsLock = std::lock_guard<std::recursive_mutex>;
+
+// The locks of all the plans of a batched call, taken in address order (each plan once), so
+// that two batched calls that share plans cannot wait for each other in a cycle.  Allocates
+// nothing: every step looks for the lowest address above the one locked last.
+class BatchLock {
+  public:
+    BatchLock(const hxt_plan_t *const *plans, int n) : plans_(plans), n_(n)
+    {
+        for (hxt_plan_t *pl = next(nullptr); pl; pl = next(pl)) pl->slots_mu.lock();
+    }
+    ~BatchLock()
+    {
+        for (hxt_plan_t *pl = next(nullptr); pl; pl = next(pl)) pl->slots_mu.unlock();
+    }
+    BatchLock(const BatchLock &) = delete;
+    BatchLock &operator=(const BatchLock &) = delete;
+
+  private:
+    hxt_plan_t *next(const hxt_plan_t *after) const
+    {
+        const hxt_plan_t *best = nullptr;
+        for (int i = 0; i < n_; ++i)
+            if (plans_[i] && std::less<const hxt_plan_t *>()(after, plans_[i]) &&
+                (!best || std::less<const hxt_plan_t *>()(plans_[i], best)))
+                best = plans_[i];
+        return const_cast<hxt_plan_t *>(best);
+    }
+    const hxt_plan_t *const *plans_;
+    int n_;
+};
 
 int claim_slots(hxt_plan_t &pl, Op op, hipStream_t st, SumCtx &cx, uint64_t *sums)
 {
@@ -291,7 +323,7 @@ int run_copy(hxt_plan_t &pl, void *const *ptrs, uint8_t *packed, uint64_t *sums,
     SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};
     std::optional<SlotsLock> lock;
     if constexpr (CSUM) {
-        lock.emplace(g_slots_mu);
+        lock.emplace(pl.slots_mu);
         const Op op = chain ? (UNPACK ? OP_UNPACK_B : OP_PACK_B) : (UNPACK ? OP_UNPACK : OP_PACK);
         int rc = claim_slots(pl, op, st, cx, sums);
         if (rc != HXT_OK) return rc;
@@ -361,7 +393,7 @@ int run_accumulate(hxt_plan_t &pl, void *const *ptrs, uint8_t *packed, uint64_t 
     SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};
     std::optional<SlotsLock> lock;
     if constexpr (CSUM) {
-        lock.emplace(g_slots_mu);
+        lock.emplace(pl.slots_mu);
         int rc = claim_slots(pl, OP_UNPACK, st, cx, sums);
         if (rc != HXT_OK) return rc;
         cx.sum_bits = pl.sum_bits_table;
@@ -575,7 +607,7 @@ int run_batch(int n, const hxt_plan_t *const *plans, void *const *const *tensors
         for (int j = 0; j < i; ++j)
             if (plans[j] == plans[i] && sums && sums[i] && sums[j]) return HXT_EINVAL;   // one accumulator set per plan
     }
-    SlotsLock lock(g_slots_mu);
+    BatchLock lock(plans, n);
     int i = 0;
     while (i < n) {
         hxt_plan_t &pl = *const_cast<hxt_plan_t *>(plans[i]);
@@ -639,7 +671,7 @@ int run_sum2(const hxt_plan_t *plan, const void *packed, int mode, void *out, co
     hxt_plan_t &pl = *const_cast<hxt_plan_t *>(plan);
     hipStream_t st = static_cast<hipStream_t>(stream);
     SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};          // callers have dealt with the empty message
-    SlotsLock lock(g_slots_mu);
+    SlotsLock lock(pl.slots_mu);
     if ((rc = claim_slots(pl, mode == SUM2_VERIFY ? (chain ? OP_SUM2_RECV_B : OP_SUM2_RECV) : (chain ? OP_SUM2_SEND_B : OP_SUM2_SEND), st, cx, nullptr)) != HXT_OK) return rc;
     const uint8_t *pk = static_cast<const uint8_t *>(packed);
     const bool ntp = packed_nontemporal(pl);
@@ -689,7 +721,7 @@ int run_copy_tag(const hxt_plan_t *plan, void *const *ptrs, void *packed, void *
         return run_sum2(plan, packed, MODE, out, work, stream, chain);
     }
     SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};
-    SlotsLock lock(g_slots_mu);
+    SlotsLock lock(pl.slots_mu);
     if ((rc = claim_slots(pl, UNPACK ? (chain ? OP_SUM2_RECV_B : OP_SUM2_RECV) : (chain ? OP_SUM2_SEND_B : OP_SUM2_SEND), st, cx, nullptr)) != HXT_OK) return rc;
     TagWork w = work;
     if (p.uniform) {
@@ -746,7 +778,7 @@ int run_tag_batch(int n, const hxt_plan_t *const *plans, void *const *const *ten
         for (int j = 0; j < i; ++j)
             if (plans[j] == plans[i]) return HXT_EINVAL;     // one accumulator set per plan
     }
-    SlotsLock lock(g_slots_mu);
+    BatchLock lock(plans, n);
     int i = 0;
     while (i < n) {
         auto work_of = [&](int j) {
@@ -837,7 +869,7 @@ int fused_direct_stream(hxt_plan_t &pl, const hxt_exchange_t &x, hipStream_t sp,
     const Plan &p = pl.p;
     const size_t T = p.tensors.size();
     const bool nt_packed = packed_nontemporal(pl);
-    SlotsLock lock(g_slots_mu);
+    SlotsLock lock(pl.slots_mu);
     for (int k = 0; k <= x.n_messages; ++k) {
         UniformArgs a;
         std::memset(&a, 0, sizeof a);
@@ -1352,7 +1384,7 @@ int hxt_checksum(const hxt_plan_t *plan, const void *packed, uint64_t *sums, voi
     hxt_plan_t &pl = *const_cast<hxt_plan_t *>(plan);
     hipStream_t st = static_cast<hipStream_t>(stream);
     SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};
-    SlotsLock lock(g_slots_mu);
+    SlotsLock lock(pl.slots_mu);
     if ((rc = claim_slots(pl, OP_CHECKSUM, st, cx, sums)) != HXT_OK) return rc;
     cx.sum_bits = pl.sum_bits_geom;
     const uint8_t *pk = static_cast<const uint8_t *>(packed);

@@ -260,6 +260,56 @@ def test_one_plan_used_from_several_threads_and_streams():
         assert not status[i].cpu().numpy().any()
 
 
+def test_batched_calls_that_share_plans_from_two_threads():
+    """Two host threads, a stream each, issue batched calls over the same three plans in opposite orders, with
+    checksums (each plan's accumulators are claimed under that plan's own lock; a batched call takes the locks of
+    its plans in one fixed order, so the two threads can neither deadlock nor interleave on a plan)."""
+    import threading
+    names = ["contig_1MB_ragged", "rows_mid", "contig_bf16_5MiB_tail"]
+    cases = [c for n in names for c in MID_CASES if c.name == n]
+    plans = [plan_of(c) for c in cases]
+    iters = 20
+    raws = [[make_storages(c, 310 + 10 * t + i) for i, c in enumerate(cases)] for t in range(2)]
+    want_packed = [[ho.pack(oracle_msg(c), raws[t][i], c.B, c.k, fill=0) for i, c in enumerate(cases)] for t in range(2)]
+    want = [[ho.checksum(oracle_msg(c), want_packed[t][i], c.B, c.k) for i, c in enumerate(cases)] for t in range(2)]
+    src = [[[to_dev(a) for a in rs] for rs in raws[t]] for t in range(2)]
+    dst = [[[torch.zeros_like(a) for a in row] for row in src[t]] for t in range(2)]
+    packed = [[torch.zeros(p.packed_bytes, dtype=torch.uint8, device=DEV) for p in plans] for _ in range(2)]
+    s_send = [[torch.zeros(iters, p.num_chunks, dtype=torch.int64, device=DEV) for p in plans] for _ in range(2)]
+    s_recv = [[torch.zeros(iters, p.num_chunks, dtype=torch.int64, device=DEV) for p in plans] for _ in range(2)]
+    streams = [torch.cuda.Stream() for _ in range(2)]
+    torch.cuda.synchronize()
+    errors = []
+
+    def work(t):
+        order = [0, 1, 2] if t == 0 else [2, 1, 0]
+        pick = lambda rows: [rows[i] for i in order]
+        try:
+            for it in range(iters):
+                say("thread", t, "batched call", it)
+                hxt.hxt_pack_batch(hxt.Batch(pick(plans), pick(src[t]), pick(packed[t]),
+                                             [s_send[t][i][it] for i in order]), streams[t])
+                hxt.hxt_unpack_batch(hxt.Batch(pick(plans), pick(dst[t]), pick(packed[t]),
+                                               [s_recv[t][i][it] for i in order]), streams[t])
+        except Exception as e:                                   # noqa: BLE001 - reported below
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(t,)) for t in range(2)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for t in range(2):
+        for i, c in enumerate(cases):
+            for arr in (s_send[t][i], s_recv[t][i]):
+                assert (arr.cpu().numpy().view(np.uint64) == want[t][i][None, :]).all(), (t, c.name)
+            dst_o = [np.zeros(r.size, np.uint8) for r in raws[t][i]]
+            ho.unpack(oracle_msg(c), want_packed[t][i], c.B, c.k, dst_o)
+            assert all(np.array_equal(b.cpu().numpy(), a) for a, b in zip(dst_o, dst[t][i])), (t, c.name)
+
+
 def test_batch_calls_equal_single_calls():
     # mixed batch: three uniform messages (one without checksums, so it cannot share a launch with its
     # neighbours), a strided one, an empty one and a multi-tensor one
