@@ -20,6 +20,17 @@ def test_more_than_one_gpu_is_refused_with_a_message():
     assert "one GPU" in (r.stdout + r.stderr)
 
 
+def test_traffic_figure_is_readable_for_this_build():
+    """roofline.traffic comes from the tracked counter summary: its `library:` line must name the version this
+    source tree builds (the line would otherwise carry null without anybody noticing)."""
+    sys.path.insert(0, ROOT)
+    import bench
+    from paper_2602_18007_amd import hxt
+    got = bench.traffic_from_profile(hxt.hxt_version())
+    assert isinstance(got, int) and got >= 4 * 33554432
+    assert bench.traffic_from_profile("some other build") is None
+
+
 def one_line(r):
     assert r.returncode == 0, r.stderr[-2000:]
     lines = [ln for ln in r.stdout.splitlines() if ln.startswith("{")]
@@ -39,7 +50,7 @@ def check_contract(out, steps, warmup):
     rf = out["roofline"]
     assert rf["bound"] == "hbm" and rf["peak"] == 8000.0 and rf["unit"] == "GB/s" and rf["region"] == "cold"
     assert abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-3
-    assert rf["traffic"] is None or rf["traffic"] >= rf["bytes_per_launch"]
+    assert isinstance(rf["traffic"], int) and rf["traffic"] >= rf["bytes_per_launch"]
     assert rf["plain_copy"]["bytes_read_plus_written"] == rf["bytes_per_launch"] and rf["plain_copy"]["gbps"] > 0
     # one stream: whole-region throughput cannot exceed what the launches achieve back to back
     assert 0 < out["regions"]["cold"]["gbps"] <= rf["achieved"] * 1.02

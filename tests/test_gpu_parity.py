@@ -672,13 +672,17 @@ def test_config_llama8b_boundary_forward_and_backward():
         round_trip_check(case_of(w), wl.make_storages(w, msg), nthreads=NT)
 
 
-def test_config_llama8b_boundary_in_the_benchmarks_launch_configuration():
+@pytest.mark.parametrize("hint", [-1, 1, 0], ids=["hint_by_size", "all_cold_non_temporal", "cacheable"])
+def test_config_llama8b_boundary_in_the_benchmarks_launch_configuration(hint):
     """Both messages of the step in one batched pack call and one batched unpack call, a plan each, fused
-    checksums, as the benchmark times them; every byte and every sum against the oracle."""
+    checksums, as the benchmark times them (hint 1 is its all-cold region: the packed side non-temporal too);
+    every byte and every sum against the oracle."""
     w = wl.llama8b_boundary()
     case = case_of(w)
     m = oracle_msg(case)
     plans = [plan_of(case) for _ in range(w.messages)]
+    for p in plans:
+        hxt.hxt_plan_set_option(p, hxt.HXT_OPT_PACKED_HINT, hint)
     raws = [wl.make_storages(w, i) for i in range(w.messages)]
     src = [[to_dev(r) for r in rs] for rs in raws]
     packed = [torch.full((p.packed_bytes,), 0xA5, dtype=torch.uint8, device=DEV) for p in plans]
@@ -699,6 +703,48 @@ def test_config_llama8b_boundary_in_the_benchmarks_launch_configuration():
         for a, b in zip(dst_o, dst[i]):
             assert np.array_equal(b.cpu().numpy(), a)
     assert not np.array_equal(raws[0][0], raws[1][0])
+
+
+def test_config_llama8b_boundary_steps_dealt_onto_two_streams():
+    """The issue order behind the benchmark's headline figure: consecutive steps go alternately to two streams,
+    each stream with a plan set of its own (two plans, packed side non-temporal), batched calls, fused checksums,
+    nothing ordering the two streams against each other.  Six steps on fresh data each; every step's packed bytes,
+    sums and destination against the oracle."""
+    w = wl.llama8b_boundary()
+    case = case_of(w)
+    m = oracle_msg(case)
+    n_steps = 6
+    plan_sets = [[plan_of(case) for _ in range(w.messages)] for _ in range(2)]
+    for ps in plan_sets:
+        for p in ps:
+            hxt.hxt_plan_set_option(p, hxt.HXT_OPT_PACKED_HINT, 1)
+    streams = [torch.cuda.Stream() for _ in range(2)]
+    raws = [[wl.make_storages(w, (3 * s_ + i) % 7 + i) for i in range(w.messages)] for s_ in range(n_steps)]
+    src = [[[to_dev(r) for r in rs] for rs in step] for step in raws]
+    dst = [[[torch.full_like(t, 0x3C) for t in row] for row in step] for step in src]
+    C, nb = plan_sets[0][0].num_chunks, plan_sets[0][0].packed_bytes
+    packed = [[torch.full((nb,), 0xA5, dtype=torch.uint8, device=DEV) for _ in range(w.messages)] for _ in range(n_steps)]
+    sums = [[torch.full((C,), -1, dtype=torch.int64, device=DEV) for _ in range(w.messages)] for _ in range(n_steps)]
+    rsums = [[torch.full((C,), -2, dtype=torch.int64, device=DEV) for _ in range(w.messages)] for _ in range(n_steps)]
+    torch.cuda.synchronize()
+    for s_ in range(n_steps):
+        say("step", s_, "on stream", s_ % 2)
+        ps, st = plan_sets[s_ % 2], streams[s_ % 2]
+        hxt.hxt_pack_batch(hxt.Batch(ps, src[s_], packed[s_], sums[s_]), st)
+        hxt.hxt_unpack_batch(hxt.Batch(ps, dst[s_], packed[s_], rsums[s_]), st)
+    torch.cuda.synchronize()
+    known = {}
+    for s_ in range(n_steps):
+        for i in range(w.messages):
+            key = raws[s_][i][0].tobytes()[:64]
+            if key not in known:
+                want = ho.pack(m, raws[s_][i], w.chunk_bytes, w.n_lanes, fill=0xA5, nthreads=NT)
+                known[key] = (want, ho.checksum(m, want, w.chunk_bytes, w.n_lanes, nthreads=NT))
+            want, ws = known[key]
+            assert np.array_equal(packed[s_][i].cpu().numpy(), want), (s_, i)
+            assert np.array_equal(sums[s_][i].cpu().numpy().view(np.uint64), ws), (s_, i)
+            assert np.array_equal(rsums[s_][i].cpu().numpy().view(np.uint64), ws), (s_, i)
+            assert np.array_equal(dst[s_][i][0].cpu().numpy(), raws[s_][i][0]), (s_, i)
 
 
 def test_config_qwen2_both_paths_same_bytes():
