@@ -604,6 +604,8 @@ def config_entries(torch, hxt, wl, a, link, headline_regions):
     direct("qwen_rows_view")
     direct("transpose_view")
     direct("rows_split_view", note="bf16 [327680, 100]: runs of 200 bytes at a pitch of 256 bytes")
+    direct("inner_stride_view", hints=("cold",), note="bf16 [4096, 4096] with strides (8192, 2): every second element, "
+           "so the tensor side moves two bytes of memory bursts per byte of payload")
     return out
 
 

@@ -198,12 +198,16 @@ void launch_generic(const hxt_plan_t &pl, uint32_t first, uint32_t count, uint32
     const Tile *tiles = pl.d_tiles + first;
     const uint32_t *ct = pl.d_chunk_tiles;
     const TensorDev *td = pl.d_tensors;
-    switch (esize) {
-    case 1: k_generic<uint8_t, UNPACK, CSUM><<<count, kThreads, 0, st>>>(tiles, ct, td, tensor_base, b, packed, cx); break;
-    case 2: k_generic<uint16_t, UNPACK, CSUM><<<count, kThreads, 0, st>>>(tiles, ct, td, tensor_base, b, packed, cx); break;
-    case 4: k_generic<uint32_t, UNPACK, CSUM><<<count, kThreads, 0, st>>>(tiles, ct, td, tensor_base, b, packed, cx); break;
-    default: k_generic<uint64_t, UNPACK, CSUM><<<count, kThreads, 0, st>>>(tiles, ct, td, tensor_base, b, packed, cx); break;
-    }
+    auto go = [&]<bool NTP>() {
+        switch (esize) {
+        case 1: k_generic<uint8_t, UNPACK, CSUM, NTP><<<count, kThreads, 0, st>>>(tiles, ct, td, tensor_base, b, packed, cx); break;
+        case 2: k_generic<uint16_t, UNPACK, CSUM, NTP><<<count, kThreads, 0, st>>>(tiles, ct, td, tensor_base, b, packed, cx); break;
+        case 4: k_generic<uint32_t, UNPACK, CSUM, NTP><<<count, kThreads, 0, st>>>(tiles, ct, td, tensor_base, b, packed, cx); break;
+        default: k_generic<uint64_t, UNPACK, CSUM, NTP><<<count, kThreads, 0, st>>>(tiles, ct, td, tensor_base, b, packed, cx); break;
+        }
+    };
+    if (packed_nontemporal(pl)) go.template operator()<true>();
+    else go.template operator()<false>();
 }
 
 // The accumulator slots of an operation are shared by all calls of that operation on this

@@ -831,9 +831,123 @@ __global__ __launch_bounds__(kThreads) void k_transpose(const Tile *__restrict__
 }
 
 // ---- generic: any strides, one element at a time -------------------------------
-// Every element's address is recomputed from its logical index.  Slow, and only used for
-// views the other kernels do not take.
-template <typename E, bool UNPACK, bool CSUM>
+// Every element's address is recomputed from its logical index.  Only used for views the
+// other kernels do not take (no dimension with stride one, or runs shorter than 16 bytes).
+template <bool NT, typename E>
+__device__ __forceinline__ E load_elem(const E *p)
+{
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+
+template <bool NT, typename E>
+__device__ __forceinline__ void store_elem(E *p, E v)
+{
+    if constexpr (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
+// The elements [e0, e0 + nel) of one tensor, every dim within reach of the multiply-shift division.
+// ND > 0: the tensor has exactly ND merged dims; ND == 0: any number, read from the descriptor.
+// The dims are copied into registers first: the loop below stores through byte pointers, which
+// may alias anything, so values read through the descriptor inside it would be read again for
+// every element.  Consecutive lanes take consecutive elements, U of them in flight per thread:
+// a wave's access is contiguous on the packed side and as dense on the tensor side as the view
+// allows.  The loads of a round are unconditional (the index is clamped into the tile), so that
+// all of them are issued before the first is waited for; only the stores are guarded.
+template <typename E, bool UNPACK, bool CSUM, bool NTP, int ND>
+__device__ __forceinline__ uint64_t generic_span(const TensorDev &td, uint64_t e0, uint32_t nel, uint8_t *user, E *p)
+{
+    constexpr int D = ND ? ND : HXT_MAX_DIMS;
+    const int nd = ND ? ND : td.ndim;
+    uint32_t shape[D], mul[D], shift[D], first[D];
+    uint64_t stride[D];
+    {
+        uint64_t idx = e0;                                  // coordinates of the span's first element
+#pragma unroll
+        for (int d = D - 1; d >= 0; --d) {
+            shape[d] = 1, mul[d] = 0, shift[d] = 0, first[d] = 0, stride[d] = 0;
+            if (d < nd) {
+                shape[d] = uint32_t(td.shape[d]);
+                mul[d] = td.dim_div[d].mul;
+                shift[d] = td.dim_div[d].shift;
+                stride[d] = uint64_t(td.stride_b[d]);
+                const uint64_t q = idx / uint64_t(td.shape[d]);
+                first[d] = uint32_t(idx - q * uint64_t(td.shape[d]));
+                idx = q;
+            }
+        }
+    }
+    // An element's coordinates are the first element's plus its number within the span, carried from
+    // the last dim upwards in 32 bits (a span has fewer than 2^30 elements and so has every dim).
+    auto locate = [&](uint32_t el) -> E * {
+        uint64_t off = 0;
+        uint32_t x = el;
+#pragma unroll
+        for (int d = D - 1; d > 0; --d) {
+            if (d < nd) {
+                x += first[d];
+                const uint32_t q = fast_div(x, FastDiv{mul[d], shift[d]});
+                off += uint64_t(x - q * shape[d]) * stride[d];
+                x = q;
+            }
+        }
+        off += uint64_t(x + first[0]) * stride[0];
+        return reinterpret_cast<E *>(user + off);
+    };
+    constexpr int U = 8;
+    uint64_t acc = 0;
+    const uint32_t last = nel - 1;
+    for (uint32_t e1 = threadIdx.x; e1 < nel; e1 += kThreads * U) {
+        E val[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t el = min(e1 + u * kThreads, last);
+            if constexpr (UNPACK) val[u] = load_elem<NTP>(p + el);
+            else val[u] = load_elem<true>(locate(el));
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t el = e1 + u * kThreads;
+            if (el < nel) {
+                if constexpr (UNPACK) store_elem<true>(locate(el), val[u]);
+                else store_elem<NTP>(p + el, val[u]);
+                if constexpr (CSUM) acc += elem_weighted(val[u], uint64_t(el) * sizeof(E));
+            }
+        }
+    }
+    return acc;
+}
+
+// The same for tensors with a dim beyond the reach of the multiply-shift division: every element's
+// index is divided out in 64 bits.
+template <typename E, bool UNPACK, bool CSUM, bool NTP>
+__device__ __noinline__ uint64_t generic_span_wide(const TensorDev &td, uint64_t e0, uint32_t nel, uint8_t *user, E *p)
+{
+    const int nd = td.ndim;
+    uint64_t acc = 0;
+    for (uint32_t el = threadIdx.x; el < nel; el += kThreads) {
+        uint64_t idx = e0 + el, off = 0;
+        for (int d = nd - 1; d >= 0; --d) {
+            const uint64_t q = idx / uint64_t(td.shape[d]);
+            off += (idx - q * uint64_t(td.shape[d])) * uint64_t(td.stride_b[d]);
+            idx = q;
+        }
+        E *at = reinterpret_cast<E *>(user + off);
+        E v;
+        if constexpr (UNPACK) {
+            v = load_elem<NTP>(p + el);
+            store_elem<true>(at, v);
+        } else {
+            v = load_elem<true>(at);
+            store_elem<NTP>(p + el, v);
+        }
+        if constexpr (CSUM) acc += elem_weighted(v, uint64_t(el) * sizeof(E));
+    }
+    return acc;
+}
+
+template <typename E, bool UNPACK, bool CSUM, bool NTP>
 __global__ __launch_bounds__(kThreads) void k_generic(const Tile *__restrict__ tiles,
                                                       const uint32_t *__restrict__ chunk_tiles,
                                                       const TensorDev *__restrict__ tensors, uint32_t tensor_base,
@@ -846,74 +960,19 @@ __global__ __launch_bounds__(kThreads) void k_generic(const Tile *__restrict__ t
     } else {
         const TensorDev &td = tensors[tensor_base + t.tensor];
         uint8_t *user = bases.p[t.tensor];
-        uint8_t *pk = packed + t.packed_off;
+        E *p = reinterpret_cast<E *>(packed + t.packed_off);
         const uint32_t nel = t.n0 / sizeof(E);
         const uint64_t e0 = t.src_off / sizeof(E);
-        // Coordinates of the tile's first element (the same for every thread).  When every dim fits the
-        // multiply-shift division, an element's coordinates are these plus its number within the tile,
-        // carried from the last dim upwards in 32 bits; otherwise each element is divided out in 64 bits.
-        const bool fast = td.all_div != 0;
-        const int nd = td.ndim;
-        uint32_t base[HXT_MAX_DIMS];
-        {
-            uint64_t idx = e0;
-#pragma unroll
-            for (int d = HXT_MAX_DIMS - 1; d >= 0; --d) {
-                base[d] = 0;
-                if (d < nd && fast) {
-                    const uint64_t q = idx / uint64_t(td.shape[d]);
-                    base[d] = uint32_t(idx - q * uint64_t(td.shape[d]));
-                    idx = q;
-                }
-            }
-        }
-        // Consecutive lanes take consecutive elements, U of them in flight per thread: a wave's access is contiguous
-        // on the packed side and as dense on the tensor side as the view allows (every other element of a line for
-        // an inner stride of 2), instead of eight scattered two-byte accesses per lane.
-        auto locate = [&](uint32_t el) -> E * {
-            uint64_t off = 0;
-            if (fast) {
-                uint32_t x = el;                                   // carry into the last dim
-#pragma unroll
-                for (int d = HXT_MAX_DIMS - 1; d >= 0; --d) {
-                    if (d < nd) {
-                        x += base[d];
-                        if (d > 0) {
-                            const uint32_t q = fast_div(x, td.dim_div[d]);
-                            off += uint64_t(x - q * uint32_t(td.shape[d])) * uint64_t(td.stride_b[d]);
-                            x = q;
-                        } else {
-                            off += uint64_t(x) * uint64_t(td.stride_b[0]);
-                        }
-                    }
-                }
-            } else {
-                uint64_t idx = e0 + el;
-                for (int d = nd - 1; d >= 0; --d) {
-                    const uint64_t q = idx / uint64_t(td.shape[d]);
-                    off += (idx - q * uint64_t(td.shape[d])) * uint64_t(td.stride_b[d]);
-                    idx = q;
-                }
-            }
-            return reinterpret_cast<E *>(user + off);
-        };
-        constexpr int U = 8;
-        E *p = reinterpret_cast<E *>(pk);
-        for (uint32_t e1 = threadIdx.x; e1 < nel; e1 += kThreads * U) {
-            E val[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const uint32_t el = e1 + u * kThreads;
-                val[u] = 0;
-                if (el < nel) val[u] = UNPACK ? p[el] : *locate(el);
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const uint32_t el = e1 + u * kThreads;
-                if (el < nel) {
-                    if constexpr (UNPACK) *locate(el) = val[u]; else p[el] = val[u];
-                    if constexpr (CSUM) acc += elem_weighted(val[u], uint64_t(el) * sizeof(E));
-                }
+        if (nel == 0) {
+        } else if (!td.all_div) {
+            acc = generic_span_wide<E, UNPACK, CSUM, NTP>(td, e0, nel, user, p);
+        } else {
+            switch (td.ndim) {
+            case 1: acc = generic_span<E, UNPACK, CSUM, NTP, 1>(td, e0, nel, user, p); break;
+            case 2: acc = generic_span<E, UNPACK, CSUM, NTP, 2>(td, e0, nel, user, p); break;
+            case 3: acc = generic_span<E, UNPACK, CSUM, NTP, 3>(td, e0, nel, user, p); break;
+            case 4: acc = generic_span<E, UNPACK, CSUM, NTP, 4>(td, e0, nel, user, p); break;
+            default: acc = generic_span<E, UNPACK, CSUM, NTP, 0>(td, e0, nel, user, p); break;
             }
         }
     }

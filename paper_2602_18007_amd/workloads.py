@@ -139,10 +139,19 @@ def rows_split_view() -> Workload:
                     note="bf16 [327680,100] view with a row pitch of 128 elements (62.5 MiB)")
 
 
+def inner_stride_view() -> Workload:
+    """Supplementary: innermost stride of two elements and no dimension with stride one (every other column of a
+    [4096, 8192] matrix): neither a row gather nor a transpose, so the per-element kernel takes it."""
+    t = TensorDesc((4096, 4096), (8192, 2))
+    return Workload("inner_stride_view", (t,), 4, 1 * MiB, "normal", 1.0, seed=BASE_SEED + 8,
+                    note="bf16 [4096,4096] view with strides (8192,2) (32 MiB out of 64 MiB of storage)")
+
+
 ALL = {
     "tiny": tiny, "llama8b_boundary": llama8b_boundary, "qwen2_7b_boundary": qwen2_7b_boundary,
     "stream_1f1b": stream_1f1b, "grad_buckets": grad_buckets,
     "qwen_rows_view": qwen_rows_view, "transpose_view": transpose_view, "rows_split_view": rows_split_view,
+    "inner_stride_view": inner_stride_view,
 }
 
 

@@ -33,6 +33,16 @@ def storage_bytes(shape, strides, esize):
     return (sum((s - 1) * st for s, st in zip(shape, strides)) + 1) * esize
 
 
+def permuted(shape, order, esize, scale=2, pad=1):
+    """A view whose dims lie in memory in the given order (order[0] varies fastest), the fastest with a stride of
+    `scale` elements and `pad` unused elements after every dim, so that no two dims merge."""
+    strides, run = [0] * len(shape), scale
+    for d in order:
+        strides[d] = run
+        run *= shape[d] + pad
+    return (tuple(shape), tuple(strides), esize)
+
+
 SMALL_CASES: List[Case] = [
     Case("u8_1000_not_256_multiple", (contig((1000,), 1),), 2, 256),
     Case("ragged_last_chunk_2p5", (contig((1280,), 2),), 3, 1024),          # 2560 B = 2.5 chunks
@@ -56,6 +66,12 @@ SMALL_CASES: List[Case] = [
     Case("empty_between", (contig((100,), 2), ((0,), (1,), 2), contig((77,), 4)), 2, 256),
     Case("inner_stride_2", (((40, 24), (48, 2), 2),), 2, 256),               # every other element
     Case("eight_dims_permuted", (((2, 3, 2, 2, 3, 2, 2, 4), (288, 48, 2, 576, 4, 1, 144, 12), 2),), 3, 256),
+    Case("five_dims_no_unit_stride", (permuted((3, 2, 4, 2, 5), (2, 0, 4, 1, 3), 2),), 3, 256),
+    Case("six_dims_no_unit_stride_u8", (permuted((2, 3, 2, 3, 2, 5), (5, 3, 1, 0, 2, 4), 1, scale=3),), 2, 512),
+    Case("eight_dims_no_unit_stride_f32", (permuted((2, 2, 3, 2, 2, 3, 2, 2), (7, 0, 6, 1, 5, 2, 4, 3), 4, pad=0),), 2, 256),
+    Case("six_dims_rows_32_byte_runs", (((2, 3, 2, 3, 2, 16), (384, 96, 1152, 24, 3456, 1), 2),), 2, 512),
+    Case("six_dims_rows_20_byte_runs", (permuted((2, 3, 2, 3, 2, 10), (5, 1, 3, 0, 4, 2), 2, scale=1),), 3, 256),
+    Case("seven_dims_f64_no_unit_stride", (permuted((2, 2, 2, 3, 2, 2, 3), (3, 6, 0, 5, 1, 4, 2), 8),), 2, 1024),
     Case("sixty_four_lanes", (contig((40000,), 2),), 64, 512),                # 157 chunks, lanes hold 3 or 2
     Case("mixed_dtypes_multi", (contig((33,), 1), ((8, 24), (32, 1), 2), ((16, 8), (1, 16), 4), contig((5,), 8)), 4, 512),
 ]
@@ -73,11 +89,12 @@ def make_storages(case: Case, seed: int) -> List[np.ndarray]:
     return [rng.integers(0, 256, size=storage_bytes(*t), dtype=np.uint8) for t in case.tensors]
 
 
-def random_view(rng):
+def random_view(rng, max_dims=4):
     """(shape, strides, esize) of a random non-negative-stride view with a small storage footprint."""
     esize = int(rng.choice([1, 2, 4, 8]))
-    nd = int(rng.integers(0, 5))
-    shape = [int(rng.choice([1, 2, 3, 5, 8, 16, 17, 40, 64, 72, 130])) for _ in range(nd)]
+    nd = int(rng.integers(0, max_dims + 1))
+    sizes = [1, 2, 3, 5, 8, 16, 17, 40, 64, 72, 130] if max_dims <= 4 else [1, 2, 2, 3, 3, 4, 5, 8, 16, 17]
+    shape = [int(rng.choice(sizes)) for _ in range(nd)]
     if rng.random() < 0.08 and nd:
         shape[int(rng.integers(0, nd))] = 0
     order = list(rng.permutation(nd))                      # order[0] is the fastest-varying dim in memory

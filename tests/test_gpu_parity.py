@@ -360,6 +360,20 @@ def test_random_views(seed):
         done += 1
 
 
+@pytest.mark.parametrize("seed", range(4))
+def test_random_views_of_up_to_eight_dims(seed):
+    rng = np.random.default_rng(7100 + seed)
+    done = 0
+    while done < 12:
+        tensors = tuple(random_view(rng, max_dims=8) for _ in range(int(rng.integers(1, 4))))
+        if sum(storage_bytes(*t) for t in tensors) > 4_000_000 or sum(int(np.prod(t[0])) * t[2] for t in tensors) > 8_000_000:
+            continue
+        case = Case("rand8_%d_%d" % (seed, done), tensors, int(rng.integers(1, 6)), int(rng.choice([256, 1024, 4096, 16384])))
+        say("random case", case.tensors, case.k, case.B)
+        round_trip_check(case, make_storages(case, seed), tile_bytes=int(rng.choice([256, 1024, 16384])))
+        done += 1
+
+
 def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
     # batched pack + unpack with checksums of two messages, captured once and replayed with fresh inputs;
     # every replay is compared with the eager result (no memset nodes: the library zero-fills nothing)
@@ -592,12 +606,14 @@ def test_words_that_change_places_show_only_in_the_weighted_sum():
 
 @pytest.mark.parametrize("case", [
     Case("beyond_4GiB_one_tensor", (contig((2**32 + 3 * 2**20 + 24,), 1),), 3, 32 << 20),
+    Case("dim_beyond_2_30_every_other_byte", (((2**30 + 5,), (2,), 1),), 2, 64 << 20),
     Case("beyond_4GiB_table", (contig((2**32 + 4096,), 1), ((1000, 256), (320, 1), 4), ((512, 384), (1, 512), 2),
                                contig((70001,), 1)), 4, 16 << 20),
 ], ids=lambda c: c.name)
 def test_offsets_beyond_32_bits(case):
     """Stream, packed and storage offsets past 2^32: the closed-form kernel, and the table-driven kernels
-    whose tiles start beyond 4 GiB."""
+    whose tiles start beyond 4 GiB; a dim of more than 2^30 elements in a view without a unit stride (the
+    per-element kernel then divides every index out in 64 bits)."""
     rng = np.random.default_rng(zlib.crc32(case.name.encode()))
     raws = []
     for t in case.tensors:
@@ -1095,7 +1111,7 @@ def test_config_grad_buckets_full_size_both_paths():
     assert bool((host[tail0:tail1] == 0).all())
 
 
-@pytest.mark.parametrize("name", ["qwen_rows_view", "transpose_view", "rows_split_view"])
+@pytest.mark.parametrize("name", ["qwen_rows_view", "transpose_view", "rows_split_view", "inner_stride_view"])
 def test_supplementary_strided_messages_full_size(name):
     w = wl.ALL[name]()
     say("supplementary", name)
