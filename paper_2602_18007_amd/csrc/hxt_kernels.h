@@ -591,53 +591,83 @@ __global__ __launch_bounds__(kThreads) void k_rows_any(const Tile *__restrict__ 
 // is then contiguous on the packed side and contiguous within each run on the tensor side (64 lanes x 4 bytes
 // = 256 bytes per instruction), whatever the run length; each piece finds its run with one multiply-shift
 // division and the run's storage offset from the outer indices.
-__device__ __forceinline__ uint64_t run_storage_offset(const TensorDev &td, uint32_t row)
-{
-    uint64_t o = 0;
-    for (int d = td.ndim - 2; d > 0; --d) {
-        const uint32_t q = fast_div(row, td.dim_div[d]);
-        o += uint64_t(row - q * uint32_t(td.shape[d])) * uint64_t(td.stride_b[d]);
-        row = q;
-    }
-    return o + uint64_t(row) * uint64_t(td.stride_b[0]);
-}
-
 template <int G> struct PieceOf;
 template <> struct PieceOf<8> { using type = uint64_t; };
 template <> struct PieceOf<4> { using type = uint32_t; };
 template <> struct PieceOf<2> { using type = uint16_t; };
 template <> struct PieceOf<1> { using type = uint8_t; };
 
-template <bool UNPACK, bool CSUM, int G>
+// TWO_D: the view has two dims (the usual padded-pitch matrix) and needs no index decomposition: run
+// row0 + dr starts (row0 + dr) * pitch into the storage, so byte x of the tile's first run sits at
+// x + dr * (pitch - run length) from that run's start.  Otherwise the run's storage offset comes from
+// its outer indices, divided out with the dims held in registers (the loop stores through byte
+// pointers, which may alias the descriptor, so anything read through it inside the loop would be
+// read again for every piece).  With pieces of 1 or 2 bytes the loads of a round are unconditional
+// (the piece number is clamped into the tile): guarded, the compiler waits for each load before it
+// goes on to the next guard, and 16 loads one after the other cost 1.8-2.4 times the time.  With pieces
+// of 4 or 8 bytes the guarded loads are issued without such waits, interleaved with the address
+// arithmetic, and that order measures 10 % faster than eight loads in one burst.
+template <bool UNPACK, bool CSUM, int G, bool TWO_D>
 __device__ __forceinline__ uint64_t rows_split_tile(const Tile &t, const TensorDev &td, uint8_t *user, uint8_t *pk)
 {
     using P = typename PieceOf<G>::type;
     const uint32_t row_bytes = td.row_bytes;
+    const FastDiv row_div = td.row_div;
     const uint64_t row0 = t.src_off / row_bytes;                    // uniform
     const uint32_t col0 = uint32_t(t.src_off - row0 * row_bytes);
     const uint32_t npiece = t.n0 / G;
     constexpr int U = G == 8 ? 8 : 16;                              // pieces in flight per thread: a 16 KiB tile in one go
-    uint64_t acc = 0;
-    // Two-dimensional views (the usual padded-pitch matrix) need no index decomposition: run row0 + dr starts
-    // (row0 + dr) * pitch into the storage, so byte x of the tile's first run sits at x + dr * (pitch - run length)
-    // from that run's start.
-    const bool two_d = td.ndim == 2;
-    uint8_t *const first_run = user + row0 * uint64_t(td.stride_b[0]);                   // uniform
-    const int64_t slack = td.stride_b[0] - int64_t(row_bytes);
+    constexpr int D = TWO_D ? 1 : HXT_MAX_DIMS - 1;                 // dims outside the run
+    const int outer = TWO_D ? 1 : td.ndim - 1;
+    uint32_t shape[D], mul[D], shift[D];
+    uint64_t stride[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        shape[d] = 1, mul[d] = 0, shift[d] = 0, stride[d] = 0;
+        if (d < outer) {
+            shape[d] = uint32_t(td.shape[d]);
+            mul[d] = td.dim_div[d].mul;
+            shift[d] = td.dim_div[d].shift;
+            stride[d] = uint64_t(td.stride_b[d]);
+        }
+    }
+    uint8_t *const first_run = user + row0 * stride[0];             // uniform
+    const int64_t slack = int64_t(stride[0]) - int64_t(row_bytes);
     auto user_piece = [&](uint32_t i) {                             // piece i of the tile -> its place in storage
         const uint32_t x = col0 + i * G;
-        const uint32_t dr = fast_div(x, td.row_div);
-        if (two_d) return reinterpret_cast<P *>(first_run + (int64_t(x) + int64_t(dr) * slack));
-        return reinterpret_cast<P *>(user + run_storage_offset(td, uint32_t(row0) + dr) + (x - dr * row_bytes));
+        const uint32_t dr = fast_div(x, row_div);
+        if constexpr (TWO_D) {
+            return reinterpret_cast<P *>(first_run + (int64_t(x) + int64_t(dr) * slack));
+        } else {
+            uint32_t row = uint32_t(row0) + dr;
+            uint64_t o = 0;
+#pragma unroll
+            for (int d = D - 1; d > 0; --d) {
+                if (d < outer) {
+                    const uint32_t q = fast_div(row, FastDiv{mul[d], shift[d]});
+                    o += uint64_t(row - q * shape[d]) * stride[d];
+                    row = q;
+                }
+            }
+            return reinterpret_cast<P *>(user + o + uint64_t(row) * stride[0] + (x - dr * row_bytes));
+        }
     };
     P *pieces = reinterpret_cast<P *>(pk);
+    uint64_t acc = 0;
+    const uint32_t last = npiece - 1;
     for (uint32_t i0 = threadIdx.x; i0 < npiece; i0 += kThreads * U) {
         P r[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const uint32_t i = i0 + u * kThreads;
-            r[u] = 0;
-            if (i < npiece) {
+            if constexpr (G >= 4) {
+                const uint32_t i = i0 + u * kThreads;
+                r[u] = 0;
+                if (i < npiece) {
+                    if constexpr (UNPACK) r[u] = pieces[i];
+                    else r[u] = __builtin_nontemporal_load(user_piece(i));
+                }
+            } else {
+                const uint32_t i = min(i0 + u * kThreads, last);
                 if constexpr (UNPACK) r[u] = pieces[i];
                 else r[u] = __builtin_nontemporal_load(user_piece(i));
             }
@@ -667,11 +697,15 @@ __global__ __launch_bounds__(kThreads) void k_rows_split(const Tile *__restrict_
     uint8_t *user = bases.p[t.tensor], *pk = packed + t.packed_off;
     // widest piece that is naturally aligned everywhere: low bits of the base address, the run length and the pitches
     const uint32_t low = (uint32_t(reinterpret_cast<uintptr_t>(user)) | td.low_or) & 15u;
+    auto run = [&]<int G>() {
+        return td.ndim == 2 ? rows_split_tile<UNPACK, CSUM, G, true>(t, td, user, pk)
+                            : rows_split_tile<UNPACK, CSUM, G, false>(t, td, user, pk);
+    };
     uint64_t acc;
-    if ((low & 7u) == 0) acc = rows_split_tile<UNPACK, CSUM, 8>(t, td, user, pk);
-    else if ((low & 3u) == 0) acc = rows_split_tile<UNPACK, CSUM, 4>(t, td, user, pk);
-    else if ((low & 1u) == 0) acc = rows_split_tile<UNPACK, CSUM, 2>(t, td, user, pk);
-    else acc = rows_split_tile<UNPACK, CSUM, 1>(t, td, user, pk);
+    if ((low & 7u) == 0) acc = run.template operator()<8>();
+    else if ((low & 3u) == 0) acc = run.template operator()<4>();
+    else if ((low & 1u) == 0) acc = run.template operator()<2>();
+    else acc = run.template operator()<1>();
     if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, chunk_tiles[t.chunk], cx);
 }
 
