@@ -139,6 +139,8 @@ int hxt_plan_destroy(hxt_plan_t *plan); /* NULL is allowed */
  *      last-level cache; non-temporal above;
  *    0 always cacheable;  1 always non-temporal (every byte goes to and comes from HBM).
  *   The environment variable HXT_NT_PACKED (0/1), read when a plan is created, sets the initial value.
+ *   Exception: the slower kernel variants taken when a tensor's base pointer is not 16-byte aligned
+ *   keep both sides cacheable whatever the hint.
  * HXT_OPT_STAGE_D2H: how hxt_stage_d2h* and the CPU-forwarding path of hxt_exchange_stream move
  *   the packed buffer to pinned host memory.
  *    0 (default) a copy command (hipMemcpyAsync: the runtime picks a DMA engine or a blit kernel of

@@ -183,12 +183,16 @@ void launch_transpose(const hxt_plan_t &pl, uint32_t first, uint32_t count, int 
 {
     const Tile *tiles = pl.d_tiles + first;
     const uint32_t *ct = pl.d_chunk_tiles;
-    switch (esize) {
-    case 1: k_transpose<uint8_t, UNPACK, CSUM><<<count, kThreads, 0, st>>>(tiles, ct, b, packed, cx); break;
-    case 2: k_transpose<uint16_t, UNPACK, CSUM><<<count, kThreads, 0, st>>>(tiles, ct, b, packed, cx); break;
-    case 4: k_transpose<uint32_t, UNPACK, CSUM><<<count, kThreads, 0, st>>>(tiles, ct, b, packed, cx); break;
-    default: k_transpose<uint64_t, UNPACK, CSUM><<<count, kThreads, 0, st>>>(tiles, ct, b, packed, cx); break;
-    }
+    auto go = [&]<bool NTP>() {
+        switch (esize) {
+        case 1: k_transpose<uint8_t, UNPACK, CSUM, NTP><<<count, kThreads, 0, st>>>(tiles, ct, b, packed, cx); break;
+        case 2: k_transpose<uint16_t, UNPACK, CSUM, NTP><<<count, kThreads, 0, st>>>(tiles, ct, b, packed, cx); break;
+        case 4: k_transpose<uint32_t, UNPACK, CSUM, NTP><<<count, kThreads, 0, st>>>(tiles, ct, b, packed, cx); break;
+        default: k_transpose<uint64_t, UNPACK, CSUM, NTP><<<count, kThreads, 0, st>>>(tiles, ct, b, packed, cx); break;
+        }
+    };
+    if (packed_nontemporal(pl)) go.template operator()<true>();
+    else go.template operator()<false>();
 }
 
 template <bool UNPACK, bool CSUM>
@@ -367,8 +371,12 @@ int run_copy(hxt_plan_t &pl, void *const *ptrs, uint8_t *packed, uint64_t *sums,
             k_rows_any<UNPACK, CSUM><<<g.count, kThreads, 0, st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, pl.d_tensors,
                                                                    g.tensor_base, b, packed, cx);
         } else if (g.kernel == K_ROWS_SPLIT) {
-            k_rows_split<UNPACK, CSUM><<<g.count, kThreads, 0, st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, pl.d_tensors,
-                                                                     g.tensor_base, b, packed, cx);
+            if (packed_nontemporal(pl))
+                k_rows_split<UNPACK, CSUM, true><<<g.count, kThreads, 0, st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, pl.d_tensors,
+                                                                               g.tensor_base, b, packed, cx);
+            else
+                k_rows_split<UNPACK, CSUM, false><<<g.count, kThreads, 0, st>>>(pl.d_tiles + g.first, pl.d_chunk_tiles, pl.d_tensors,
+                                                                                g.tensor_base, b, packed, cx);
         } else {
             // The transpose and per-element kernels are instantiated per element size: issue one
             // launch per run of tiles whose tensors share it (host table, same order as on the device).

@@ -72,6 +72,20 @@ __device__ __forceinline__ void store16(u32x4 *p, u32x4 v)
     else *p = v;
 }
 
+template <bool NT, typename E>
+__device__ __forceinline__ E load_elem(const E *p)
+{
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+
+template <bool NT, typename E>
+__device__ __forceinline__ void store_elem(E *p, E v)
+{
+    if constexpr (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
 __device__ __forceinline__ uint64_t words_sum(u32x4 v)
 {
     return (uint64_t(v.x) + uint64_t(v.y)) + (uint64_t(v.z) + uint64_t(v.w));
@@ -607,7 +621,7 @@ template <> struct PieceOf<1> { using type = uint8_t; };
 // goes on to the next guard, and 16 loads one after the other cost 1.8-2.4 times the time.  With pieces
 // of 4 or 8 bytes the guarded loads are issued without such waits, interleaved with the address
 // arithmetic, and that order measures 10 % faster than eight loads in one burst.
-template <bool UNPACK, bool CSUM, int G, bool TWO_D>
+template <bool UNPACK, bool CSUM, bool NTP, int G, bool TWO_D>
 __device__ __forceinline__ uint64_t rows_split_tile(const Tile &t, const TensorDev &td, uint8_t *user, uint8_t *pk)
 {
     using P = typename PieceOf<G>::type;
@@ -663,12 +677,12 @@ __device__ __forceinline__ uint64_t rows_split_tile(const Tile &t, const TensorD
                 const uint32_t i = i0 + u * kThreads;
                 r[u] = 0;
                 if (i < npiece) {
-                    if constexpr (UNPACK) r[u] = pieces[i];
+                    if constexpr (UNPACK) r[u] = load_elem<NTP>(pieces + i);
                     else r[u] = __builtin_nontemporal_load(user_piece(i));
                 }
             } else {
                 const uint32_t i = min(i0 + u * kThreads, last);
-                if constexpr (UNPACK) r[u] = pieces[i];
+                if constexpr (UNPACK) r[u] = load_elem<NTP>(pieces + i);
                 else r[u] = __builtin_nontemporal_load(user_piece(i));
             }
         }
@@ -677,7 +691,7 @@ __device__ __forceinline__ uint64_t rows_split_tile(const Tile &t, const TensorD
             const uint32_t i = i0 + u * kThreads;
             if (i < npiece) {
                 if constexpr (UNPACK) __builtin_nontemporal_store(r[u], user_piece(i));
-                else pieces[i] = r[u];
+                else store_elem<NTP>(pieces + i, r[u]);
                 if constexpr (CSUM && G == 8) acc += (uint64_t(r[u]) & 0xFFFFFFFFull) + (uint64_t(r[u]) >> 32);
                 if constexpr (CSUM && G < 8) acc += uint64_t(r[u]) << (8 * ((i * G) & 3));
             }
@@ -686,7 +700,7 @@ __device__ __forceinline__ uint64_t rows_split_tile(const Tile &t, const TensorD
     return acc;
 }
 
-template <bool UNPACK, bool CSUM>
+template <bool UNPACK, bool CSUM, bool NTP>
 __global__ __launch_bounds__(kThreads) void k_rows_split(const Tile *__restrict__ tiles,
                                                          const uint32_t *__restrict__ chunk_tiles,
                                                          const TensorDev *__restrict__ tensors, uint32_t tensor_base,
@@ -698,8 +712,8 @@ __global__ __launch_bounds__(kThreads) void k_rows_split(const Tile *__restrict_
     // widest piece that is naturally aligned everywhere: low bits of the base address, the run length and the pitches
     const uint32_t low = (uint32_t(reinterpret_cast<uintptr_t>(user)) | td.low_or) & 15u;
     auto run = [&]<int G>() {
-        return td.ndim == 2 ? rows_split_tile<UNPACK, CSUM, G, true>(t, td, user, pk)
-                            : rows_split_tile<UNPACK, CSUM, G, false>(t, td, user, pk);
+        return td.ndim == 2 ? rows_split_tile<UNPACK, CSUM, NTP, G, true>(t, td, user, pk)
+                            : rows_split_tile<UNPACK, CSUM, NTP, G, false>(t, td, user, pk);
     };
     uint64_t acc;
     if ((low & 7u) == 0) acc = run.template operator()<8>();
@@ -732,7 +746,7 @@ __device__ __forceinline__ uint64_t elem_weighted(E v, uint64_t packed_pos)
 // FULL: the tile is T x T, so every index computation folds to shifts and masks and each thread moves exactly
 // T * T / (V * kThreads) vectors per phase, all of whose global loads are issued before the first LDS store
 // (measured with counters: with run-time extents the kernel was bound by its integer divisions, not by memory).
-template <typename E, bool SRC_IS_PACKED, bool CSUM, int UA, bool FULL>
+template <typename E, bool SRC_IS_PACKED, bool CSUM, bool NTP, int UA, bool FULL>
 __device__ __forceinline__ uint64_t transpose_vec(const uint8_t *src, uint64_t src_pitch, uint32_t R_in, uint32_t Cc_in,
                                                   uint8_t *dst, uint64_t dst_pitch, uint8_t *lds)
 {
@@ -743,8 +757,8 @@ __device__ __forceinline__ uint64_t transpose_vec(const uint8_t *src, uint64_t s
     auto load_src = [&](uint32_t v, uint32_t &slot) {
         const uint32_t r = v / nvs, cv = v - r * nvs;
         slot = r * ROWB + ((cv ^ ((r / V) % NV)) * 16);
-        // the user tensor is streamed once (non-temporal) and may be only UA-byte aligned; the packed side stays cacheable
-        if constexpr (SRC_IS_PACKED) return load16<false>(reinterpret_cast<const u32x4 *>(src + r * src_pitch + cv * 16));
+        // the user tensor is streamed once (non-temporal) and may be only UA-byte aligned; the packed side as the plan says
+        if constexpr (SRC_IS_PACKED) return load16<NTP>(reinterpret_cast<const u32x4 *>(src + r * src_pitch + cv * 16));
         else return load_user<UA, true>(src + r * src_pitch + cv * 16);
     };
     if constexpr (FULL) {
@@ -794,7 +808,7 @@ __device__ __forceinline__ uint64_t transpose_vec(const uint8_t *src, uint64_t s
         }
         if constexpr (CSUM && !SRC_IS_PACKED) acc += words_sum(o.x);
         if constexpr (SRC_IS_PACKED) store_user<UA, true>(dst + c * dst_pitch + dv * 16, o.x);
-        else store16<false>(reinterpret_cast<u32x4 *>(dst + c * dst_pitch + dv * 16), o.x);
+        else store16<NTP>(reinterpret_cast<u32x4 *>(dst + c * dst_pitch + dv * 16), o.x);
     };
     if constexpr (FULL) {
         static_assert(NV % 8 == 0, "a full tile's dst rows must be whole groups of 8 vectors");
@@ -807,7 +821,7 @@ __device__ __forceinline__ uint64_t transpose_vec(const uint8_t *src, uint64_t s
     return acc;
 }
 
-template <typename E, bool UNPACK, bool CSUM>
+template <typename E, bool UNPACK, bool CSUM, bool NTP>
 __global__ __launch_bounds__(kThreads) void k_transpose(const Tile *__restrict__ tiles,
                                                         const uint32_t *__restrict__ chunk_tiles, BasePtrs bases,
                                                         uint8_t *__restrict__ packed, SumCtx cx)
@@ -824,8 +838,8 @@ __global__ __launch_bounds__(kThreads) void k_transpose(const Tile *__restrict__
         // storage: nj rows (pitch a) of ni contiguous elements; packed: ni rows (pitch b) of nj elements.  Every
         // storage row of the tile is off a 16-byte boundary by the same amount (the pitch is a multiple of 16).
         auto run = [&]<int UA, bool FULL = false>() {
-            if constexpr (!UNPACK) return transpose_vec<E, false, CSUM, UA, FULL>(user, t.a, nj, ni, pk, t.b, lds_raw);
-            else return transpose_vec<E, true, CSUM, UA, FULL>(pk, t.b, ni, nj, user, t.a, lds_raw);
+            if constexpr (!UNPACK) return transpose_vec<E, false, CSUM, NTP, UA, FULL>(user, t.a, nj, ni, pk, t.b, lds_raw);
+            else return transpose_vec<E, true, CSUM, NTP, UA, FULL>(pk, t.b, ni, nj, user, t.a, lds_raw);
         };
         const uint32_t mis = uint32_t(reinterpret_cast<uintptr_t>(user)) & 15u;
         if (mis == 0 && ni == T && nj == T) acc = run.template operator()<16, true>();      // the common case
@@ -834,31 +848,51 @@ __global__ __launch_bounds__(kThreads) void k_transpose(const Tile *__restrict__
         else if ((mis & 1u) == 0) acc = run.template operator()<2>();
         else acc = run.template operator()<1>();
     } else {
+        // Element by element (extents or pitches that are not multiples of 16 bytes).  Eight global loads
+        // per thread are issued before the first of them is needed (the row number is clamped into the
+        // tile, so the loads need no guard of their own).
         E(*lds)[T + 1] = reinterpret_cast<E(*)[T + 1]>(lds_raw);
         const uint32_t tx = threadIdx.x & (T - 1), ty = threadIdx.x / T;
-        constexpr uint32_t TY = kThreads / T;
+        constexpr uint32_t TY = kThreads / T, U = 8;
         if constexpr (!UNPACK) {
             if (tx < ni)
-                for (uint32_t j = ty; j < nj; j += TY) lds[j][tx] = *reinterpret_cast<const E *>(user + j * t.a + tx * sizeof(E));
+                for (uint32_t j0 = ty; j0 < nj; j0 += TY * U) {
+                    E v[U];
+#pragma unroll
+                    for (uint32_t u = 0; u < U; ++u)
+                        v[u] = __builtin_nontemporal_load(reinterpret_cast<const E *>(user + uint64_t(min(j0 + u * TY, nj - 1)) * t.a + tx * sizeof(E)));
+#pragma unroll
+                    for (uint32_t u = 0; u < U; ++u)
+                        if (j0 + u * TY < nj) lds[j0 + u * TY][tx] = v[u];
+                }
             __syncthreads();
             if (tx < nj)
                 for (uint32_t i = ty; i < ni; i += TY) {
                     const E v = lds[tx][i];
                     const uint64_t pos = i * t.b + tx * sizeof(E);
-                    *reinterpret_cast<E *>(pk + pos) = v;
+                    store_elem<NTP>(reinterpret_cast<E *>(pk + pos), v);
                     if constexpr (CSUM) acc += elem_weighted(v, t.packed_off + pos);
                 }
         } else {
             if (tx < nj)
-                for (uint32_t i = ty; i < ni; i += TY) {
-                    const uint64_t pos = i * t.b + tx * sizeof(E);
-                    const E v = *reinterpret_cast<const E *>(pk + pos);
-                    lds[tx][i] = v;
-                    if constexpr (CSUM) acc += elem_weighted(v, t.packed_off + pos);
+                for (uint32_t i0 = ty; i0 < ni; i0 += TY * U) {
+                    E v[U];
+#pragma unroll
+                    for (uint32_t u = 0; u < U; ++u)
+                        v[u] = load_elem<NTP>(reinterpret_cast<const E *>(pk + uint64_t(min(i0 + u * TY, ni - 1)) * t.b + tx * sizeof(E)));
+#pragma unroll
+                    for (uint32_t u = 0; u < U; ++u) {
+                        const uint32_t i = i0 + u * TY;
+                        if (i < ni) {
+                            lds[tx][i] = v[u];
+                            if constexpr (CSUM) acc += elem_weighted(v[u], t.packed_off + i * t.b + tx * sizeof(E));
+                        }
+                    }
                 }
             __syncthreads();
             if (tx < ni)
-                for (uint32_t j = ty; j < nj; j += TY) *reinterpret_cast<E *>(user + j * t.a + tx * sizeof(E)) = lds[j][tx];
+                for (uint32_t j = ty; j < nj; j += TY)
+                    __builtin_nontemporal_store(lds[j][tx], reinterpret_cast<E *>(user + j * t.a + tx * sizeof(E)));
         }
     }
     if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, chunk_tiles[t.chunk], cx);
@@ -867,20 +901,6 @@ __global__ __launch_bounds__(kThreads) void k_transpose(const Tile *__restrict__
 // ---- generic: any strides, one element at a time -------------------------------
 // Every element's address is recomputed from its logical index.  Only used for views the
 // other kernels do not take (no dimension with stride one, or runs shorter than 16 bytes).
-template <bool NT, typename E>
-__device__ __forceinline__ E load_elem(const E *p)
-{
-    if constexpr (NT) return __builtin_nontemporal_load(p);
-    else return *p;
-}
-
-template <bool NT, typename E>
-__device__ __forceinline__ void store_elem(E *p, E v)
-{
-    if constexpr (NT) __builtin_nontemporal_store(v, p);
-    else *p = v;
-}
-
 // The elements [e0, e0 + nel) of one tensor, every dim within reach of the multiply-shift division.
 // ND > 0: the tensor has exactly ND merged dims; ND == 0: any number, read from the descriptor.
 // The dims are copied into registers first: the loop below stores through byte pointers, which
