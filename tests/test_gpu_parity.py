@@ -61,10 +61,12 @@ def specified_mask(m, B, k, nbytes):
     return spec
 
 
-def round_trip_check(case, raws, tile_bytes=None, base_offset=0, nthreads=1, two_word=False):
+def round_trip_check(case, raws, tile_bytes=None, base_offset=0, nthreads=1, two_word=False, hint=None):
     """pack / checksum / unpack on the GPU vs the oracle; returns the device packed buffer."""
     m = oracle_msg(case)
     p = plan_of(case, tile_bytes, two_word)
+    if hint is not None:
+        hxt.hxt_plan_set_option(p, hxt.HXT_OPT_PACKED_HINT, hint)
     B, k = case.B, case.k
     want = ho.pack(m, raws, B, k, fill=0xA5, nthreads=nthreads)
     want_sums = ho.checksum(m, want, B, k, nthreads=nthreads)
@@ -171,6 +173,11 @@ def test_mid_size_messages_with_element_aligned_bases(name, offset):
     kernels, with narrower accesses on the tensor side, and so do transposes.  Same bytes and sums."""
     case = [c for c in MID_CASES if c.name == name][0]
     round_trip_check(case, make_storages(case, 321), None, base_offset=offset)
+
+
+@pytest.mark.parametrize("case", MID_CASES, ids=lambda c: c.name)
+def test_mid_size_cases_with_the_packed_side_non_temporal(case):
+    round_trip_check(case, make_storages(case, 12), hint=1)
 
 
 @pytest.mark.parametrize("case", MID_CASES, ids=lambda c: c.name)
@@ -369,8 +376,9 @@ def test_random_views_of_up_to_eight_dims(seed):
         if sum(storage_bytes(*t) for t in tensors) > 4_000_000 or sum(int(np.prod(t[0])) * t[2] for t in tensors) > 8_000_000:
             continue
         case = Case("rand8_%d_%d" % (seed, done), tensors, int(rng.integers(1, 6)), int(rng.choice([256, 1024, 4096, 16384])))
-        say("random case", case.tensors, case.k, case.B)
-        round_trip_check(case, make_storages(case, seed), tile_bytes=int(rng.choice([256, 1024, 16384])))
+        hint = int(rng.choice([-1, 0, 1]))
+        say("random case", case.tensors, case.k, case.B, "hint", hint)
+        round_trip_check(case, make_storages(case, seed), tile_bytes=int(rng.choice([256, 1024, 16384])), hint=hint)
         done += 1
 
 
@@ -1111,8 +1119,10 @@ def test_config_grad_buckets_full_size_both_paths():
     assert bool((host[tail0:tail1] == 0).all())
 
 
+@pytest.mark.parametrize("hint", [None, 1], ids=["hint_by_size", "all_cold_non_temporal"])
 @pytest.mark.parametrize("name", ["qwen_rows_view", "transpose_view", "rows_split_view", "inner_stride_view"])
-def test_supplementary_strided_messages_full_size(name):
+def test_supplementary_strided_messages_full_size(name, hint):
+    """hint 1: the packed side non-temporal as well, as in the benchmark's all-cold figures."""
     w = wl.ALL[name]()
-    say("supplementary", name)
-    round_trip_check(case_of(w), wl.make_storages(w), nthreads=NT)
+    say("supplementary", name, hint)
+    round_trip_check(case_of(w), wl.make_storages(w), nthreads=NT, hint=hint)
