@@ -86,6 +86,16 @@ __device__ __forceinline__ void store_elem(E *p, E v)
     else *p = v;
 }
 
+// Vector v of a span of nvec (>= 1) vectors, zeros beyond its end.  The load itself is unconditional (the
+// index is clamped into the span): the loads of an unrolled round are then all issued before the first
+// of them is waited for, where guarded loads are waited for one by one.
+template <bool NT>
+__device__ __forceinline__ u32x4 load16_or_zero(const u32x4 *s, uint32_t v, uint32_t nvec)
+{
+    const u32x4 x = load16<NT>(s + min(v, nvec - 1));
+    return v < nvec ? x : u32x4{0, 0, 0, 0};
+}
+
 __device__ __forceinline__ uint64_t words_sum(u32x4 v)
 {
     return (uint64_t(v.x) + uint64_t(v.y)) + (uint64_t(v.z) + uint64_t(v.w));
@@ -1045,7 +1055,7 @@ __global__ __launch_bounds__(kThreads) void k_checksum(ChunkGeom g, const uint8_
         u32x4 r[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u)
-            r[u] = (v + u * kThreads < nvec) ? load16<NTP>(s + v + u * kThreads) : u32x4{0, 0, 0, 0};
+            r[u] = load16_or_zero<NTP>(s, v + u * kThreads, nvec);
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) acc += words_sum(r[u]);
     }
@@ -1235,7 +1245,7 @@ __global__ __launch_bounds__(kThreads) void k_checksum2(ChunkGeom g, const uint8
         u32x4 r[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u)
-            r[u] = (v + u * kThreads < nvec) ? load16<NTP>(s + v + u * kThreads) : u32x4{0, 0, 0, 0};
+            r[u] = load16_or_zero<NTP>(s, v + u * kThreads, nvec);
         uint64_t blockS = 0, blockN = 0;     // this block's sum_u S_u and sum_u u*S_u
 #pragma unroll
         for (int u = kUnroll - 1; u >= 0; --u) {
