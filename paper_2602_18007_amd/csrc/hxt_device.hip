@@ -1134,16 +1134,16 @@ int hxt_host_forward(const hxt_plan_t *plan, int lane, const void *from, void *t
     if (lane < -1 || lane >= p.k) return HXT_EINVAL;
     if (p.C == 0) return HXT_OK;
     if (!from || !to) return HXT_EINVAL;
-    std::vector<int> lanes;
-    for (int l = (lane < 0 ? 0 : lane); l < (lane < 0 ? p.k : lane + 1); ++l) lanes.push_back(l);
+    const int first = lane < 0 ? 0 : lane;                       // lanes first .. first + n_lanes - 1
+    const size_t n_lanes = lane < 0 ? size_t(p.k) : 1;
     auto copy_lane = [&](int l) {
         uint64_t r[2][2];
         if (stage_ranges(p, l, r))
             std::memcpy(static_cast<uint8_t *>(to) + r[0][0], static_cast<const uint8_t *>(from) + r[0][0], r[0][1]);
     };
-    const size_t workers = std::min<size_t>(lanes.size(), n_threads < 1 ? lanes.size() : size_t(n_threads));
+    const size_t workers = std::min<size_t>(n_lanes, n_threads < 1 ? n_lanes : size_t(n_threads));
     if (workers <= 1) {
-        for (int l : lanes) copy_lane(l);
+        for (size_t i = 0; i < n_lanes; ++i) copy_lane(first + int(i));
         return HXT_OK;
     }
     // A worker takes lanes w, w + workers, ...  If a thread cannot be created, the threads that did start
@@ -1151,7 +1151,7 @@ int hxt_host_forward(const hxt_plan_t *plan, int lane, const void *from, void *t
     std::thread pool[64];
     const size_t n_pool = std::min<size_t>(workers, 64);
     auto work = [&](size_t w) {
-        for (size_t i = w; i < lanes.size(); i += n_pool) copy_lane(lanes[i]);
+        for (size_t i = w; i < n_lanes; i += n_pool) copy_lane(first + int(i));
     };
     size_t started = 0;
     try {
