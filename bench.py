@@ -62,7 +62,7 @@ def parse():
     ap.add_argument("--tags", action="store_true",
                     help="chunk tags sealed and verified inside the copies instead of the plain checksums")
     ap.add_argument("--accumulate", action="store_true",
-                    help="receive with hxt_unpack_accumulate (old + arriving); one call per message")
+                    help="receive with hxt_unpack_accumulate_batch (old + arriving)")
     ap.add_argument("--no-checksum", action="store_true", help="diagnostic only: copies without checksums")
     ap.add_argument("--path", default="device_direct", choices=["device_direct", "cpu_forward"],
                     help="for --workload stream_1f1b")
@@ -122,7 +122,7 @@ class DirectStep:
         self.sets -= self.sets % 2                       # even: a set always belongs to the same chain
         self.S = [[MessageSet(torch, w, p0, w.seed + 1000 * s + m * max(w.seed_step, 1)) for m in range(self.nmsg)]
                   for s in range(self.sets)]
-        use_sums = mode == "sums"
+        use_sums = mode in ("sums", "accumulate")
         self.pack_b, self.unpack_b = [], []
         for s, S in enumerate(self.S):
             pl = self.plans[s % 2]
@@ -143,7 +143,7 @@ class DirectStep:
             self.kernel = "hxt::k_contig_tag"
         else:
             self.kernel = " + ".join("hxt::k_" + k for k in kinds)
-        self.per_launch = min(self.nmsg, 4) if (batched and self.uniform and mode != "accumulate") else 1
+        self.per_launch = min(self.nmsg, 4) if (batched and self.uniform) else 1
         self.launches_per_step = 2 * self.nmsg // self.per_launch if self.uniform or len(kinds) == 1 else None
         # pack: read N + write N; unpack: the same; accumulate: read N arriving + read N old + write N
         self.step_bytes = (5 if mode == "accumulate" else 4) * self.N * self.nmsg
@@ -166,9 +166,12 @@ class DirectStep:
                     hxt.hxt_pack_seal(p, ms.src, ms.packed, i, m, ms.tags, stream)
                     hxt.hxt_unpack_verify(p, ms.packed, ms.tags, i, m, ms.dst, ms.status, stream)
             return
-        if self.batched and self.mode != "accumulate":
+        if self.batched:
             hxt.hxt_pack_batch(self.pack_b[s], stream)
-            hxt.hxt_unpack_batch(self.unpack_b[s], stream)
+            if self.mode == "accumulate":
+                hxt.hxt_unpack_accumulate_batch(self.unpack_b[s], stream)
+            else:
+                hxt.hxt_unpack_batch(self.unpack_b[s], stream)
             return
         use = self.mode != "none"
         for m, ms in enumerate(self.S[s]):

@@ -241,6 +241,15 @@ int hxt_unpack(const hxt_plan_t *plan, const void *packed, void *const *dst,
 int hxt_unpack_accumulate(const hxt_plan_t *plan, const void *packed, void *const *dst,
                           uint64_t *sums, void *stream);
 
+/* The same for n messages at once, like hxt_unpack_batch: messages that are one contiguous
+ * 16-byte aligned tensor each share kernel launches (up to 4 per launch), the others are
+ * enqueued one by one; results are those of n hxt_unpack_accumulate calls.  sums: NULL, or an
+ * array of n entries each NULL or a device array of that plan's num_chunks values; a plan may
+ * appear twice only if at most one of its entries asks for sums (HXT_EINVAL otherwise).
+ * Everything is validated before anything is enqueued. */
+int hxt_unpack_accumulate_batch(int n, const hxt_plan_t *const *plans, const void *const *packed,
+                                void *const *const *dst, uint64_t *const *sums, void *stream);
+
 /* ---- steps 2 and 4 for several messages at once -------------------------------
  * A stage boundary is crossed in both directions at the same point of the schedule
  * (Section 3.1: two pipeline stages; the forward activation of one micro-batch and

@@ -1210,6 +1210,76 @@ int hxt_unpack_accumulate(const hxt_plan_t *plan, const void *packed, void *cons
     return sums ? run_accumulate<true>(pl, dst, pk, sums, st) : run_accumulate<false>(pl, dst, pk, nullptr, st);
 }
 
+// Batched receive-and-accumulate: messages that are one contiguous 16-byte aligned tensor share launches of
+// up to kMaxBatch (same checksum choice within a launch); the rest go one by one.
+int hxt_unpack_accumulate_batch(int n, const hxt_plan_t *const *plans, const void *const *packed,
+                                void *const *const *dst, uint64_t *const *sums, void *stream)
+{
+    if (n < 0 || (n > 0 && (!plans || !dst || !packed))) return HXT_EINVAL;
+    for (int i = 0; i < n; ++i) {                      // validate everything before enqueuing anything
+        int rc = check_common(plans[i], packed[i]);
+        if (rc != HXT_OK) return rc;
+        if (plans[i]->p.C == 0) continue;
+        if ((rc = check_tensor_pointers(plans[i]->p, dst[i])) != HXT_OK) return rc;
+        if (!plans[i]->p.can_accumulate) return HXT_EUNSUPPORTED;
+        for (int j = 0; j < i; ++j)
+            if (plans[j] == plans[i] && sums && sums[i] && sums[j]) return HXT_EINVAL;   // one accumulator set per plan
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    BatchLock lock(plans, n);
+    int i = 0;
+    while (i < n) {
+        hxt_plan_t &pl = *const_cast<hxt_plan_t *>(plans[i]);
+        const Plan &p = pl.p;
+        uint64_t *sm = sums ? sums[i] : nullptr;
+        auto fusable = [&](int j) {
+            const Plan &q = plans[j]->p;
+            return q.C != 0 && q.uniform && reinterpret_cast<uintptr_t>(dst[j][q.uniform_tensor]) % 16 == 0 &&
+                   ((sums ? sums[j] : nullptr) != nullptr) == (sm != nullptr);
+        };
+        if (p.C == 0) {
+            ++i;
+            continue;
+        }
+        if (!fusable(i)) {
+            uint8_t *pk = const_cast<uint8_t *>(static_cast<const uint8_t *>(packed[i]));
+            int rc = sm ? run_accumulate<true>(pl, dst[i], pk, sm, st) : run_accumulate<false>(pl, dst[i], pk, nullptr, st);
+            if (rc != HXT_OK) return rc;
+            ++i;
+            continue;
+        }
+        UniformArgs a;
+        std::memset(&a, 0, sizeof a);
+        uint64_t tiles = 0, bytes = 0;
+        int j = i;
+        while (j < n && a.n < uint32_t(kMaxBatch) && fusable(j) && tiles + plans[j]->p.geom.ntiles < (uint64_t(1) << 31)) {
+            hxt_plan_t &pj = *const_cast<hxt_plan_t *>(plans[j]);
+            SumCtx cx{nullptr, nullptr, 0, 0, 1, 0};
+            if (sm) {
+                int rc = claim_slots(pj, OP_UNPACK, st, cx, sums[j]);
+                if (rc != HXT_OK) return rc;
+                cx.sum_bits = pj.sum_bits_geom;
+            }
+            const TensorPlan &tp = pj.p.tensors[pj.p.uniform_tensor];
+            // `unpack` carries the element kind here: 1 = f32, 0 = bf16
+            a.it[a.n++] = UniformItem{pj.p.geom, static_cast<uint8_t *>(dst[j][pj.p.uniform_tensor]),
+                                      const_cast<uint8_t *>(static_cast<const uint8_t *>(packed[j])), cx, uint32_t(tiles),
+                                      tp.dtype == HXT_F32 ? 1u : 0u};
+            tiles += pj.p.geom.ntiles;
+            bytes += pj.p.C * pj.p.B;
+            ++j;
+        }
+        const bool ntp = plans[i]->nt_packed >= 0 ? plans[i]->nt_packed != 0 : packed_nontemporal(bytes);
+        with_hints(ntp, [&]<bool NTU, bool NTP>() {
+            if (sm) k_uniform_accumulate<true, NTU, NTP><<<uint32_t(tiles), kThreads, 0, st>>>(a);
+            else k_uniform_accumulate<false, NTU, NTP><<<uint32_t(tiles), kThreads, 0, st>>>(a);
+        });
+        HXT_HIP(hipGetLastError());
+        i = j;
+    }
+    return HXT_OK;
+}
+
 int hxt_exchange_stream(const hxt_plan_t *plan, const hxt_exchange_t *x)
 {
     if (!plan || !x || x->n_messages < 0 || x->n_buffers < 1) return HXT_EINVAL;

@@ -458,9 +458,13 @@ __global__ __launch_bounds__(kThreads) void k_contig_any(const Tile *__restrict_
 template <bool CSUM, bool NTU, bool NTP>
 __global__ __launch_bounds__(kThreads) void k_uniform_accumulate(UniformArgs a)
 {
-    const UniformItem &it = a.it[0];
+    uint32_t m = 0;                                    // up to kMaxBatch messages per launch, as in k_uniform
+#pragma unroll
+    for (uint32_t i = 1; i < kMaxBatch; ++i)
+        if (i < a.n && blockIdx.x >= a.it[i].first_tile) m = i;
+    const UniformItem &it = a.it[m];
     const ChunkGeom &g = it.g;
-    const TileSpan t = locate_tile(g, blockIdx.x);
+    const TileSpan t = locate_tile(g, blockIdx.x - it.first_tile);
     const uint64_t left = g.N > t.stream_off ? g.N - t.stream_off : 0;
     const uint32_t data = left < t.len ? uint32_t(left) : t.len;
     uint8_t *pk = it.packed + t.packed_off;

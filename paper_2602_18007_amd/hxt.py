@@ -32,7 +32,7 @@ EXPORTS = (
     "hxt_pack_batch", "hxt_unpack_batch", "hxt_exchange_stream", "hxt_unpack_accumulate",
     "hxt_host_forward", "hxt_stage_hop", "hxt_checksum2", "hxt_seal", "hxt_verify", "hxt_pack_seal", "hxt_unpack_verify",
     "hxt_pack_noalloc", "hxt_plan_set_option", "hxt_pack_seal_batch", "hxt_unpack_verify_batch",
-    "hxt_stage_d2h_slots", "hxt_stage_h2d_slots",
+    "hxt_stage_d2h_slots", "hxt_stage_h2d_slots", "hxt_unpack_accumulate_batch",
     "hxt_strerror", "hxt_last_hip_error", "hxt_version",
 )
 
@@ -128,6 +128,7 @@ def lib():
             "hxt_unpack_accumulate": (i, [vp, vp, C.POINTER(vp), u64p, vp]),
             "hxt_pack_batch": (i, [i, C.POINTER(vp), C.POINTER(C.POINTER(vp)), C.POINTER(vp), C.POINTER(vp), vp]),
             "hxt_unpack_batch": (i, [i, C.POINTER(vp), C.POINTER(vp), C.POINTER(C.POINTER(vp)), C.POINTER(vp), vp]),
+            "hxt_unpack_accumulate_batch": (i, [i, C.POINTER(vp), C.POINTER(vp), C.POINTER(C.POINTER(vp)), C.POINTER(vp), vp]),
             "hxt_exchange_stream": (i, [vp, C.POINTER(_Exchange)]),
             "hxt_pack_seal_batch": (i, [i, C.POINTER(vp), C.POINTER(C.POINTER(vp)), C.POINTER(vp), C.POINTER(C.c_uint64),
                                         C.POINTER(C.c_uint32), C.POINTER(vp), vp]),
@@ -337,6 +338,15 @@ def hxt_pack_batch(batch: Batch, stream=None) -> None:
 def hxt_unpack_batch(batch: Batch, stream=None) -> None:
     _check(lib().hxt_unpack_batch(batch.n, batch.plans, batch.packed, batch.tensors, batch.sums, _stream(stream)),
            "hxt_unpack_batch")
+
+
+def hxt_unpack_accumulate_batch(batch: Batch, stream=None) -> None:
+    for p in batch._keep[0]:
+        if not p.arithmetic:
+            raise ValueError("hxt_unpack_accumulate_batch adds bf16 or f32 values: build every plan with "
+                             "torch.bfloat16 / torch.float32")
+    _check(lib().hxt_unpack_accumulate_batch(batch.n, batch.plans, batch.packed, batch.tensors, batch.sums,
+                                             _stream(stream)), "hxt_unpack_accumulate_batch")
 
 
 class Exchange:

@@ -134,6 +134,66 @@ def test_accumulate_into_element_aligned_destinations(case, offset):
     assert np.array_equal(sums.cpu().numpy().view(np.uint64), ho.checksum(m, packed_o, case.B, case.k))
 
 
+def test_batched_accumulate_equals_the_oracle_message_by_message():
+    """hxt_unpack_accumulate_batch over a mixed set: single-tensor bf16 and f32 messages (these share launches),
+    one of them without checksums (it cannot share a launch with its neighbours), a multi-tensor bucket, an empty
+    message, a destination that is only element aligned, and the LLaMA-shaped pair of 32 MiB messages."""
+    big = Case("llama_shaped", (contig((4096, 1, 4096), 2),), 4, 1 << 20)
+    cases = [CASES[0], CASES[1], CASES[0], CASES[3], Case("empty", (contig((0,), 2),), 2, 256), CASES[2], CASES[1], big, big]
+    want_sums = [True, True, False, True, True, True, True, True, True]
+    offsets = [0, 0, 0, 0, 0, 0, 4, 0, 0]
+    rng = np.random.default_rng(77)
+    plans, packed, dst, views, sums, wants, wsums, locals_ = [], [], [], [], [], [], [], []
+    for c, ws, off in zip(cases, want_sums, offsets):
+        m = ho.Message([ho.TensorSpec(tuple(s), tuple(st), e) for (s, st, e) in c.tensors])
+        kinds = [ho.KIND_BF16 if e == 2 else ho.KIND_F32 for (_, _, e) in c.tensors]
+        sizes = [int(np.prod(s)) * e for (s, _, e) in c.tensors]
+        mode = "grad" if c is big else "near"
+        incoming = [draw(rng, n, e, mode) for n, (_, _, e) in zip(sizes, c.tensors)]
+        local = [draw(rng, n, e, mode) for n, (_, _, e) in zip(sizes, c.tensors)]
+        packed_o = ho.pack(m, incoming, c.B, c.k, fill=0x5A, nthreads=8)
+        want = [x.copy() for x in local]
+        ho.unpack_accumulate(m, kinds, packed_o, c.B, c.k, want, nthreads=8)
+        p = hxt.hxt_plan_multi([(s, st, FLOAT_OF[e]) for (s, st, e) in c.tensors], c.k, c.B)
+        plans.append(p)
+        packed.append(torch.from_numpy(packed_o).to(DEV) if packed_o.size else torch.zeros(256, dtype=torch.uint8, device=DEV))
+        bufs = []
+        for x in local:
+            buf = torch.full((x.size + off + 32,), 0x3C, dtype=torch.uint8, device=DEV)
+            buf[off:off + x.size].copy_(torch.from_numpy(x))
+            bufs.append(buf)
+        dst.append(bufs)
+        views.append([b[off:off + x.size] for b, x in zip(bufs, local)])
+        sums.append(torch.full((max(p.num_chunks, 1),), -1, dtype=torch.int64, device=DEV) if ws else None)
+        wants.append(want)
+        wsums.append(ho.checksum(m, packed_o, c.B, c.k))
+        locals_.append(local)
+    print("batched accumulate of", len(cases), flush=True)
+    hxt.hxt_unpack_accumulate_batch(hxt.Batch(plans, views, packed, sums))
+    torch.cuda.synchronize()
+    for i, c in enumerate(cases):
+        off = offsets[i]
+        for a, b, x in zip(wants[i], dst[i], locals_[i]):
+            got = b.cpu().numpy()
+            assert np.array_equal(got[off:off + x.size], a), (i, c.name)
+            assert (got[:off] == 0x3C).all() and (got[off + x.size:] == 0x3C).all(), (i, c.name)
+        if sums[i] is not None:
+            assert np.array_equal(sums[i].cpu().numpy().view(np.uint64)[:wsums[i].size], wsums[i]), (i, c.name)
+    # the same plan twice with checksums is refused, and so is a plan that cannot accumulate; nothing is enqueued
+    with pytest.raises(hxt.HxtError) as e:
+        hxt.hxt_unpack_accumulate_batch(hxt.Batch([plans[0], plans[0]], [views[0], views[0]], [packed[0], packed[0]],
+                                                  [sums[0], sums[0]]))
+    assert e.value.status == hxt.HXT_EINVAL
+    strided = hxt.hxt_plan((8, 64), (128, 1), torch.bfloat16, 2, 256)
+    buf = torch.zeros(4096, dtype=torch.uint8, device=DEV)
+    before = [b.clone() for b in dst[0]]
+    with pytest.raises(hxt.HxtError) as e:
+        hxt.hxt_unpack_accumulate_batch(hxt.Batch([plans[0], strided], [views[0], [buf]], [packed[0], buf], None))
+    assert e.value.status == hxt.HXT_EUNSUPPORTED
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, b) for a, b in zip(before, dst[0]))
+
+
 def test_accumulate_gradient_bucket_shape():
     # one LLaMA-8B layer's worth of bf16 gradients (218 M elements) is too slow for the per-byte oracle
     # to add in a test; a 1/64 scale model of the nine tensors keeps the structure (two tiny norms,

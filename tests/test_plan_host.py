@@ -215,6 +215,9 @@ def test_argument_errors_of_the_newer_entry_points():
     assert L.hxt_pack_seal_batch(1, None, None, None, None, None, None, None) == hxt.HXT_EINVAL
     assert L.hxt_unpack_verify_batch(1, None, None, None, None, None, None, None, None) == hxt.HXT_EINVAL
     assert L.hxt_pack_seal_batch(0, None, None, None, None, None, None, None) == hxt.HXT_OK
+    assert L.hxt_unpack_accumulate_batch(-1, None, None, None, None, None) == hxt.HXT_EINVAL
+    assert L.hxt_unpack_accumulate_batch(2, None, None, None, None, None) == hxt.HXT_EINVAL
+    assert L.hxt_unpack_accumulate_batch(0, None, None, None, None, None) == hxt.HXT_OK
     assert L.hxt_pack_noalloc(None, 100, 0, 256, None, None, None) == hxt.HXT_EINVAL
     assert L.hxt_pack_noalloc(None, 100, 2, 100, None, None, None) == hxt.HXT_EINVAL
     assert L.hxt_pack_noalloc(None, 100, 2, 256, None, None, None) == hxt.HXT_EINVAL      # NULL buffers
