@@ -134,7 +134,8 @@ def test_accumulate_into_element_aligned_destinations(case, offset):
     assert np.array_equal(sums.cpu().numpy().view(np.uint64), ho.checksum(m, packed_o, case.B, case.k))
 
 
-def test_batched_accumulate_equals_the_oracle_message_by_message():
+@pytest.mark.parametrize("hint", [-1, 1], ids=["hint_by_size", "all_cold_non_temporal"])
+def test_batched_accumulate_equals_the_oracle_message_by_message(hint):
     """hxt_unpack_accumulate_batch over a mixed set: single-tensor bf16 and f32 messages (these share launches),
     one of them without checksums (it cannot share a launch with its neighbours), a multi-tensor bucket, an empty
     message, a destination that is only element aligned, and the LLaMA-shaped pair of 32 MiB messages."""
@@ -155,6 +156,7 @@ def test_batched_accumulate_equals_the_oracle_message_by_message():
         want = [x.copy() for x in local]
         ho.unpack_accumulate(m, kinds, packed_o, c.B, c.k, want, nthreads=8)
         p = hxt.hxt_plan_multi([(s, st, FLOAT_OF[e]) for (s, st, e) in c.tensors], c.k, c.B)
+        hxt.hxt_plan_set_option(p, hxt.HXT_OPT_PACKED_HINT, hint)
         plans.append(p)
         packed.append(torch.from_numpy(packed_o).to(DEV) if packed_o.size else torch.zeros(256, dtype=torch.uint8, device=DEV))
         bufs = []

@@ -270,12 +270,15 @@ def test_batched_fused_tag_calls_match_the_oracle(offset):
     torch.cuda.synchronize()
 
 
-def test_batched_fused_tag_calls_on_the_full_size_boundary_step():
+@pytest.mark.parametrize("hint", [-1, 1], ids=["hint_by_size", "all_cold_non_temporal"])
+def test_batched_fused_tag_calls_on_the_full_size_boundary_step(hint):
     """The benchmark's tagged step: both LLaMA-shaped messages sealed inside one batched pack launch and verified
-    inside one batched unpack launch."""
+    inside one batched unpack launch (hint 1: with the packed side non-temporal, its all-cold figure)."""
     w = wl.llama8b_boundary()
     m = ho.Message([ho.TensorSpec(t.shape, t.strides, t.esize) for t in w.tensors])
     plans = [hxt.hxt_plan_multi([(t.shape, t.strides, t.esize) for t in w.tensors], w.n_lanes, w.chunk_bytes) for _ in range(2)]
+    for p in plans:
+        hxt.hxt_plan_set_option(p, hxt.HXT_OPT_PACKED_HINT, hint)
     raws = [wl.make_storages(w, i) for i in range(2)]
     src = [[torch.from_numpy(r).to(DEV) for r in rs] for rs in raws]
     dst = [[torch.zeros_like(t) for t in ts] for ts in src]
