@@ -49,7 +49,8 @@ struct Tile {
     uint32_t n0;
     uint32_t n1;
     uint32_t ordinal;  // position of this tile among the tiles of its chunk (0 .. chunk_tiles[chunk] - 1)
-    uint32_t reserved[2];
+    uint32_t estep;    // TRANSPOSE: bytes between neighbouring elements along the tensor side's fast direction
+    uint32_t reserved;
 };
 static_assert(sizeof(Tile) == 64, "Tile must stay 64 bytes");
 

@@ -847,7 +847,8 @@ __global__ __launch_bounds__(kThreads) void k_transpose(const Tile *__restrict__
     uint8_t *pk = packed + t.packed_off;
     const uint32_t ni = t.n0, nj = t.n1;
     uint64_t acc = 0;
-    const bool vec_ok = ((ni | nj) % V) == 0 && ((reinterpret_cast<uintptr_t>(pk) | t.a | t.b) % 16) == 0;
+    const uint32_t es = t.estep;                       // tensor side: bytes from element i to element i + 1 (sizeof(E) or more)
+    const bool vec_ok = es == sizeof(E) && ((ni | nj) % V) == 0 && ((reinterpret_cast<uintptr_t>(pk) | t.a | t.b) % 16) == 0;
     if (vec_ok) {
         // storage: nj rows (pitch a) of ni contiguous elements; packed: ni rows (pitch b) of nj elements.  Every
         // storage row of the tile is off a 16-byte boundary by the same amount (the pitch is a multiple of 16).
@@ -862,7 +863,8 @@ __global__ __launch_bounds__(kThreads) void k_transpose(const Tile *__restrict__
         else if ((mis & 1u) == 0) acc = run.template operator()<2>();
         else acc = run.template operator()<1>();
     } else {
-        // Element by element (extents or pitches that are not multiples of 16 bytes).  Eight global loads
+        // Element by element (extents or pitches that are not multiples of 16 bytes, or a tensor side whose
+        // fast direction has a stride of a few elements instead of one).  Eight global loads
         // per thread are issued before the first of them is needed (the row number is clamped into the
         // tile, so the loads need no guard of their own).
         E(*lds)[T + 1] = reinterpret_cast<E(*)[T + 1]>(lds_raw);
@@ -874,7 +876,7 @@ __global__ __launch_bounds__(kThreads) void k_transpose(const Tile *__restrict__
                     E v[U];
 #pragma unroll
                     for (uint32_t u = 0; u < U; ++u)
-                        v[u] = __builtin_nontemporal_load(reinterpret_cast<const E *>(user + uint64_t(min(j0 + u * TY, nj - 1)) * t.a + tx * sizeof(E)));
+                        v[u] = __builtin_nontemporal_load(reinterpret_cast<const E *>(user + uint64_t(min(j0 + u * TY, nj - 1)) * t.a + tx * es));
 #pragma unroll
                     for (uint32_t u = 0; u < U; ++u)
                         if (j0 + u * TY < nj) lds[j0 + u * TY][tx] = v[u];
@@ -906,7 +908,7 @@ __global__ __launch_bounds__(kThreads) void k_transpose(const Tile *__restrict__
             __syncthreads();
             if (tx < ni)
                 for (uint32_t j = ty; j < nj; j += TY)
-                    __builtin_nontemporal_store(lds[j][tx], reinterpret_cast<E *>(user + j * t.a + tx * sizeof(E)));
+                    __builtin_nontemporal_store(lds[j][tx], reinterpret_cast<E *>(user + j * t.a + tx * es));
         }
     }
     if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, chunk_tiles[t.chunk], cx);

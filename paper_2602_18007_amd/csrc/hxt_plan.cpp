@@ -114,7 +114,7 @@ static bool view_is_injective(const TensorPlan &t)
     return true;
 }
 
-static Kind classify(const TensorPlan &t)
+static Kind classify(const TensorPlan &t, uint64_t chunk_bytes)
 {
     if (t.elems == 0) return K_NONE;
     if (t.ndim == 0) return K_CONTIG;                               // one element
@@ -133,7 +133,14 @@ static Kind classify(const TensorPlan &t)
         for (int d = 0; d < last; ++d) split = split && t.shape[d] < (int64_t(1) << 31);
         return split ? K_ROWS_SPLIT : K_GENERIC;
     }
+    // The dim before the last runs along the storage and the last dim jumps further: a transpose through LDS.
     if (t.ndim >= 2 && t.stride[last] > 1 && t.stride[last - 1] == 1) return K_TRANSPOSE;
+    // The same when the storage-fast dim has a stride of a few elements (at most 16 bytes, so that neighbouring
+    // elements still share memory bursts), provided a chunk holds at least 32 rows of the packed side: tiles
+    // never cross chunks, and flatter ones than that are served better element by element.
+    if (t.ndim >= 2 && t.stride[last - 1] > 1 && t.stride[last] > t.stride[last - 1] &&
+        uint64_t(t.stride[last - 1]) * t.esize <= 16 && uint64_t(t.shape[last]) * t.esize * 32 <= chunk_bytes)
+        return K_TRANSPOSE;
     return K_GENERIC;
 }
 
@@ -175,10 +182,10 @@ struct Builder {
     explicit Builder(Plan &plan) : p(plan) {}
 
     void add(Kind kernel, Kind kind, uint32_t tensor, uint64_t packed_off, uint64_t src_off, uint64_t a,
-             uint64_t b, uint32_t chunk, uint32_t n0, uint32_t n1)
+             uint64_t b, uint32_t chunk, uint32_t n0, uint32_t n1, uint32_t estep = 0)
     {
         RawTile r;
-        r.t = Tile{packed_off, src_off, a, b, chunk, 0, uint32_t(kind), n0, n1, 0, {0, 0}};
+        r.t = Tile{packed_off, src_off, a, b, chunk, 0, uint32_t(kind), n0, n1, 0, estep, 0};
         r.tensor_abs = tensor;
         by_kernel[kernel].push_back(r);
     }
@@ -201,7 +208,7 @@ struct Builder {
     {
         const TensorPlan &t = p.tensors[ti];
         const int n = t.ndim;
-        const uint64_t e = t.esize, I = t.shape[n - 2], J = t.shape[n - 1], sJ = t.stride[n - 1];
+        const uint64_t e = t.esize, I = t.shape[n - 2], J = t.shape[n - 1], sI = t.stride[n - 2], sJ = t.stride[n - 1];
         const uint64_t T = transpose_tile(uint32_t(e));
         auto batch_off = [&](uint64_t batch) {           // storage offset (elements) of a batch index
             uint64_t off = 0;
@@ -220,7 +227,8 @@ struct Builder {
                     uint64_t nj = std::min(T, c_hi - cc);
                     uint64_t stream = t.stream_off + (rr * J + cc) * e;
                     add(K_TRANSPOSE, K_TRANSPOSE, ti, p.chunk_packed_off(c) + (stream - c * p.B),
-                        (batch_off(batch) + i0 + cc * sJ) * e, sJ * e, J * e, uint32_t(c), uint32_t(ni), uint32_t(nj));
+                        (batch_off(batch) + i0 * sI + cc * sJ) * e, sJ * e, J * e, uint32_t(c), uint32_t(ni), uint32_t(nj),
+                        uint32_t(sI * e));
                 }
                 rr += ni;
             }
@@ -285,7 +293,7 @@ int build_plan(const hxt_tensor_desc_t *descs, int n_tensors, int n_lanes, size_
         t.bytes = elems * t.esize;
         t.stream_off = off;
         if (elems > 0) merge_dims(d, t);
-        t.kind = classify(t);
+        t.kind = classify(t, chunk_bytes);
         t.unpack_safe = elems == 0 || view_is_injective(t);
         p.all_unpack_safe = p.all_unpack_safe && t.unpack_safe;
         if (elems > 0 && !(t.kind == K_CONTIG && (t.dtype == HXT_BF16 || t.dtype == HXT_F32))) p.can_accumulate = false;

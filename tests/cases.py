@@ -72,6 +72,11 @@ SMALL_CASES: List[Case] = [
     Case("six_dims_rows_32_byte_runs", (((2, 3, 2, 3, 2, 16), (384, 96, 1152, 24, 3456, 1), 2),), 2, 512),
     Case("six_dims_rows_20_byte_runs", (permuted((2, 3, 2, 3, 2, 10), (5, 1, 3, 0, 4, 2), 2, scale=1),), 3, 256),
     Case("seven_dims_f64_no_unit_stride", (permuted((2, 2, 2, 3, 2, 2, 3), (3, 6, 0, 5, 1, 4, 2), 8),), 2, 1024),
+    Case("transpose_inner_stride_2", (((24, 40), (2, 48), 2),), 2, 4096),    # storage-fast dim strided by two elements
+    Case("transpose_inner_stride_3_u8", (((5, 17, 33), (4000, 3, 60), 1),), 3, 2048),
+    Case("transpose_inner_stride_2_f64", (((20, 12), (2, 48), 8),), 2, 4096),  # 16 bytes from element to element
+    Case("inner_stride_3_f64_too_wide", (((20, 12), (3, 72), 8),), 2, 4096),   # 24 bytes: the per-element kernel
+    Case("inner_stride_2_flat_chunks", (((24, 40), (2, 48), 2),), 2, 256),     # a chunk holds 3 packed rows: per element
     Case("sixty_four_lanes", (contig((40000,), 2),), 64, 512),                # 157 chunks, lanes hold 3 or 2
     Case("mixed_dtypes_multi", (contig((33,), 1), ((8, 24), (32, 1), 2), ((16, 8), (1, 16), 4), contig((5,), 8)), 4, 512),
 ]

@@ -135,11 +135,12 @@ extern "C" int plan_interp(const hxt_tensor_desc_t *descs, int n_tensors, int n_
                 break;
             case K_TRANSPOSE:
                 if (g.kernel != K_TRANSPOSE || t.n0 > transpose_tile(td.esize) || t.n1 > transpose_tile(td.esize)) return -5;
+                if (t.estep < uint32_t(td.esize) || t.estep % uint32_t(td.esize) || t.estep > 16) return -5;
                 for (uint64_t i2 = 0; i2 < t.n0 && !rc; ++i2)
                     for (uint64_t j = 0; j < t.n1 && !rc; ++j)
                         for (uint64_t b = 0; b < uint64_t(td.esize) && !rc; ++b)
                             rc = put(t.packed_off + i2 * t.b + j * td.esize + b,
-                                     t.src_off + j * t.a + i2 * td.esize + b, false);
+                                     t.src_off + j * t.a + i2 * t.estep + b, false);
                 break;
             default: return -5;
             }

@@ -126,6 +126,10 @@ def test_kernel_family_per_view():
     for name in ("five_dims_no_unit_stride", "six_dims_no_unit_stride_u8", "eight_dims_no_unit_stride_f32",
                  "seven_dims_f64_no_unit_stride", "eight_dims_permuted"):
         assert kinds[name] == ["generic"], name                # more than four dims that do not merge
+    for name in ("transpose_inner_stride_2", "transpose_inner_stride_3_u8", "transpose_inner_stride_2_f64"):
+        assert kinds[name] == ["transpose"], name              # the storage-fast dim strided by up to 16 bytes
+    assert kinds["inner_stride_3_f64_too_wide"] == ["generic"]
+    assert kinds["inner_stride_2_flat_chunks"] == ["generic"]
     assert kinds["six_dims_rows_32_byte_runs"] == ["rows"]
     assert kinds["six_dims_rows_20_byte_runs"] == ["rows_split"]
     assert kinds["size_one_dims"] == ["contig"]
