@@ -45,6 +45,7 @@ struct hxt_plan {
     Tile *d_tiles = nullptr;
     uint32_t *d_chunk_tiles = nullptr;
     TensorDev *d_tensors = nullptr;
+    uint32_t *d_inc = nullptr;                  // Plan::inc (tiles of the transpose that span chunks)
     uint32_t acc_stride = 0;
     uint32_t fan = 1;                           // first-level accumulator slots per chunk
     uint32_t sum_bits_table = 0, sum_bits_geom = 0;   // see slot_arrive: table-driven copies / closed-form kernels
@@ -189,6 +190,25 @@ void launch_transpose(const hxt_plan_t &pl, uint32_t first, uint32_t count, int 
         case 2: k_transpose<uint16_t, UNPACK, CSUM, NTP><<<count, kThreads, 0, st>>>(tiles, ct, b, packed, cx); break;
         case 4: k_transpose<uint32_t, UNPACK, CSUM, NTP><<<count, kThreads, 0, st>>>(tiles, ct, b, packed, cx); break;
         default: k_transpose<uint64_t, UNPACK, CSUM, NTP><<<count, kThreads, 0, st>>>(tiles, ct, b, packed, cx); break;
+        }
+    };
+    if (packed_nontemporal(pl)) go.template operator()<true>();
+    else go.template operator()<false>();
+}
+
+template <bool UNPACK, bool CSUM>
+void launch_transpose_span(const hxt_plan_t &pl, uint32_t first, uint32_t count, int esize, const BasePtrs &b,
+                           uint8_t *packed, const SumCtx &cx, hipStream_t st)
+{
+    const Tile *tiles = pl.d_tiles + first;
+    const uint32_t *ct = pl.d_chunk_tiles, *inc = pl.d_inc;
+    const ChunkGeom &g = pl.p.geom;
+    auto go = [&]<bool NTP>() {
+        switch (esize) {
+        case 1: k_transpose_span<uint8_t, UNPACK, CSUM, NTP><<<count, kThreads, 0, st>>>(tiles, ct, inc, g, b, packed, cx); break;
+        case 2: k_transpose_span<uint16_t, UNPACK, CSUM, NTP><<<count, kThreads, 0, st>>>(tiles, ct, inc, g, b, packed, cx); break;
+        case 4: k_transpose_span<uint32_t, UNPACK, CSUM, NTP><<<count, kThreads, 0, st>>>(tiles, ct, inc, g, b, packed, cx); break;
+        default: k_transpose_span<uint64_t, UNPACK, CSUM, NTP><<<count, kThreads, 0, st>>>(tiles, ct, inc, g, b, packed, cx); break;
         }
     };
     if (packed_nontemporal(pl)) go.template operator()<true>();
@@ -387,6 +407,8 @@ int run_copy(hxt_plan_t &pl, void *const *ptrs, uint8_t *packed, uint64_t *sums,
                 while (j < g.count && p.tensors[g.tensor_base + p.tiles[g.first + j].tensor].esize == es) ++j;
                 if (g.kernel == K_TRANSPOSE)
                     launch_transpose<UNPACK, CSUM>(pl, g.first + i, j - i, es, b, packed, cx, st);
+                else if (g.kernel == K_TRANSPOSE_SPAN)
+                    launch_transpose_span<UNPACK, CSUM>(pl, g.first + i, j - i, es, b, packed, cx, st);
                 else
                     launch_generic<UNPACK, CSUM>(pl, g.first + i, j - i, g.tensor_base, es, b, packed, cx, st);
                 i = j;
@@ -508,6 +530,7 @@ int upload(hxt_plan_t &pl)
     if ((rc = to_device(&pl.d_tiles, p.tiles)) != HXT_OK) return rc;
     if ((rc = to_device(&pl.d_chunk_tiles, p.chunk_tiles)) != HXT_OK) return rc;
     if ((rc = to_device(&pl.d_tensors, p.tdev)) != HXT_OK) return rc;
+    if (!p.inc.empty() && (rc = to_device(&pl.d_inc, p.inc)) != HXT_OK) return rc;
     // Accumulator slots: fan-out as choose_fan says; slots are 256 bytes apart (separate memory
     // channels) unless that would be large.
     uint32_t most = p.geom.tpc;
@@ -1014,6 +1037,7 @@ int hxt_plan_destroy(hxt_plan_t *plan)
     release(plan->d_tiles);
     release(plan->d_chunk_tiles);
     release(plan->d_tensors);
+    release(plan->d_inc);
     for (OpState &o : plan->ops) {
         release(o.acc);
         if (o.ev && hipEventDestroy(o.ev) != hipSuccess) rc = HXT_EHIP;

@@ -24,8 +24,10 @@ enum Kind : uint16_t {
     K_TRANSPOSE = 3,  // innermost logical dim strided, second innermost contiguous: LDS tile transpose
     K_GENERIC = 4,    // anything else: one element at a time
     K_ZERO = 5,       // pad bytes between tensors / after the last one (byte granular, < 256 bytes)
-    K_ROWS_SPLIT = 6  // innermost dimension contiguous, runs of 16 bytes or more whose length or pitch is not a
+    K_ROWS_SPLIT = 6, // innermost dimension contiguous, runs of 16 bytes or more whose length or pitch is not a
                       // multiple of 16: a 16-byte packed vector may end one run and begin the next
+    K_TRANSPOSE_SPAN = 7  // the transpose when a chunk holds fewer than 32 rows of the packed side: a tile is a
+                          // full block of the logical matrix and its rows may lie in different chunks
 };
 
 // One unit of work for one workgroup.  64 bytes of 32/64-bit fields, read with scalar loads.
@@ -38,6 +40,9 @@ enum Kind : uint16_t {
 //     packed_off : packed byte of element (i0, j0);  b = packed row pitch in bytes
 //     src_off    : storage byte of element (i0, j0); a = storage pitch between columns in bytes
 //     n0 = ni (rows, contiguous in storage), n1 = nj (columns, contiguous in the packed stream)
+//   TRANSPOSE_SPAN (the same block, not confined to one chunk): as TRANSPOSE, except
+//     packed_off : byte of element (i0, j0) in the logical stream (the kernel finds every row's chunk from it)
+//     chunk      : index of the tile's first entry in Plan::inc;  ordinal = number of entries (chunks it touches)
 struct Tile {
     uint64_t packed_off;
     uint64_t src_off;
@@ -151,7 +156,10 @@ struct Plan {
     uint32_t tile_bytes = 0;
     std::vector<Tile> tiles;             // grouped by kernel family, stream order inside a group
     std::vector<Group> groups;
-    std::vector<uint32_t> chunk_tiles;   // tiles of the table that belong to each chunk
+    std::vector<uint32_t> chunk_tiles;   // arrivals each chunk's checksum expects: its tiles, plus one per TRANSPOSE_SPAN
+                                         // tile that touches it
+    std::vector<uint32_t> inc;           // TRANSPOSE_SPAN tiles: pairs (chunk, ordinal of this arrival among the chunk's),
+                                         // a tile's pairs consecutive and ascending by chunk
     std::vector<TensorDev> tdev;
     bool all_unpack_safe = true;
     bool can_accumulate = true;          // every non-empty tensor is contiguous bf16 or f32

@@ -132,6 +132,24 @@ __device__ __forceinline__ bool slot_arrive(Acc *a, unsigned long long &value, u
 // arrivals over `fan` first-level slots (tile ordinal mod fan) so that they do not queue on
 // one address; the last arrival of a first-level slot carries that slot's total to the chunk's
 // second-level slot, and the last arrival there writes sums[chunk].
+// One arrival, made by one thread: `s` is a finished partial sum for `chunk`, this being arrival number
+// `ordinal` of the `expected` the chunk gets.
+__device__ __forceinline__ void commit_total(unsigned long long s, uint32_t chunk, uint32_t ordinal, uint32_t expected,
+                                             const SumCtx &cx)
+{
+    Acc *top = reinterpret_cast<Acc *>(cx.acc + (size_t(cx.chunks) * cx.fan + chunk) * cx.stride);
+    bool last;
+    if (cx.fan == 1 || expected < 2 * cx.fan) {
+        last = slot_arrive(top, s, expected, cx.sum_bits);
+    } else {
+        const uint32_t sub = ordinal & (cx.fan - 1);
+        const uint32_t share = expected / cx.fan + (sub < (expected & (cx.fan - 1)) ? 1u : 0u);
+        Acc *first = reinterpret_cast<Acc *>(cx.acc + (size_t(chunk) * cx.fan + sub) * cx.stride);
+        last = slot_arrive(first, s, share, cx.sum_bits) && slot_arrive(top, s, cx.fan, cx.sum_bits);
+    }
+    if (last) cx.sums[chunk] = s;
+}
+
 __device__ __forceinline__ void chunk_commit(uint64_t acc, uint32_t chunk, uint32_t ordinal, uint32_t expected,
                                              const SumCtx &cx)
 {
@@ -144,17 +162,7 @@ __device__ __forceinline__ void chunk_commit(uint64_t acc, uint32_t chunk, uint3
         unsigned long long s = 0;
 #pragma unroll
         for (int w = 0; w < kThreads / 64; ++w) s += part[w];
-        Acc *top = reinterpret_cast<Acc *>(cx.acc + (size_t(cx.chunks) * cx.fan + chunk) * cx.stride);
-        bool last;
-        if (cx.fan == 1 || expected < 2 * cx.fan) {
-            last = slot_arrive(top, s, expected, cx.sum_bits);
-        } else {
-            const uint32_t sub = ordinal & (cx.fan - 1);
-            const uint32_t share = expected / cx.fan + (sub < (expected & (cx.fan - 1)) ? 1u : 0u);
-            Acc *first = reinterpret_cast<Acc *>(cx.acc + (size_t(chunk) * cx.fan + sub) * cx.stride);
-            last = slot_arrive(first, s, share, cx.sum_bits) && slot_arrive(top, s, cx.fan, cx.sum_bits);
-        }
-        if (last) cx.sums[chunk] = s;
+        commit_total(s, chunk, ordinal, expected, cx);
     }
 }
 
@@ -912,6 +920,145 @@ __global__ __launch_bounds__(kThreads) void k_transpose(const Tile *__restrict__
         }
     }
     if constexpr (CSUM) chunk_commit(acc, t.chunk, t.ordinal, chunk_tiles[t.chunk], cx);
+}
+
+// ---- transpose whose tiles span chunks -------------------------------------------
+// For matrices whose packed rows are long against the chunk: a tile is a full block of the logical matrix
+// (so that every memory burst of the tensor side is used whole) and row i of it starts at stream byte
+// s0 + i * b, wherever that falls; a tile row is shorter than a chunk, so it meets at most one chunk
+// border.  Thread i first places row i (its chunk, the packed address of its first byte, how many of its
+// columns lie before the border and where the rest go) and leaves that in LDS, so that the copy loop only
+// reads it back.  Checksums are taken on the tensor side, where a thread holds elements of one row only, and
+// added to the tile's per-chunk partial sums in LDS; at the end one thread per chunk touched makes that
+// chunk's arrival (inc holds the tile's chunks, ascending, and the ordinal of each arrival).
+template <typename E, bool UNPACK, bool CSUM, bool NTP>
+__global__ __launch_bounds__(kThreads) void k_transpose_span(const Tile *__restrict__ tiles,
+                                                             const uint32_t *__restrict__ chunk_tiles,
+                                                             const uint32_t *__restrict__ inc, ChunkGeom g,
+                                                             BasePtrs bases, uint8_t *__restrict__ packed, SumCtx cx)
+{
+    constexpr uint32_t T = transpose_tile(sizeof(E));
+    constexpr uint32_t TY = kThreads / T, MAXC = 2 * T + 2;
+    static_assert(T <= kThreads, "one thread places one row");
+    __shared__ __attribute__((aligned(16))) uint8_t lds_raw[T * (T + 1) * sizeof(E)];
+    __shared__ unsigned long long part[MAXC];          // partial sum per chunk touched
+    __shared__ uint32_t touched[MAXC];                 // those chunks
+    // per row: packed offset of column j is row_p0 + j * sizeof(E) for j < row_first, row_p1 + j * sizeof(E) from there on
+    __shared__ uint64_t row_p0[T], row_p1[T];
+    __shared__ uint32_t row_first[T], row_at[T], row_low[T];   // row_at: entry of the row's first chunk; row_low: low bits of
+                                                               // its first byte's position (for the weights of the sum)
+    const Tile t = tiles[blockIdx.x];
+    uint8_t *user = bases.p[t.tensor] + t.src_off;
+    const uint32_t ni = t.n0, nj = t.n1, es = t.estep, n_inc = t.ordinal;
+    const uint32_t *my = inc + 2 * size_t(t.chunk);
+    E(*lds)[T + 1] = reinterpret_cast<E(*)[T + 1]>(lds_raw);
+    const uint32_t tx = threadIdx.x & (T - 1);
+    const uint32_t ty = threadIdx.x / T;
+    for (uint32_t i = threadIdx.x; i < n_inc; i += kThreads) {
+        touched[i] = my[2 * i];
+        part[i] = 0;
+    }
+    __syncthreads();
+    if (threadIdx.x < ni) {                             // place row threadIdx.x
+        const uint64_t B = g.B, s = t.packed_off + uint64_t(threadIdx.x) * t.b;
+        const uint64_t c = s / B, rem = s - c * B;
+        uint32_t lo = 0, hi = n_inc - 1;                // the entry that names chunk c (it is there)
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi) / 2;
+            if (touched[mid] < uint32_t(c)) lo = mid + 1;
+            else hi = mid;
+        }
+        auto chunk_base = [&](uint64_t ch) {
+            const uint32_t slot = fast_div(uint32_t(ch), g.div_k), lane = uint32_t(ch) - slot * g.k;
+            return (uint64_t(lane) * g.q + (lane < g.r ? lane : g.r) + slot) * B;
+        };
+        const uint64_t room = B - rem;                  // bytes of chunk c from the row's start on
+        const uint32_t first = room >= uint64_t(nj) * sizeof(E) ? nj : uint32_t(room / sizeof(E));
+        row_at[threadIdx.x] = lo;
+        row_first[threadIdx.x] = first;
+        row_low[threadIdx.x] = uint32_t(rem) & 3u;
+        row_p0[threadIdx.x] = chunk_base(c) + rem;
+        row_p1[threadIdx.x] = first < nj ? chunk_base(c + 1) + rem - B : 0;     // (+ j * sizeof(E) >= B - rem for those columns)
+    }
+    __syncthreads();
+    // The tensor side of the tile: thread (tx, ty) moves columns ty, ty + TY, ... of row tx between the tensor and
+    // LDS, and while it holds them adds them to the row's sums (the part before the chunk border and the part
+    // after it), which go to the tile's per-chunk partial sums: no reduction across lanes.
+    constexpr uint32_t U = 8;
+    auto tensor_side = [&]() {
+        if (tx >= ni) return;
+        const uint32_t first = row_first[tx], low = row_low[tx];
+        unsigned long long a0 = 0, a1 = 0;
+        auto count = [&](E v, uint32_t j) {
+            const unsigned long long w = elem_weighted(v, uint64_t(low) + uint64_t(j) * sizeof(E));
+            if (j < first) a0 += w;
+            else a1 += w;
+        };
+        if constexpr (!UNPACK) {
+            for (uint32_t j0 = ty; j0 < nj; j0 += TY * U) {
+                E v[U];
+#pragma unroll
+                for (uint32_t u = 0; u < U; ++u)
+                    v[u] = __builtin_nontemporal_load(reinterpret_cast<const E *>(user + uint64_t(min(j0 + u * TY, nj - 1)) * t.a + tx * es));
+#pragma unroll
+                for (uint32_t u = 0; u < U; ++u)
+                    if (j0 + u * TY < nj) {
+                        lds[j0 + u * TY][tx] = v[u];
+                        if constexpr (CSUM) count(v[u], j0 + u * TY);
+                    }
+            }
+        } else {
+            for (uint32_t j = ty; j < nj; j += TY) {
+                const E v = lds[j][tx];
+                __builtin_nontemporal_store(v, reinterpret_cast<E *>(user + j * t.a + tx * es));
+                if constexpr (CSUM) count(v, j);
+            }
+        }
+        if constexpr (CSUM) {
+            const uint32_t at = row_at[tx];
+            if (a0) __hip_atomic_fetch_add(&part[at], a0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (a1) __hip_atomic_fetch_add(&part[at + 1], a1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+    };
+    // The packed side, rows ty, ty + TY, ...: pack stores what is in LDS, unpack fills it.  The loads of an unpack
+    // need no guard (a row beyond the tile repeats the last one, lanes beyond its width shadow its last column),
+    // so all U of a round are in flight before the first is used.
+    auto packed_side = [&]() {
+        const uint32_t txc = min(tx, nj - 1);
+        for (uint32_t i0 = ty; i0 < ni; i0 += TY * U) {
+            E *p[U];
+            E v[U];
+#pragma unroll
+            for (uint32_t u = 0; u < U; ++u) {
+                const uint32_t i = min(i0 + u * TY, ni - 1);
+                const uint64_t off = (txc < row_first[i] ? row_p0[i] : row_p1[i]) + uint64_t(txc) * sizeof(E);
+                p[u] = reinterpret_cast<E *>(packed + off);
+                if constexpr (UNPACK) v[u] = load_elem<NTP>(p[u]);
+            }
+#pragma unroll
+            for (uint32_t u = 0; u < U; ++u) {
+                const uint32_t i = i0 + u * TY;
+                if (i < ni && tx < nj) {
+                    if constexpr (UNPACK) lds[tx][i] = v[u];
+                    else store_elem<NTP>(p[u], lds[tx][i]);
+                }
+            }
+        }
+    };
+    if constexpr (!UNPACK) {
+        tensor_side();
+        __syncthreads();
+        packed_side();
+    } else {
+        packed_side();
+        __syncthreads();
+        tensor_side();
+    }
+    if constexpr (CSUM) {
+        __syncthreads();
+        for (uint32_t i = threadIdx.x; i < n_inc; i += kThreads)
+            commit_total(part[i], touched[i], my[2 * i + 1], chunk_tiles[touched[i]], cx);
+    }
 }
 
 // ---- generic: any strides, one element at a time -------------------------------

@@ -133,14 +133,19 @@ static Kind classify(const TensorPlan &t, uint64_t chunk_bytes)
         for (int d = 0; d < last; ++d) split = split && t.shape[d] < (int64_t(1) << 31);
         return split ? K_ROWS_SPLIT : K_GENERIC;
     }
-    // The dim before the last runs along the storage and the last dim jumps further: a transpose through LDS.
-    if (t.ndim >= 2 && t.stride[last] > 1 && t.stride[last - 1] == 1) return K_TRANSPOSE;
-    // The same when the storage-fast dim has a stride of a few elements (at most 16 bytes, so that neighbouring
-    // elements still share memory bursts), provided a chunk holds at least 32 rows of the packed side: tiles
-    // never cross chunks, and flatter ones than that are served better element by element.
-    if (t.ndim >= 2 && t.stride[last - 1] > 1 && t.stride[last] > t.stride[last - 1] &&
-        uint64_t(t.stride[last - 1]) * t.esize <= 16 && uint64_t(t.shape[last]) * t.esize * 32 <= chunk_bytes)
-        return K_TRANSPOSE;
+    // The dim before the last runs along the storage (stride one, or a few elements: at most 16 bytes, so that
+    // neighbouring elements still share memory bursts) and the last dim jumps further: a transpose through LDS.
+    // Tiles stay inside one chunk when a chunk holds at least 32 rows of the packed side; flatter chunks get
+    // tiles that span chunks (chunks of at least 1 KiB, so that a tile row meets at most one chunk border).
+    const bool classic = t.ndim >= 2 && t.stride[last] > 1 && t.stride[last - 1] == 1;
+    const bool strided = t.ndim >= 2 && t.stride[last - 1] > 1 && t.stride[last] > t.stride[last - 1] &&
+                         uint64_t(t.stride[last - 1]) * t.esize <= 16;
+    if (classic || strided) {
+        const bool tall = uint64_t(t.shape[last]) * t.esize * 32 <= chunk_bytes;
+        if (tall) return K_TRANSPOSE;
+        if (chunk_bytes >= 1024) return K_TRANSPOSE_SPAN;
+        if (classic) return K_TRANSPOSE;
+    }
     return K_GENERIC;
 }
 
@@ -178,7 +183,7 @@ struct RawTile {
 
 struct Builder {
     Plan &p;
-    std::vector<RawTile> by_kernel[7];   // indexed by kernel kind (1..4 and 6)
+    std::vector<RawTile> by_kernel[8];   // indexed by kernel kind (1..4, 6 and 7)
     explicit Builder(Plan &plan) : p(plan) {}
 
     void add(Kind kernel, Kind kind, uint32_t tensor, uint64_t packed_off, uint64_t src_off, uint64_t a,
@@ -250,6 +255,45 @@ struct Builder {
                 if (c1 != 0) region(c, r1, r1 + 1, 0, c1);
             }
             s = end;
+        }
+    }
+
+    // The same blocks of the logical matrix without regard to chunks: every tile is a full T x T block (clipped by
+    // the matrix only).  A tile's entries in p.inc name the chunks its rows lie in; their ordinals are set once
+    // all tiles are known.
+    void transpose_span(uint32_t ti)
+    {
+        const TensorPlan &t = p.tensors[ti];
+        const int n = t.ndim;
+        const uint64_t e = t.esize, I = t.shape[n - 2], J = t.shape[n - 1], sI = t.stride[n - 2], sJ = t.stride[n - 1];
+        const uint64_t T = transpose_tile(uint32_t(e)), batches = t.elems / (I * J);
+        for (uint64_t batch = 0; batch < batches; ++batch) {
+            uint64_t boff = 0, rest = batch;             // storage offset (elements) of the batch index
+            for (int d = n - 3; d >= 0; --d) {
+                boff += (rest % uint64_t(t.shape[d])) * uint64_t(t.stride[d]);
+                rest /= uint64_t(t.shape[d]);
+            }
+            for (uint64_t i0 = 0; i0 < I; i0 += T) {
+                const uint64_t ni = std::min(T, I - i0);
+                for (uint64_t j0 = 0; j0 < J; j0 += T) {
+                    const uint64_t nj = std::min(T, J - j0);
+                    const uint64_t s0 = t.stream_off + ((batch * I + i0) * J + j0) * e;
+                    const size_t first = p.inc.size() / 2;
+                    uint64_t last_c = ~uint64_t(0);
+                    for (uint64_t i = 0; i < ni; ++i) {
+                        const uint64_t s = s0 + i * J * e;
+                        for (uint64_t c : {s / p.B, (s + nj * e - 1) / p.B})
+                            if (c != last_c) {
+                                p.inc.push_back(uint32_t(c));
+                                p.inc.push_back(0);
+                                last_c = c;
+                            }
+                    }
+                    add(K_TRANSPOSE_SPAN, K_TRANSPOSE_SPAN, ti, s0, (boff + i0 * sI + j0 * sJ) * e, sJ * e, J * e,
+                        uint32_t(first), uint32_t(ni), uint32_t(nj), uint32_t(sI * e));
+                    by_kernel[K_TRANSPOSE_SPAN].back().t.ordinal = uint32_t(p.inc.size() / 2 - first);
+                }
+            }
         }
     }
 };
@@ -327,6 +371,7 @@ int build_plan(const hxt_tensor_desc_t *descs, int n_tensors, int n_lanes, size_
         case K_ROWS_SPLIT: b.linear(K_ROWS_SPLIT, K_ROWS_SPLIT, i, t.stream_off, data_end, 0, tile_bytes); break;
         case K_GENERIC: b.linear(K_GENERIC, K_GENERIC, i, t.stream_off, data_end, 0, tile_bytes); break;
         case K_TRANSPOSE: b.transpose(i); break;
+        case K_TRANSPOSE_SPAN: b.transpose_span(i); break;
         default: break;
         }
         if (ext_end > data_end) b.linear(K_CONTIG, K_ZERO, i, data_end, ext_end, t.bytes, HXT_ALIGN);
@@ -336,7 +381,8 @@ int build_plan(const hxt_tensor_desc_t *descs, int n_tensors, int n_lanes, size_
     if (total >= (uint64_t(1) << 31)) return HXT_EUNSUPPORTED;
     p.tiles.reserve(total);
     p.chunk_tiles.assign(p.C, 0);
-    for (Kind kern : {K_CONTIG, K_ROWS, K_ROWS_SPLIT, K_TRANSPOSE, K_GENERIC}) {
+    if (p.inc.size() / 2 >= (uint64_t(1) << 31)) return HXT_EUNSUPPORTED;
+    for (Kind kern : {K_CONTIG, K_ROWS, K_ROWS_SPLIT, K_TRANSPOSE, K_GENERIC, K_TRANSPOSE_SPAN}) {
         auto &v = b.by_kernel[kern];
         size_t i = 0;
         while (i < v.size()) {
@@ -345,7 +391,14 @@ int build_plan(const hxt_tensor_desc_t *descs, int n_tensors, int n_lanes, size_
                 Tile t = v[i].t;
                 t.tensor = v[i].tensor_abs - g.tensor_base;
                 g.n_tensors = std::max(g.n_tensors, t.tensor + 1);
-                t.ordinal = p.chunk_tiles[t.chunk]++;
+                if (kern == K_TRANSPOSE_SPAN) {              // one arrival at every chunk the tile touches
+                    for (uint32_t e = 0; e < t.ordinal; ++e) {
+                        const size_t at = 2 * (size_t(t.chunk) + e);
+                        p.inc[at + 1] = p.chunk_tiles[p.inc[at]]++;
+                    }
+                } else {
+                    t.ordinal = p.chunk_tiles[t.chunk]++;
+                }
                 p.tiles.push_back(t);
                 ++g.count;
                 ++i;

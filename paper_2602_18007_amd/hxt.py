@@ -21,7 +21,7 @@ LIB_PATH = os.path.join(_PKG, "libhxt.so")
 HXT_OK, HXT_EINVAL, HXT_EALIGN, HXT_EUNSUPPORTED, HXT_EOVERLAP, HXT_EHIP, HXT_ENOMEM = 0, -1, -2, -3, -4, -5, -6
 HXT_U8, HXT_F16, HXT_BF16, HXT_F32, HXT_F64 = 1, 2, 3, 4, 5
 HXT_MAX_DIMS = 8
-KIND_NAMES = {0: "none", 1: "contig", 2: "rows", 3: "transpose", 4: "generic", 6: "rows_split"}
+KIND_NAMES = {0: "none", 1: "contig", 2: "rows", 3: "transpose", 4: "generic", 6: "rows_split", 7: "transpose_span"}
 
 # every symbol include/hxt.h declares
 EXPORTS = (

@@ -77,6 +77,11 @@ SMALL_CASES: List[Case] = [
     Case("transpose_inner_stride_2_f64", (((20, 12), (2, 48), 8),), 2, 4096),  # 16 bytes from element to element
     Case("inner_stride_3_f64_too_wide", (((20, 12), (3, 72), 8),), 2, 4096),   # 24 bytes: the per-element kernel
     Case("inner_stride_2_flat_chunks", (((24, 40), (2, 48), 2),), 2, 256),     # a chunk holds 3 packed rows: per element
+    Case("transpose_span_bf16", (((40, 300), (1, 40), 2),), 3, 1024),          # 600-byte packed rows: tiles span chunks
+    Case("transpose_span_f32_batched", (((3, 70, 90), (70 * 100, 1, 70), 4),), 4, 1024),
+    Case("transpose_span_u8_long_rows", (((5, 3000), (1, 8), 1),), 2, 1024),   # a packed row is longer than a chunk
+    Case("transpose_span_strided_f64", (((20, 50), (2, 48), 8),), 2, 2048),
+    Case("transpose_span_between_contig", (contig((100,), 1), ((64, 200), (1, 64), 2), contig((700,), 4)), 4, 1024),
     Case("sixty_four_lanes", (contig((40000,), 2),), 64, 512),                # 157 chunks, lanes hold 3 or 2
     Case("mixed_dtypes_multi", (contig((33,), 1), ((8, 24), (32, 1), 2), ((16, 8), (1, 16), 4), contig((5,), 8)), 4, 512),
 ]

@@ -87,7 +87,8 @@ extern "C" int plan_interp(const hxt_tensor_desc_t *descs, int n_tensors, int n_
             const uint32_t ta = g.tensor_base + t.tensor;
             if (t.tensor >= g.n_tensors || ta >= uint32_t(n_tensors)) return -5;
             const TensorDev &td = p.tdev[ta];
-            const uint64_t c_lo = p.chunk_packed_off(t.chunk), c_hi = c_lo + p.chunk_padded(t.chunk);
+            const bool span = t.kind == K_TRANSPOSE_SPAN;      // its rows name their chunks one by one (below)
+            uint64_t c_lo = span ? 0 : p.chunk_packed_off(t.chunk), c_hi = span ? 0 : c_lo + p.chunk_padded(t.chunk);
             auto put = [&](uint64_t poff, uint64_t uoff, bool zero) -> int {
                 if (!c.packed_ok(poff, 1)) return -3;
                 if (poff < c_lo || poff >= c_hi) return -4;
@@ -105,7 +106,7 @@ extern "C" int plan_interp(const hxt_tensor_desc_t *descs, int n_tensors, int n_
             };
             int rc = 0;
             // linear tiles record where they start inside their chunk (the fused tag kernels weigh words by it)
-            if (t.kind != K_TRANSPOSE && t.a != t.packed_off - c_lo) return -8;
+            if (t.kind != K_TRANSPOSE && !span && t.a != t.packed_off - c_lo) return -8;
             // the per-element kernel's carried arithmetic must hold for every linear tile, whichever kernel ends up serving it
             if ((t.kind == K_CONTIG || t.kind == K_ROWS || t.kind == K_ROWS_SPLIT || t.kind == K_GENERIC) && td.all_div) {
                 if (t.src_off % td.esize || t.n0 % td.esize) return -7;
@@ -142,6 +143,31 @@ extern "C" int plan_interp(const hxt_tensor_desc_t *descs, int n_tensors, int n_
                             rc = put(t.packed_off + i2 * t.b + j * td.esize + b,
                                      t.src_off + j * t.a + i2 * t.estep + b, false);
                 break;
+            case K_TRANSPOSE_SPAN: {
+                if (g.kernel != K_TRANSPOSE_SPAN || t.n0 > transpose_tile(td.esize) || t.n1 > transpose_tile(td.esize)) return -5;
+                if (t.estep < uint32_t(td.esize) || t.estep % uint32_t(td.esize) || t.estep > 16) return -5;
+                if (p.B < 1024 || t.ordinal == 0 || uint64_t(t.chunk) + t.ordinal > p.inc.size() / 2) return -5;
+                const uint32_t *my = p.inc.data() + 2 * size_t(t.chunk);
+                std::vector<uint8_t> touched(t.ordinal, 0);
+                for (uint32_t e = 1; e < t.ordinal; ++e)
+                    if (my[2 * e] <= my[2 * (e - 1)]) return -5;                    // ascending, each chunk once
+                for (uint64_t i2 = 0; i2 < t.n0 && !rc; ++i2)
+                    for (uint64_t j = 0; j < t.n1 && !rc; ++j)
+                        for (uint64_t b = 0; b < uint64_t(td.esize) && !rc; ++b) {
+                            const uint64_t s = t.packed_off + i2 * t.b + j * td.esize + b;   // byte of the logical stream
+                            const uint64_t ch = s / p.B;
+                            if (ch >= p.C) return -3;
+                            uint32_t e = 0;
+                            while (e < t.ordinal && my[2 * e] != ch) ++e;
+                            if (e == t.ordinal) return -5;                          // a chunk the tile does not announce
+                            touched[e] = 1;
+                            c_lo = p.chunk_packed_off(ch), c_hi = c_lo + p.chunk_padded(ch);
+                            rc = put(c_lo + (s - ch * p.B), t.src_off + j * t.a + i2 * t.estep + b, false);
+                        }
+                for (uint8_t x : touched)
+                    if (!x) return -5;                                              // an arrival announced for nothing
+                break;
+            }
             default: return -5;
             }
             if (rc) return rc;
@@ -153,6 +179,15 @@ extern "C" int plan_interp(const hxt_tensor_desc_t *descs, int n_tensors, int n_
     std::vector<std::vector<uint8_t>> ord(p.C);
     for (uint64_t ch = 0; ch < p.C; ++ch) ord[ch].assign(p.chunk_tiles[ch], 0);
     for (const Tile &t : p.tiles) {
+        if (t.kind == K_TRANSPOSE_SPAN) {                   // one arrival per chunk touched, numbered in the table
+            for (uint32_t e = 0; e < t.ordinal; ++e) {
+                const uint32_t ch = p.inc[2 * (size_t(t.chunk) + e)], o = p.inc[2 * (size_t(t.chunk) + e) + 1];
+                if (ch >= p.C) return -5;
+                ++count[ch];
+                if (o >= p.chunk_tiles[ch] || ord[ch][o]++) return -5;
+            }
+            continue;
+        }
         ++count[t.chunk];
         if (t.ordinal >= p.chunk_tiles[t.chunk] || ord[t.chunk][t.ordinal]++) return -5;   // ordinals are a permutation
     }
