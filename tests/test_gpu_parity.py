@@ -156,6 +156,8 @@ MID_CASES = [
     Case("transpose_storage_stride_2", (((4096, 512), (2, 8192), 2),), 4, 65536),         # the storage-fast dim strided
     Case("transpose_storage_stride_4_u8_batched", (((3, 200, 130), (4 * 200 * 130, 4, 800), 1),), 2, 8192),
     Case("transpose_storage_stride_3_f32", (((129, 131), (3, 400), 4),), 3, 32768),
+    Case("transpose_span_one_row_per_chunk", (((64, 32768), (1, 64), 2),), 4, 65536),     # tiles that span 64 chunks
+    Case("transpose_span_rows_longer_than_chunks", (((40, 3, 9000), (1, 40 * 9000, 40), 4),), 3, 8192),
     Case("generic_mid", (((50, 30, 20), (20, 1000, 1), 2),), 3, 4096),
     Case("multi_mid", (contig((70001,), 1), ((64, 2, 128), (128, 64 * 128, 1), 2), ((96, 80), (1, 96), 4),
                        contig((3, 1000), 8), ((33, 10), (20, 2), 2)), 4, 8192),
