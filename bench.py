@@ -607,6 +607,8 @@ def config_entries(torch, hxt, wl, a, link, headline_regions):
     direct("qwen_rows_view")
     direct("transpose_view")
     direct("rows_split_view", note="bf16 [327680, 100]: runs of 200 bytes at a pitch of 256 bytes")
+    direct("wide_transpose_view", hints=("cold",), note="bf16 [256, 65536] with strides (1, 256): 8 rows of the packed side per "
+           "chunk, transpose tiles span chunks")
     direct("inner_stride_view", hints=("cold",), note="bf16 [4096, 4096] with strides (8192, 2): every second element, "
            "so the tensor side moves two bytes of memory bursts per byte of payload")
     return out

@@ -768,9 +768,37 @@ __device__ __forceinline__ uint64_t elem_weighted(E v, uint64_t packed_pos)
 // FULL: the tile is T x T, so every index computation folds to shifts and masks and each thread moves exactly
 // T * T / (V * kThreads) vectors per phase, all of whose global loads are issued before the first LDS store
 // (measured with counters: with run-time extents the kernel was bound by its integer divisions, not by memory).
-template <typename E, bool SRC_IS_PACKED, bool CSUM, bool NTP, int UA, bool FULL>
-__device__ __forceinline__ uint64_t transpose_vec(const uint8_t *src, uint64_t src_pitch, uint32_t R_in, uint32_t Cc_in,
-                                                  uint8_t *dst, uint64_t dst_pitch, uint8_t *lds)
+// Where the rows of a tile lie on the packed side, and where their sums go.
+// PitchRows: a tile inside one chunk, rows a fixed pitch apart, one sum for the tile.
+struct PitchRows {
+    uint8_t *base;
+    uint64_t pitch;
+    __device__ __forceinline__ uint8_t *at(uint32_t row, uint32_t byte) const { return base + row * pitch + byte; }
+    __device__ __forceinline__ void count(uint32_t, uint32_t, uint64_t s, uint64_t &acc) const { acc += s; }
+};
+// SpanRows: every row placed on its own (k_transpose_span keeps the placement in LDS): bytes below first_b[row]
+// lie p0[row] into the packed buffer, the rest p1[row]; a vector's sum goes to the partial sum of its chunk.
+struct SpanRows {
+    uint8_t *packed;
+    const uint64_t *p0, *p1;
+    const uint32_t *first_b, *entry;
+    unsigned long long *part;
+    __device__ __forceinline__ uint8_t *at(uint32_t row, uint32_t byte) const
+    {
+        return packed + (byte < first_b[row] ? p0[row] : p1[row]) + byte;
+    }
+    __device__ __forceinline__ void count(uint32_t row, uint32_t byte, uint64_t s, uint64_t &) const
+    {
+        __hip_atomic_fetch_add(&part[entry[row] + (byte < first_b[row] ? 0u : 1u)], (unsigned long long)s, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+};
+
+// user / user_pitch: the tensor side (rows of the tile as the tensor stores them); pk: the packed side.
+// SRC_IS_PACKED: unpack (packed rows are the source), else pack.
+template <typename E, bool SRC_IS_PACKED, bool CSUM, bool NTP, int UA, bool FULL, class PK>
+__device__ __forceinline__ uint64_t transpose_vec(uint8_t *user, uint64_t user_pitch, uint32_t R_in, uint32_t Cc_in,
+                                                  const PK &pk, uint8_t *lds)
 {
     constexpr uint32_t T = transpose_tile(sizeof(E)), V = 16 / sizeof(E), ROWB = T * sizeof(E), NV = T / V;
     const uint32_t R = FULL ? T : R_in, Cc = FULL ? T : Cc_in;
@@ -780,8 +808,14 @@ __device__ __forceinline__ uint64_t transpose_vec(const uint8_t *src, uint64_t s
         const uint32_t r = v / nvs, cv = v - r * nvs;
         slot = r * ROWB + ((cv ^ ((r / V) % NV)) * 16);
         // the user tensor is streamed once (non-temporal) and may be only UA-byte aligned; the packed side as the plan says
-        if constexpr (SRC_IS_PACKED) return load16<NTP>(reinterpret_cast<const u32x4 *>(src + r * src_pitch + cv * 16));
-        else return load_user<UA, true>(src + r * src_pitch + cv * 16);
+        if constexpr (SRC_IS_PACKED) return load16<NTP>(reinterpret_cast<const u32x4 *>(pk.at(r, cv * 16)));
+        else return load_user<UA, true>(user + r * user_pitch + cv * 16);
+    };
+    auto count_src = [&](uint32_t v, const u32x4 &x) {     // after the loads, so that none of them waits for a sum
+        if constexpr (CSUM && SRC_IS_PACKED) {
+            const uint32_t r = v / nvs, cv = v - r * nvs;
+            pk.count(r, cv * 16, words_sum(x), acc);
+        }
     };
     if constexpr (FULL) {
         constexpr uint32_t PER = T * T / (V * kThreads);   // 8 vectors per thread (4 for 1-byte elements)
@@ -791,14 +825,14 @@ __device__ __forceinline__ uint64_t transpose_vec(const uint8_t *src, uint64_t s
         for (uint32_t u = 0; u < PER; ++u) x[u] = load_src(threadIdx.x + u * kThreads, slot[u]);
 #pragma unroll
         for (uint32_t u = 0; u < PER; ++u) {
-            if constexpr (CSUM && SRC_IS_PACKED) acc += words_sum(x[u]);
+            count_src(threadIdx.x + u * kThreads, x[u]);
             *reinterpret_cast<u32x4 *>(lds + slot[u]) = x[u];
         }
     } else {
         for (uint32_t v = threadIdx.x; v < R * nvs; v += kThreads) {
             uint32_t slot;
             const u32x4 x = load_src(v, slot);
-            if constexpr (CSUM && SRC_IS_PACKED) acc += words_sum(x);
+            count_src(v, x);
             *reinterpret_cast<u32x4 *>(lds + slot) = x;
         }
     }
@@ -828,9 +862,9 @@ __device__ __forceinline__ uint64_t transpose_vec(const uint8_t *src, uint64_t s
             const uint32_t r = dv * V + q;
             o.e[q] = *reinterpret_cast<const E *>(lds + r * ROWB + (((c / V) ^ ((r / V) % NV)) * 16) + (c % V) * sizeof(E));
         }
-        if constexpr (CSUM && !SRC_IS_PACKED) acc += words_sum(o.x);
-        if constexpr (SRC_IS_PACKED) store_user<UA, true>(dst + c * dst_pitch + dv * 16, o.x);
-        else store16<NTP>(reinterpret_cast<u32x4 *>(dst + c * dst_pitch + dv * 16), o.x);
+        if constexpr (CSUM && !SRC_IS_PACKED) pk.count(c, dv * 16, words_sum(o.x), acc);
+        if constexpr (SRC_IS_PACKED) store_user<UA, true>(user + c * user_pitch + dv * 16, o.x);
+        else store16<NTP>(reinterpret_cast<u32x4 *>(pk.at(c, dv * 16)), o.x);
     };
     if constexpr (FULL) {
         static_assert(NV % 8 == 0, "a full tile's dst rows must be whole groups of 8 vectors");
@@ -861,8 +895,9 @@ __global__ __launch_bounds__(kThreads) void k_transpose(const Tile *__restrict__
         // storage: nj rows (pitch a) of ni contiguous elements; packed: ni rows (pitch b) of nj elements.  Every
         // storage row of the tile is off a 16-byte boundary by the same amount (the pitch is a multiple of 16).
         auto run = [&]<int UA, bool FULL = false>() {
-            if constexpr (!UNPACK) return transpose_vec<E, false, CSUM, NTP, UA, FULL>(user, t.a, nj, ni, pk, t.b, lds_raw);
-            else return transpose_vec<E, true, CSUM, NTP, UA, FULL>(pk, t.b, ni, nj, user, t.a, lds_raw);
+            const PitchRows rows{pk, t.b};
+            if constexpr (!UNPACK) return transpose_vec<E, false, CSUM, NTP, UA, FULL>(user, t.a, nj, ni, rows, lds_raw);
+            else return transpose_vec<E, true, CSUM, NTP, UA, FULL>(user, t.a, ni, nj, rows, lds_raw);
         };
         const uint32_t mis = uint32_t(reinterpret_cast<uintptr_t>(user)) & 15u;
         if (mis == 0 && ni == T && nj == T) acc = run.template operator()<16, true>();      // the common case
@@ -1045,7 +1080,25 @@ __global__ __launch_bounds__(kThreads) void k_transpose_span(const Tile *__restr
             }
         }
     };
-    if constexpr (!UNPACK) {
+    // 16-byte vectors on both sides when every extent, pitch and row start allows it (then a row's chunk border
+    // falls between two vectors too); the tensor side may be less than 16-byte aligned as a whole.
+    constexpr uint32_t V = 16 / sizeof(E);
+    const bool vec_ok = es == sizeof(E) && ((ni | nj) % V) == 0 && ((t.packed_off | t.a | t.b) % 16) == 0;
+    if (vec_ok) {
+        const SpanRows rows{packed, row_p0, row_p1, row_first, row_at, part};    // row_first in bytes: see below
+        if (threadIdx.x < ni) row_first[threadIdx.x] *= uint32_t(sizeof(E));     // (its own entry: no other thread reads it yet)
+        __syncthreads();
+        auto run = [&]<int UA, bool FULL = false>() {
+            if constexpr (!UNPACK) transpose_vec<E, false, CSUM, NTP, UA, FULL>(user, t.a, nj, ni, rows, lds_raw);
+            else transpose_vec<E, true, CSUM, NTP, UA, FULL>(user, t.a, ni, nj, rows, lds_raw);
+        };
+        const uint32_t mis = uint32_t(reinterpret_cast<uintptr_t>(user)) & 15u;
+        if (mis == 0 && ni == T && nj == T) run.template operator()<16, true>();
+        else if (mis == 0) run.template operator()<16>();
+        else if ((mis & 3u) == 0) run.template operator()<4>();
+        else if ((mis & 1u) == 0) run.template operator()<2>();
+        else run.template operator()<1>();
+    } else if constexpr (!UNPACK) {
         tensor_side();
         __syncthreads();
         packed_side();

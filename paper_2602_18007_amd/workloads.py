@@ -147,11 +147,19 @@ def inner_stride_view() -> Workload:
                     note="bf16 [4096,4096] view with strides (8192,2) (32 MiB out of 64 MiB of storage)")
 
 
+def wide_transpose_view() -> Workload:
+    """Supplementary: a transposed view whose packed rows are long against the chunk (128 KiB rows, 1 MiB chunks:
+    8 rows per chunk), so that full transpose tiles span chunks."""
+    t = TensorDesc((256, 65536), (1, 256))
+    return Workload("wide_transpose_view", (t,), 4, 1 * MiB, "normal", 1.0, seed=BASE_SEED + 9,
+                    note="bf16 logical [256,65536] with strides (1,256) (32 MiB)")
+
+
 ALL = {
     "tiny": tiny, "llama8b_boundary": llama8b_boundary, "qwen2_7b_boundary": qwen2_7b_boundary,
     "stream_1f1b": stream_1f1b, "grad_buckets": grad_buckets,
     "qwen_rows_view": qwen_rows_view, "transpose_view": transpose_view, "rows_split_view": rows_split_view,
-    "inner_stride_view": inner_stride_view,
+    "inner_stride_view": inner_stride_view, "wide_transpose_view": wide_transpose_view,
 }
 
 

@@ -82,7 +82,7 @@ def test_default_run_lists_every_benchmark_message():
                  ("qwen2_7b_boundary", "cpu_forward"), ("stream_1f1b", "device_direct"), ("stream_1f1b", "cpu_forward"),
                  ("grad_buckets", "device_direct"), ("grad_buckets", "cpu_forward"), ("qwen_rows_view", "device_direct"),
                  ("transpose_view", "device_direct"), ("rows_split_view", "device_direct"),
-                 ("inner_stride_view", "device_direct")):
+                 ("inner_stride_view", "device_direct"), ("wide_transpose_view", "device_direct")):
         assert want in names, want
     for e in out["configs"]:
         if e["path"] == "device_direct":

@@ -1125,7 +1125,8 @@ def test_config_grad_buckets_full_size_both_paths():
 
 
 @pytest.mark.parametrize("hint", [None, 1], ids=["hint_by_size", "all_cold_non_temporal"])
-@pytest.mark.parametrize("name", ["qwen_rows_view", "transpose_view", "rows_split_view", "inner_stride_view"])
+@pytest.mark.parametrize("name", ["qwen_rows_view", "transpose_view", "rows_split_view", "inner_stride_view",
+                                  "wide_transpose_view"])
 def test_supplementary_strided_messages_full_size(name, hint):
     """hint 1: the packed side non-temporal as well, as in the benchmark's all-cold figures."""
     w = wl.ALL[name]()
