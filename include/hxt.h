@@ -171,7 +171,7 @@ int hxt_plan_tensor_unpack_safe(const hxt_plan_t *plan, int t);
 /* which kernel family serves tensor t: 0 none (empty), 1 contiguous copy, 2 row gather (runs and
  * pitches that are multiples of 16 bytes), 3 LDS transpose, 4 per-element, 6 row gather in narrower
  * pieces (runs of 16 bytes or more whose length or pitch is not a multiple of 16), 7 LDS transpose
- * whose tiles span chunks (a chunk holds fewer than 32 rows of the packed side) */
+ * whose tiles span chunks (a chunk holds fewer rows of the packed side than a tile is high) */
 int hxt_plan_tensor_kind(const hxt_plan_t *plan, int t);
 
 /* ---- step 2: pack (Section 2.2: user buffer -> chunk buffer, device to device)

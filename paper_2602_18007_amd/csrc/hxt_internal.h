@@ -26,8 +26,8 @@ enum Kind : uint16_t {
     K_ZERO = 5,       // pad bytes between tensors / after the last one (byte granular, < 256 bytes)
     K_ROWS_SPLIT = 6, // innermost dimension contiguous, runs of 16 bytes or more whose length or pitch is not a
                       // multiple of 16: a 16-byte packed vector may end one run and begin the next
-    K_TRANSPOSE_SPAN = 7  // the transpose when a chunk holds fewer than 32 rows of the packed side: a tile is a
-                          // full block of the logical matrix and its rows may lie in different chunks
+    K_TRANSPOSE_SPAN = 7  // the transpose when a chunk holds fewer rows of the packed side than a tile is high: a tile
+                          // is a full block of the logical matrix and its rows may lie in different chunks
 };
 
 // One unit of work for one workgroup.  64 bytes of 32/64-bit fields, read with scalar loads.

@@ -135,13 +135,14 @@ static Kind classify(const TensorPlan &t, uint64_t chunk_bytes)
     }
     // The dim before the last runs along the storage (stride one, or a few elements: at most 16 bytes, so that
     // neighbouring elements still share memory bursts) and the last dim jumps further: a transpose through LDS.
-    // Tiles stay inside one chunk when a chunk holds at least 32 rows of the packed side; flatter chunks get
-    // tiles that span chunks (chunks of at least 1 KiB, so that a tile row meets at most one chunk border).
+    // Tiles stay inside one chunk when a chunk holds at least a tile's height of rows of the packed side, so that
+    // all but the tiles at chunk borders are full; flatter chunks get tiles that span chunks (chunks of at least
+    // 1 KiB, so that a tile row meets at most one chunk border).
     const bool classic = t.ndim >= 2 && t.stride[last] > 1 && t.stride[last - 1] == 1;
     const bool strided = t.ndim >= 2 && t.stride[last - 1] > 1 && t.stride[last] > t.stride[last - 1] &&
                          uint64_t(t.stride[last - 1]) * t.esize <= 16;
     if (classic || strided) {
-        const bool tall = uint64_t(t.shape[last]) * t.esize * 32 <= chunk_bytes;
+        const bool tall = uint64_t(t.shape[last]) * t.esize * transpose_tile(uint32_t(t.esize)) <= chunk_bytes;
         if (tall) return K_TRANSPOSE;
         if (chunk_bytes >= 1024) return K_TRANSPOSE_SPAN;
         if (classic) return K_TRANSPOSE;

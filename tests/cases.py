@@ -72,11 +72,11 @@ SMALL_CASES: List[Case] = [
     Case("six_dims_rows_32_byte_runs", (((2, 3, 2, 3, 2, 16), (384, 96, 1152, 24, 3456, 1), 2),), 2, 512),
     Case("six_dims_rows_20_byte_runs", (permuted((2, 3, 2, 3, 2, 10), (5, 1, 3, 0, 4, 2), 2, scale=1),), 3, 256),
     Case("seven_dims_f64_no_unit_stride", (permuted((2, 2, 2, 3, 2, 2, 3), (3, 6, 0, 5, 1, 4, 2), 8),), 2, 1024),
-    Case("transpose_inner_stride_2", (((24, 40), (2, 48), 2),), 2, 4096),    # storage-fast dim strided by two elements
-    Case("transpose_inner_stride_3_u8", (((5, 17, 33), (4000, 3, 60), 1),), 3, 2048),
-    Case("transpose_inner_stride_2_f64", (((20, 12), (2, 48), 8),), 2, 4096),  # 16 bytes from element to element
-    Case("inner_stride_3_f64_too_wide", (((20, 12), (3, 72), 8),), 2, 4096),   # 24 bytes: the per-element kernel
-    Case("inner_stride_2_flat_chunks", (((24, 40), (2, 48), 2),), 2, 256),     # a chunk holds 3 packed rows: per element
+    Case("transpose_inner_stride_2", (((24, 40), (2, 48), 2),), 2, 16384),   # storage-fast dim strided by two elements
+    Case("transpose_inner_stride_3_u8", (((5, 17, 33), (4000, 3, 60), 1),), 3, 8192),
+    Case("transpose_inner_stride_2_f64", (((20, 12), (2, 48), 8),), 2, 8192),  # 16 bytes from element to element
+    Case("inner_stride_3_f64_too_wide", (((20, 12), (3, 72), 8),), 2, 8192),   # 24 bytes: the per-element kernel
+    Case("inner_stride_2_flat_chunks", (((24, 40), (2, 48), 2),), 2, 256),     # chunks below 1 KiB that hold 3 packed rows: per element
     Case("transpose_span_bf16", (((40, 300), (1, 40), 2),), 3, 1024),          # 600-byte packed rows: tiles span chunks
     Case("transpose_span_f32_batched", (((3, 70, 90), (70 * 100, 1, 70), 4),), 4, 1024),
     Case("transpose_span_u8_long_rows", (((5, 3000), (1, 8), 1),), 2, 1024),   # a packed row is longer than a chunk

@@ -147,13 +147,16 @@ MID_CASES = [
     Case("rows_4d", (((5, 7, 3, 64), (64, 5 * 3 * 64, 5 * 64, 1), 2),), 2, 2048),
     Case("transpose_mid", (((200, 150), (1, 200), 2),), 2, 4096),
     Case("transpose_512", (((512, 384), (1, 512), 2),), 4, 65536),
+    Case("transpose_512_tall_chunks", (((512, 384), (1, 512), 2),), 4, 131072),   # tiles confined to chunks, vector path
+    Case("transpose_u8_vec_tall_chunks", (((128, 96), (1, 128), 1),), 2, 16384),
+    Case("transpose_mid_tall_chunks", (((200, 150), (1, 200), 2),), 2, 65536),
     Case("transpose_batch_f32", (((3, 70, 90), (70 * 100, 1, 70), 4),), 4, 1024),
     Case("transpose_u8", (((130, 67), (1, 130), 1),), 2, 512),
     Case("transpose_f64", (((100, 60), (1, 128), 8),), 3, 2048),
     Case("transpose_u8_vec", (((128, 96), (1, 128), 1),), 2, 4096),
     Case("transpose_bf16_vec_partial", (((72, 40), (1, 80), 2),), 2, 8192),
     Case("transpose_f32_vec_batched", (((5, 128, 68), (128, 1, 5 * 128), 4),), 4, 32768),
-    Case("transpose_storage_stride_2", (((4096, 512), (2, 8192), 2),), 4, 65536),         # the storage-fast dim strided
+    Case("transpose_storage_stride_2", (((4096, 512), (2, 8192), 2),), 4, 262144),        # the storage-fast dim strided
     Case("transpose_storage_stride_4_u8_batched", (((3, 200, 130), (4 * 200 * 130, 4, 800), 1),), 2, 8192),
     Case("transpose_storage_stride_3_f32", (((129, 131), (3, 400), 4),), 3, 32768),
     Case("transpose_span_one_row_per_chunk", (((64, 32768), (1, 64), 2),), 4, 65536),     # tiles that span 64 chunks

@@ -130,7 +130,7 @@ def test_kernel_family_per_view():
         assert kinds[name] == ["transpose"], name              # the storage-fast dim strided by up to 16 bytes
     for name in ("transpose_span_bf16", "transpose_span_f32_batched", "transpose_span_u8_long_rows",
                  "transpose_span_strided_f64"):
-        assert kinds[name] == ["transpose_span"], name         # a chunk holds fewer than 32 rows of the packed side
+        assert kinds[name] == ["transpose_span"], name         # a chunk holds fewer rows of the packed side than a tile is high
     assert kinds["transpose_span_between_contig"] == ["contig", "transpose_span", "contig"]
     assert kinds["true_transpose_64x48"] == ["transpose"]      # chunks below 1 KiB: tiles stay inside chunks
     assert kinds["inner_stride_3_f64_too_wide"] == ["generic"]
@@ -370,7 +370,7 @@ def test_work_tables_for_mid_size_strided_messages(interp):
         got = np.full(want.size, 0x99, np.uint8)
         rc, _, kinds = run_interp(interp, case, raws, got, 0, 2048)
         assert rc == 0 and np.array_equal(got, want), case.name
-        # 150- and 90-element rows against 4 KiB and 1 KiB chunks: fewer than 32 packed rows per chunk, tiles span chunks
+        # 150- and 90-element rows against 4 KiB and 1 KiB chunks: fewer packed rows per chunk than a tile is high, tiles span chunks
         assert kinds[0] == {"rows_mid": 2, "transpose_mid": 7, "transpose_batch_mid": 7, "transpose_u8": 3}[case.name]
 
 
