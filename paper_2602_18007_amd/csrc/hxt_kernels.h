@@ -6,12 +6,14 @@
 // unsigned integers so that any bit pattern survives unchanged.
 //
 // Work decomposition: the host planner cuts the message into tiles (one per
-// workgroup, never crossing a chunk or a tensor); a workgroup reads its 64-byte
-// tile record with scalar loads and moves the bytes with 128-bit vector
-// accesses.  Checksums are accumulated per thread in 64-bit integers, reduced
-// across the 64-lane wavefront with shuffles, across the four waves through
-// LDS, and added to the chunk's total with one 64-bit atomic per workgroup;
-// integer addition makes the result independent of the order of arrival.
+// workgroup, never crossing a tensor, and never a chunk except in
+// k_transpose_span); a workgroup reads its 64-byte tile record with scalar
+// loads and moves the bytes with 128-bit vector accesses where the view allows.
+// Checksums are accumulated per thread in 64-bit integers, reduced across the
+// 64-lane wavefront with shuffles, across the four waves through LDS, and added
+// to the chunk's total with one 64-bit atomic per workgroup (k_transpose_span:
+// one per chunk its tile touches); integer addition makes the result
+// independent of the order of arrival.
 #ifndef HXT_KERNELS_H
 #define HXT_KERNELS_H
 
