@@ -932,7 +932,8 @@ def run_exchange(case, raws_per_msg, path, n_buffers, streams, **how):
 def test_exchange_stream_small_messages(path, n_buffers):
     say("exchange", path, "buffers", n_buffers)
     streams = [torch.cuda.Stream() for _ in range(3)]
-    for name, nmsg in (("contig_1MB_ragged", 7), ("multi_mid", 5), ("rows_mid", 4)):
+    for name, nmsg in (("contig_1MB_ragged", 7), ("multi_mid", 5), ("rows_mid", 4), ("transpose_span_one_row_per_chunk", 4),
+                       ("transpose_storage_stride_2", 3)):
         case = [c for c in MID_CASES if c.name == name][0]
         run_exchange(case, [make_storages(case, 3000 + i) for i in range(nmsg)], path, n_buffers, streams)
     # all three roles on one stream: the steps simply serialise
